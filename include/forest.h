@@ -1,0 +1,166 @@
+/*
+ * forest.h -- C ABI of the MI355X (gfx950) tree-ensemble inference library.
+ *
+ * The library evaluates random forests and gradient-boosted trees the way the paper's
+ * operator representation does (Section 3.1.2, Table 2, Fig. 2): every internal node of
+ * every tree is evaluated for every row (feature selection W1/A as a gather, element-wise
+ * comparison against the thresholds W2/B), the reached leaf is resolved from the split
+ * outcomes (W3 + first argmax, equivalently the signed path matrix C with path lengths D),
+ * leaf payloads E are gathered and reduced across trees, and an optional monotone transform
+ * is applied; labels are taken before the transform (Section 4.3.3, redundant elimination).
+ *
+ * All functions are extern "C", take plain pointers and sizes, return 0 or a negative
+ * FOREST_E* code, never throw and never abort.
+ */
+#ifndef FOREST_H_
+#define FOREST_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct forest forest; /* opaque, immutable after forest_load */
+
+enum { FOREST_AGG_SUM = 0, FOREST_AGG_MEAN = 1 };
+enum { FOREST_TRANSFORM_NONE = 0, FOREST_TRANSFORM_SIGMOID = 1, FOREST_TRANSFORM_SOFTMAX = 2 };
+enum { FOREST_OUT_SCORES = 0, FOREST_OUT_LABELS = 1, FOREST_OUT_BOTH = 2 };
+
+enum {
+    FOREST_OK = 0,
+    FOREST_EINVAL = -1,     /* null pointer, bad size or bad enum value */
+    FOREST_ETREE = -2,      /* malformed tree: child out of range, node reached twice, cycle,
+                               unreachable node, empty tree */
+    FOREST_EFEATURE = -3,   /* split feature >= n_features */
+    FOREST_ENONFINITE = -4, /* NaN threshold (+-Inf thresholds are legal) */
+    FOREST_ENOMEM = -5,     /* host or device allocation failed */
+    FOREST_EHIP = -6,       /* a HIP runtime call failed (no device, launch error, ...) */
+    FOREST_ELIMIT = -7      /* model exceeds a documented limit of the kernels */
+};
+
+/* Documented limits (checked at load; FOREST_ELIMIT): */
+#define FOREST_MAX_FEATURES 4096  /* n_features */
+#define FOREST_MAX_OUTPUTS 32     /* n_outputs (K) */
+#define FOREST_MAX_DEPTH 64       /* longest root-to-leaf path, in tests */
+
+/*
+ * A forest as the caller holds it: per-node arrays, trees concatenated.  All pointers are
+ * HOST memory, borrowed for the duration of forest_load only.
+ *
+ * Tree t owns nodes [tree_offset[t], tree_offset[t+1]); its root is the first node of the
+ * range; left/right are indices local to the tree.  A node with feature < 0 is a leaf (a
+ * root may be a leaf).  A row goes LEFT iff x[feature] <= threshold, as an IEEE float32
+ * ordered comparison (a NaN feature goes right).
+ *
+ * leaf_width == 1: a leaf of tree t adds leaf_value[node] into output column
+ * tree_output[t] (column 0 when tree_output is NULL).  leaf_width == n_outputs: a leaf adds
+ * leaf_value[node * n_outputs + k] into every column k.
+ *
+ * Per column: raw = base_score[k] + (aggregate == MEAN ? sum / #trees feeding k : sum),
+ * accumulated in double and rounded once.  scores = transform(raw).  label (n_outputs >= 2)
+ * = smallest k with maximal raw; n_outputs == 1: raw > 0.5 (no transform) or raw > 0 (sigmoid).
+ */
+typedef struct forest_desc {
+    int32_t n_trees;
+    int32_t n_features;
+    int32_t n_outputs;         /* K >= 1 */
+    int32_t leaf_width;        /* 1 or n_outputs */
+    const int64_t *tree_offset; /* [n_trees + 1], non-decreasing, tree_offset[0] == 0 */
+    const int32_t *feature;    /* [n_nodes] */
+    const float *threshold;    /* [n_nodes] */
+    const int32_t *left;       /* [n_nodes] */
+    const int32_t *right;      /* [n_nodes] */
+    const float *leaf_value;   /* [n_nodes * leaf_width] */
+    const int32_t *tree_output; /* [n_trees] or NULL */
+    int32_t aggregate;         /* FOREST_AGG_* */
+    const float *base_score;   /* [n_outputs] or NULL (zeros) */
+    int32_t transform;         /* FOREST_TRANSFORM_*; SOFTMAX needs n_outputs >= 2 */
+    int32_t output;            /* FOREST_OUT_* */
+} forest_desc;
+
+typedef struct forest_info_t {
+    int32_t n_trees, n_features, n_outputs, leaf_width;
+    int64_t n_internal;    /* sum of N_I over trees = comparisons evaluated per row */
+    int64_t n_leaves;      /* sum of N_L over trees */
+    int32_t max_depth;     /* longest root-to-leaf path */
+    int32_t kernel_kind;   /* which specialised kernel forest_predict launches (0 = generic) */
+    int64_t packed_bytes;  /* device-resident size of the packed model */
+} forest_info_t;
+
+/*
+ * Host-side model compiler + upload (Section 3.1.2 numbering: internal nodes level order,
+ * leaves in-order; Table 2 weights, stored as a packed split program, walk tables and the
+ * leaf table E).  Validates the description, packs it and copies it to the current HIP
+ * device.  On success *out owns device memory until forest_free.  On error *out is untouched.
+ * Validation happens before any HIP call, so malformed input is reported even without a GPU.
+ */
+int forest_load(const forest_desc *desc, forest **out);
+
+/* Releases host and device memory. forest_free(NULL) is a no-op. */
+void forest_free(forest *f);
+
+int forest_info(const forest *f, forest_info_t *info);
+
+/* Bytes forest_predict writes for n_rows rows; negative FOREST_E* on error. */
+int64_t forest_out_bytes(const forest *f, int64_t n_rows);
+
+/*
+ * Byte offsets inside `out`: scores are float32 [n_rows * n_outputs] at *scores_offset,
+ * labels int32 [n_rows] at *labels_offset; an absent part reports -1.
+ */
+int forest_out_layout(const forest *f, int64_t n_rows, int64_t *scores_offset, int64_t *labels_offset);
+
+/*
+ * One pass of the whole path (Fig. 2 steps (1)-(3) + leaf gather + cross-tree reduction +
+ * transform) over a batch.
+ *   X       DEVICE pointer, row-major contiguous float32 [n_rows * n_features]
+ *   out     DEVICE pointer, forest_out_bytes(f, n_rows) bytes, 4-byte aligned
+ *   stream  hipStream_t (NULL = default stream)
+ * Asynchronous: enqueues kernels and returns; reports launch errors only.  n_rows == 0 is a
+ * successful no-op.  The caller keeps X and out alive until the stream has run the work.
+ * Allocates nothing.  Concurrent calls on one handle from different streams are allowed.
+ */
+int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream);
+
+/*
+ * Output of Table 2 ("the leaf node each sample reaches"), for tests and debugging:
+ * leaf_node_id is a DEVICE pointer to int32 [n_rows * n_trees]; entry (r, t) receives the
+ * caller's tree-local node index of the leaf row r reaches in tree t.
+ */
+int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32_t *leaf_node_id,
+                          void *stream);
+
+/*
+ * Host-only view of the packed model for tests of the model compiler (no GPU needed):
+ * compiles `desc` exactly as forest_load does, without uploading, and evaluates nothing.
+ * The arrays below are HOST memory owned by the handle, valid until forest_pack_free.
+ */
+typedef struct forest_packed_view {
+    int32_t n_trees;
+    int32_t kernel_kind;
+    const int32_t *tree_n_internal; /* [n_trees] N_I */
+    const int32_t *tree_depth;      /* [n_trees] longest path; full trees: every path */
+    const int32_t *tree_is_full;    /* [n_trees] 1 if every leaf sits at tree_depth */
+    const int64_t *node_base;       /* [n_trees + 1] offsets into the per-internal-node arrays */
+    const int64_t *leaf_base;       /* [n_trees + 1] offsets into the per-leaf arrays */
+    const int32_t *split_feature;   /* [sum N_I] level order (I_0, I_1, ...) */
+    const float *split_threshold;   /* [sum N_I] */
+    const int32_t *child_left;      /* [sum N_I] >= 0: internal ordinal; < 0: ~leaf ordinal */
+    const int32_t *child_right;     /* [sum N_I] */
+    const int32_t *leaf_node;       /* [sum N_L] caller's tree-local node index of L_j (in-order) */
+    const float *leaf_value;        /* [sum N_L * leaf_width] the table E */
+} forest_packed_view;
+
+typedef struct forest_packed forest_packed;
+int forest_pack(const forest_desc *desc, forest_packed **out);
+int forest_pack_view(const forest_packed *p, forest_packed_view *view);
+void forest_pack_free(forest_packed *p);
+
+const char *forest_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOREST_H_ */

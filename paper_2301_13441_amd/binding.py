@@ -1,0 +1,260 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+AGG_SUM, AGG_MEAN = 0, 1
+TRANSFORM_NONE, TRANSFORM_SIGMOID, TRANSFORM_SOFTMAX = 0, 1, 2
+OUT_SCORES, OUT_LABELS, OUT_BOTH = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libforest_hip.so")
+_lib = None
+
+_p = ctypes.c_void_p
+_i32, _i64 = ctypes.c_int32, ctypes.c_int64
+
+
+class ForestError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {code} ({_strerror(code)})")
+        self.code = code
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("n_trees", _i32), ("n_features", _i32), ("n_outputs", _i32), ("leaf_width", _i32),
+                ("tree_offset", _p), ("feature", _p), ("threshold", _p), ("left", _p), ("right", _p),
+                ("leaf_value", _p), ("tree_output", _p), ("aggregate", _i32), ("base_score", _p),
+                ("transform", _i32), ("output", _i32)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("n_trees", _i32), ("n_features", _i32), ("n_outputs", _i32), ("leaf_width", _i32),
+                ("n_internal", _i64), ("n_leaves", _i64), ("max_depth", _i32), ("kernel_kind", _i32),
+                ("packed_bytes", _i64)]
+
+
+class _View(ctypes.Structure):
+    _fields_ = [("n_trees", _i32), ("kernel_kind", _i32), ("tree_n_internal", _p), ("tree_depth", _p),
+                ("tree_is_full", _p), ("node_base", _p), ("leaf_base", _p), ("split_feature", _p),
+                ("split_threshold", _p), ("child_left", _p), ("child_right", _p), ("leaf_node", _p),
+                ("leaf_value", _p)]
+
+
+EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
+           "forest_predict", "forest_predict_leaves", "forest_pack", "forest_pack_view",
+           "forest_pack_free", "forest_strerror"]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2301_13441_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.forest_load.restype = ctypes.c_int
+    lib.forest_load.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(_p)]
+    lib.forest_free.restype = None
+    lib.forest_free.argtypes = [_p]
+    lib.forest_info.restype = ctypes.c_int
+    lib.forest_info.argtypes = [_p, ctypes.POINTER(_Info)]
+    lib.forest_out_bytes.restype = _i64
+    lib.forest_out_bytes.argtypes = [_p, _i64]
+    lib.forest_out_layout.restype = ctypes.c_int
+    lib.forest_out_layout.argtypes = [_p, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
+    lib.forest_predict.restype = ctypes.c_int
+    lib.forest_predict.argtypes = [_p, _p, _i64, _p, _p]
+    lib.forest_predict_leaves.restype = ctypes.c_int
+    lib.forest_predict_leaves.argtypes = [_p, _p, _i64, _p, _p]
+    lib.forest_pack.restype = ctypes.c_int
+    lib.forest_pack.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(_p)]
+    lib.forest_pack_view.restype = ctypes.c_int
+    lib.forest_pack_view.argtypes = [_p, ctypes.POINTER(_View)]
+    lib.forest_pack_free.restype = None
+    lib.forest_pack_free.argtypes = [_p]
+    lib.forest_strerror.restype = ctypes.c_char_p
+    lib.forest_strerror.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _strerror(code: int) -> str:
+    try:
+        return load_library().forest_strerror(int(code)).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _desc_from(forest):
+    """Marshal an object with the fields of the C forest_desc (numpy arrays) into the struct.
+    Returns (struct, keepalive list)."""
+    keep = []
+
+    def arr(a, dt):
+        if a is None:
+            return None
+        a = np.ascontiguousarray(a, dtype=dt)
+        keep.append(a)
+        return a.ctypes.data_as(_p)
+
+    d = _Desc()
+    d.n_trees = len(forest.tree_offset) - 1
+    d.n_features = int(forest.n_features)
+    d.n_outputs = int(forest.n_outputs)
+    d.leaf_width = int(forest.leaf_width)
+    d.tree_offset = arr(forest.tree_offset, np.int64)
+    d.feature = arr(forest.feature, np.int32)
+    d.threshold = arr(forest.threshold, np.float32)
+    d.left = arr(forest.left, np.int32)
+    d.right = arr(forest.right, np.int32)
+    d.leaf_value = arr(forest.leaf_value, np.float32)
+    d.tree_output = arr(getattr(forest, "tree_output", None), np.int32)
+    d.aggregate = int(forest.aggregate)
+    d.base_score = arr(getattr(forest, "base_score", None), np.float32)
+    d.transform = int(forest.transform)
+    d.output = int(forest.output)
+    return d, keep
+
+
+def forest_pack(forest) -> dict:
+    """Run the host model compiler only and return its tables as numpy arrays (no GPU needed)."""
+    lib = load_library()
+    d, keep = _desc_from(forest)
+    h = _p()
+    rc = lib.forest_pack(ctypes.byref(d), ctypes.byref(h))
+    if rc != 0:
+        raise ForestError(rc, "forest_pack")
+    try:
+        v = _View()
+        rc = lib.forest_pack_view(h, ctypes.byref(v))
+        if rc != 0:
+            raise ForestError(rc, "forest_pack_view")
+        T = v.n_trees
+
+        def get(ptr, n, dt):
+            if n == 0:
+                return np.zeros(0, dtype=dt)
+            return np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(np.ctypeslib.as_ctypes_type(dt))),
+                                         shape=(n,)).copy()
+
+        node_base = get(v.node_base, T + 1, np.int64)
+        leaf_base = get(v.leaf_base, T + 1, np.int64)
+        ni, nl = int(node_base[-1]), int(leaf_base[-1])
+        return dict(
+            n_trees=T, kernel_kind=v.kernel_kind,
+            tree_n_internal=get(v.tree_n_internal, T, np.int32),
+            tree_depth=get(v.tree_depth, T, np.int32),
+            tree_is_full=get(v.tree_is_full, T, np.int32),
+            node_base=node_base, leaf_base=leaf_base,
+            split_feature=get(v.split_feature, ni, np.int32),
+            split_threshold=get(v.split_threshold, ni, np.float32),
+            child_left=get(v.child_left, ni, np.int32),
+            child_right=get(v.child_right, ni, np.int32),
+            leaf_node=get(v.leaf_node, nl, np.int32),
+            leaf_value=get(v.leaf_value, nl * int(forest.leaf_width), np.float32).reshape(nl, -1),
+        )
+    finally:
+        lib.forest_pack_free(h)
+
+
+class Forest:
+    """Owner of a loaded model handle.  predict()/predict_leaves() take torch CUDA tensors."""
+
+    def __init__(self, handle, lib):
+        self._h = handle
+        self._lib = lib
+        info = _Info()
+        rc = lib.forest_info(handle, ctypes.byref(info))
+        if rc != 0:
+            raise ForestError(rc, "forest_info")
+        self.info = {name: getattr(info, name) for name, _ in _Info._fields_}
+        self.n_outputs = info.n_outputs
+        self.n_features = info.n_features
+        self.n_trees = info.n_trees
+
+    def close(self):
+        if self._h is not None:
+            self._lib.forest_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def out_bytes(self, n_rows: int) -> int:
+        n = self._lib.forest_out_bytes(self._h, n_rows)
+        if n < 0:
+            raise ForestError(int(n), "forest_out_bytes")
+        return int(n)
+
+    def out_layout(self, n_rows: int):
+        so, lo = _i64(), _i64()
+        rc = self._lib.forest_out_layout(self._h, n_rows, ctypes.byref(so), ctypes.byref(lo))
+        if rc != 0:
+            raise ForestError(rc, "forest_out_layout")
+        return so.value, lo.value
+
+    def predict_raw(self, x_ptr: int, n_rows: int, out_ptr: int, stream: int = 0) -> None:
+        """forest_predict on raw device pointers."""
+        rc = self._lib.forest_predict(self._h, _p(x_ptr), n_rows, _p(out_ptr), _p(stream))
+        if rc != 0:
+            raise ForestError(rc, "forest_predict")
+
+    def predict(self, X, out=None, stream=None):
+        """X: torch float32 CUDA tensor [n_rows, F], contiguous.  Returns (scores, labels) views
+        into one uint8 output buffer (either may be None, per the model's output kind)."""
+        import torch
+        assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous()
+        assert X.dim() == 2 and X.shape[1] == self.n_features
+        n = X.shape[0]
+        nbytes = self.out_bytes(n)
+        if out is None:
+            out = torch.empty(max(nbytes, 4), dtype=torch.uint8, device=X.device)
+        assert out.is_cuda and out.numel() * out.element_size() >= nbytes
+        s = torch.cuda.current_stream(X.device) if stream is None else stream
+        self.predict_raw(X.data_ptr(), n, out.data_ptr(), s.cuda_stream)
+        so, lo = self.out_layout(n)
+        flat = out.view(torch.uint8).reshape(-1)
+        scores = labels = None
+        if so >= 0:
+            scores = flat[so:so + 4 * n * self.n_outputs].view(torch.float32).reshape(n, self.n_outputs)
+        if lo >= 0:
+            labels = flat[lo:lo + 4 * n].view(torch.int32)
+        return scores, labels
+
+    def predict_leaves(self, X, stream=None):
+        import torch
+        assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous()
+        n = X.shape[0]
+        out = torch.empty((n, self.n_trees), dtype=torch.int32, device=X.device)
+        s = torch.cuda.current_stream(X.device) if stream is None else stream
+        rc = self._lib.forest_predict_leaves(self._h, _p(X.data_ptr()), n, _p(out.data_ptr()),
+                                             _p(s.cuda_stream))
+        if rc != 0:
+            raise ForestError(rc, "forest_predict_leaves")
+        return out
+
+
+def forest_load(forest) -> Forest:
+    """forest_load: validate, pack and upload to the current HIP device."""
+    lib = load_library()
+    d, keep = _desc_from(forest)
+    h = _p()
+    rc = lib.forest_load(ctypes.byref(d), ctypes.byref(h))
+    if rc != 0:
+        raise ForestError(rc, "forest_load")
+    return Forest(h, lib)

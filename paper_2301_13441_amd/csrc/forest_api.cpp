@@ -1,0 +1,269 @@
+// C ABI of the library (see include/forest.h): validation, packing, upload, launch.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "forest_device.hpp"
+
+using namespace forest_impl;
+
+struct forest_packed {
+    PackedModel m;
+};
+
+struct forest {
+    PackedModel host;  // tables kept for forest_info; large arrays are released after upload
+    DevModel dev{};
+    void *blob = nullptr;  // one device allocation holding every table
+    int64_t blob_bytes = 0;
+    int device = 0;
+};
+
+namespace {
+
+std::once_flag g_init_once;
+hipError_t g_init_status = hipSuccess;
+
+template <class T>
+size_t place(size_t &cursor, size_t count)
+{
+    cursor = (cursor + 255) & ~size_t{255};
+    const size_t at = cursor;
+    cursor += sizeof(T) * (count ? count : 1);
+    return at;
+}
+
+int check_out_args(const forest *f, int64_t n_rows)
+{
+    if (!f || n_rows < 0) return FOREST_EINVAL;
+    return FOREST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int forest_pack(const forest_desc *desc, forest_packed **out)
+{
+    if (!desc || !out) return FOREST_EINVAL;
+    forest_packed *p = new (std::nothrow) forest_packed;
+    if (!p) return FOREST_ENOMEM;
+    int rc;
+    try {
+        rc = compile_forest(*desc, p->m);
+    } catch (const std::bad_alloc &) {
+        rc = FOREST_ENOMEM;
+    }
+    if (rc != FOREST_OK) {
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return FOREST_OK;
+}
+
+int forest_pack_view(const forest_packed *p, forest_packed_view *v)
+{
+    if (!p || !v) return FOREST_EINVAL;
+    const PackedModel &m = p->m;
+    v->n_trees = m.n_trees;
+    v->kernel_kind = m.kind;
+    v->tree_n_internal = m.v_n_internal.data();
+    v->tree_depth = m.v_depth.data();
+    v->tree_is_full = m.v_is_full.data();
+    v->node_base = m.v_node_base.data();
+    v->leaf_base = m.v_leaf_base.data();
+    v->split_feature = m.v_feature.data();
+    v->split_threshold = m.v_threshold.data();
+    v->child_left = m.v_left.data();
+    v->child_right = m.v_right.data();
+    v->leaf_node = m.v_leaf_node.data();
+    v->leaf_value = m.v_leaf_value.data();
+    return FOREST_OK;
+}
+
+void forest_pack_free(forest_packed *p) { delete p; }
+
+int forest_load(const forest_desc *desc, forest **out)
+{
+    if (!desc || !out) return FOREST_EINVAL;
+    forest *f = new (std::nothrow) forest;
+    if (!f) return FOREST_ENOMEM;
+    int rc;
+    try {
+        rc = compile_forest(*desc, f->host);
+    } catch (const std::bad_alloc &) {
+        rc = FOREST_ENOMEM;
+    }
+    if (rc != FOREST_OK) {
+        delete f;
+        return rc;
+    }
+    if (!model_fits(f->host)) {
+        delete f;
+        return FOREST_ELIMIT;
+    }
+    // Everything below needs a device.
+    std::call_once(g_init_once, [] { g_init_status = init_kernels(); });
+    if (g_init_status != hipSuccess || hipGetDevice(&f->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete f;
+        return FOREST_EHIP;
+    }
+    PackedModel &m = f->host;
+    size_t cur = 0;
+    const size_t o_prog = place<SplitEntry>(cur, m.prog.size());
+    const size_t o_child = place<ChildRef>(cur, m.child.size());
+    const size_t o_leafv = place<float>(cur, m.leaf_value.size());
+    const size_t o_leafn = place<int32_t>(cur, m.leaf_node.size());
+    const size_t o_tree = place<TreeMeta>(cur, m.tree.size());
+    const size_t o_colt = place<double>(cur, m.col_trees.size());
+    const size_t o_base = place<float>(cur, m.base.size());
+    cur = (cur + 255) & ~size_t{255};
+    if (hipMalloc(&f->blob, cur) != hipSuccess) {
+        (void)hipGetLastError();
+        delete f;
+        return FOREST_ENOMEM;
+    }
+    f->blob_bytes = static_cast<int64_t>(cur);
+    char *b = static_cast<char *>(f->blob);
+    auto up = [&](size_t off, const void *src, size_t bytes) {
+        return bytes == 0 || hipMemcpy(b + off, src, bytes, hipMemcpyHostToDevice) == hipSuccess;
+    };
+    const bool ok = up(o_prog, m.prog.data(), m.prog.size() * sizeof(SplitEntry)) &&
+                    up(o_child, m.child.data(), m.child.size() * sizeof(ChildRef)) &&
+                    up(o_leafv, m.leaf_value.data(), m.leaf_value.size() * sizeof(float)) &&
+                    up(o_leafn, m.leaf_node.data(), m.leaf_node.size() * sizeof(int32_t)) &&
+                    up(o_tree, m.tree.data(), m.tree.size() * sizeof(TreeMeta)) &&
+                    up(o_colt, m.col_trees.data(), m.col_trees.size() * sizeof(double)) &&
+                    up(o_base, m.base.data(), m.base.size() * sizeof(float));
+    if (!ok) {
+        (void)hipGetLastError();
+        (void)hipFree(f->blob);
+        delete f;
+        return FOREST_EHIP;
+    }
+    DevModel &d = f->dev;
+    d.prog = reinterpret_cast<const SplitEntry *>(b + o_prog);
+    d.child = reinterpret_cast<const ChildRef *>(b + o_child);
+    d.leaf_value = reinterpret_cast<const float *>(b + o_leafv);
+    d.leaf_node = reinterpret_cast<const int32_t *>(b + o_leafn);
+    d.tree = reinterpret_cast<const TreeMeta *>(b + o_tree);
+    d.col_trees = reinterpret_cast<const double *>(b + o_colt);
+    d.base = reinterpret_cast<const float *>(b + o_base);
+    d.n_trees = m.n_trees;
+    d.n_features = m.n_features;
+    d.n_outputs = m.n_outputs;
+    d.leaf_width = m.leaf_width;
+    d.aggregate = m.aggregate;
+    d.transform = m.transform;
+    d.output = m.output;
+    d.kind = m.kind;
+    d.max_words = m.max_words;
+    // the caller-order views are only for forest_pack_view; drop the bulk on the load path
+    m.prog = {};
+    m.child = {};
+    m.v_feature = {};
+    m.v_threshold = {};
+    m.v_left = {};
+    m.v_right = {};
+    m.v_leaf_node = {};
+    m.v_leaf_value = {};
+    *out = f;
+    return FOREST_OK;
+}
+
+void forest_free(forest *f)
+{
+    if (!f) return;
+    if (f->blob) (void)hipFree(f->blob);
+    delete f;
+}
+
+int forest_info(const forest *f, forest_info_t *info)
+{
+    if (!f || !info) return FOREST_EINVAL;
+    const PackedModel &m = f->host;
+    info->n_trees = m.n_trees;
+    info->n_features = m.n_features;
+    info->n_outputs = m.n_outputs;
+    info->leaf_width = m.leaf_width;
+    info->n_internal = m.n_internal;
+    info->n_leaves = m.n_leaves;
+    info->max_depth = m.max_depth;
+    info->kernel_kind = m.kind;
+    info->packed_bytes = f->blob_bytes;
+    return FOREST_OK;
+}
+
+int forest_out_layout(const forest *f, int64_t n_rows, int64_t *scores_offset, int64_t *labels_offset)
+{
+    if (int rc = check_out_args(f, n_rows)) return rc;
+    const int64_t score_bytes = n_rows * f->host.n_outputs * static_cast<int64_t>(sizeof(float));
+    int64_t so = -1, lo = -1;
+    switch (f->host.output) {
+        case FOREST_OUT_SCORES: so = 0; break;
+        case FOREST_OUT_LABELS: lo = 0; break;
+        default: so = 0; lo = score_bytes; break;
+    }
+    if (scores_offset) *scores_offset = so;
+    if (labels_offset) *labels_offset = lo;
+    return FOREST_OK;
+}
+
+int64_t forest_out_bytes(const forest *f, int64_t n_rows)
+{
+    if (int rc = check_out_args(f, n_rows)) return rc;
+    const int64_t score_bytes = n_rows * f->host.n_outputs * static_cast<int64_t>(sizeof(float));
+    const int64_t label_bytes = n_rows * static_cast<int64_t>(sizeof(int32_t));
+    switch (f->host.output) {
+        case FOREST_OUT_SCORES: return score_bytes;
+        case FOREST_OUT_LABELS: return label_bytes;
+        default: return score_bytes + label_bytes;
+    }
+}
+
+int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream)
+{
+    if (int rc = check_out_args(f, n_rows)) return rc;
+    if (n_rows == 0) return FOREST_OK;
+    if (!X || !out) return FOREST_EINVAL;
+    int64_t so, lo;
+    forest_out_layout(f, n_rows, &so, &lo);
+    char *o = static_cast<char *>(out);
+    float *scores = so >= 0 ? reinterpret_cast<float *>(o + so) : nullptr;
+    int32_t *labels = lo >= 0 ? reinterpret_cast<int32_t *>(o + lo) : nullptr;
+    const hipError_t e = launch_predict(f->dev, X, n_rows, scores, labels, nullptr,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
+}
+
+int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32_t *leaf_node_id,
+                          void *stream)
+{
+    if (int rc = check_out_args(f, n_rows)) return rc;
+    if (n_rows == 0 || f->host.n_trees == 0) return FOREST_OK;
+    if (!X || !leaf_node_id) return FOREST_EINVAL;
+    const hipError_t e = launch_predict(f->dev, X, n_rows, nullptr, nullptr, leaf_node_id,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
+}
+
+const char *forest_strerror(int code)
+{
+    switch (code) {
+        case FOREST_OK: return "ok";
+        case FOREST_EINVAL: return "invalid argument";
+        case FOREST_ETREE: return "malformed tree";
+        case FOREST_EFEATURE: return "split feature out of range";
+        case FOREST_ENONFINITE: return "NaN threshold or base score";
+        case FOREST_ENOMEM: return "out of memory";
+        case FOREST_EHIP: return "HIP runtime error";
+        case FOREST_ELIMIT: return "model exceeds a kernel limit";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Device-resident view of a packed model, passed by value to the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "forest_model.hpp"
+
+namespace forest_impl {
+
+struct DevModel {
+    const SplitEntry *prog;
+    const ChildRef *child;
+    const float *leaf_value;
+    const int32_t *leaf_node;
+    const TreeMeta *tree;
+    const double *col_trees;
+    const float *base;
+    int32_t n_trees, n_features, n_outputs, leaf_width;
+    int32_t aggregate, transform, output, kind;
+    int32_t max_words;
+};
+
+// Enqueues one pass over `n_rows` rows on `stream`.  `scores` / `labels` / `leaf_out` may be
+// null (that part is not written).  Returns the launch error, if any.
+hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
+                          int32_t *labels, int32_t *leaf_out, hipStream_t stream);
+
+// Whether the kernels' LDS working set for this model fits a compute unit (host-only check).
+bool model_fits(const PackedModel &m);
+
+// One-time per-process kernel attribute setup (dynamic LDS limits).
+hipError_t init_kernels();
+
+}  // namespace forest_impl

@@ -1,0 +1,76 @@
+// Internal data model shared by the host model compiler and the kernels' launcher.
+//
+// The packed model is the operator representation of Table 2 in a bit-level layout:
+//   * W1 (feature selector, one 1 per column) is stored as the feature index of every
+//     internal node, i.e. matmul(X, W1) is a gather (Section 4.3.2, sparse operator
+//     replacing in its limit: one non-zero per column);
+//   * W2 is the threshold of every internal node, stored next to the feature index as one
+//     8-byte "split program" entry;
+//   * W3 / (C, D) -- which leaves lie left/right below which internal node -- is stored as
+//     child references between level-ordered internal nodes and in-ordered leaves
+//     (Section 3.1.2 numbering), which is what a lane needs to pick, from its split-outcome
+//     bits, the unique leaf whose root path agrees with them;
+//   * E is the leaf table in in-order.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "../../include/forest.h"
+
+namespace forest_impl {
+
+// Kernel families.  A forest whose trees are all full with one common depth 1..8 runs the
+// register-resident kernel (kind = depth); everything else runs the generic kernel (kind 0).
+constexpr int KIND_GENERIC = 0;
+constexpr int FULL_MAX_DEPTH = 8;
+
+// One entry of the split program: which feature an internal node tests and its threshold.
+struct SplitEntry {
+    int32_t feature_slot;  // feature index pre-multiplied by the row-tile width (64)
+    float threshold;
+};
+
+// Per-tree record in processing order (trees are sorted by output column, stable).
+struct TreeMeta {
+    int32_t prog_base;   // first split-program entry of the tree
+    int32_t n_words;     // 32-bit outcome words (generic kernel)
+    int32_t child_base;  // first entry of the tree in the child-reference tables
+    int32_t leaf_base;   // first entry of the tree in the per-leaf tables
+    int32_t root_ref;    // 0 if the root is internal, ~0 (= -1) if the root is leaf L_0
+    int32_t column;      // output column of a scalar-leaf tree
+    int32_t caller_tree; // index of the tree in the caller's description
+    int32_t n_internal;
+};
+
+struct ChildRef {
+    int32_t left, right;  // >= 0: internal ordinal (level order); < 0: ~(in-order leaf ordinal)
+};
+
+struct PackedModel {
+    int32_t n_trees = 0, n_features = 0, n_outputs = 0, leaf_width = 1;
+    int32_t aggregate = 0, transform = 0, output = 0;
+    int32_t kind = KIND_GENERIC;
+    int32_t max_depth = 0;
+    int32_t max_words = 0;  // largest TreeMeta::n_words
+    int64_t n_internal = 0, n_leaves = 0;
+
+    std::vector<TreeMeta> tree;      // processing order
+    std::vector<SplitEntry> prog;    // evaluation order (see forest_pack.cpp)
+    std::vector<ChildRef> child;     // [sum N_I]
+    std::vector<float> leaf_value;   // E, [sum N_L * leaf_width]
+    std::vector<int32_t> leaf_node;  // [sum N_L] caller's node index of each leaf
+    std::vector<double> col_trees;   // [K] number of trees feeding each column
+    std::vector<float> base;         // [K]
+
+    // caller-order views used only by forest_pack_view
+    std::vector<int32_t> v_n_internal, v_depth, v_is_full;
+    std::vector<int64_t> v_node_base, v_leaf_base;
+    std::vector<int32_t> v_feature, v_left, v_right, v_leaf_node;
+    std::vector<float> v_threshold, v_leaf_value;
+};
+
+// Validates `d` and fills `out`.  Returns FOREST_OK or a negative FOREST_E* code.
+int compile_forest(const forest_desc &d, PackedModel &out);
+
+}  // namespace forest_impl

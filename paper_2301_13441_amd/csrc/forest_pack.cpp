@@ -1,0 +1,232 @@
+// Host-side model compiler: caller's per-node arrays -> packed operator representation.
+//
+// Follows Section 3.1.2 / Table 2: internal nodes are numbered in level order (I_0, I_1, ..),
+// leaves in in-order (L_0, L_1, ..).  The weights W1 (feature selection) and W2 (thresholds)
+// become the split program; W3 (equivalently the path matrix C and path lengths D) becomes
+// child references; the leaf payloads become the table E.  All weights are converted at
+// compile time so that nothing is re-typed at run time (Section 3.2, "weights can be handled
+// both during compilation and runtime").
+//
+// Split-program order.  The kernels shift one outcome bit per entry into a 32-bit word
+// (word = 2 * word + outcome), so the first entry of a 32-entry block lands in bit 31.  To
+// make bit j of word w the outcome of position 32 * w + j, each block is stored in
+// descending position.  "Position" is the level-order ordinal i for the generic kernel and
+// the heap index h = i + 1 for full trees (root 1, children 2h and 2h + 1, position 0 is
+// padding), which keeps every level of a full tree inside whole words from depth 5 on.
+// Padding entries test feature 0 against +Inf; the walk never visits them.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <numeric>
+
+#include "forest_model.hpp"
+
+namespace forest_impl {
+namespace {
+
+struct TreeShape {
+    std::vector<int32_t> internal;      // caller node index of I_0, I_1, ... (level order)
+    std::vector<int32_t> leaves;        // caller node index of L_0, L_1, ... (in-order)
+    std::vector<int32_t> ordinal;       // per caller node: internal ordinal or ~leaf ordinal
+    int32_t depth = 0;                  // longest root-to-leaf path, counted in tests
+    bool full = true;                   // every leaf at `depth`
+};
+
+// Level-order walk from the root.  Rejects out-of-range children, nodes reached twice
+// (shared subtrees and cycles) and nodes never reached.
+int analyse_tree(const forest_desc &d, int64_t base, int64_t n, TreeShape &s)
+{
+    if (n < 1 || n > std::numeric_limits<int32_t>::max()) return FOREST_ETREE;
+    std::vector<uint8_t> seen(static_cast<size_t>(n), 0);
+    std::vector<int32_t> level{0}, next;
+    std::vector<int32_t> node_depth(static_cast<size_t>(n), 0);
+    seen[0] = 1;
+    s.ordinal.assign(static_cast<size_t>(n), 0);
+    int32_t depth = 0, leaf_min = std::numeric_limits<int32_t>::max(), leaf_max = 0;
+    int64_t reached = 0;
+    while (!level.empty()) {
+        next.clear();
+        for (int32_t v : level) {
+            ++reached;
+            const int32_t f = d.feature[base + v];
+            if (f < 0) {
+                leaf_min = std::min(leaf_min, depth);
+                leaf_max = std::max(leaf_max, depth);
+                continue;
+            }
+            if (f >= d.n_features) return FOREST_EFEATURE;
+            if (std::isnan(d.threshold[base + v])) return FOREST_ENONFINITE;
+            s.ordinal[v] = static_cast<int32_t>(s.internal.size());
+            s.internal.push_back(v);
+            const int32_t kids[2] = {d.left[base + v], d.right[base + v]};
+            for (int32_t c : kids) {
+                if (c < 0 || c >= n) return FOREST_ETREE;
+                if (seen[c]) return FOREST_ETREE;
+                seen[c] = 1;
+                next.push_back(c);
+            }
+        }
+        level.swap(next);
+        if (!level.empty()) ++depth;
+        if (depth > FOREST_MAX_DEPTH) return FOREST_ELIMIT;
+    }
+    if (reached != n) return FOREST_ETREE;  // unreachable nodes
+    s.depth = leaf_max;
+    s.full = (leaf_min == leaf_max);
+
+    // In-order leaf numbering: left subtree, node, right subtree; only leaves get a number.
+    std::vector<int32_t> stack;
+    int32_t v = 0;
+    for (;;) {
+        while (d.feature[base + v] >= 0) {
+            stack.push_back(v);
+            v = d.left[base + v];
+        }
+        s.ordinal[v] = ~static_cast<int32_t>(s.leaves.size());
+        s.leaves.push_back(v);
+        if (stack.empty()) break;
+        v = d.right[base + stack.back()];
+        stack.pop_back();
+    }
+    return FOREST_OK;
+}
+
+int check_desc(const forest_desc &d)
+{
+    if (d.n_trees < 0 || d.n_features < 1 || d.n_outputs < 1) return FOREST_EINVAL;
+    if (d.n_features > FOREST_MAX_FEATURES || d.n_outputs > FOREST_MAX_OUTPUTS) return FOREST_ELIMIT;
+    if (d.leaf_width != 1 && d.leaf_width != d.n_outputs) return FOREST_EINVAL;
+    if (d.aggregate != FOREST_AGG_SUM && d.aggregate != FOREST_AGG_MEAN) return FOREST_EINVAL;
+    if (d.transform < FOREST_TRANSFORM_NONE || d.transform > FOREST_TRANSFORM_SOFTMAX) return FOREST_EINVAL;
+    if (d.transform == FOREST_TRANSFORM_SOFTMAX && d.n_outputs < 2) return FOREST_EINVAL;
+    if (d.output < FOREST_OUT_SCORES || d.output > FOREST_OUT_BOTH) return FOREST_EINVAL;
+    if (!d.tree_offset) return FOREST_EINVAL;
+    if (d.tree_offset[0] != 0) return FOREST_EINVAL;
+    for (int32_t t = 0; t < d.n_trees; ++t)
+        if (d.tree_offset[t + 1] <= d.tree_offset[t]) return FOREST_ETREE;  // empty tree
+    if (d.n_trees > 0 && (!d.feature || !d.threshold || !d.left || !d.right || !d.leaf_value))
+        return FOREST_EINVAL;
+    if (d.tree_output && d.leaf_width == 1)
+        for (int32_t t = 0; t < d.n_trees; ++t)
+            if (d.tree_output[t] < 0 || d.tree_output[t] >= d.n_outputs) return FOREST_EINVAL;
+    if (d.base_score)
+        for (int32_t k = 0; k < d.n_outputs; ++k)
+            if (std::isnan(d.base_score[k])) return FOREST_ENONFINITE;
+    return FOREST_OK;
+}
+
+}  // namespace
+
+int compile_forest(const forest_desc &d, PackedModel &m)
+{
+    if (int rc = check_desc(d)) return rc;
+    const int32_t T = d.n_trees, K = d.n_outputs, W = d.leaf_width;
+    m = PackedModel{};
+    m.n_trees = T;
+    m.n_features = d.n_features;
+    m.n_outputs = K;
+    m.leaf_width = W;
+    m.aggregate = d.aggregate;
+    m.transform = d.transform;
+    m.output = d.output;
+    m.col_trees.assign(K, 0.0);
+    m.base.assign(K, 0.0f);
+    if (d.base_score) std::copy(d.base_score, d.base_score + K, m.base.begin());
+
+    std::vector<TreeShape> shape(static_cast<size_t>(T));
+    bool all_full = T > 0;
+    int32_t common_depth = -1;
+    for (int32_t t = 0; t < T; ++t) {
+        const int64_t base = d.tree_offset[t], n = d.tree_offset[t + 1] - base;
+        if (int rc = analyse_tree(d, base, n, shape[t])) return rc;
+        const TreeShape &s = shape[t];
+        m.max_depth = std::max(m.max_depth, s.depth);
+        m.n_internal += static_cast<int64_t>(s.internal.size());
+        m.n_leaves += static_cast<int64_t>(s.leaves.size());
+        if (!s.full) all_full = false;
+        if (common_depth < 0) common_depth = s.depth;
+        else if (common_depth != s.depth) all_full = false;
+        if (W == 1) m.col_trees[d.tree_output ? d.tree_output[t] : 0] += 1.0;
+        else for (int32_t k = 0; k < K; ++k) m.col_trees[k] += 1.0;
+    }
+    if (m.n_internal > (int64_t{1} << 30) || m.n_leaves > (int64_t{1} << 30)) return FOREST_ELIMIT;
+    m.kind = (all_full && common_depth >= 1 && common_depth <= FULL_MAX_DEPTH) ? common_depth
+                                                                              : KIND_GENERIC;
+
+    // caller-order views (tests of the compiler read these)
+    m.v_node_base.assign(1, 0);
+    m.v_leaf_base.assign(1, 0);
+    for (int32_t t = 0; t < T; ++t) {
+        const TreeShape &s = shape[t];
+        const int64_t base = d.tree_offset[t];
+        m.v_n_internal.push_back(static_cast<int32_t>(s.internal.size()));
+        m.v_depth.push_back(s.depth);
+        m.v_is_full.push_back(s.full ? 1 : 0);
+        for (int32_t v : s.internal) {
+            m.v_feature.push_back(d.feature[base + v]);
+            m.v_threshold.push_back(d.threshold[base + v]);
+            m.v_left.push_back(s.ordinal[d.left[base + v]]);
+            m.v_right.push_back(s.ordinal[d.right[base + v]]);
+        }
+        for (int32_t v : s.leaves) {
+            m.v_leaf_node.push_back(v);
+            for (int32_t k = 0; k < W; ++k) m.v_leaf_value.push_back(d.leaf_value[(base + v) * W + k]);
+        }
+        m.v_node_base.push_back(static_cast<int64_t>(m.v_feature.size()));
+        m.v_leaf_base.push_back(static_cast<int64_t>(m.v_leaf_node.size()));
+    }
+
+    // processing order: by output column, ties in caller order (keeps each column's sum in
+    // ascending tree index)
+    std::vector<int32_t> order(static_cast<size_t>(T));
+    std::iota(order.begin(), order.end(), 0);
+    auto column_of = [&](int32_t t) { return (W == 1 && d.tree_output) ? d.tree_output[t] : 0; };
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return column_of(a) < column_of(b); });
+
+    const float inf = std::numeric_limits<float>::infinity();
+    const SplitEntry pad{0, inf};
+    for (int32_t t : order) {
+        const TreeShape &s = shape[t];
+        const int64_t base = d.tree_offset[t];
+        const int32_t n_int = static_cast<int32_t>(s.internal.size());
+        TreeMeta tm{};
+        tm.prog_base = static_cast<int32_t>(m.prog.size());
+        tm.child_base = static_cast<int32_t>(m.child.size());
+        tm.leaf_base = static_cast<int32_t>(m.leaf_node.size());
+        tm.root_ref = n_int > 0 ? 0 : ~0;
+        tm.column = column_of(t);
+        tm.caller_tree = t;
+        tm.n_internal = n_int;
+
+        // positions: heap index for the full-tree kernels, level-order ordinal otherwise
+        const int32_t shift = (m.kind != KIND_GENERIC) ? 1 : 0;
+        const int32_t n_pos = n_int + shift;
+        const int32_t block = (m.kind != KIND_GENERIC && m.kind < 5) ? (1 << m.kind) : 32;
+        const int32_t n_blocks = std::max(1, (n_pos + block - 1) / block);
+        tm.n_words = n_blocks;
+        for (int32_t w = 0; w < n_blocks; ++w)
+            for (int32_t j = 0; j < block; ++j) {
+                const int32_t pos = w * block + (block - 1 - j);
+                const int32_t i = pos - shift;
+                if (i < 0 || i >= n_int) {
+                    m.prog.push_back(pad);
+                } else {
+                    const int32_t v = s.internal[i];
+                    m.prog.push_back(SplitEntry{d.feature[base + v] * 64, d.threshold[base + v]});
+                }
+            }
+        m.max_words = std::max(m.max_words, n_blocks);
+        for (int32_t v : s.internal)
+            m.child.push_back(ChildRef{s.ordinal[d.left[base + v]], s.ordinal[d.right[base + v]]});
+        for (int32_t v : s.leaves) {
+            m.leaf_node.push_back(v);
+            for (int32_t k = 0; k < W; ++k) m.leaf_value.push_back(d.leaf_value[(base + v) * W + k]);
+        }
+        m.tree.push_back(tm);
+    }
+    return FOREST_OK;
+}
+
+}  // namespace forest_impl
