@@ -162,6 +162,9 @@ int forest_load(const forest_desc *desc, forest **out)
     d.output = m.output;
     d.kind = m.kind;
     d.max_words = m.max_words;
+    d.x_in_registers = m.x_in_registers;
+    d.reg_nv = m.reg_nv;
+    d.reg_r = m.reg_r;
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
     m.child = {};
@@ -195,6 +198,8 @@ int forest_info(const forest *f, forest_info_t *info)
     info->max_depth = m.max_depth;
     info->kernel_kind = m.kind;
     info->packed_bytes = f->blob_bytes;
+    info->x_in_registers = m.x_in_registers;
+    info->rows_per_workgroup = m.x_in_registers ? 64 * m.reg_r : 64;
     return FOREST_OK;
 }
 

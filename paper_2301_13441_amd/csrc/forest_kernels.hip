@@ -1,8 +1,8 @@
 // HIP kernels for gfx950: dense tree-ensemble inference, one lane per row.
 //
 // Mapping of the paper's operator graph (Fig. 2, Table 2) to a wavefront:
-//   (1) matmul(X, W1)   -> gather: the wave reads feature f of its 64 rows from an LDS tile
-//                          that holds X transposed ([feature][row]), filled by coalesced
+//   (1) matmul(X, W1)   -> gather: feature f of the wave's 64 rows, read from an LDS tile that
+//                          holds X transposed ([feature][row]) and is filled by coalesced
 //                          row-major reads of X;
 //   (2) greater(., W2)  -> one v_cmp per (row, internal node); the threshold is wave-uniform
 //                          (scalar register), the outcome is shifted into a per-lane bit word;
@@ -12,42 +12,26 @@
 //   leaf gather from E, cross-tree reduction in double, LDS-staged across the waves of a
 //   workgroup, then the transform; labels are taken before the transform (Section 4.3.3).
 //
-// A workgroup (4 wavefronts) owns a tile of 64 rows; the trees are split over its waves.
+// This file holds the kernels that read features from the LDS tile for every comparison
+// (any number of features, any tree shape) and the launcher.  forest_kernels_reg.hip holds
+// the kernels that keep the features in vector registers.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
 #include "forest_device.hpp"
+#include "forest_kernel_common.hpp"
 
 namespace forest_impl {
 namespace {
 
-constexpr int TILE = 64;      // rows per workgroup = lanes per wavefront
-constexpr int WAVES = 4;      // wavefronts per workgroup
-constexpr int BLOCK = TILE * WAVES;
-
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-// Copies rows [row0, row0 + 64) of row-major X into xs[f * 64 + r]; rows past n_rows read as 0.
-__device__ __forceinline__ void stage_x_tile(float *xs, const float *X, int64_t row0, int64_t n_rows,
-                                             int F)
-{
-    const int64_t rows_here = min(static_cast<int64_t>(TILE), n_rows - row0);
-    const int n_valid = static_cast<int>(rows_here) * F;
-    const float *src = X + row0 * F;
-    for (int e = threadIdx.x; e < TILE * F; e += BLOCK) {
-        const int r = e / F, f = e - r * F;
-        xs[f * TILE + r] = (e < n_valid) ? src[e] : 0.0f;
-    }
-}
-
 struct Lds {
-    float *xs;       // [F][64]            (staged X tile; unused when !STAGED)
     double *acc;     // [WAVES][K][64]     per-wave partial sums
+    float *xs;       // [F][64]            (staged X tile; unused when !STAGED)
     uint32_t *bits;  // [WAVES][max_words][64] outcome words (generic kernel only)
 };
 
-__device__ __forceinline__ Lds carve_lds(char *smem, const DevModel &m, bool staged, bool generic)
+__device__ __forceinline__ Lds carve_lds(char *smem, const DevModel &m, bool staged)
 {
     Lds l;
     size_t off = 0;
@@ -56,82 +40,8 @@ __device__ __forceinline__ Lds carve_lds(char *smem, const DevModel &m, bool sta
     l.xs = reinterpret_cast<float *>(smem + off);
     if (staged) off += sizeof(float) * m.n_features * TILE;
     l.bits = reinterpret_cast<uint32_t *>(smem + off);
-    (void)generic;
     return l;
 }
-
-// Cross-wave reduction, aggregate, label, transform, store.  Runs on wave 0, lane = row.
-__device__ __forceinline__ void finish_rows(const DevModel &m, double *acc, int64_t row, bool valid,
-                                            float *scores, int32_t *labels, int lane)
-{
-    const int K = m.n_outputs;
-    double best = 0.0;
-    int best_k = 0;
-    for (int k = 0; k < K; ++k) {
-        double s = acc[(0 * K + k) * TILE + lane];
-        for (int w = 1; w < WAVES; ++w) s += acc[(w * K + k) * TILE + lane];
-        if (m.aggregate == FOREST_AGG_MEAN) s = s / m.col_trees[k];
-        s = static_cast<double>(m.base[k]) + s;
-        acc[k * TILE + lane] = s;  // wave 0's slice now holds the raw value
-        if (k == 0 || s > best) {
-            best = s;
-            best_k = k;
-        }
-    }
-    if (!valid) return;
-    if (labels) {
-        int lab = best_k;
-        if (K == 1) lab = (m.transform == FOREST_TRANSFORM_SIGMOID) ? (best > 0.0) : (best > 0.5);
-        labels[row] = lab;
-    }
-    if (!scores) return;
-    float *dst = scores + row * K;
-    if (m.transform == FOREST_TRANSFORM_SOFTMAX) {
-        double z = 0.0;
-        for (int k = 0; k < K; ++k) z += exp(acc[k * TILE + lane] - best);
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(exp(acc[k * TILE + lane] - best) / z);
-    } else if (m.transform == FOREST_TRANSFORM_SIGMOID) {
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(1.0 / (1.0 + exp(-acc[k * TILE + lane])));
-    } else {
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(acc[k * TILE + lane]);
-    }
-}
-
-// Adds the payload of leaf `leaf` (index into the per-leaf tables) to the wave's partial sums.
-// Scalar leaves accumulate in a register per column run; vector leaves go straight to LDS.
-struct Accumulator {
-    double run = 0.0;
-    int col = 0;
-    double *mine;  // this wave's [K][64] slice
-    int lane, K, W;
-
-    __device__ __forceinline__ void init(double *acc, int wave, int lane_, const DevModel &m)
-    {
-        K = m.n_outputs;
-        W = m.leaf_width;
-        lane = lane_;
-        mine = acc + static_cast<size_t>(wave) * K * TILE;
-        for (int k = 0; k < K; ++k) mine[k * TILE + lane] = 0.0;
-    }
-    __device__ __forceinline__ void add(const DevModel &m, int column, int leaf)
-    {
-        if (W == 1) {
-            if (column != col) {  // wave-uniform
-                mine[col * TILE + lane] += run;
-                run = 0.0;
-                col = column;
-            }
-            run += static_cast<double>(m.leaf_value[leaf]);
-        } else {
-            const float *v = m.leaf_value + static_cast<size_t>(leaf) * K;
-            for (int k = 0; k < K; ++k) mine[k * TILE + lane] += static_cast<double>(v[k]);
-        }
-    }
-    __device__ __forceinline__ void flush()
-    {
-        if (W == 1) mine[col * TILE + lane] += run;
-    }
-};
 
 // ---------------------------------------------------------------------------------------
 // Full trees of one common depth D (1..8): outcome words live in registers, the walk is the
@@ -143,7 +53,7 @@ __global__ __launch_bounds__(BLOCK) void forest_full_kernel(DevModel m, const fl
                                                             int32_t *labels, int32_t *leaf_out)
 {
     extern __shared__ __align__(16) char smem[];
-    const Lds lds = carve_lds(smem, m, STAGED, false);
+    const Lds lds = carve_lds(smem, m, STAGED);
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * TILE;
@@ -152,12 +62,12 @@ __global__ __launch_bounds__(BLOCK) void forest_full_kernel(DevModel m, const fl
     const int F = m.n_features;
 
     if (STAGED) {
-        stage_x_tile(lds.xs, X, row0, n_rows, F);
+        stage_x_tile(lds.xs, X, row0, n_rows, F, TILE);
         __syncthreads();
     }
     const float *xrow = X + (valid ? row : row0) * F;  // !STAGED: direct reads of the lane's row
 
-    Accumulator accu;
+    Accumulator<1> accu;
     accu.init(lds.acc, wave, lane, m);
 
     constexpr int N_POS = 1 << D;
@@ -181,35 +91,19 @@ __global__ __launch_bounds__(BLOCK) void forest_full_kernel(DevModel m, const fl
             }
             word[w] = b;
         }
-        // walk: h = heap index of the node the row stands on
-        uint32_t h = 1;
-#pragma unroll
-        for (int l = 0; l < D; ++l) {
-            // level l occupies heap positions [2^l, 2^(l+1)): word 0 up to level 4, then
-            // word 1, words 2-3, words 4-7
-            uint32_t wsel;
-            if (l < 5 || NW == 1) wsel = word[0];
-            else if (l == 5) wsel = word[1 % NW];
-            else if (l == 6) wsel = (h & 32u) ? word[3 % NW] : word[2 % NW];
-            else {
-                const uint32_t lo = (h & 32u) ? word[5 % NW] : word[4 % NW];
-                const uint32_t hi = (h & 32u) ? word[7 % NW] : word[6 % NW];
-                wsel = (h & 64u) ? hi : lo;
-            }
-            h = h + h + ((wsel >> (h & 31u)) & 1u);
-        }
-        const int leaf = (t << D) + static_cast<int>(h - N_POS);
+        const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word));
         const TreeMeta tm = m.tree[t];
         if (LEAVES) {
             if (valid) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
         } else {
-            accu.add(m, tm.column, leaf);
+            accu.begin_tree(tm.column);
+            accu.add(m, 0, leaf);
         }
     }
     if (LEAVES) return;
     accu.flush();
     __syncthreads();
-    if (wave == 0) finish_rows(m, lds.acc, row, valid, scores, labels, lane);
+    if (wave == 0) finish_row(m, lds.acc, TILE, lane, row, valid, scores, labels);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -222,7 +116,7 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
                                                                int32_t *labels, int32_t *leaf_out)
 {
     extern __shared__ __align__(16) char smem[];
-    const Lds lds = carve_lds(smem, m, STAGED, true);
+    const Lds lds = carve_lds(smem, m, STAGED);
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * TILE;
@@ -231,12 +125,12 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
     const int F = m.n_features;
 
     if (STAGED) {
-        stage_x_tile(lds.xs, X, row0, n_rows, F);
+        stage_x_tile(lds.xs, X, row0, n_rows, F, TILE);
         __syncthreads();
     }
     const float *xrow = X + (valid ? row : row0) * F;
 
-    Accumulator accu;
+    Accumulator<1> accu;
     accu.init(lds.acc, wave, lane, m);
     uint32_t *mybits = lds.bits + static_cast<size_t>(wave) * m.max_words * TILE;
 
@@ -273,13 +167,14 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
         if (LEAVES) {
             if (valid) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
         } else {
-            accu.add(m, tm.column, leaf);
+            accu.begin_tree(tm.column);
+            accu.add(m, 0, leaf);
         }
     }
     if (LEAVES) return;
     accu.flush();
     __syncthreads();
-    if (wave == 0) finish_rows(m, lds.acc, row, valid, scores, labels, lane);
+    if (wave == 0) finish_row(m, lds.acc, TILE, lane, row, valid, scores, labels);
 }
 
 constexpr size_t LDS_LIMIT = 160 * 1024;  // LDS of one gfx950 compute unit
@@ -297,8 +192,6 @@ size_t lds_bytes(const DevModel &m, bool staged)
 {
     return lds_bytes(m.kind, m.n_features, m.n_outputs, m.max_words, staged);
 }
-
-using KernelFn = void (*)(DevModel, const float *, int64_t, float *, int32_t *, int32_t *);
 
 template <bool LEAVES, bool STAGED>
 KernelFn pick_kernel(int kind)
@@ -326,6 +219,7 @@ KernelFn pick(int kind, bool leaves, bool staged)
 
 bool model_fits(const PackedModel &m)
 {
+    if (m.x_in_registers) return true;  // its LDS need is bounded by construction
     return lds_bytes(m.kind, m.n_features, m.n_outputs, m.max_words, false) <= LDS_LIMIT;
 }
 
@@ -345,13 +239,14 @@ hipError_t init_kernels()
                                                    static_cast<int>(g_lds_limit));
                 if (e != hipSuccess) return e;
             }
-    return hipSuccess;
+    return init_reg_kernels(g_lds_limit);
 }
 
 hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
                           int32_t *labels, int32_t *leaf_out, hipStream_t stream)
 {
     if (n_rows <= 0) return hipSuccess;
+    if (m.x_in_registers) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
     bool staged = true;
     if (lds_bytes(m, true) > g_lds_limit) staged = false;
     const size_t lds = lds_bytes(m, staged);

@@ -27,7 +27,7 @@ constexpr int FULL_MAX_DEPTH = 8;
 
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {
-    int32_t feature_slot;  // feature index pre-multiplied by the row-tile width (64)
+    int32_t feature_slot;  // LDS kernels: feature index * 64 (row-tile width); register kernels: feature index
     float threshold;
 };
 
@@ -53,6 +53,9 @@ struct PackedModel {
     int32_t kind = KIND_GENERIC;
     int32_t max_depth = 0;
     int32_t max_words = 0;  // largest TreeMeta::n_words
+    // register-resident kernel family: features live in 32 * reg_nv vector registers per row
+    // slot, reg_r row slots per lane; the split program then stores plain feature indices
+    int32_t x_in_registers = 0, reg_nv = 0, reg_r = 0;
     int64_t n_internal = 0, n_leaves = 0;
 
     std::vector<TreeMeta> tree;      // processing order

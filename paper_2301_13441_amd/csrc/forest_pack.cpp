@@ -154,6 +154,17 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     m.kind = (all_full && common_depth >= 1 && common_depth <= FULL_MAX_DEPTH) ? common_depth
                                                                               : KIND_GENERIC;
 
+    // Full trees over at most 128 features run with the features held in vector registers.
+    if (m.kind != KIND_GENERIC && d.n_features <= 128) {
+        m.x_in_registers = 1;
+        m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
+        m.reg_r = m.reg_nv == 4 ? 1 : 2;
+        const size_t rows = 64 * static_cast<size_t>(m.reg_r);
+        const size_t lds = sizeof(double) * 4 * K * rows + sizeof(float) * 32 * m.reg_nv * rows;
+        if (lds > 64 * 1024) m.x_in_registers = m.reg_nv = m.reg_r = 0;  // many outputs: LDS family
+    }
+    const int32_t feature_scale = m.x_in_registers ? 1 : 64;
+
     // caller-order views (tests of the compiler read these)
     m.v_node_base.assign(1, 0);
     m.v_leaf_base.assign(1, 0);
@@ -214,7 +225,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                     m.prog.push_back(pad);
                 } else {
                     const int32_t v = s.internal[i];
-                    m.prog.push_back(SplitEntry{d.feature[base + v] * 64, d.threshold[base + v]});
+                    m.prog.push_back(SplitEntry{d.feature[base + v] * feature_scale, d.threshold[base + v]});
                 }
             }
         m.max_words = std::max(m.max_words, n_blocks);
@@ -226,6 +237,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
         m.tree.push_back(tm);
     }
+    // One batch of padding: the register kernels prefetch the batch after the one they evaluate.
+    for (int j = 0; j < 16; ++j) m.prog.push_back(pad);
     return FOREST_OK;
 }
 
