@@ -121,6 +121,9 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_tree = place<TreeMeta>(cur, m.tree.size());
     const size_t o_colt = place<double>(cur, m.col_trees.size());
     const size_t o_base = place<float>(cur, m.base.size());
+    const size_t o_thrs = place<float>(cur, m.thr_sorted.size());
+    const size_t o_ftb = place<int32_t>(cur, m.feat_thr_base.size());
+    const size_t o_fvf = place<int32_t>(cur, m.feat_vfirst.size());
     cur = (cur + 255) & ~size_t{255};
     if (hipMalloc(&f->blob, cur) != hipSuccess) {
         (void)hipGetLastError();
@@ -138,7 +141,10 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_leafn, m.leaf_node.data(), m.leaf_node.size() * sizeof(int32_t)) &&
                     up(o_tree, m.tree.data(), m.tree.size() * sizeof(TreeMeta)) &&
                     up(o_colt, m.col_trees.data(), m.col_trees.size() * sizeof(double)) &&
-                    up(o_base, m.base.data(), m.base.size() * sizeof(float));
+                    up(o_base, m.base.data(), m.base.size() * sizeof(float)) &&
+                    up(o_thrs, m.thr_sorted.data(), m.thr_sorted.size() * sizeof(float)) &&
+                    up(o_ftb, m.feat_thr_base.data(), m.feat_thr_base.size() * sizeof(int32_t)) &&
+                    up(o_fvf, m.feat_vfirst.data(), m.feat_vfirst.size() * sizeof(int32_t));
     if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(f->blob);
@@ -162,12 +168,18 @@ int forest_load(const forest_desc *desc, forest **out)
     d.output = m.output;
     d.kind = m.kind;
     d.max_words = m.max_words;
-    d.x_in_registers = m.x_in_registers;
+    d.path = m.path;
     d.reg_nv = m.reg_nv;
     d.reg_r = m.reg_r;
+    d.rank_regs = m.rank_regs;
+    d.rank_steps = m.rank_steps;
+    d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);
+    d.feat_thr_base = reinterpret_cast<const int32_t *>(b + o_ftb);
+    d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
     m.child = {};
+    m.thr_sorted = {};
     m.v_feature = {};
     m.v_threshold = {};
     m.v_left = {};
@@ -199,6 +211,7 @@ int forest_info(const forest *f, forest_info_t *info)
     info->kernel_kind = m.kind;
     info->packed_bytes = f->blob_bytes;
     info->x_in_registers = m.x_in_registers;
+    info->kernel_path = m.path;
     info->rows_per_workgroup = m.x_in_registers ? 64 * m.reg_r : 64;
     return FOREST_OK;
 }

@@ -20,8 +20,13 @@ struct DevModel {
     int32_t n_trees, n_features, n_outputs, leaf_width;
     int32_t aggregate, transform, output, kind;
     int32_t max_words;
-    int32_t x_in_registers;  // 1: register-resident kernel family (full trees, <= 128 features)
-    int32_t reg_nv, reg_r;   // its shape: 32 * reg_nv feature registers, reg_r rows per lane
+    int32_t path;            // PATH_LDS / PATH_REG / PATH_RANK
+    int32_t reg_nv, reg_r;   // REG family: 32 * reg_nv feature registers, reg_r rows per lane
+    // RANK family
+    int32_t rank_regs, rank_steps;
+    const float *thr_sorted;
+    const int32_t *feat_thr_base;
+    const int32_t *feat_vfirst;
 };
 
 // Enqueues one pass over `n_rows` rows on `stream`.  `scores` / `labels` / `leaf_out` may be
@@ -33,6 +38,11 @@ hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, flo
 hipError_t init_reg_kernels(size_t lds_limit);
 hipError_t launch_reg(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                       int32_t *leaf_out, hipStream_t stream);
+
+// Rank family (forest_kernels_rank.hip).
+hipError_t init_rank_kernels(size_t lds_limit);
+hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                       int32_t *leaf_out, hipStream_t stream);
 
 // Whether the kernels' LDS working set for this model fits a compute unit (host-only check).
 bool model_fits(const PackedModel &m);

@@ -219,7 +219,7 @@ KernelFn pick(int kind, bool leaves, bool staged)
 
 bool model_fits(const PackedModel &m)
 {
-    if (m.x_in_registers) return true;  // its LDS need is bounded by construction
+    if (m.path != PATH_LDS) return true;  // their LDS need is bounded at pack time
     return lds_bytes(m.kind, m.n_features, m.n_outputs, m.max_words, false) <= LDS_LIMIT;
 }
 
@@ -239,14 +239,16 @@ hipError_t init_kernels()
                                                    static_cast<int>(g_lds_limit));
                 if (e != hipSuccess) return e;
             }
-    return init_reg_kernels(g_lds_limit);
+    if (hipError_t e = init_reg_kernels(g_lds_limit); e != hipSuccess) return e;
+    return init_rank_kernels(g_lds_limit);
 }
 
 hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
                           int32_t *labels, int32_t *leaf_out, hipStream_t stream)
 {
     if (n_rows <= 0) return hipSuccess;
-    if (m.x_in_registers) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
+    if (m.path == PATH_RANK) return launch_rank(m, X, n_rows, scores, labels, leaf_out, stream);
+    if (m.path == PATH_REG) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
     bool staged = true;
     if (lds_bytes(m, true) > g_lds_limit) staged = false;
     const size_t lds = lds_bytes(m, staged);

@@ -1,0 +1,310 @@
+// Rank kernels for full trees (gfx950): X rewritten, exactly, as per-feature threshold ranks.
+//
+// A comparison x <= tau only needs to know where x falls among the thresholds it can meet
+// (Section 4.3.1, dtype rewriting, applied to the input): with the distinct thresholds of
+// feature f sorted, rank(x) = #{i : tau_i < x}, and a node holding tau_j sends x right iff
+// rank(x) > j.  Ranks and node indices are small integers, exact in f16, and two rows share
+// one register (low / high half), so one packed instruction handles two rows:
+//     v_pk_add_f16  d,   rank[reg], (-j', -j')  clamp   -- d = 1.0 iff rank > j  (step (2) of Fig. 2)
+//     v_pk_fma_f16  acc, acc, 2.0, d                    -- shift the outcome into the accumulator
+// i.e. ONE vector instruction per (row, node).  The register is selected with the VGPR index
+// mode (s_set_gpr_idx_on / _idx: M0 = wave-uniform register index), so step (1), the feature
+// selection matmul(X, W1), costs no vector instruction.  The accumulator starts at 4.0; after
+// 8 entries it holds 1024 + bits, and the low mantissa byte of each half IS the 8 outcome
+// bits.  Four such bytes are gathered into the same 32-bit heap-ordered outcome words the
+// other kernels use (v_perm_b32), and the walk, leaf gather and reduction are shared.
+//
+// Prologue: every workgroup computes the ranks of its 128 rows by binary search over the
+// sorted threshold tables (global memory, cache resident), reading X coalesced.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "forest_device.hpp"
+#include "forest_kernel_common.hpp"
+
+namespace forest_impl {
+namespace {
+
+typedef uint32_t v32u __attribute__((ext_vector_type(32)));
+
+constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half) and l + 64 (high half)
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) SplitEntry *ProgPtr;
+#else
+typedef const SplitEntry *ProgPtr;  // host pass: the kernel body is only parsed
+#endif
+
+struct Entry4 {
+    int32_t f[4];
+    uint32_t t[4];
+};
+
+// Four split-program entries applied to the lane's two rows.
+template <int NVR>
+struct RankStep;
+
+#define FOREST_RANK_ASM                                   \
+    "s_set_gpr_idx_on %[f0], 0x1\n\t"                     \
+    "v_pk_add_f16 %[d0], v64, %[t0] clamp\n\t"            \
+    "s_set_gpr_idx_idx %[f1]\n\t"                         \
+    "v_pk_add_f16 %[d1], v64, %[t1] clamp\n\t"            \
+    "s_set_gpr_idx_idx %[f2]\n\t"                         \
+    "v_pk_add_f16 %[d2], v64, %[t2] clamp\n\t"            \
+    "s_set_gpr_idx_idx %[f3]\n\t"                         \
+    "v_pk_add_f16 %[d3], v64, %[t3] clamp\n\t"            \
+    "s_set_gpr_idx_off\n\t"                               \
+    "v_pk_fma_f16 %[a], %[a], %[two], %[d0]\n\t"          \
+    "v_pk_fma_f16 %[a], %[a], %[two], %[d1]\n\t"          \
+    "v_pk_fma_f16 %[a], %[a], %[two], %[d2]\n\t"          \
+    "v_pk_fma_f16 %[a], %[a], %[two], %[d3]"
+
+template <>
+struct RankStep<2> {
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry4 &e, uint32_t two, const v32u (&x)[2])
+    {
+        uint32_t d0, d1, d2, d3;
+        asm volatile(FOREST_RANK_ASM
+                     : [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3)
+                     : [f0] "s"(e.f[0]), [f1] "s"(e.f[1]), [f2] "s"(e.f[2]), [f3] "s"(e.f[3]),
+                       [t0] "s"(e.t[0]), [t1] "s"(e.t[1]), [t2] "s"(e.t[2]), [t3] "s"(e.t[3]),
+                       [two] "s"(two), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+    }
+};
+
+template <>
+struct RankStep<4> {
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry4 &e, uint32_t two, const v32u (&x)[4])
+    {
+        uint32_t d0, d1, d2, d3;
+        asm volatile(FOREST_RANK_ASM
+                     : [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3)
+                     : [f0] "s"(e.f[0]), [f1] "s"(e.f[1]), [f2] "s"(e.f[2]), [f3] "s"(e.f[3]),
+                       [t0] "s"(e.t[0]), [t1] "s"(e.t[1]), [t2] "s"(e.t[2]), [t3] "s"(e.t[3]),
+                       [two] "s"(two), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]), "{v[128:159]}"(x[2]),
+                       "{v[160:191]}"(x[3]));
+    }
+};
+
+template <int N>
+struct Batch {
+    Entry4 q[N / 4];
+};
+
+template <int N>
+__device__ __forceinline__ Batch<N> load_batch(ProgPtr p)
+{
+    Batch<N> b;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        b.q[j / 4].f[j % 4] = p[j].feature_slot;
+        b.q[j / 4].t[j % 4] = __float_as_uint(p[j].threshold);
+    }
+    return b;
+}
+
+__device__ __forceinline__ uint16_t f16_bits(int v)
+{
+    const _Float16 h = static_cast<_Float16>(static_cast<float>(v));  // exact for |v| <= 2048
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as f16 halves
+// into rk[reg * 64 + (r & 63)] (low half: rows 0..63 of the tile, high half: rows 64..127).
+__device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
+                                          int64_t row0, int64_t n_rows)
+{
+    constexpr int U = 4;  // searches in flight per thread
+    const int F = m.n_features;
+    const int64_t left = n_rows - row0;
+    const int n_valid = (left < RROWS ? static_cast<int>(left) : RROWS) * F;
+    const float *src = X + row0 * F;
+    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
+    for (int e0 = threadIdx.x; e0 < RROWS * F; e0 += BLOCK * U) {
+        float x[U];
+        int lo[U], hi[U], base[U], f[U], r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * BLOCK;
+            const bool in = e < RROWS * F;
+            r[u] = in ? e / F : 0;
+            f[u] = in ? e - r[u] * F : 0;
+            x[u] = (e < n_valid) ? src[e] : 0.0f;
+            base[u] = m.feat_thr_base[f[u]];
+            lo[u] = 0;
+            hi[u] = in ? m.feat_thr_base[f[u] + 1] - base[u] : 0;
+        }
+        for (int s = 0; s < m.rank_steps; ++s) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (lo[u] < hi[u]) {
+                    const int mid = (lo[u] + hi[u]) >> 1;
+                    if (m.thr_sorted[base[u] + mid] < x[u]) lo[u] = mid + 1;
+                    else hi[u] = mid;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * BLOCK;
+            if (e >= RROWS * F) continue;
+            const int n_thr = m.feat_thr_base[f[u] + 1] - base[u];
+            const int rank = (x[u] != x[u]) ? n_thr : lo[u];  // NaN is right of every threshold
+            const int reg0 = m.feat_vfirst[f[u]];
+            for (int s = 0, first = 0; first < n_thr; ++s, first += RANK_SEG) {
+                const int len = n_thr - first < RANK_SEG ? n_thr - first : RANK_SEG;
+                int rv = rank - first;
+                rv = rv < 0 ? 0 : (rv > len ? len : rv);
+                rk16[((reg0 + s) * TILE + (r[u] & 63)) * 2 + (r[u] >> 6)] = f16_bits(rv - RANK_BIAS);
+            }
+        }
+    }
+}
+
+template <int D, int NVR>
+__global__ __launch_bounds__(BLOCK) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
+                                                            int64_t n_rows, float *scores,
+                                                            int32_t *labels, int32_t *leaf_out)
+{
+    constexpr int R = 2;
+    extern __shared__ __align__(16) char smem[];
+    uint32_t *rk = reinterpret_cast<uint32_t *>(smem);  // [32 * NVR][64] packed ranks, then reused as:
+    double *acc = reinterpret_cast<double *>(smem);     // [WAVES][K][128] partial sums
+
+    const int lane = threadIdx.x & (TILE - 1);
+    const int wave = uniform(threadIdx.x >> 6);
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
+
+    rank_rows(rk, m, X, row0, n_rows);
+    __syncthreads();
+    v32u x[NVR];
+#pragma unroll
+    for (int q = 0; q < NVR; ++q)
+#pragma unroll
+        for (int i = 0; i < 32; ++i) x[q][i] = rk[(q * 32 + i) * TILE + lane];
+    __syncthreads();  // rk is dead from here on; acc takes its place
+
+    const bool LEAVES = leaf_out != nullptr;  // wave-uniform: debug output instead of scores
+    Accumulator<R> accu;
+    accu.init(acc, wave, lane, m);
+
+    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);  // entries per tree
+    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;     // outcome words per tree and row
+    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups per word
+    constexpr int NB = N_ENT < 16 ? N_ENT : 16;         // entries per scalar load batch
+    const int T = m.n_trees;
+    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
+    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    const uint32_t two = 0x40004000u;   // (2.0h, 2.0h)
+    const uint32_t four = 0x44004400u;  // (4.0h, 4.0h)
+
+    // The wave's trees are one contiguous stream of entries; the batch after the last one
+    // read here is padding the host appended to the program.
+    ProgPtr p = (ProgPtr)(m.prog + static_cast<size_t>(t_begin) * N_ENT);
+    Batch<NB> cur = load_batch<NB>(p);
+    for (int t = t_begin; t < t_end; ++t) {
+        uint32_t word[R][NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            uint32_t g[GW];
+#pragma unroll
+            for (int gi = 0; gi < GW; ++gi) g[gi] = four;
+#pragma unroll
+            for (int b = 0; b < GW * 8 / NB; ++b) {
+                // first four entries, then issue the next batch's loads, then the rest
+                RankStep<NVR>::step(g[(b * NB) / 8], cur.q[0], two, x);
+                p += NB;
+                const Batch<NB> nxt = load_batch<NB>(p);
+#pragma unroll
+                for (int j = 1; j < NB / 4; ++j) RankStep<NVR>::step(g[(b * NB + j * 4) / 8], cur.q[j], two, x);
+                cur = nxt;
+            }
+            // low byte of each half = 8 outcome bits; gather the bytes of row A and of row B
+            if (GW == 4) {
+                const uint32_t t01 = __builtin_amdgcn_perm(g[1], g[0], 0x06020400u);  // A0 A1 B0 B1
+                const uint32_t t23 = __builtin_amdgcn_perm(g[3 % GW], g[2 % GW], 0x06020400u);
+                word[0][w] = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+                word[1][w] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
+            } else if (GW == 2) {
+                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);
+                word[0][w] = t01 & 0xffffu;
+                word[1][w] = t01 >> 16;
+            } else {
+                word[0][w] = g[0] & 0xffu;
+                word[1][w] = (g[0] >> 16) & 0xffu;
+            }
+        }
+        const TreeMeta tm = m.tree[t];
+        if (!LEAVES) accu.begin_tree(tm.column);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word[r]));
+            if (LEAVES) {
+                const int64_t row = row0 + r * TILE + lane;
+                if (row < n_rows) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
+            } else {
+                accu.add(m, r, leaf);
+            }
+        }
+    }
+    if (LEAVES) return;
+    accu.flush();
+    __syncthreads();
+    const int li = threadIdx.x;
+    if (li < RROWS) finish_row(m, acc, RROWS, li, row0 + li, row0 + li < n_rows, scores, labels);
+}
+
+size_t rank_lds_bytes(const DevModel &m, int nvr)
+{
+    const size_t a = sizeof(double) * WAVES * m.n_outputs * RROWS;
+    const size_t b = sizeof(uint32_t) * 32 * nvr * TILE;
+    return a > b ? a : b;
+}
+
+template <int NVR>
+KernelFn pick_depth(int d)
+{
+    switch (d) {
+        case 1: return forest_rank_kernel<1, NVR>;
+        case 2: return forest_rank_kernel<2, NVR>;
+        case 3: return forest_rank_kernel<3, NVR>;
+        case 4: return forest_rank_kernel<4, NVR>;
+        case 5: return forest_rank_kernel<5, NVR>;
+        case 6: return forest_rank_kernel<6, NVR>;
+        case 7: return forest_rank_kernel<7, NVR>;
+        case 8: return forest_rank_kernel<8, NVR>;
+        default: return nullptr;
+    }
+}
+
+KernelFn pick_rank(int nvr, int d) { return nvr == 2 ? pick_depth<2>(d) : pick_depth<4>(d); }
+
+}  // namespace
+
+hipError_t init_rank_kernels(size_t lds_limit)
+{
+    for (int nvr = 2; nvr <= 4; nvr += 2)
+        for (int d = 1; d <= FULL_MAX_DEPTH; ++d) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_rank(nvr, d)),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               static_cast<int>(lds_limit));
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
+hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                       int32_t *leaf_out, hipStream_t stream)
+{
+    if (m.rank_regs > RANK_MAX_REGS || m.kind < 1 || m.kind > FULL_MAX_DEPTH) return hipErrorInvalidValue;
+    const int nvr = m.rank_regs <= 64 ? 2 : 4;
+    KernelFn fn = pick_rank(nvr, m.kind);
+    const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
+    if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks)), dim3(BLOCK), rank_lds_bytes(m, nvr), stream, m,
+                       X, n_rows, scores, labels, leaf_out);
+    return hipGetLastError();
+}
+
+}  // namespace forest_impl

@@ -25,10 +25,21 @@ namespace forest_impl {
 constexpr int KIND_GENERIC = 0;
 constexpr int FULL_MAX_DEPTH = 8;
 
+// Kernel families (PackedModel::path).
+constexpr int PATH_LDS = 0;   // features read from the LDS tile for every comparison (any model)
+constexpr int PATH_REG = 1;   // full trees, float32 features in vector registers
+constexpr int PATH_RANK = 2;  // full trees, features rewritten as packed f16 threshold ranks
+
+// Rank family: one rank register covers RANK_SEG consecutive thresholds of a feature.
+constexpr int RANK_SEG = 4095;
+constexpr int RANK_BIAS = 2048;
+constexpr int RANK_MAX_REGS = 128;
+
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {
-    int32_t feature_slot;  // LDS kernels: feature index * 64 (row-tile width); register kernels: feature index
-    float threshold;
+    int32_t feature_slot;  // LDS family: feature index * 64; REG family: feature index;
+                           // RANK family: index of the rank register
+    float threshold;       // RANK family: bit pattern of the f16 pair (-j', -j'), see forest_pack.cpp
 };
 
 // Per-tree record in processing order (trees are sorted by output column, stable).
@@ -56,6 +67,14 @@ struct PackedModel {
     // register-resident kernel family: features live in 32 * reg_nv vector registers per row
     // slot, reg_r row slots per lane; the split program then stores plain feature indices
     int32_t x_in_registers = 0, reg_nv = 0, reg_r = 0;
+    // which kernel family runs the model
+    int32_t path = PATH_LDS;
+    // rank family: X is rewritten, exactly, as per-feature threshold ranks (see forest_pack.cpp)
+    int32_t rank_regs = 0;        // packed rank registers per lane (one per virtual feature)
+    int32_t rank_steps = 0;       // binary-search steps that cover the longest threshold table
+    std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
+    std::vector<int32_t> feat_thr_base;   // [F + 1] offsets into thr_sorted
+    std::vector<int32_t> feat_vfirst;     // [F] first rank register of the feature
     int64_t n_internal = 0, n_leaves = 0;
 
     std::vector<TreeMeta> tree;      // processing order

@@ -14,7 +14,24 @@
 // the heap index h = i + 1 for full trees (root 1, children 2h and 2h + 1, position 0 is
 // padding), which keeps every level of a full tree inside whole words from depth 5 on.
 // Padding entries test feature 0 against +Inf; the walk never visits them.
+//
+// Rank family (dtype rewriting of the INPUT, Section 4.3.1 taken one step further: a
+// comparison only needs to know where x falls among the thresholds it is compared with).
+// For feature f let tau_0 < tau_1 < ... < tau_{m-1} be the distinct thresholds of all nodes
+// that test f, and rank(x) = #{i : tau_i < x} (m for NaN).  A node with threshold tau_j sends
+// x right iff !(x <= tau_j) iff rank(x) > j: an integer comparison with exactly the float
+// comparison's result for every x, including NaN, infinities and signed zeros.  Ranks and
+// node indices are stored as f16, which is exact for integers in [-2048, 2047]; one rank
+// register therefore covers a segment of RANK_SEG = 4095 consecutive thresholds:
+//     rv = clamp(rank - 4095 s, 0, L_s) - 2048,   j' = (j - 4095 s) - 2048,
+// and clamp_[0,1](rv - j') is the outcome bit (differences beyond +-2048 round, but keep
+// their sign and a magnitude above 1).  Two rows share a register (low / high half), so one
+// packed instruction compares two rows.  The kernel shifts outcomes into an f16 accumulator
+// that starts at 4.0: after 8 entries its value is 1024 + bits, whose low mantissa byte is
+// the 8 outcome bits, first entry in bit 7.  Entries are therefore stored in blocks of 8,
+// descending position inside a block.
 #include <algorithm>
+#include <cassert>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -92,6 +109,15 @@ int analyse_tree(const forest_desc &d, int64_t base, int64_t n, TreeShape &s)
     return FOREST_OK;
 }
 
+uint16_t f16_bits_of_small_int(int v)
+{
+    // exact for |v| <= 2048
+    const _Float16 h = static_cast<_Float16>(static_cast<float>(v));
+    uint16_t u;
+    std::memcpy(&u, &h, sizeof(u));
+    return u;
+}
+
 int check_desc(const forest_desc &d)
 {
     if (d.n_trees < 0 || d.n_features < 1 || d.n_outputs < 1) return FOREST_EINVAL;
@@ -154,16 +180,68 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     m.kind = (all_full && common_depth >= 1 && common_depth <= FULL_MAX_DEPTH) ? common_depth
                                                                               : KIND_GENERIC;
 
-    // Full trees over at most 128 features run with the features held in vector registers.
-    if (m.kind != KIND_GENERIC && d.n_features <= 128) {
-        m.x_in_registers = 1;
-        m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
-        m.reg_r = m.reg_nv == 4 ? 1 : 2;
-        const size_t rows = 64 * static_cast<size_t>(m.reg_r);
-        const size_t lds = sizeof(double) * 4 * K * rows + sizeof(float) * 32 * m.reg_nv * rows;
-        if (lds > 64 * 1024) m.x_in_registers = m.reg_nv = m.reg_r = 0;  // many outputs: LDS family
+    // Choice of kernel family for full trees.
+    if (m.kind != KIND_GENERIC) {
+        // rank family: per-feature sorted distinct thresholds
+        std::vector<std::vector<float>> per_feature(static_cast<size_t>(d.n_features));
+        for (int32_t t = 0; t < T; ++t)
+            for (int32_t v : shape[t].internal)
+                per_feature[d.feature[d.tree_offset[t] + v]].push_back(d.threshold[d.tree_offset[t] + v]);
+        int64_t regs = 0;
+        size_t longest = 0;
+        for (auto &v : per_feature) {
+            std::sort(v.begin(), v.end());
+            v.erase(std::unique(v.begin(), v.end()), v.end());  // -0 == +0: one threshold
+            regs += static_cast<int64_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
+            longest = std::max(longest, v.size());
+        }
+        const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128, sizeof(uint32_t) * 64 * static_cast<size_t>(regs));
+        if (regs <= RANK_MAX_REGS && rank_lds <= 64 * 1024) {
+            m.path = PATH_RANK;
+            m.x_in_registers = 1;
+            m.reg_r = 2;
+            m.rank_regs = static_cast<int32_t>(regs);
+            m.feat_thr_base.assign(1, 0);
+            int32_t next_reg = 0;
+            for (auto &v : per_feature) {
+                m.feat_vfirst.push_back(next_reg);
+                next_reg += static_cast<int32_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
+                m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
+                m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
+            }
+            while ((size_t{1} << m.rank_steps) < longest + 1) ++m.rank_steps;
+        } else if (d.n_features <= 128) {
+            // float32 features in vector registers
+            m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
+            m.reg_r = m.reg_nv == 4 ? 1 : 2;
+            const size_t rows = 64 * static_cast<size_t>(m.reg_r);
+            const size_t lds = sizeof(double) * 4 * K * rows + sizeof(float) * 32 * m.reg_nv * rows;
+            if (lds <= 64 * 1024) {
+                m.path = PATH_REG;
+                m.x_in_registers = 1;
+            } else {
+                m.reg_nv = m.reg_r = 0;  // many outputs: LDS family
+            }
+        }
     }
-    const int32_t feature_scale = m.x_in_registers ? 1 : 64;
+    const int32_t feature_scale = m.path == PATH_REG ? 1 : 64;
+    // split-program entry of internal node `v` of tree `t`
+    auto entry_of = [&](int32_t t, int32_t v) -> SplitEntry {
+        const int64_t n = d.tree_offset[t] + v;
+        const int32_t f = d.feature[n];
+        if (m.path != PATH_RANK) return SplitEntry{f * feature_scale, d.threshold[n]};
+        const float *lo = m.thr_sorted.data() + m.feat_thr_base[f];
+        const float *hi = m.thr_sorted.data() + m.feat_thr_base[f + 1];
+        const int32_t j = static_cast<int32_t>(std::lower_bound(lo, hi, d.threshold[n]) - lo);
+        assert(lo + j < hi && lo[j] == d.threshold[n]);
+        const int32_t seg = j / RANK_SEG;
+        const uint32_t h = f16_bits_of_small_int(-((j - seg * RANK_SEG) - RANK_BIAS));
+        const uint32_t pair = h | (h << 16);
+        SplitEntry e;
+        e.feature_slot = m.feat_vfirst[f] + seg;
+        std::memcpy(&e.threshold, &pair, sizeof(pair));
+        return e;
+    };
 
     // caller-order views (tests of the compiler read these)
     m.v_node_base.assign(1, 0);
@@ -197,7 +275,13 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                      [&](int32_t a, int32_t b) { return column_of(a) < column_of(b); });
 
     const float inf = std::numeric_limits<float>::infinity();
-    const SplitEntry pad{0, inf};
+    SplitEntry pad{0, inf};
+    if (m.path == PATH_RANK) {
+        // register 0 against j' = 2047: rv - 2047 <= 0 for every rank, the outcome bit is 0
+        const uint32_t h = f16_bits_of_small_int(-2047);
+        const uint32_t pair = h | (h << 16);
+        std::memcpy(&pad.threshold, &pair, sizeof(pair));
+    }
     for (int32_t t : order) {
         const TreeShape &s = shape[t];
         const int64_t base = d.tree_offset[t];
@@ -214,7 +298,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         // positions: heap index for the full-tree kernels, level-order ordinal otherwise
         const int32_t shift = (m.kind != KIND_GENERIC) ? 1 : 0;
         const int32_t n_pos = n_int + shift;
-        const int32_t block = (m.kind != KIND_GENERIC && m.kind < 5) ? (1 << m.kind) : 32;
+        const int32_t block = m.path == PATH_RANK ? 8
+                              : (m.kind != KIND_GENERIC && m.kind < 5) ? (1 << m.kind) : 32;
         const int32_t n_blocks = std::max(1, (n_pos + block - 1) / block);
         tm.n_words = n_blocks;
         for (int32_t w = 0; w < n_blocks; ++w)
@@ -224,8 +309,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 if (i < 0 || i >= n_int) {
                     m.prog.push_back(pad);
                 } else {
-                    const int32_t v = s.internal[i];
-                    m.prog.push_back(SplitEntry{d.feature[base + v] * feature_scale, d.threshold[base + v]});
+                    m.prog.push_back(entry_of(t, s.internal[i]));
                 }
             }
         m.max_words = std::max(m.max_words, n_blocks);
