@@ -115,6 +115,7 @@ int forest_load(const forest_desc *desc, forest **out)
     PackedModel &m = f->host;
     size_t cur = 0;
     const size_t o_prog = place<SplitEntry>(cur, m.prog.size());
+    const size_t o_prog32 = place<uint32_t>(cur, m.prog32.size());
     const size_t o_child = place<ChildRef>(cur, m.child.size());
     const size_t o_leafv = place<float>(cur, m.leaf_value.size());
     const size_t o_leafn = place<int32_t>(cur, m.leaf_node.size());
@@ -136,6 +137,7 @@ int forest_load(const forest_desc *desc, forest **out)
         return bytes == 0 || hipMemcpy(b + off, src, bytes, hipMemcpyHostToDevice) == hipSuccess;
     };
     const bool ok = up(o_prog, m.prog.data(), m.prog.size() * sizeof(SplitEntry)) &&
+                    up(o_prog32, m.prog32.data(), m.prog32.size() * sizeof(uint32_t)) &&
                     up(o_child, m.child.data(), m.child.size() * sizeof(ChildRef)) &&
                     up(o_leafv, m.leaf_value.data(), m.leaf_value.size() * sizeof(float)) &&
                     up(o_leafn, m.leaf_node.data(), m.leaf_node.size() * sizeof(int32_t)) &&
@@ -153,6 +155,7 @@ int forest_load(const forest_desc *desc, forest **out)
     }
     DevModel &d = f->dev;
     d.prog = reinterpret_cast<const SplitEntry *>(b + o_prog);
+    d.prog32 = reinterpret_cast<const uint32_t *>(b + o_prog32);
     d.child = reinterpret_cast<const ChildRef *>(b + o_child);
     d.leaf_value = reinterpret_cast<const float *>(b + o_leafv);
     d.leaf_node = reinterpret_cast<const int32_t *>(b + o_leafn);
@@ -178,6 +181,7 @@ int forest_load(const forest_desc *desc, forest **out)
     d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
+    m.prog32 = {};
     m.child = {};
     m.thr_sorted = {};
     m.v_feature = {};

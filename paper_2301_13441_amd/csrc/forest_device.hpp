@@ -11,6 +11,7 @@ namespace forest_impl {
 
 struct DevModel {
     const SplitEntry *prog;
+    const uint32_t *prog32;
     const ChildRef *child;
     const float *leaf_value;
     const int32_t *leaf_node;

@@ -118,6 +118,8 @@ struct Accumulator {
             for (int k = 0; k < K; ++k) mine[k * rows + r * TILE + lane] += static_cast<double>(v[k]);
         }
     }
+    // scalar leaves only: adds a leaf value that was fetched earlier
+    __device__ __forceinline__ void add_value(int r, float v) { run[r] += static_cast<double>(v); }
     __device__ __forceinline__ void flush()
     {
         if (W == 1) {
@@ -145,7 +147,7 @@ __device__ __forceinline__ uint32_t heap_walk(const uint32_t (&word)[NW])
             const uint32_t hi = (h & 32u) ? word[7 % NW] : word[6 % NW];
             wsel = (h & 64u) ? hi : lo;
         }
-        h = h + h + ((wsel >> (h & 31u)) & 1u);
+        h = h + h + __builtin_amdgcn_ubfe(wsel, h, 1u);  // bit (h mod 32) of the word
     }
     return h - (1u << D);
 }

@@ -31,65 +31,64 @@ typedef uint32_t v32u __attribute__((ext_vector_type(32)));
 constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half) and l + 64 (high half)
 
 #if defined(__HIP_DEVICE_COMPILE__)
-typedef const __attribute__((address_space(4))) SplitEntry *ProgPtr;
+typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
 #else
-typedef const SplitEntry *ProgPtr;  // host pass: the kernel body is only parsed
+typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
 #endif
 
-struct Entry4 {
-    int32_t f[4];
-    uint32_t t[4];
+// One entry of the compact split program is one scalar register: f16(-j') in the high half,
+// the rank register's index in the low byte.  s_set_gpr_idx_* reads only the low byte; the
+// packed add reads the high half for both rows (op_sel:[0,1] op_sel_hi:[1,1]).
+struct Entry8 {
+    uint32_t e[8];
 };
 
-// Four split-program entries applied to the lane's two rows.
+// Eight entries (one outcome byte) applied to the lane's two rows.
 template <int NVR>
 struct RankStep;
 
-#define FOREST_RANK_ASM                                   \
-    "s_set_gpr_idx_on %[f0], 0x1\n\t"                     \
-    "v_pk_add_f16 %[d0], v64, %[t0] clamp\n\t"            \
-    "s_set_gpr_idx_idx %[f1]\n\t"                         \
-    "v_pk_add_f16 %[d1], v64, %[t1] clamp\n\t"            \
-    "s_set_gpr_idx_idx %[f2]\n\t"                         \
-    "v_pk_add_f16 %[d2], v64, %[t2] clamp\n\t"            \
-    "s_set_gpr_idx_idx %[f3]\n\t"                         \
-    "v_pk_add_f16 %[d3], v64, %[t3] clamp\n\t"            \
-    "s_set_gpr_idx_off\n\t"                               \
-    "v_pk_fma_f16 %[a], %[a], %[two], %[d0]\n\t"          \
-    "v_pk_fma_f16 %[a], %[a], %[two], %[d1]\n\t"          \
-    "v_pk_fma_f16 %[a], %[a], %[two], %[d2]\n\t"          \
-    "v_pk_fma_f16 %[a], %[a], %[two], %[d3]"
+#define FOREST_RANK_CMP(n) "v_pk_add_f16 %[d" #n "], v64, %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+#define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
+#define FOREST_RANK_ACC(n) "v_pk_fma_f16 %[a], %[a], %[two], %[d" #n "]\n\t"
+#define FOREST_RANK_ASM                                                                          \
+    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(1)    \
+        FOREST_RANK_IDX(2) FOREST_RANK_CMP(2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(3)              \
+            FOREST_RANK_IDX(4) FOREST_RANK_CMP(4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(5)          \
+                FOREST_RANK_IDX(6) FOREST_RANK_CMP(6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(7)      \
+                    "s_set_gpr_idx_off\n\t" FOREST_RANK_ACC(0) FOREST_RANK_ACC(1) FOREST_RANK_ACC(2) \
+                        FOREST_RANK_ACC(3) FOREST_RANK_ACC(4) FOREST_RANK_ACC(5) FOREST_RANK_ACC(6)  \
+                            "v_pk_fma_f16 %[a], %[a], %[two], %[d7]"
+#define FOREST_RANK_OUTS                                                                              \
+    [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3), [d4] "=&v"(d4), \
+        [d5] "=&v"(d5), [d6] "=&v"(d6), [d7] "=&v"(d7)
+#define FOREST_RANK_INS                                                                                   \
+    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),            \
+        [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [two] "s"(two)
 
 template <>
 struct RankStep<2> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry4 &e, uint32_t two, const v32u (&x)[2])
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, uint32_t two, const v32u (&x)[2])
     {
-        uint32_t d0, d1, d2, d3;
-        asm volatile(FOREST_RANK_ASM
-                     : [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3)
-                     : [f0] "s"(e.f[0]), [f1] "s"(e.f[1]), [f2] "s"(e.f[2]), [f3] "s"(e.f[3]),
-                       [t0] "s"(e.t[0]), [t1] "s"(e.t[1]), [t2] "s"(e.t[2]), [t3] "s"(e.t[3]),
-                       [two] "s"(two), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+        uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
+        asm volatile(FOREST_RANK_ASM : FOREST_RANK_OUTS : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
     }
 };
 
 template <>
 struct RankStep<4> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry4 &e, uint32_t two, const v32u (&x)[4])
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, uint32_t two, const v32u (&x)[4])
     {
-        uint32_t d0, d1, d2, d3;
+        uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
         asm volatile(FOREST_RANK_ASM
-                     : [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3)
-                     : [f0] "s"(e.f[0]), [f1] "s"(e.f[1]), [f2] "s"(e.f[2]), [f3] "s"(e.f[3]),
-                       [t0] "s"(e.t[0]), [t1] "s"(e.t[1]), [t2] "s"(e.t[2]), [t3] "s"(e.t[3]),
-                       [two] "s"(two), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]), "{v[128:159]}"(x[2]),
+                     : FOREST_RANK_OUTS
+                     : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]), "{v[128:159]}"(x[2]),
                        "{v[160:191]}"(x[3]));
     }
 };
 
 template <int N>
 struct Batch {
-    Entry4 q[N / 4];
+    Entry8 q[N / 8];
 };
 
 template <int N>
@@ -97,10 +96,7 @@ __device__ __forceinline__ Batch<N> load_batch(ProgPtr p)
 {
     Batch<N> b;
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        b.q[j / 4].f[j % 4] = p[j].feature_slot;
-        b.q[j / 4].t[j % 4] = __float_as_uint(p[j].threshold);
-    }
+    for (int j = 0; j < N; ++j) b.q[j / 8].e[j % 8] = p[j];
     return b;
 }
 
@@ -115,7 +111,7 @@ __device__ __forceinline__ uint16_t f16_bits(int v)
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
                                           int64_t row0, int64_t n_rows)
 {
-    constexpr int U = 4;  // searches in flight per thread
+    constexpr int U = 8;  // searches in flight per thread
     const int F = m.n_features;
     const int64_t left = n_rows - row0;
     const int n_valid = (left < RROWS ? static_cast<int>(left) : RROWS) * F;
@@ -191,38 +187,46 @@ __global__ __launch_bounds__(BLOCK) void forest_rank_kernel(DevModel m, const fl
 
     constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);  // entries per tree
     constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;     // outcome words per tree and row
-    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups per word
-    constexpr int NB = N_ENT < 16 ? N_ENT : 16;         // entries per scalar load batch
+    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups (outcome bytes) per word
+    constexpr int NB = GW * 8;                          // entries per scalar load batch = one word
     const int T = m.n_trees;
     const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
     const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
     const uint32_t two = 0x40004000u;   // (2.0h, 2.0h)
     const uint32_t four = 0x44004400u;  // (4.0h, 4.0h)
+    const bool scalar_leaves = m.leaf_width == 1;
 
     // The wave's trees are one contiguous stream of entries; the batch after the last one
     // read here is padding the host appended to the program.
-    ProgPtr p = (ProgPtr)(m.prog + static_cast<size_t>(t_begin) * N_ENT);
+    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
     Batch<NB> cur = load_batch<NB>(p);
+    // Scalar leaf values are fetched one tree ahead of their use, so the gather's latency is
+    // covered by the next tree's comparisons.
+    float pending[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
+    int pending_col = 0;
     for (int t = t_begin; t < t_end; ++t) {
+        const TreeMeta tm = m.tree[t];
         uint32_t word[R][NW];
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             uint32_t g[GW];
+            // first group, then issue the next word's loads, then the rest: the loads are in
+            // flight while this word is evaluated
+            g[0] = four;
+            RankStep<NVR>::step(g[0], cur.q[0], two, x);
+            p += NB;
+            const Batch<NB> nxt = load_batch<NB>(p);
 #pragma unroll
-            for (int gi = 0; gi < GW; ++gi) g[gi] = four;
-#pragma unroll
-            for (int b = 0; b < GW * 8 / NB; ++b) {
-                // first four entries, then issue the next batch's loads, then the rest
-                RankStep<NVR>::step(g[(b * NB) / 8], cur.q[0], two, x);
-                p += NB;
-                const Batch<NB> nxt = load_batch<NB>(p);
-#pragma unroll
-                for (int j = 1; j < NB / 4; ++j) RankStep<NVR>::step(g[(b * NB + j * 4) / 8], cur.q[j], two, x);
-                cur = nxt;
+            for (int gi = 1; gi < GW; ++gi) {
+                g[gi] = four;
+                RankStep<NVR>::step(g[gi], cur.q[gi], two, x);
             }
+            cur = nxt;
             // low byte of each half = 8 outcome bits; gather the bytes of row A and of row B
             if (GW == 4) {
-                const uint32_t t01 = __builtin_amdgcn_perm(g[1], g[0], 0x06020400u);  // A0 A1 B0 B1
+                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);  // A0 A1 B0 B1
                 const uint32_t t23 = __builtin_amdgcn_perm(g[3 % GW], g[2 % GW], 0x06020400u);
                 word[0][w] = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
                 word[1][w] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
@@ -235,18 +239,29 @@ __global__ __launch_bounds__(BLOCK) void forest_rank_kernel(DevModel m, const fl
                 word[1][w] = (g[0] >> 16) & 0xffu;
             }
         }
-        const TreeMeta tm = m.tree[t];
-        if (!LEAVES) accu.begin_tree(tm.column);
+        if (!LEAVES && scalar_leaves) {
+            accu.begin_tree(pending_col);
+#pragma unroll
+            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+            pending_col = tm.column;
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word[r]));
             if (LEAVES) {
                 const int64_t row = row0 + r * TILE + lane;
                 if (row < n_rows) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
+            } else if (scalar_leaves) {
+                pending[r] = m.leaf_value[leaf];
             } else {
                 accu.add(m, r, leaf);
             }
         }
+    }
+    if (!LEAVES && scalar_leaves) {
+        accu.begin_tree(pending_col);
+#pragma unroll
+        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
     }
     if (LEAVES) return;
     accu.flush();

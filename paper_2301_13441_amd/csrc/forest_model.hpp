@@ -78,7 +78,8 @@ struct PackedModel {
     int64_t n_internal = 0, n_leaves = 0;
 
     std::vector<TreeMeta> tree;      // processing order
-    std::vector<SplitEntry> prog;    // evaluation order (see forest_pack.cpp)
+    std::vector<SplitEntry> prog;    // evaluation order (see forest_pack.cpp); LDS and REG families
+    std::vector<uint32_t> prog32;    // RANK family: (f16(-j') << 16) | rank register
     std::vector<ChildRef> child;     // [sum N_I]
     std::vector<float> leaf_value;   // E, [sum N_L * leaf_width]
     std::vector<int32_t> leaf_node;  // [sum N_L] caller's node index of each leaf

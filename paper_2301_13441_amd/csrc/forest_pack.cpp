@@ -322,7 +322,18 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         m.tree.push_back(tm);
     }
     // One batch of padding: the register kernels prefetch the batch after the one they evaluate.
-    for (int j = 0; j < 16; ++j) m.prog.push_back(pad);
+    for (int j = 0; j < 32; ++j) m.prog.push_back(pad);
+    if (m.path == PATH_RANK) {
+        // compact form: one dword per entry, f16(-j') in the high half, rank register in the low byte
+        m.prog32.reserve(m.prog.size());
+        for (const SplitEntry &e : m.prog) {
+            uint32_t pair;
+            std::memcpy(&pair, &e.threshold, sizeof(pair));
+            m.prog32.push_back((pair & 0xffff0000u) | static_cast<uint32_t>(e.feature_slot));
+        }
+        m.prog.clear();
+        m.prog.shrink_to_fit();
+    }
     return FOREST_OK;
 }
 
