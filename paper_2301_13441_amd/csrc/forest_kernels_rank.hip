@@ -6,12 +6,12 @@
 // rank(x) > j.  Ranks and node indices are small integers, exact in f16, and two rows share
 // one register (low / high half), so one packed instruction handles two rows:
 //     v_pk_add_f16  d,   rank[reg], (-j', -j')  clamp   -- d = 1.0 iff rank > j  (step (2) of Fig. 2)
-//     v_pk_fma_f16  acc, acc, 2.0, d                    -- shift the outcome into the accumulator
+//     v_pk_fma_f16  d,   d, 2^k, d'                     -- combine outcomes into bit positions
 // i.e. ONE vector instruction per (row, node).  The register is selected with the VGPR index
 // mode (s_set_gpr_idx_on / _idx: M0 = wave-uniform register index), so step (1), the feature
-// selection matmul(X, W1), costs no vector instruction.  The accumulator starts at 4.0; after
-// 8 entries it holds 1024 + bits, and the low mantissa byte of each half IS the 8 outcome
-// bits.  Four such bytes are gathered into the same 32-bit heap-ordered outcome words the
+// selection matmul(X, W1), costs no vector instruction.  Eight outcomes are combined by a
+// tree of fused multiply-adds into 1024 + bits, whose low mantissa byte in each half IS the
+// 8 outcome bits (first entry in bit 7).  Four such bytes are gathered into the same 32-bit heap-ordered outcome words the
 // other kernels use (v_perm_b32), and the walk, leaf gather and reduction are shared.
 //
 // Prologue: every workgroup computes the ranks of its 128 rows by binary search over the
@@ -32,8 +32,10 @@ constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half
 
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
+typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
 #else
 typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
+typedef const TreeMeta *MetaPtr;
 #endif
 
 // One entry of the compact split program is one scalar register: f16(-j') in the high half,
@@ -47,42 +49,49 @@ struct Entry8 {
 template <int NVR>
 struct RankStep;
 
-#define FOREST_RANK_CMP(n) "v_pk_add_f16 %[d" #n "], v64, %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+#define FOREST_RANK_CMP(B, n) "v_pk_add_f16 %[d" #n "], " B ", %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
 #define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
-#define FOREST_RANK_ACC(n) "v_pk_fma_f16 %[a], %[a], %[two], %[d" #n "]\n\t"
-#define FOREST_RANK_ASM                                                                          \
-    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(1)    \
-        FOREST_RANK_IDX(2) FOREST_RANK_CMP(2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(3)              \
-            FOREST_RANK_IDX(4) FOREST_RANK_CMP(4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(5)          \
-                FOREST_RANK_IDX(6) FOREST_RANK_CMP(6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(7)      \
-                    "s_set_gpr_idx_off\n\t" FOREST_RANK_ACC(0) FOREST_RANK_ACC(1) FOREST_RANK_ACC(2) \
-                        FOREST_RANK_ACC(3) FOREST_RANK_ACC(4) FOREST_RANK_ACC(5) FOREST_RANK_ACC(6)  \
-                            "v_pk_fma_f16 %[a], %[a], %[two], %[d7]"
+#define FOREST_RANK_ASM(B)                                                                       \
+    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
+        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
+            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
+                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
+                    "s_set_gpr_idx_off\n\t"                                                      \
+                    "v_pk_fma_f16 %[d0], %[d0], %[c2], %[d1]\n\t"                                \
+                    "v_pk_fma_f16 %[d2], %[d2], %[c2], %[d3]\n\t"                                \
+                    "v_pk_fma_f16 %[d4], %[d4], %[c2], %[d5]\n\t"                                \
+                    "v_pk_fma_f16 %[d6], %[d6], %[c2], %[d7]\n\t"                                \
+                    "v_pk_fma_f16 %[d0], %[d0], %[c4], %[d2]\n\t"                                \
+                    "v_pk_fma_f16 %[d4], %[d4], %[c4], %[d6]\n\t"                                \
+                    "v_pk_fma_f16 %[d0], %[d0], %[c16], %[d4]\n\t"                               \
+                    "v_pk_add_f16 %[a], %[d0], %[c1024]"
 #define FOREST_RANK_OUTS                                                                              \
-    [a] "+v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3), [d4] "=&v"(d4), \
+    [a] "=v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3), [d4] "=&v"(d4), \
         [d5] "=&v"(d5), [d6] "=&v"(d6), [d7] "=&v"(d7)
 #define FOREST_RANK_INS                                                                                   \
     [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),            \
-        [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [two] "s"(two)
+        [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [c2] "s"(0x40004000u), [c4] "s"(0x44004400u), \
+        [c16] "s"(0x4c004c00u), [c1024] "s"(0x64006400u)
 
 template <>
 struct RankStep<2> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, uint32_t two, const v32u (&x)[2])
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, const v32u (&x)[2])
     {
         uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
-        asm volatile(FOREST_RANK_ASM : FOREST_RANK_OUTS : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+        asm volatile(FOREST_RANK_ASM("v64") : FOREST_RANK_OUTS : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
     }
 };
 
 template <>
 struct RankStep<4> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, uint32_t two, const v32u (&x)[4])
+    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, const v32u (&x)[4])
     {
         uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
-        asm volatile(FOREST_RANK_ASM
+        // base v32: with 128 pinned registers the kernel must fit 168 VGPRs for 3 waves per SIMD
+        asm volatile(FOREST_RANK_ASM("v32")
                      : FOREST_RANK_OUTS
-                     : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]), "{v[128:159]}"(x[2]),
-                       "{v[160:191]}"(x[3]));
+                     : FOREST_RANK_INS, "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1]), "{v[96:127]}"(x[2]),
+                       "{v[128:159]}"(x[3]));
     }
 };
 
@@ -158,8 +167,95 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
     }
 }
 
+enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
+
+// The wave's share of the trees: dense evaluation, walk, leaf gather.  One instantiation per
+// output mode so that each loop only keeps the scalar registers it needs.
+template <int D, int NVR, int MODE>
+__device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
+                                           int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
+{
+    constexpr int R = 2;
+    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);  // entries per tree
+    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;     // outcome words per tree and row
+    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups (outcome bytes) per word
+    constexpr int NB = GW * 8;                          // entries per scalar load batch = one word
+    const int T = m.n_trees;
+    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
+    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+
+    // The wave's trees are one contiguous stream of entries; the batch after the last one
+    // read here is padding the host appended to the program.
+    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
+    MetaPtr meta = (MetaPtr)m.tree;
+    Batch<NB> cur = load_batch<NB>(p);
+    // Scalar leaf values are fetched one tree ahead of their use, so the gather's latency is
+    // covered by the next tree's comparisons.
+    float pending[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
+    int pending_col = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        // scalar loads, in flight together with the first batch of the tree
+        const int column = meta[t].column;
+        const int caller_tree = meta[t].caller_tree;
+        uint32_t word[R][NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            uint32_t g[GW];
+            // first group, then issue the next word's loads, then the rest: the loads are in
+            // flight while this word is evaluated
+            RankStep<NVR>::step(g[0], cur.q[0], x);
+            p += NB;
+            const Batch<NB> nxt = load_batch<NB>(p);
+#pragma unroll
+            for (int gi = 1; gi < GW; ++gi) RankStep<NVR>::step(g[gi], cur.q[gi], x);
+            cur = nxt;
+            // low byte of each half = 8 outcome bits; gather the bytes of row A and of row B
+            if (GW == 4) {
+                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);  // A0 A1 B0 B1
+                const uint32_t t23 = __builtin_amdgcn_perm(g[3 % GW], g[2 % GW], 0x06020400u);
+                word[0][w] = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+                word[1][w] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
+            } else if (GW == 2) {
+                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);
+                word[0][w] = t01 & 0xffffu;
+                word[1][w] = t01 >> 16;
+            } else {
+                word[0][w] = g[0] & 0xffu;
+                word[1][w] = (g[0] >> 16) & 0xffu;
+            }
+        }
+        if (MODE == MODE_SCALAR) {
+            accu.begin_tree(pending_col);
+#pragma unroll
+            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+            pending_col = column;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word[r]));
+            if (MODE == MODE_LEAVES) {
+                const int64_t row = row0 + r * TILE + lane;
+                if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
+            } else if (MODE == MODE_SCALAR) {
+                pending[r] = m.leaf_value[leaf];
+            } else {
+                accu.add(m, r, leaf);
+            }
+        }
+    }
+    if (MODE == MODE_SCALAR) {
+        accu.begin_tree(pending_col);
+#pragma unroll
+        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+    }
+}
+
+// Register budget: 64 (NVR = 2) or 128 (NVR = 4) pinned rank registers plus the working set must
+// leave room for 4 resp. 3 waves per SIMD (128 resp. 168 VGPRs).
 template <int D, int NVR>
-__global__ __launch_bounds__(BLOCK) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
+__global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
                                                             int64_t n_rows, float *scores,
                                                             int32_t *labels, int32_t *leaf_out)
 {
@@ -181,89 +277,14 @@ __global__ __launch_bounds__(BLOCK) void forest_rank_kernel(DevModel m, const fl
         for (int i = 0; i < 32; ++i) x[q][i] = rk[(q * 32 + i) * TILE + lane];
     __syncthreads();  // rk is dead from here on; acc takes its place
 
-    const bool LEAVES = leaf_out != nullptr;  // wave-uniform: debug output instead of scores
     Accumulator<R> accu;
     accu.init(acc, wave, lane, m);
-
-    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);  // entries per tree
-    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;     // outcome words per tree and row
-    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups (outcome bytes) per word
-    constexpr int NB = GW * 8;                          // entries per scalar load batch = one word
-    const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
-    const uint32_t two = 0x40004000u;   // (2.0h, 2.0h)
-    const uint32_t four = 0x44004400u;  // (4.0h, 4.0h)
-    const bool scalar_leaves = m.leaf_width == 1;
-
-    // The wave's trees are one contiguous stream of entries; the batch after the last one
-    // read here is padding the host appended to the program.
-    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
-    Batch<NB> cur = load_batch<NB>(p);
-    // Scalar leaf values are fetched one tree ahead of their use, so the gather's latency is
-    // covered by the next tree's comparisons.
-    float pending[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
-    int pending_col = 0;
-    for (int t = t_begin; t < t_end; ++t) {
-        const TreeMeta tm = m.tree[t];
-        uint32_t word[R][NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            uint32_t g[GW];
-            // first group, then issue the next word's loads, then the rest: the loads are in
-            // flight while this word is evaluated
-            g[0] = four;
-            RankStep<NVR>::step(g[0], cur.q[0], two, x);
-            p += NB;
-            const Batch<NB> nxt = load_batch<NB>(p);
-#pragma unroll
-            for (int gi = 1; gi < GW; ++gi) {
-                g[gi] = four;
-                RankStep<NVR>::step(g[gi], cur.q[gi], two, x);
-            }
-            cur = nxt;
-            // low byte of each half = 8 outcome bits; gather the bytes of row A and of row B
-            if (GW == 4) {
-                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);  // A0 A1 B0 B1
-                const uint32_t t23 = __builtin_amdgcn_perm(g[3 % GW], g[2 % GW], 0x06020400u);
-                word[0][w] = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
-                word[1][w] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
-            } else if (GW == 2) {
-                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);
-                word[0][w] = t01 & 0xffffu;
-                word[1][w] = t01 >> 16;
-            } else {
-                word[0][w] = g[0] & 0xffu;
-                word[1][w] = (g[0] >> 16) & 0xffu;
-            }
-        }
-        if (!LEAVES && scalar_leaves) {
-            accu.begin_tree(pending_col);
-#pragma unroll
-            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-            pending_col = tm.column;
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word[r]));
-            if (LEAVES) {
-                const int64_t row = row0 + r * TILE + lane;
-                if (row < n_rows) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
-            } else if (scalar_leaves) {
-                pending[r] = m.leaf_value[leaf];
-            } else {
-                accu.add(m, r, leaf);
-            }
-        }
+    if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
+        rank_trees<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+        return;
     }
-    if (!LEAVES && scalar_leaves) {
-        accu.begin_tree(pending_col);
-#pragma unroll
-        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-    }
-    if (LEAVES) return;
+    if (m.leaf_width == 1) rank_trees<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    else rank_trees<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
     accu.flush();
     __syncthreads();
     const int li = threadIdx.x;
