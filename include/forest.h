@@ -143,7 +143,9 @@ int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32
  */
 typedef struct forest_packed_view {
     int32_t n_trees;
-    int32_t kernel_kind;
+    int32_t kernel_kind;            /* common depth of a forest of full trees (1..8), else 0 */
+    int32_t kernel_path;            /* as forest_info_t.kernel_path */
+    int32_t rank_registers;         /* kernel_path 2: rank registers per lane (virtual features) */
     const int32_t *tree_n_internal; /* [n_trees] N_I */
     const int32_t *tree_depth;      /* [n_trees] longest path; full trees: every path */
     const int32_t *tree_is_full;    /* [n_trees] 1 if every leaf sits at tree_depth */

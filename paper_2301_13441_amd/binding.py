@@ -39,7 +39,8 @@ class _Info(ctypes.Structure):
 
 
 class _View(ctypes.Structure):
-    _fields_ = [("n_trees", _i32), ("kernel_kind", _i32), ("tree_n_internal", _p), ("tree_depth", _p),
+    _fields_ = [("n_trees", _i32), ("kernel_kind", _i32), ("kernel_path", _i32), ("rank_registers", _i32),
+                ("tree_n_internal", _p), ("tree_depth", _p),
                 ("tree_is_full", _p), ("node_base", _p), ("leaf_base", _p), ("split_feature", _p),
                 ("split_threshold", _p), ("child_left", _p), ("child_right", _p), ("leaf_node", _p),
                 ("leaf_value", _p)]
@@ -153,7 +154,8 @@ def forest_pack(forest) -> dict:
         leaf_base = get(v.leaf_base, T + 1, np.int64)
         ni, nl = int(node_base[-1]), int(leaf_base[-1])
         return dict(
-            n_trees=T, kernel_kind=v.kernel_kind,
+            n_trees=T, kernel_kind=v.kernel_kind, kernel_path=v.kernel_path,
+            rank_registers=v.rank_registers,
             tree_n_internal=get(v.tree_n_internal, T, np.int32),
             tree_depth=get(v.tree_depth, T, np.int32),
             tree_is_full=get(v.tree_is_full, T, np.int32),

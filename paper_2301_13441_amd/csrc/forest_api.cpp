@@ -70,6 +70,8 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     const PackedModel &m = p->m;
     v->n_trees = m.n_trees;
     v->kernel_kind = m.kind;
+    v->kernel_path = m.path;
+    v->rank_registers = m.rank_regs;
     v->tree_n_internal = m.v_n_internal.data();
     v->tree_depth = m.v_depth.data();
     v->tree_is_full = m.v_is_full.data();

@@ -118,3 +118,107 @@ def test_repeated_runs_are_bit_identical():
         b, lb = f.predict(xd)
         assert torch.equal(a, b) and torch.equal(la, lb)
     f.close()
+
+
+# ----------------------------------------------------------------------------- kernel families
+
+def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=1, **kw):
+    rng = np.random.default_rng(seed)
+    arrs = wl._full_forest(rng, n_trees, depth, n_features, wl._normal_thr,
+                           lambda r, s: r.standard_normal(s, dtype=np.float32))
+    if feature_bias is not None:  # send most nodes to feature 0
+        internal = arrs["feature"] >= 0
+        hit = internal & (rng.random(arrs["feature"].shape) < feature_bias)
+        arrs["feature"] = np.where(hit, 0, arrs["feature"]).astype(np.int32)
+    out = (rng.integers(0, n_outputs, size=n_trees).astype(np.int32))
+    return wl.Forest(n_features=n_features, n_outputs=n_outputs, leaf_width=1, tree_output=out,
+                     aggregate=wl.AGG_SUM, **arrs, **kw)
+
+
+@pytest.mark.parametrize("what,path", [
+    ("rank_three_segments", 2),   # > 2 * 4095 distinct thresholds on one feature
+    ("rank_wide", 2),             # 128 features -> 128 rank registers (the 3-waves variant)
+    ("reg_fallback", 1),          # too many rank registers -> float32 feature registers
+    ("lds_full", 0),              # full trees over > 128 features
+    ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the register kernels
+])
+def test_kernel_families(what, path):
+    rng = np.random.default_rng(42)
+    if what == "rank_three_segments":
+        f = _full_forest(1, 40, 8, 2)
+    elif what == "rank_wide":
+        f = _full_forest(2, 30, 7, 128, n_outputs=3, transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "reg_fallback":
+        f = _full_forest(3, 40, 8, 128, feature_bias=0.9)
+    elif what == "lds_full":
+        f = _full_forest(4, 12, 5, 200)
+    else:
+        f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
+    X = rng.standard_normal((517, f.n_features)).astype(np.float32)
+    # rows that sit exactly on thresholds of their feature
+    thr = f.threshold[f.feature == 0]
+    X[:64, 0] = np.resize(thr, 64)
+    info = _check(f, X)
+    assert info["kernel_path"] == path, info
+
+
+def test_duplicate_thresholds_and_unused_features():
+    w = wl.make_workload("c3", n_rows=700, n_trees=60)      # thresholds from a 255-value grid
+    f = w.forest
+    feat = np.where(f.feature >= 0, f.feature % 7, f.feature).astype(np.int32)  # 43 features unused
+    g = wl.Forest(**{**f.__dict__, "feature": feat})
+    X = w.make_x(700).copy()
+    grid = wl.normal_quantile_grid(255)
+    X[:300, :7] = grid[np.random.default_rng(3).integers(0, 255, size=(300, 7))]  # x == threshold
+    assert _check(g, X)["kernel_path"] == 2
+
+
+# ----------------------------------------------------------------------------- full-size runs
+
+def _full_size(name, leaf_rows=4096):
+    """The bench's launch configuration (full row count, device-resident X); outputs of the
+    first 65 536 rows and of 65 536 seeded random rows are compared with the oracle."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload(name)
+    n, F = w.n_rows, w.forest.n_features
+    rng = np.random.default_rng(wl.SEEDS[name] + 7)
+    n_head = min(n, 65536)
+    pick = np.unique(np.concatenate([np.arange(n_head), rng.integers(0, n, size=65536)]))
+    xd = torch.empty((n, F), dtype=torch.float32, device="cuda")
+    xs = np.empty((len(pick), F), dtype=np.float32)
+    pos = 0
+    for chunk in w.x_chunks(n):
+        xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
+        sel = pick[(pick >= pos) & (pick < pos + len(chunk))]
+        xs[np.searchsorted(pick, sel)] = chunk[sel - pos]
+        pos += len(chunk)
+    f = pk.forest_load(w.forest)
+    try:
+        scores, labels = f.predict(xd)
+        torch.cuda.synchronize()
+        idx = torch.from_numpy(pick).cuda()
+        got_scores = None if scores is None else scores[idx].cpu().numpy()
+        got_labels = None if labels is None else labels[idx].cpu().numpy()
+        # leaf ids: every tree, on the first rows of the sample (through the same kernels)
+        lv = f.predict_leaves(xd[:n_head])
+        torch.cuda.synchronize()
+        got_leaves = lv[:leaf_rows].cpu().numpy()
+        info = f.info
+    finally:
+        f.close()
+    ref = oracle.predict(w.forest, xs, n_threads=16)
+    ref_leaves = oracle.predict(w.forest, xs[:leaf_rows], want_leaves=True, n_threads=16).leaf_node_id
+    assert (pick[:leaf_rows] == np.arange(leaf_rows)).all()
+    np.testing.assert_array_equal(got_leaves, ref_leaves)
+    if got_labels is not None:
+        np.testing.assert_array_equal(got_labels, ref.labels)
+    if got_scores is not None:
+        np.testing.assert_allclose(got_scores, ref.scores, rtol=RTOL, atol=ATOL)
+    return info
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_full_size_sampled(name):
+    info = _full_size(name)
+    assert info["n_trees"] == {"c2": 500, "c3": 1000, "c4": 2000, "c5": 128}[name]
