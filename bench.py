@@ -27,7 +27,11 @@ HBM_PEAK = 8.0e12
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 62,991 x 2.000 (copy-kernel scale) KiB read,
+    # WRITE_SIZE 7,812.5 x 1.000 KiB written
+    "c2": 129.0e6 + 8.0e6,
+}
 
 
 def main() -> int:
@@ -105,6 +109,10 @@ def main() -> int:
         "peak": ALU_PEAK_LANE_OPS / 1e12,
         "unit": "Tcompare/s",
         "frac": achieved / ALU_PEAK_LANE_OPS,
+        "peak_basis": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one float32 compare per lane-op",
+        # the rank kernels evaluate two comparisons per packed-f16 lane-op: their own ceiling is 2x
+        "frac_vs_packed_f16_peak": (achieved / (2 * ALU_PEAK_LANE_OPS)
+                                    if info["kernel_path"] == 2 else None),
         "kernel_ms_avg": kernel_s * 1e3,
         "kernel_ms_min": float(np.min(kernel_ms)),
         "algorithmic_bytes": algo_bytes,
@@ -144,12 +152,14 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32 compare, f64 accumulate",
+        "dtype": ("f16 threshold ranks (exact rewrite of the f32 compare), f64 accumulate"
+                  if info["kernel_path"] == 2 else "f32 compare, f64 accumulate"),
         "data": "synthetic (seeded; stands in for YearPrediction and the paper's unstated models)",
         "config": {"workload": args.workload, "n_rows": n_rows, "n_features": F,
                    "n_trees": info["n_trees"], "max_depth": info["max_depth"],
                    "n_internal_nodes": info["n_internal"], "n_outputs": info["n_outputs"],
-                   "kernel_kind": info["kernel_kind"], "packed_bytes": info["packed_bytes"]},
+                   "kernel_kind": info["kernel_kind"], "kernel_path": info["kernel_path"],
+                   "packed_bytes": info["packed_bytes"]},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
