@@ -14,8 +14,9 @@
 // 8 outcome bits (first entry in bit 7).  Four such bytes are gathered into the same 32-bit heap-ordered outcome words the
 // other kernels use (v_perm_b32), and the walk, leaf gather and reduction are shared.
 //
-// Prologue: every workgroup computes the ranks of its 128 rows by binary search over the
-// sorted threshold tables (global memory, cache resident), reading X coalesced.
+// Prologue: every workgroup computes the ranks of its 128 rows by a two-level binary search
+// (pivots staged in LDS, then one block of the sorted threshold table in global memory),
+// reading X coalesced.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -117,8 +118,10 @@ __device__ __forceinline__ uint16_t f16_bits(int v)
 
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as f16 halves
 // into rk[reg * 64 + (r & 63)] (low half: rows 0..63 of the tile, high half: rows 64..127).
-__device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
-                                          int64_t row0, int64_t n_rows)
+// Two-level search: first over the feature's pivots (LDS: the last threshold of every block
+// of 2^pivot_shift), then inside one block of the sorted table (global memory).
+__device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const DevModel &m,
+                                          const float *__restrict__ X, int64_t row0, int64_t n_rows)
 {
     constexpr int U = 8;  // searches in flight per thread
     const int F = m.n_features;
@@ -126,9 +129,10 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
     const int n_valid = (left < RROWS ? static_cast<int>(left) : RROWS) * F;
     const float *src = X + row0 * F;
     uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
+    const int block = 1 << m.pivot_shift;
     for (int e0 = threadIdx.x; e0 < RROWS * F; e0 += BLOCK * U) {
         float x[U];
-        int lo[U], hi[U], base[U], f[U], r[U];
+        int lo[U], hi[U], base[U], n_thr[U], f[U], r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * BLOCK;
@@ -136,11 +140,31 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
             r[u] = in ? e / F : 0;
             f[u] = in ? e - r[u] * F : 0;
             x[u] = (e < n_valid) ? src[e] : 0.0f;
-            base[u] = m.feat_thr_base[f[u]];
+            base[u] = m.feat_pivot_base[f[u]];
             lo[u] = 0;
-            hi[u] = in ? m.feat_thr_base[f[u] + 1] - base[u] : 0;
+            hi[u] = in ? m.feat_pivot_base[f[u] + 1] - base[u] : 0;
         }
+        // first block whose last threshold is not below x
         for (int s = 0; s < m.rank_steps; ++s) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (lo[u] < hi[u]) {
+                    const int mid = (lo[u] + hi[u]) >> 1;
+                    if (piv[base[u] + mid] < x[u]) lo[u] = mid + 1;
+                    else hi[u] = mid;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            base[u] = m.feat_thr_base[f[u]];
+            n_thr[u] = (e0 + u * BLOCK < RROWS * F) ? m.feat_thr_base[f[u] + 1] - base[u] : 0;
+            lo[u] = lo[u] << m.pivot_shift;
+            hi[u] = lo[u] + block < n_thr[u] ? lo[u] + block : n_thr[u];
+            if (lo[u] > hi[u]) lo[u] = hi[u];  // x is above every pivot: rank = number of thresholds
+        }
+        // position inside the block
+        for (int s = 0; s <= m.pivot_shift; ++s) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (lo[u] < hi[u]) {
@@ -154,11 +178,10 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * BLOCK;
             if (e >= RROWS * F) continue;
-            const int n_thr = m.feat_thr_base[f[u] + 1] - base[u];
-            const int rank = (x[u] != x[u]) ? n_thr : lo[u];  // NaN is right of every threshold
+            const int rank = (x[u] != x[u]) ? n_thr[u] : lo[u];  // NaN is right of every threshold
             const int reg0 = m.feat_vfirst[f[u]];
-            for (int s = 0, first = 0; first < n_thr; ++s, first += RANK_SEG) {
-                const int len = n_thr - first < RANK_SEG ? n_thr - first : RANK_SEG;
+            for (int s = 0, first = 0; first < n_thr[u]; ++s, first += RANK_SEG) {
+                const int len = n_thr[u] - first < RANK_SEG ? n_thr[u] - first : RANK_SEG;
                 int rv = rank - first;
                 rv = rv < 0 ? 0 : (rv > len ? len : rv);
                 rk16[((reg0 + s) * TILE + (r[u] & 63)) * 2 + (r[u] >> 6)] = f16_bits(rv - RANK_BIAS);
@@ -268,7 +291,10 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
-    rank_rows(rk, m, X, row0, n_rows);
+    float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
+    for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
+    __syncthreads();
+    rank_rows(rk, piv, m, X, row0, n_rows);
     __syncthreads();
     v32u x[NVR];
 #pragma unroll
@@ -294,7 +320,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
 size_t rank_lds_bytes(const DevModel &m, int nvr)
 {
     const size_t a = sizeof(double) * WAVES * m.n_outputs * RROWS;
-    const size_t b = sizeof(uint32_t) * 32 * nvr * TILE;
+    const size_t b = sizeof(uint32_t) * 32 * nvr * TILE + sizeof(float) * m.n_pivots;
     return a > b ? a : b;
 }
 

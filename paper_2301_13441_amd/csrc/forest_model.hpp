@@ -34,6 +34,7 @@ constexpr int PATH_RANK = 2;  // full trees, features rewritten as packed f16 th
 constexpr int RANK_SEG = 4095;
 constexpr int RANK_BIAS = 2048;
 constexpr int RANK_MAX_REGS = 128;
+constexpr int RANK_MAX_PIVOTS = 4096;  // pivot thresholds staged in LDS by every workgroup
 
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {
@@ -71,7 +72,10 @@ struct PackedModel {
     int32_t path = PATH_LDS;
     // rank family: X is rewritten, exactly, as per-feature threshold ranks (see forest_pack.cpp)
     int32_t rank_regs = 0;        // packed rank registers per lane (one per virtual feature)
-    int32_t rank_steps = 0;       // binary-search steps that cover the longest threshold table
+    int32_t rank_steps = 0;       // binary-search steps that cover the longest pivot list
+    int32_t pivot_shift = 0;      // every 2^pivot_shift-th threshold (the last of each block) is a pivot
+    std::vector<float> pivots;            // per feature: last threshold of each block, concatenated
+    std::vector<int32_t> feat_pivot_base; // [F + 1] offsets into pivots
     std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
     std::vector<int32_t> feat_thr_base;   // [F + 1] offsets into thr_sorted
     std::vector<int32_t> feat_vfirst;     // [F] first rank register of the feature

@@ -195,7 +195,9 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             regs += static_cast<int64_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
             longest = std::max(longest, v.size());
         }
-        const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128, sizeof(uint32_t) * 64 * static_cast<size_t>(regs));
+        const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128,
+                                         sizeof(uint32_t) * 64 * static_cast<size_t>(regs > 64 ? 128 : 64) +
+                                             sizeof(float) * RANK_MAX_PIVOTS);
         if (regs <= RANK_MAX_REGS && rank_lds <= 64 * 1024) {
             m.path = PATH_RANK;
             m.x_in_registers = 1;
@@ -209,7 +211,23 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
                 m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
             }
-            while ((size_t{1} << m.rank_steps) < longest + 1) ++m.rank_steps;
+            // Two-level search: the last threshold of every block of 2^pivot_shift is a pivot; the
+            // pivots of all features fit RANK_MAX_PIVOTS and are searched in LDS, the block itself
+            // in global memory.
+            for (;; ++m.pivot_shift) {
+                size_t total = 0;
+                for (auto &v : per_feature) total += (v.size() + (size_t{1} << m.pivot_shift) - 1) >> m.pivot_shift;
+                if (total <= RANK_MAX_PIVOTS) break;
+            }
+            const size_t block = size_t{1} << m.pivot_shift;
+            m.feat_pivot_base.assign(1, 0);
+            size_t most_pivots = 0;
+            for (auto &v : per_feature) {
+                for (size_t b = 0; b < v.size(); b += block) m.pivots.push_back(v[std::min(b + block, v.size()) - 1]);
+                most_pivots = std::max(most_pivots, (v.size() + block - 1) / block);
+                m.feat_pivot_base.push_back(static_cast<int32_t>(m.pivots.size()));
+            }
+            while ((size_t{1} << m.rank_steps) < most_pivots + 1) ++m.rank_steps;
         } else if (d.n_features <= 128) {
             // float32 features in vector registers
             m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
