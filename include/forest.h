@@ -89,7 +89,8 @@ typedef struct forest_info_t {
     int64_t packed_bytes;  /* device-resident size of the packed model */
     int32_t x_in_registers;     /* 1 if the kernel keeps the features in vector registers */
     int32_t kernel_path;        /* 0: features from the LDS tile; 1: float32 feature registers;
-                                   2: packed f16 threshold-rank registers */
+                                   2: packed f16 threshold-rank registers;
+                                   3: packed f16 threshold ranks in LDS (any tree shape) */
     int32_t rows_per_workgroup; /* rows one workgroup (4 wavefronts) owns */
 } forest_info_t;
 

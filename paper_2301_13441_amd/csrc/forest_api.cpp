@@ -226,7 +226,7 @@ int forest_info(const forest *f, forest_info_t *info)
     info->packed_bytes = f->blob_bytes;
     info->x_in_registers = m.x_in_registers;
     info->kernel_path = m.path;
-    info->rows_per_workgroup = m.x_in_registers ? 64 * m.reg_r : 64;
+    info->rows_per_workgroup = m.path == PATH_RANK_LDS ? 128 : m.x_in_registers ? 64 * m.reg_r : 64;
     return FOREST_OK;
 }
 

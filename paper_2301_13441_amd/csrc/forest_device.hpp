@@ -47,6 +47,11 @@ hipError_t init_rank_kernels(size_t lds_limit);
 hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                        int32_t *leaf_out, hipStream_t stream);
 
+// LDS-resident rank family (forest_kernels_ranklds.hip).
+hipError_t init_ranklds_kernels(size_t lds_limit);
+hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                          int32_t *leaf_out, size_t lds_limit, hipStream_t stream);
+
 // Whether the kernels' LDS working set for this model fits a compute unit (host-only check).
 bool model_fits(const PackedModel &m);
 

@@ -36,16 +36,16 @@ __device__ __forceinline__ void stage_x_tile(float *xs, const float *X, int64_t 
 }
 
 // Cross-wave reduction, aggregate, label, transform, store for tile row `li` (0 <= li < rows).
-// `acc` is [WAVES][K][rows]; wave 0's slice is overwritten with the raw values.
+// `acc` is [n_waves][K][rows]; wave 0's slice is overwritten with the raw values.
 __device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int rows, int li, int64_t row,
-                                           bool valid, float *scores, int32_t *labels)
+                                           bool valid, float *scores, int32_t *labels, int n_waves = WAVES)
 {
     const int K = m.n_outputs;
     double best = 0.0;
     int best_k = 0;
     for (int k = 0; k < K; ++k) {
         double s = acc[(0 * K + k) * rows + li];
-        for (int w = 1; w < WAVES; ++w) s += acc[(w * K + k) * rows + li];
+        for (int w = 1; w < n_waves; ++w) s += acc[(w * K + k) * rows + li];
         if (m.aggregate == FOREST_AGG_MEAN) s = s / m.col_trees[k];
         s = static_cast<double>(m.base[k]) + s;
         acc[k * rows + li] = s;

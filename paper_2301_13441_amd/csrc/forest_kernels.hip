@@ -240,7 +240,8 @@ hipError_t init_kernels()
                 if (e != hipSuccess) return e;
             }
     if (hipError_t e = init_reg_kernels(g_lds_limit); e != hipSuccess) return e;
-    return init_rank_kernels(g_lds_limit);
+    if (hipError_t e = init_rank_kernels(g_lds_limit); e != hipSuccess) return e;
+    return init_ranklds_kernels(g_lds_limit);
 }
 
 hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
@@ -248,6 +249,7 @@ hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, flo
 {
     if (n_rows <= 0) return hipSuccess;
     if (m.path == PATH_RANK) return launch_rank(m, X, n_rows, scores, labels, leaf_out, stream);
+    if (m.path == PATH_RANK_LDS) return launch_ranklds(m, X, n_rows, scores, labels, leaf_out, g_lds_limit, stream);
     if (m.path == PATH_REG) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
     bool staged = true;
     if (lds_bytes(m, true) > g_lds_limit) staged = false;

@@ -23,13 +23,13 @@
 
 #include "forest_device.hpp"
 #include "forest_kernel_common.hpp"
+#include "forest_rank_common.hpp"
 
 namespace forest_impl {
 namespace {
 
 typedef uint32_t v32u __attribute__((ext_vector_type(32)));
 
-constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half) and l + 64 (high half)
 
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
@@ -108,86 +108,6 @@ __device__ __forceinline__ Batch<N> load_batch(ProgPtr p)
 #pragma unroll
     for (int j = 0; j < N; ++j) b.q[j / 8].e[j % 8] = p[j];
     return b;
-}
-
-__device__ __forceinline__ uint16_t f16_bits(int v)
-{
-    const _Float16 h = static_cast<_Float16>(static_cast<float>(v));  // exact for |v| <= 2048
-    return __builtin_bit_cast(uint16_t, h);
-}
-
-// Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as f16 halves
-// into rk[reg * 64 + (r & 63)] (low half: rows 0..63 of the tile, high half: rows 64..127).
-// Two-level search: first over the feature's pivots (LDS: the last threshold of every block
-// of 2^pivot_shift), then inside one block of the sorted table (global memory).
-__device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const DevModel &m,
-                                          const float *__restrict__ X, int64_t row0, int64_t n_rows)
-{
-    constexpr int U = 8;  // searches in flight per thread
-    const int F = m.n_features;
-    const int64_t left = n_rows - row0;
-    const int n_valid = (left < RROWS ? static_cast<int>(left) : RROWS) * F;
-    const float *src = X + row0 * F;
-    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
-    const int block = 1 << m.pivot_shift;
-    for (int e0 = threadIdx.x; e0 < RROWS * F; e0 += BLOCK * U) {
-        float x[U];
-        int lo[U], hi[U], base[U], n_thr[U], f[U], r[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * BLOCK;
-            const bool in = e < RROWS * F;
-            r[u] = in ? e / F : 0;
-            f[u] = in ? e - r[u] * F : 0;
-            x[u] = (e < n_valid) ? src[e] : 0.0f;
-            base[u] = m.feat_pivot_base[f[u]];
-            lo[u] = 0;
-            hi[u] = in ? m.feat_pivot_base[f[u] + 1] - base[u] : 0;
-        }
-        // first block whose last threshold is not below x
-        for (int s = 0; s < m.rank_steps; ++s) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (lo[u] < hi[u]) {
-                    const int mid = (lo[u] + hi[u]) >> 1;
-                    if (piv[base[u] + mid] < x[u]) lo[u] = mid + 1;
-                    else hi[u] = mid;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            base[u] = m.feat_thr_base[f[u]];
-            n_thr[u] = (e0 + u * BLOCK < RROWS * F) ? m.feat_thr_base[f[u] + 1] - base[u] : 0;
-            lo[u] = lo[u] << m.pivot_shift;
-            hi[u] = lo[u] + block < n_thr[u] ? lo[u] + block : n_thr[u];
-            if (lo[u] > hi[u]) lo[u] = hi[u];  // x is above every pivot: rank = number of thresholds
-        }
-        // position inside the block
-        for (int s = 0; s <= m.pivot_shift; ++s) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (lo[u] < hi[u]) {
-                    const int mid = (lo[u] + hi[u]) >> 1;
-                    if (m.thr_sorted[base[u] + mid] < x[u]) lo[u] = mid + 1;
-                    else hi[u] = mid;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * BLOCK;
-            if (e >= RROWS * F) continue;
-            const int rank = (x[u] != x[u]) ? n_thr[u] : lo[u];  // NaN is right of every threshold
-            const int reg0 = m.feat_vfirst[f[u]];
-            for (int s = 0, first = 0; first < n_thr[u]; ++s, first += RANK_SEG) {
-                const int len = n_thr[u] - first < RANK_SEG ? n_thr[u] - first : RANK_SEG;
-                int rv = rank - first;
-                rv = rv < 0 ? 0 : (rv > len ? len : rv);
-                rk16[((reg0 + s) * TILE + (r[u] & 63)) * 2 + (r[u] >> 6)] = f16_bits(rv - RANK_BIAS);
-            }
-        }
-    }
 }
 
 enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
@@ -294,7 +214,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
     for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
     __syncthreads();
-    rank_rows(rk, piv, m, X, row0, n_rows);
+    rank_rows<BLOCK>(rk, piv, m, X, row0, n_rows);
     __syncthreads();
     v32u x[NVR];
 #pragma unroll

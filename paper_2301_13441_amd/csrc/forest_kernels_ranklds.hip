@@ -1,0 +1,274 @@
+// Rank kernel for trees of any shape (gfx950): packed f16 threshold ranks held in LDS.
+//
+// Same exact rewrite of the comparison as forest_kernels_rank.hip (rank(x) > j instead of
+// !(x <= tau_j), two rows per 32-bit word, v_pk_add_f16 with clamp as the comparison), for
+// models whose rank tile does not fit the vector registers: up to 256 rank rows of 64 words
+// sit in LDS and every entry of the split program reads its row
+//     v_and_or_b32  a, entry, 0xff00, lane * 4          -- LDS address of the row, no scalar op
+//     ds_read_b32   x, a
+//     v_pk_add_f16  d, x, entry.hi  clamp               -- step (2) of Fig. 2 for two rows
+//     v_pk_fma_f16  ...                                 -- 8 outcomes -> one outcome byte
+// i.e. three vector instructions and one LDS read per (node, two rows).
+//
+// Trees are stored level by level (internal nodes in level order, Section 3.1.2; every level
+// padded to whole groups of 8 entries).  After the last group of a level the wave has that
+// level's outcome bytes in its LDS buffer and every lane moves from its node to the child the
+// bits select (the bit-level form of picking the leaf with matmul(., W3) + argmax); a child
+// reference is either the child's ordinal in the next level or a leaf.  One pass over the
+// stream therefore resolves the leaf with a working set of one level.
+//
+// A workgroup is 8 wavefronts on 128 rows; the trees are split over the waves.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "forest_device.hpp"
+#include "forest_kernel_common.hpp"
+#include "forest_rank_common.hpp"
+
+namespace forest_impl {
+namespace {
+
+constexpr int LWAVES = 8;
+constexpr int LBLOCK = TILE * LWAVES;
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
+typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
+#else
+typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
+typedef const TreeMeta *MetaPtr;
+#endif
+
+struct Entry8 {
+    uint32_t e[8];
+};
+
+// LDS between the rank tile and the partial sums: the pivots during the prologue, then one
+// chunk of outcome bytes (8 groups x 2 rows x 64 lanes) per wave.
+__host__ __device__ inline size_t ranklds_region2_bytes(int n_pivots)
+{
+    const size_t piv = sizeof(float) * static_cast<size_t>(n_pivots);
+    const size_t buf = static_cast<size_t>(8) * 8 * 2 * 64;
+    return ((piv > buf ? piv : buf) + 15) / 16 * 16;
+}
+
+__device__ __forceinline__ Entry8 load_group(ProgPtr p)
+{
+    Entry8 q;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q.e[j] = p[j];
+    return q;
+}
+
+#define FOREST_LDS_ADDR(n) "v_and_or_b32 %[a" #n "], %[e" #n "], %[mask], %[l4]\n\t"
+#define FOREST_LDS_READ(n) "ds_read_b32 %[a" #n "], %[a" #n "]\n\t"
+#define FOREST_LDS_CMP(n) "v_pk_add_f16 %[a" #n "], %[a" #n "], %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+
+// One group of 8 entries for the lane's two rows: returns 1024 + bits in each f16 half, i.e.
+// the low byte of each half holds the 8 outcome bits, first entry in bit 7.
+__device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, uint32_t l4)
+{
+    uint32_t acc, a0, a1, a2, a3, a4, a5, a6, a7;
+    asm volatile(
+        FOREST_LDS_ADDR(0) FOREST_LDS_ADDR(1) FOREST_LDS_ADDR(2) FOREST_LDS_ADDR(3)
+        FOREST_LDS_ADDR(4) FOREST_LDS_ADDR(5) FOREST_LDS_ADDR(6) FOREST_LDS_ADDR(7)
+        FOREST_LDS_READ(0) FOREST_LDS_READ(1) FOREST_LDS_READ(2) FOREST_LDS_READ(3)
+        FOREST_LDS_READ(4) FOREST_LDS_READ(5) FOREST_LDS_READ(6) FOREST_LDS_READ(7)
+        // LDS returns in order; a scalar load issued before this block may still be counted,
+        // so "at most 4 outstanding" guarantees at least the first three reads, "0" all.
+        "s_waitcnt lgkmcnt(4)\n\t"
+        FOREST_LDS_CMP(0) FOREST_LDS_CMP(1) FOREST_LDS_CMP(2)
+        "s_waitcnt lgkmcnt(0)\n\t"
+        FOREST_LDS_CMP(3) FOREST_LDS_CMP(4) FOREST_LDS_CMP(5) FOREST_LDS_CMP(6) FOREST_LDS_CMP(7)
+        "v_pk_fma_f16 %[a0], %[a0], %[c2], %[a1]\n\t"
+        "v_pk_fma_f16 %[a2], %[a2], %[c2], %[a3]\n\t"
+        "v_pk_fma_f16 %[a4], %[a4], %[c2], %[a5]\n\t"
+        "v_pk_fma_f16 %[a6], %[a6], %[c2], %[a7]\n\t"
+        "v_pk_fma_f16 %[a0], %[a0], %[c4], %[a2]\n\t"
+        "v_pk_fma_f16 %[a4], %[a4], %[c4], %[a6]\n\t"
+        "v_pk_fma_f16 %[a0], %[a0], %[c16], %[a4]\n\t"
+        "v_pk_add_f16 %[acc], %[a0], %[c1024]"
+        : [acc] "=v"(acc), [a0] "=&v"(a0), [a1] "=&v"(a1), [a2] "=&v"(a2), [a3] "=&v"(a3), [a4] "=&v"(a4),
+          [a5] "=&v"(a5), [a6] "=&v"(a6), [a7] "=&v"(a7)
+        : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
+          [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4),
+          [c2] "s"(0x40004000u), [c4] "s"(0x44004400u), [c16] "s"(0x4c004c00u), [c1024] "s"(0x64006400u)
+        : "memory");
+    return acc;
+}
+
+// Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
+// two columns) keep their partial sums in registers until every wave is done, so the partial
+// sums can reuse the LDS of the rank tile; GENERAL keeps them in an LDS region of its own.
+enum { MODE_SCALAR1 = 0, MODE_VECTOR2 = 1, MODE_GENERAL = 2, MODE_LEAVES = 3 };
+
+constexpr int CHUNK_GROUPS = 8;  // a level is walked in chunks of 8 groups = 64 nodes
+
+template <int MODE>
+__device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes, Accumulator<2> &accu,
+                                              double (&sum)[2][2], int wave, int lane, int64_t row0,
+                                              int64_t n_rows, int32_t *leaf_out)
+{
+    const int T = m.n_trees;
+    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / LWAVES);
+    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / LWAVES);
+    if (t_begin >= t_end) return;
+    MetaPtr meta = (MetaPtr)m.tree;
+    const uint32_t mask = 0xff00u;
+    const uint32_t l4 = static_cast<uint32_t>(lane) * 4u;
+
+    // The wave's trees are one contiguous stream of groups; the group after the last one read
+    // here is padding the host appended to the program.
+    int pos = meta[t_begin].prog_base;  // stream position of the current group
+    // one past the wave's last group (n_words = number of groups of a tree): the loop below ends
+    // with the last tree's closing flag, and in any case here
+    const int end_pos = meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8;
+    ProgPtr p = (ProgPtr)m.prog32 + pos;
+    Entry8 cur = load_group(p);
+    int t = t_begin;
+    int level_start = pos;  // stream position of the current level's first entry
+    int chunk = 0;          // chunk index inside the level
+    int gi = 0;             // group index inside the chunk
+    // ref: ordinal of the lane's node inside the current level, or ~leaf once a leaf is reached;
+    // step: where the lane goes next, filled in when the chunk that holds its node is complete
+    int ref[2], step[2];
+    ref[0] = ref[1] = meta[t].root_ref;
+    step[0] = step[1] = 0;
+    while (pos < end_pos) {
+        const uint32_t flags = cur.e[0];
+        p += 8;
+        const Entry8 nxt = load_group(p);  // in flight while this group is evaluated
+        const uint32_t g = eval_group(cur, mask, l4);
+        // outcome byte of row A (low half) and of row B (high half)
+        bytes[(gi * 2 + 0) * TILE + lane] = static_cast<uint8_t>(g);
+        bytes[(gi * 2 + 1) * TILE + lane] = static_cast<uint8_t>(g >> 16);
+        ++gi;
+        pos += 8;
+        if (gi == CHUNK_GROUPS || (flags & 1u)) {  // chunk complete: lanes whose node is in it pick a child
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
+                    const uint32_t b = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
+                    const ChildRef c = m.child[level_start + ref[r]];
+                    step[r] = ((b >> (ref[r] & 7)) & 1u) ? c.right : c.left;
+                }
+            }
+            ++chunk;
+            gi = 0;
+        }
+        if (flags & 1u) {  // level complete: every lane that was on a node has its next position
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                if (ref[r] >= 0) ref[r] = step[r];
+            level_start = pos;
+            chunk = 0;
+        }
+        if (flags & 2u) {  // tree complete: every lane stands on a leaf
+            const TreeMeta tm = meta[t];
+            if (MODE == MODE_GENERAL) accu.begin_tree(tm.column);
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int leaf = tm.leaf_base + (ref[r] < 0 ? ~ref[r] : 0);
+                if (MODE == MODE_LEAVES) {
+                    const int64_t row = row0 + r * TILE + lane;
+                    if (row < n_rows) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
+                } else if (MODE == MODE_SCALAR1) {
+                    sum[r][0] += static_cast<double>(m.leaf_value[leaf]);
+                } else if (MODE == MODE_VECTOR2) {
+                    const float *v = m.leaf_value + static_cast<size_t>(leaf) * m.n_outputs;
+                    sum[r][0] += static_cast<double>(v[0]);
+                    if (m.n_outputs > 1) sum[r][1] += static_cast<double>(v[1]);
+                } else {
+                    accu.add(m, r, leaf);
+                }
+            }
+            if (++t == t_end) break;
+            ref[0] = ref[1] = meta[t].root_ref;
+        }
+        cur = nxt;
+    }
+}
+
+__global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, const float *__restrict__ X,
+                                                                int64_t n_rows, float *scores,
+                                                                int32_t *labels, int32_t *leaf_out)
+{
+    extern __shared__ __align__(16) char smem[];
+    const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
+    const int K = m.n_outputs;
+    // LDS: [ rank tile | pivots, later one outcome-byte chunk per wave | partial sums (GENERAL) ].
+    // The rank tile must start at LDS address 0: eval_group forms addresses as
+    // (row offset | lane * 4).  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
+    // every wave has finished.
+    uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
+    char *region2 = smem + sizeof(uint32_t) * TILE * regs;
+    const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
+    const size_t r2_bytes = ranklds_region2_bytes(m.n_pivots);
+    double *acc = deferred ? reinterpret_cast<double *>(smem) : reinterpret_cast<double *>(region2 + r2_bytes);
+
+    const int lane = threadIdx.x & (TILE - 1);
+    const int wave = uniform(threadIdx.x >> 6);
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
+
+    float *piv = reinterpret_cast<float *>(region2);
+    for (int i = threadIdx.x; i < m.n_pivots; i += LBLOCK) piv[i] = m.pivots[i];
+    if (m.rank_regs == 0) rk[threadIdx.x & (TILE - 1)] = 0;  // the padding entries read row 0
+    __syncthreads();
+    rank_rows<LBLOCK>(rk, piv, m, X, row0, n_rows);
+    __syncthreads();  // ranks complete; the pivots are dead, their space becomes the byte chunks
+
+    uint8_t *bytes = reinterpret_cast<uint8_t *>(region2) + static_cast<size_t>(wave) * CHUNK_GROUPS * 2 * TILE;
+    Accumulator<2> accu;
+    double sum[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
+    if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
+        ranklds_trees<MODE_LEAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, leaf_out);
+        return;
+    }
+    if (deferred) {
+        if (m.leaf_width == 1) ranklds_trees<MODE_SCALAR1>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        else ranklds_trees<MODE_VECTOR2>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        __syncthreads();  // no wave reads the rank tile any more
+        for (int r = 0; r < 2; ++r)
+            for (int k = 0; k < K; ++k) acc[(wave * K + k) * RROWS + r * TILE + lane] = sum[r][k];
+    } else {
+        accu.init(acc, wave, lane, m);
+        ranklds_trees<MODE_GENERAL>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        accu.flush();
+    }
+    __syncthreads();
+    const int li = threadIdx.x;
+    if (li < RROWS) finish_row(m, acc, RROWS, li, row0 + li, row0 + li < n_rows, scores, labels, LWAVES);
+}
+
+}  // namespace
+
+size_t ranklds_lds_bytes(const DevModel &m)
+{
+    const size_t regs = m.rank_regs > 0 ? m.rank_regs : 1;
+    const int K = m.n_outputs;
+    const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
+    const size_t sums = sizeof(double) * LWAVES * K * RROWS;
+    const size_t front = sizeof(uint32_t) * TILE * regs + ranklds_region2_bytes(m.n_pivots);
+    return deferred ? (front > sums ? front : sums) : front + sums;
+}
+
+hipError_t init_ranklds_kernels(size_t lds_limit)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+}
+
+hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                          int32_t *leaf_out, size_t lds_limit, hipStream_t stream)
+{
+    const size_t lds = ranklds_lds_bytes(m);
+    if (lds > lds_limit || m.rank_regs > RANKLDS_MAX_REGS) return hipErrorInvalidValue;
+    const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
+    if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(forest_ranklds_kernel, dim3(static_cast<unsigned>(n_blocks)), dim3(LBLOCK), lds, stream, m,
+                       X, n_rows, scores, labels, leaf_out);
+    return hipGetLastError();
+}
+
+}  // namespace forest_impl

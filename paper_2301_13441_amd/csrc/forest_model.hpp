@@ -29,12 +29,16 @@ constexpr int FULL_MAX_DEPTH = 8;
 constexpr int PATH_LDS = 0;   // features read from the LDS tile for every comparison (any model)
 constexpr int PATH_REG = 1;   // full trees, float32 features in vector registers
 constexpr int PATH_RANK = 2;  // full trees, features rewritten as packed f16 threshold ranks
+constexpr int PATH_RANK_LDS = 3;  // any trees, packed f16 threshold ranks read from LDS
 
 // Rank family: one rank register covers RANK_SEG consecutive thresholds of a feature.
 constexpr int RANK_SEG = 4095;
 constexpr int RANK_BIAS = 2048;
 constexpr int RANK_MAX_REGS = 128;
 constexpr int RANK_MAX_PIVOTS = 4096;  // pivot thresholds staged in LDS by every workgroup
+constexpr int RANKLDS_MAX_PIVOTS = 2048;       // smaller pivot budget: two workgroups share a CU's LDS
+constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
+constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel
 
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {

@@ -46,6 +46,7 @@ struct TreeShape {
     std::vector<int32_t> internal;      // caller node index of I_0, I_1, ... (level order)
     std::vector<int32_t> leaves;        // caller node index of L_0, L_1, ... (in-order)
     std::vector<int32_t> ordinal;       // per caller node: internal ordinal or ~leaf ordinal
+    std::vector<int32_t> level_begin;   // internal[level_begin[l] .. level_begin[l+1]) sit at depth l
     int32_t depth = 0;                  // longest root-to-leaf path, counted in tests
     bool full = true;                   // every leaf at `depth`
 };
@@ -64,6 +65,7 @@ int analyse_tree(const forest_desc &d, int64_t base, int64_t n, TreeShape &s)
     int64_t reached = 0;
     while (!level.empty()) {
         next.clear();
+        s.level_begin.push_back(static_cast<int32_t>(s.internal.size()));
         for (int32_t v : level) {
             ++reached;
             const int32_t f = d.feature[base + v];
@@ -89,6 +91,10 @@ int analyse_tree(const forest_desc &d, int64_t base, int64_t n, TreeShape &s)
         if (depth > FOREST_MAX_DEPTH) return FOREST_ELIMIT;
     }
     if (reached != n) return FOREST_ETREE;  // unreachable nodes
+    while (s.level_begin.size() > 1 && s.level_begin.back() == static_cast<int32_t>(s.internal.size()))
+        s.level_begin.pop_back();  // levels that hold only leaves
+    if (s.internal.empty()) s.level_begin.clear();
+    s.level_begin.push_back(static_cast<int32_t>(s.internal.size()));
     s.depth = leaf_max;
     s.full = (leaf_min == leaf_max);
 
@@ -180,21 +186,46 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     m.kind = (all_full && common_depth >= 1 && common_depth <= FULL_MAX_DEPTH) ? common_depth
                                                                               : KIND_GENERIC;
 
-    // Choice of kernel family for full trees.
-    if (m.kind != KIND_GENERIC) {
-        // rank family: per-feature sorted distinct thresholds
-        std::vector<std::vector<float>> per_feature(static_cast<size_t>(d.n_features));
-        for (int32_t t = 0; t < T; ++t)
-            for (int32_t v : shape[t].internal)
-                per_feature[d.feature[d.tree_offset[t] + v]].push_back(d.threshold[d.tree_offset[t] + v]);
-        int64_t regs = 0;
-        size_t longest = 0;
+    // Choice of kernel family.  The rank families need the per-feature sorted distinct thresholds.
+    std::vector<std::vector<float>> per_feature(static_cast<size_t>(d.n_features));
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t v : shape[t].internal)
+            per_feature[d.feature[d.tree_offset[t] + v]].push_back(d.threshold[d.tree_offset[t] + v]);
+    int64_t regs = 0;
+    for (auto &v : per_feature) {
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());  // -0 == +0: one threshold
+        regs += static_cast<int64_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
+    }
+    auto build_rank_tables = [&](size_t max_pivots) {
+        m.rank_regs = static_cast<int32_t>(regs);
+        m.feat_thr_base.assign(1, 0);
+        int32_t next_reg = 0;
         for (auto &v : per_feature) {
-            std::sort(v.begin(), v.end());
-            v.erase(std::unique(v.begin(), v.end()), v.end());  // -0 == +0: one threshold
-            regs += static_cast<int64_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
-            longest = std::max(longest, v.size());
+            m.feat_vfirst.push_back(next_reg);
+            next_reg += static_cast<int32_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
+            m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
+            m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
         }
+        // Two-level search: the last threshold of every block of 2^pivot_shift is a pivot; the
+        // pivots of all features fit RANK_MAX_PIVOTS and are searched in LDS, the block itself
+        // in global memory.
+        for (;; ++m.pivot_shift) {
+            size_t total = 0;
+            for (auto &v : per_feature) total += (v.size() + (size_t{1} << m.pivot_shift) - 1) >> m.pivot_shift;
+            if (total <= max_pivots) break;
+        }
+        const size_t block = size_t{1} << m.pivot_shift;
+        m.feat_pivot_base.assign(1, 0);
+        size_t most_pivots = 0;
+        for (auto &v : per_feature) {
+            for (size_t b = 0; b < v.size(); b += block) m.pivots.push_back(v[std::min(b + block, v.size()) - 1]);
+            most_pivots = std::max(most_pivots, (v.size() + block - 1) / block);
+            m.feat_pivot_base.push_back(static_cast<int32_t>(m.pivots.size()));
+        }
+        while ((size_t{1} << m.rank_steps) < most_pivots + 1) ++m.rank_steps;
+    };
+    if (m.kind != KIND_GENERIC) {
         const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128,
                                          sizeof(uint32_t) * 64 * static_cast<size_t>(regs > 64 ? 128 : 64) +
                                              sizeof(float) * RANK_MAX_PIVOTS);
@@ -202,32 +233,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             m.path = PATH_RANK;
             m.x_in_registers = 1;
             m.reg_r = 2;
-            m.rank_regs = static_cast<int32_t>(regs);
-            m.feat_thr_base.assign(1, 0);
-            int32_t next_reg = 0;
-            for (auto &v : per_feature) {
-                m.feat_vfirst.push_back(next_reg);
-                next_reg += static_cast<int32_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
-                m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
-                m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
-            }
-            // Two-level search: the last threshold of every block of 2^pivot_shift is a pivot; the
-            // pivots of all features fit RANK_MAX_PIVOTS and are searched in LDS, the block itself
-            // in global memory.
-            for (;; ++m.pivot_shift) {
-                size_t total = 0;
-                for (auto &v : per_feature) total += (v.size() + (size_t{1} << m.pivot_shift) - 1) >> m.pivot_shift;
-                if (total <= RANK_MAX_PIVOTS) break;
-            }
-            const size_t block = size_t{1} << m.pivot_shift;
-            m.feat_pivot_base.assign(1, 0);
-            size_t most_pivots = 0;
-            for (auto &v : per_feature) {
-                for (size_t b = 0; b < v.size(); b += block) m.pivots.push_back(v[std::min(b + block, v.size()) - 1]);
-                most_pivots = std::max(most_pivots, (v.size() + block - 1) / block);
-                m.feat_pivot_base.push_back(static_cast<int32_t>(m.pivots.size()));
-            }
-            while ((size_t{1} << m.rank_steps) < most_pivots + 1) ++m.rank_steps;
+            build_rank_tables(RANK_MAX_PIVOTS);
         } else if (d.n_features <= 128) {
             // float32 features in vector registers
             m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
@@ -242,12 +248,26 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
         }
     }
+    if (m.path == PATH_LDS && T > 0) {
+        // Rank family with the ranks held in LDS: any tree shape.  Needs, per workgroup of 8
+        // waves: the rank tile, the pivots (later one chunk of outcome bytes per wave) and, unless
+        // the partial sums can wait in registers, the partial sums.
+        const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
+        const size_t front = sizeof(uint32_t) * 64 * static_cast<size_t>(std::max<int64_t>(regs, 1)) +
+                             std::max(sizeof(float) * RANKLDS_MAX_PIVOTS, size_t{8} * 8 * 2 * 64);
+        const size_t sums = sizeof(double) * 8 * K * 128;
+        const size_t lds = deferred ? std::max(front, sums) : front + sums;
+        if (regs <= RANKLDS_MAX_REGS && lds <= RANKLDS_MAX_LDS) {
+            m.path = PATH_RANK_LDS;
+            build_rank_tables(RANKLDS_MAX_PIVOTS);
+        }
+    }
     const int32_t feature_scale = m.path == PATH_REG ? 1 : 64;
     // split-program entry of internal node `v` of tree `t`
     auto entry_of = [&](int32_t t, int32_t v) -> SplitEntry {
         const int64_t n = d.tree_offset[t] + v;
         const int32_t f = d.feature[n];
-        if (m.path != PATH_RANK) return SplitEntry{f * feature_scale, d.threshold[n]};
+        if (m.path != PATH_RANK && m.path != PATH_RANK_LDS) return SplitEntry{f * feature_scale, d.threshold[n]};
         const float *lo = m.thr_sorted.data() + m.feat_thr_base[f];
         const float *hi = m.thr_sorted.data() + m.feat_thr_base[f + 1];
         const int32_t j = static_cast<int32_t>(std::lower_bound(lo, hi, d.threshold[n]) - lo);
@@ -294,7 +314,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
 
     const float inf = std::numeric_limits<float>::infinity();
     SplitEntry pad{0, inf};
-    if (m.path == PATH_RANK) {
+    if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
         // register 0 against j' = 2047: rv - 2047 <= 0 for every rank, the outcome bit is 0
         const uint32_t h = f16_bits_of_small_int(-2047);
         const uint32_t pair = h | (h << 16);
@@ -313,6 +333,47 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         tm.caller_tree = t;
         tm.n_internal = n_int;
 
+        if (m.path == PATH_RANK_LDS) {
+            // Stream of 8-entry groups, level by level (each level padded to whole groups).  The
+            // first entry of a group carries two flags in its low byte: bit 0 = last group of
+            // its level, bit 1 = last group of the tree.  The child-reference table is indexed
+            // like the stream; a reference >= 0 is the node's ordinal inside the next level.
+            const size_t n_levels = s.level_begin.size() - 1;
+            if (n_levels == 0) {  // the root is a leaf: one group of padding closes the tree
+                for (int j = 0; j < 8; ++j) {
+                    m.prog.push_back(pad);
+                    m.child.push_back(ChildRef{~0, ~0});
+                }
+                m.prog[m.prog.size() - 8].feature_slot |= 3 << 16;
+            }
+            for (size_t l = 0; l < n_levels; ++l) {
+                const int32_t lb = s.level_begin[l], le = s.level_begin[l + 1];
+                const int32_t next_begin = le;  // ordinals of the next level start here
+                // entries: groups of 8 in descending ordinal (the first entry of a group becomes
+                // bit 7 of the outcome byte); child references: ascending ordinal
+                for (int32_t g0 = lb; g0 < le; g0 += 8)
+                    for (int32_t k = 7; k >= 0; --k)
+                        m.prog.push_back(g0 + k < le ? entry_of(t, s.internal[g0 + k]) : pad);
+                for (int32_t i = lb; i < le; ++i) {
+                    const int32_t v = s.internal[i];
+                    auto ref_of = [&](int32_t c) {
+                        const int32_t o = s.ordinal[c];
+                        return o >= 0 ? o - next_begin : o;
+                    };
+                    m.child.push_back(ChildRef{ref_of(d.left[base + v]), ref_of(d.right[base + v])});
+                }
+                while (m.child.size() < m.prog.size()) m.child.push_back(ChildRef{~0, ~0});
+                const size_t last_group = m.prog.size() - 8;
+                m.prog[last_group].feature_slot |= (l + 1 == n_levels ? 3 : 1) << 16;
+            }
+            tm.n_words = static_cast<int32_t>((m.prog.size() - tm.prog_base) / 8);
+            for (int32_t v : s.leaves) {
+                m.leaf_node.push_back(v);
+                for (int32_t k = 0; k < W; ++k) m.leaf_value.push_back(d.leaf_value[(base + v) * W + k]);
+            }
+            m.tree.push_back(tm);
+            continue;
+        }
         // positions: heap index for the full-tree kernels, level-order ordinal otherwise
         const int32_t shift = (m.kind != KIND_GENERIC) ? 1 : 0;
         const int32_t n_pos = n_int + shift;
@@ -341,13 +402,17 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     }
     // One batch of padding: the register kernels prefetch the batch after the one they evaluate.
     for (int j = 0; j < 32; ++j) m.prog.push_back(pad);
-    if (m.path == PATH_RANK) {
-        // compact form: one dword per entry, f16(-j') in the high half, rank register in the low byte
+    if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
+        // compact form: one dword per entry, f16(-j') in the high half.  RANK: rank register in
+        // the low byte.  RANK_LDS: rank register in bits 8..15 (its LDS row offset is reg * 256),
+        // group flags in the low byte.
         m.prog32.reserve(m.prog.size());
         for (const SplitEntry &e : m.prog) {
             uint32_t pair;
             std::memcpy(&pair, &e.threshold, sizeof(pair));
-            m.prog32.push_back((pair & 0xffff0000u) | static_cast<uint32_t>(e.feature_slot));
+            const uint32_t reg = static_cast<uint32_t>(e.feature_slot) & 0xffffu;
+            const uint32_t flags = static_cast<uint32_t>(e.feature_slot) >> 16;
+            m.prog32.push_back((pair & 0xffff0000u) | (m.path == PATH_RANK ? reg : (reg << 8) | flags));
         }
         m.prog.clear();
         m.prog.shrink_to_fit();

@@ -45,7 +45,7 @@ def _check(forest, X, leaves=True):
     ("c2", 1000, 40, 8),          # depth 8: 8 outcome words per (row, tree)
     ("c3", 777, 100, 6),          # ragged tail: 777 = 12 tiles + 9 rows
     ("c4", 600, 200, 6),          # 10 classes, softmax + argmax, 30 % zeros in X
-    ("c5", 300, 8, 0),            # deep irregular trees, vector leaves
+    ("c5", 300, 9, 0),            # deep irregular trees, vector leaves (9 trees over 8 waves)
 ])
 def test_configs_small(name, rows, trees, kind):
     w = wl.make_workload(name, n_rows=rows, n_trees=trees)
@@ -71,7 +71,8 @@ def test_irregular_forests_with_ties(seed):
                          transform=wl.TRANSFORM_SOFTMAX, aggregate=wl.AGG_MEAN)
     rng = np.random.default_rng(seed)
     X = (rng.integers(-3, 4, size=(200, 5)).astype(np.float32) * np.float32(0.5))
-    assert _check(f, X)["kernel_kind"] == 0
+    info = _check(f, X)
+    assert info["kernel_kind"] == 0 and info["kernel_path"] == 3
 
 
 def test_special_values_nan_inf_signed_zero():
@@ -139,8 +140,10 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
     ("rank_three_segments", 2),   # > 2 * 4095 distinct thresholds on one feature
     ("rank_wide", 2),             # 128 features -> 128 rank registers (the 3-waves variant)
     ("reg_fallback", 1),          # too many rank registers -> float32 feature registers
-    ("lds_full", 0),              # full trees over > 128 features
-    ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the register kernels
+    ("ranklds_full_wide", 3),     # full trees over > 128 features: ranks in LDS
+    ("ranklds_irregular", 3),     # irregular trees, 3 output columns
+    ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the rank kernels
+    ("lds_generic_many_outputs", 0),
 ])
 def test_kernel_families(what, path):
     rng = np.random.default_rng(42)
@@ -150,10 +153,16 @@ def test_kernel_families(what, path):
         f = _full_forest(2, 30, 7, 128, n_outputs=3, transform=wl.TRANSFORM_SOFTMAX)
     elif what == "reg_fallback":
         f = _full_forest(3, 40, 8, 128, feature_bias=0.9)
-    elif what == "lds_full":
+    elif what == "ranklds_full_wide":
         f = _full_forest(4, 12, 5, 200)
-    else:
+    elif what == "ranklds_irregular":
+        f = wl.random_forest(6, n_trees=37, n_features=11, max_depth=10, stop_prob=0.12, n_outputs=3,
+                             transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "lds_many_outputs":
         f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
+    else:
+        f = wl.random_forest(7, n_trees=21, n_features=7, max_depth=8, stop_prob=0.2, n_outputs=20,
+                             transform=wl.TRANSFORM_SOFTMAX)
     X = rng.standard_normal((517, f.n_features)).astype(np.float32)
     # rows that sit exactly on thresholds of their feature
     thr = f.threshold[f.feature == 0]

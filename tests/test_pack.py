@@ -129,8 +129,15 @@ def test_kernel_family_choice():
     assert v["kernel_path"] == 2 and v["rank_registers"] == 128
     v = pk.forest_pack(_full_forest(3, 40, 8, 128, feature_bias=0.9))
     assert v["kernel_path"] == 1                                     # 130 rank registers would be needed
-    assert pk.forest_pack(_full_forest(4, 12, 5, 200))["kernel_path"] == 0
+    assert pk.forest_pack(_full_forest(4, 12, 5, 200))["kernel_path"] == 3      # too wide for registers
     assert pk.forest_pack(_full_forest(5, 60, 4, 9, n_outputs=20))["kernel_path"] == 0
+    irregular = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7)
+    assert pk.forest_pack(irregular)["kernel_path"] == 3
+    many = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7, n_outputs=20)
+    assert pk.forest_pack(many)["kernel_path"] == 0
+    w = wl.make_workload("c5", n_rows=1, n_trees=4)
+    v = pk.forest_pack(w.forest)
+    assert v["kernel_path"] == 3 and v["rank_registers"] == 256
     w = wl.make_workload("c2", n_rows=1)
     v = pk.forest_pack(w.forest)
     assert v["kernel_path"] == 2 and v["rank_registers"] == 56       # ~4550 thresholds per feature
