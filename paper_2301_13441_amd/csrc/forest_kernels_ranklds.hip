@@ -121,21 +121,28 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     // The wave's trees are one contiguous stream of groups; the group after the last one read
     // here is padding the host appended to the program.
     int pos = meta[t_begin].prog_base;  // stream position of the current group
-    // one past the wave's last group (n_words = number of groups of a tree): the loop below ends
-    // with the last tree's closing flag, and in any case here
-    const int end_pos = meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8;
+    // number of groups of the wave's trees (n_words = number of groups of a tree); the last one
+    // carries the closing flag of the last tree
+    const int n_groups = (meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8 - pos) / 8;
     ProgPtr p = (ProgPtr)m.prog32 + pos;
     Entry8 cur = load_group(p);
     int t = t_begin;
     int level_start = pos;  // stream position of the current level's first entry
     int chunk = 0;          // chunk index inside the level
     int gi = 0;             // group index inside the chunk
-    // ref: ordinal of the lane's node inside the current level, or ~leaf once a leaf is reached;
-    // step: where the lane goes next, filled in when the chunk that holds its node is complete
-    int ref[2], step[2];
+    // ref: ordinal of the lane's node inside the current level; ~leaf once a leaf is reached;
+    // WAITING once the lane has picked its child in this level.  The child references are
+    // fetched when the chunk that holds the node is complete and consumed one group into the
+    // next level (or at the end of the tree), so the gather's latency is covered.
+    constexpr int WAITING = static_cast<int>(0x80000000u);
+    int ref[2];
+    ChildRef pair[2];
+    uint32_t went_right[2];
+    bool resolve = false;  // wave-uniform: a level has ended since the last resolution
     ref[0] = ref[1] = meta[t].root_ref;
-    step[0] = step[1] = 0;
-    while (pos < end_pos) {
+    pair[0] = pair[1] = ChildRef{0, 0};
+    went_right[0] = went_right[1] = 0;
+    for (int group = 0; group < n_groups; ++group) {
         const uint32_t flags = cur.e[0];
         p += 8;
         const Entry8 nxt = load_group(p);  // in flight while this group is evaluated
@@ -146,25 +153,34 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         ++gi;
         pos += 8;
         if (gi == CHUNK_GROUPS || (flags & 1u)) {  // chunk complete: lanes whose node is in it pick a child
+            if (resolve) {
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    if (ref[r] == WAITING) ref[r] = went_right[r] ? pair[r].right : pair[r].left;
+                resolve = false;
+            }
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
                     const uint32_t b = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
-                    const ChildRef c = m.child[level_start + ref[r]];
-                    step[r] = ((b >> (ref[r] & 7)) & 1u) ? c.right : c.left;
+                    pair[r] = m.child[level_start + ref[r]];
+                    went_right[r] = (b >> (ref[r] & 7)) & 1u;
+                    ref[r] = WAITING;
                 }
             }
             ++chunk;
             gi = 0;
         }
-        if (flags & 1u) {  // level complete: every lane that was on a node has its next position
-#pragma unroll
-            for (int r = 0; r < 2; ++r)
-                if (ref[r] >= 0) ref[r] = step[r];
+        if (flags & 1u) {  // level complete: every lane that was on a node has picked its child
+            resolve = true;
             level_start = pos;
             chunk = 0;
         }
         if (flags & 2u) {  // tree complete: every lane stands on a leaf
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                if (ref[r] == WAITING) ref[r] = went_right[r] ? pair[r].right : pair[r].left;
+            resolve = false;
             const TreeMeta tm = meta[t];
             if (MODE == MODE_GENERAL) accu.begin_tree(tm.column);
 #pragma unroll
@@ -183,7 +199,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
                     accu.add(m, r, leaf);
                 }
             }
-            if (++t == t_end) break;
+            ++t;  // the metadata table has one spare record after the last tree
             ref[0] = ref[1] = meta[t].root_ref;
         }
         cur = nxt;

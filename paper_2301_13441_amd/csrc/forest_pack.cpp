@@ -400,6 +400,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
         m.tree.push_back(tm);
     }
+    m.tree.push_back(TreeMeta{});  // spare record: the stream kernels read the root of "the next tree"
     // One batch of padding: the register kernels prefetch the batch after the one they evaluate.
     for (int j = 0; j < 32; ++j) m.prog.push_back(pad);
     if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
