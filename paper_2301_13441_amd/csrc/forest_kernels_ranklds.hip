@@ -33,11 +33,9 @@ constexpr int LWAVES = 8;
 constexpr int LBLOCK = TILE * LWAVES;
 
 #if defined(__HIP_DEVICE_COMPILE__)
-typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
 typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
 #else
-typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
-typedef const TreeMeta *MetaPtr;
+typedef const TreeMeta *MetaPtr;  // host pass: the kernel body is only parsed
 #endif
 
 struct Entry8 {
@@ -53,11 +51,14 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int n_pivots)
     return ((piv > buf ? piv : buf) + 15) / 16 * 16;
 }
 
-__device__ __forceinline__ Entry8 load_group(ProgPtr p)
+// Every lane loads the same eight words (one 32-byte piece of the stream).
+__device__ __forceinline__ Entry8 load_group(const uint32_t *__restrict__ p)
 {
+    const uint4 lo = *reinterpret_cast<const uint4 *>(p);
+    const uint4 hi = *reinterpret_cast<const uint4 *>(p + 4);
     Entry8 q;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) q.e[j] = p[j];
+    q.e[0] = lo.x; q.e[1] = lo.y; q.e[2] = lo.z; q.e[3] = lo.w;
+    q.e[4] = hi.x; q.e[5] = hi.y; q.e[6] = hi.z; q.e[7] = hi.w;
     return q;
 }
 
@@ -67,6 +68,10 @@ __device__ __forceinline__ Entry8 load_group(ProgPtr p)
 
 // One group of 8 entries for the lane's two rows: returns 1024 + bits in each f16 half, i.e.
 // the low byte of each half holds the 8 outcome bits, first entry in bit 7.
+//
+// The entries arrive through the vector memory path (every lane loads the same words), not
+// through scalar loads: vector loads are counted in vmcnt, so waiting for the LDS reads
+// (lgkmcnt) never waits for the program stream, which is fetched two groups ahead.
 __device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, uint32_t l4)
 {
     uint32_t acc, a0, a1, a2, a3, a4, a5, a6, a7;
@@ -75,8 +80,8 @@ __device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, u
         FOREST_LDS_ADDR(4) FOREST_LDS_ADDR(5) FOREST_LDS_ADDR(6) FOREST_LDS_ADDR(7)
         FOREST_LDS_READ(0) FOREST_LDS_READ(1) FOREST_LDS_READ(2) FOREST_LDS_READ(3)
         FOREST_LDS_READ(4) FOREST_LDS_READ(5) FOREST_LDS_READ(6) FOREST_LDS_READ(7)
-        // LDS returns in order; a scalar load issued before this block may still be counted,
-        // so "at most 4 outstanding" guarantees at least the first three reads, "0" all.
+        // LDS operations complete in order; a scalar load of tree metadata may still be counted,
+        // so "at most 4 outstanding" guarantees at least the first three reads
         "s_waitcnt lgkmcnt(4)\n\t"
         FOREST_LDS_CMP(0) FOREST_LDS_CMP(1) FOREST_LDS_CMP(2)
         "s_waitcnt lgkmcnt(0)\n\t"
@@ -91,8 +96,8 @@ __device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, u
         "v_pk_add_f16 %[acc], %[a0], %[c1024]"
         : [acc] "=v"(acc), [a0] "=&v"(a0), [a1] "=&v"(a1), [a2] "=&v"(a2), [a3] "=&v"(a3), [a4] "=&v"(a4),
           [a5] "=&v"(a5), [a6] "=&v"(a6), [a7] "=&v"(a7)
-        : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
-          [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4),
+        : [e0] "v"(q.e[0]), [e1] "v"(q.e[1]), [e2] "v"(q.e[2]), [e3] "v"(q.e[3]), [e4] "v"(q.e[4]),
+          [e5] "v"(q.e[5]), [e6] "v"(q.e[6]), [e7] "v"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4),
           [c2] "s"(0x40004000u), [c4] "s"(0x44004400u), [c16] "s"(0x4c004c00u), [c1024] "s"(0x64006400u)
         : "memory");
     return acc;
@@ -124,8 +129,13 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     // number of groups of the wave's trees (n_words = number of groups of a tree); the last one
     // carries the closing flag of the last tree
     const int n_groups = (meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8 - pos) / 8;
-    ProgPtr p = (ProgPtr)m.prog32 + pos;
-    Entry8 cur = load_group(p);
+    // Three buffers in rotation, two groups in flight: group g uses buffer g mod 3 and, before it
+    // is evaluated, the fetch of group g + 2 into the buffer group g - 1 has just released is
+    // issued.  The loop is unrolled by three so that no buffer is ever copied.
+    const uint32_t *__restrict__ p = m.prog32 + pos;
+    Entry8 buf0 = load_group(p);
+    Entry8 buf1 = load_group(p + 8);
+    Entry8 buf2;
     int t = t_begin;
     int level_start = pos;  // stream position of the current level's first entry
     int chunk = 0;          // chunk index inside the level
@@ -142,10 +152,8 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     ref[0] = ref[1] = meta[t].root_ref;
     pair[0] = pair[1] = ChildRef{0, 0};
     went_right[0] = went_right[1] = 0;
-    for (int group = 0; group < n_groups; ++group) {
-        const uint32_t flags = cur.e[0];
-        p += 8;
-        const Entry8 nxt = load_group(p);  // in flight while this group is evaluated
+    auto one_group = [&](const Entry8 &cur) {
+        const uint32_t flags = static_cast<uint32_t>(uniform(static_cast<int>(cur.e[0])));
         const uint32_t g = eval_group(cur, mask, l4);
         // outcome byte of row A (low half) and of row B (high half)
         bytes[(gi * 2 + 0) * TILE + lane] = static_cast<uint8_t>(g);
@@ -202,7 +210,18 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             ++t;  // the metadata table has one spare record after the last tree
             ref[0] = ref[1] = meta[t].root_ref;
         }
-        cur = nxt;
+    };
+    // The fetches are unconditional (past the end of the wave's stream they read the next
+    // wave's groups or the padding at the end of the program), so that exactly two fetches are
+    // issued between a buffer's fill and its use on every path.
+    for (int group = 0; group < n_groups; group += 3) {
+        buf2 = load_group(p + 16);
+        one_group(buf0);
+        buf0 = load_group(p + 24);
+        if (group + 1 < n_groups) one_group(buf1);
+        buf1 = load_group(p + 32);
+        if (group + 2 < n_groups) one_group(buf2);
+        p += 24;
     }
 }
 

@@ -401,8 +401,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         m.tree.push_back(tm);
     }
     m.tree.push_back(TreeMeta{});  // spare record: the stream kernels read the root of "the next tree"
-    // One batch of padding: the register kernels prefetch the batch after the one they evaluate.
-    for (int j = 0; j < 32; ++j) m.prog.push_back(pad);
+    // Padding: the kernels prefetch up to five groups past the entries they evaluate.
+    for (int j = 0; j < 64; ++j) m.prog.push_back(pad);
     if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
         // compact form: one dword per entry, f16(-j') in the high half.  RANK: rank register in
         // the low byte.  RANK_LDS: rank register in bits 8..15 (its LDS row offset is reg * 256),
