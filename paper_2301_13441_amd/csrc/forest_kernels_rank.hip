@@ -214,7 +214,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
     for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
     __syncthreads();
-    rank_rows<BLOCK>(rk, piv, m, X, row0, n_rows);
+    rank_rows<WAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
     __syncthreads();
     v32u x[NVR];
 #pragma unroll

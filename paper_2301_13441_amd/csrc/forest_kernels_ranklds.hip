@@ -250,7 +250,7 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     for (int i = threadIdx.x; i < m.n_pivots; i += LBLOCK) piv[i] = m.pivots[i];
     if (m.rank_regs == 0) rk[threadIdx.x & (TILE - 1)] = 0;  // the padding entries read row 0
     __syncthreads();
-    rank_rows<LBLOCK>(rk, piv, m, X, row0, n_rows);
+    rank_rows<LWAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
     __syncthreads();  // ranks complete; the pivots are dead, their space becomes the byte chunks
 
     uint8_t *bytes = reinterpret_cast<uint8_t *>(region2) + static_cast<size_t>(wave) * CHUNK_GROUPS * 2 * TILE;

@@ -23,76 +23,105 @@ __device__ __forceinline__ uint16_t f16_bits(int v)
     return __builtin_bit_cast(uint16_t, h);
 }
 
-// Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as f16 halves
-// into rk[reg * 64 + (r & 63)] (low half: rows 0..63 of the tile, high half: rows 64..127).
-// Two-level search: first over the feature's pivots (LDS: the last threshold of every block
-// of 2^pivot_shift), then inside one block of the sorted table (global memory).
-template <int THREADS>
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) int32_t *RankTablePtr;
+#else
+typedef const int32_t *RankTablePtr;  // host pass: the kernel body is only parsed
+#endif
+
+// Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
+// pairs into rk[reg * 64 + lane] (low half: row `lane` of the tile, high half: row lane + 64).
+// The features are dealt to the waves; inside a wave every lane searches the same feature for
+// its own two rows, two features at a time, so the per-feature tables are read with scalar
+// loads and the 64 lanes' probes fall into one table.  Two-level search: first over the
+// feature's pivots (LDS: the last threshold of every block of 2^pivot_shift), then inside one
+// block of the sorted table (global memory).
+template <int NWAVES>
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const DevModel &m,
-                                          const float *__restrict__ X, int64_t row0, int64_t n_rows)
+                                          const float *__restrict__ X, int64_t row0, int64_t n_rows, int wave,
+                                          int lane)
 {
-    constexpr int U = 8;  // searches in flight per thread
+    constexpr int U = 2;  // features searched together (2 rows each: 4 searches in flight per lane)
     const int F = m.n_features;
-    const int64_t left = n_rows - row0;
-    const int n_valid = (left < RROWS ? static_cast<int>(left) : RROWS) * F;
-    const float *src = X + row0 * F;
-    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
     const int block = 1 << m.pivot_shift;
-    for (int e0 = threadIdx.x; e0 < RROWS * F; e0 += THREADS * U) {
-        float x[U];
-        int lo[U], hi[U], base[U], n_thr[U], f[U], r[U];
+    RankTablePtr thr_base = (RankTablePtr)m.feat_thr_base;
+    RankTablePtr piv_base = (RankTablePtr)m.feat_pivot_base;
+    RankTablePtr vfirst = (RankTablePtr)m.feat_vfirst;
+    const float *xrow[2];
+    bool have[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int64_t row = row0 + r * TILE + lane;
+        have[r] = row < n_rows;
+        xrow[r] = X + (have[r] ? row : row0) * F;
+    }
+    for (int f0 = wave * U; f0 < F; f0 += NWAVES * U) {
+        float x[U][2];
+        int lo[U][2], hi[U][2], tb[U], n_thr[U], pb[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * THREADS;
-            const bool in = e < RROWS * F;
-            r[u] = in ? e / F : 0;
-            f[u] = in ? e - r[u] * F : 0;
-            x[u] = (e < n_valid) ? src[e] : 0.0f;
-            base[u] = m.feat_pivot_base[f[u]];
-            lo[u] = 0;
-            hi[u] = in ? m.feat_pivot_base[f[u] + 1] - base[u] : 0;
+            const int f = f0 + u < F ? f0 + u : F - 1;  // wave-uniform; the duplicate is not stored
+            tb[u] = thr_base[f];
+            n_thr[u] = thr_base[f + 1] - tb[u];
+            pb[u] = piv_base[f];
+            const int n_piv = piv_base[f + 1] - pb[u];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                x[u][r] = have[r] ? xrow[r][f] : 0.0f;
+                lo[u][r] = 0;
+                hi[u][r] = n_piv;
+            }
         }
         // first block whose last threshold is not below x
         for (int s = 0; s < m.rank_steps; ++s) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (lo[u] < hi[u]) {
-                    const int mid = (lo[u] + hi[u]) >> 1;
-                    if (piv[base[u] + mid] < x[u]) lo[u] = mid + 1;
-                    else hi[u] = mid;
-                }
-            }
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    if (lo[u][r] < hi[u][r]) {
+                        const int mid = (lo[u][r] + hi[u][r]) >> 1;
+                        if (piv[pb[u] + mid] < x[u][r]) lo[u][r] = mid + 1;
+                        else hi[u][r] = mid;
+                    }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            base[u] = m.feat_thr_base[f[u]];
-            n_thr[u] = (e0 + u * THREADS < RROWS * F) ? m.feat_thr_base[f[u] + 1] - base[u] : 0;
-            lo[u] = lo[u] << m.pivot_shift;
-            hi[u] = lo[u] + block < n_thr[u] ? lo[u] + block : n_thr[u];
-            if (lo[u] > hi[u]) lo[u] = hi[u];  // x is above every pivot: rank = number of thresholds
-        }
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                lo[u][r] = lo[u][r] << m.pivot_shift;
+                hi[u][r] = lo[u][r] + block < n_thr[u] ? lo[u][r] + block : n_thr[u];
+                if (lo[u][r] > hi[u][r]) lo[u][r] = hi[u][r];  // x is above every pivot: rank = n_thr
+            }
         // position inside the block
         for (int s = 0; s <= m.pivot_shift; ++s) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (lo[u] < hi[u]) {
-                    const int mid = (lo[u] + hi[u]) >> 1;
-                    if (m.thr_sorted[base[u] + mid] < x[u]) lo[u] = mid + 1;
-                    else hi[u] = mid;
-                }
-            }
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    if (lo[u][r] < hi[u][r]) {
+                        const int mid = (lo[u][r] + hi[u][r]) >> 1;
+                        if (m.thr_sorted[tb[u] + mid] < x[u][r]) lo[u][r] = mid + 1;
+                        else hi[u][r] = mid;
+                    }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * THREADS;
-            if (e >= RROWS * F) continue;
-            const int rank = (x[u] != x[u]) ? n_thr[u] : lo[u];  // NaN is right of every threshold
-            const int reg0 = m.feat_vfirst[f[u]];
+            if (f0 + u >= F) continue;
+            int rank[2];
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+                rank[r] = (x[u][r] != x[u][r]) ? n_thr[u] : lo[u][r];  // NaN is right of every threshold
+            const int reg0 = vfirst[f0 + u];
             for (int s = 0, first = 0; first < n_thr[u]; ++s, first += RANK_SEG) {
                 const int len = n_thr[u] - first < RANK_SEG ? n_thr[u] - first : RANK_SEG;
-                int rv = rank - first;
-                rv = rv < 0 ? 0 : (rv > len ? len : rv);
-                rk16[((reg0 + s) * TILE + (r[u] & 63)) * 2 + (r[u] >> 6)] = f16_bits(rv - RANK_BIAS);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    int rv = rank[r] - first;
+                    rv = rv < 0 ? 0 : (rv > len ? len : rv);
+                    packed |= static_cast<uint32_t>(f16_bits(rv - RANK_BIAS)) << (16 * r);
+                }
+                rk[(reg0 + s) * TILE + lane] = packed;
             }
         }
     }
