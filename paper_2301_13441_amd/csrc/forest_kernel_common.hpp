@@ -131,9 +131,9 @@ struct Accumulator {
 
 // The heap walk of a full tree of depth D over outcome words laid out by heap position:
 // level l occupies positions [2^l, 2^(l+1)), i.e. word 0 up to level 4, then word 1,
-// words 2-3, words 4-7.  Returns the in-order leaf ordinal.
+// words 2-3, words 4-7.  Returns the heap position reached, 2^D + in-order leaf ordinal.
 template <int D, int NW>
-__device__ __forceinline__ uint32_t heap_walk(const uint32_t (&word)[NW])
+__device__ __forceinline__ uint32_t heap_walk_pos(const uint32_t (&word)[NW])
 {
     uint32_t h = 1;
 #pragma unroll
@@ -149,7 +149,14 @@ __device__ __forceinline__ uint32_t heap_walk(const uint32_t (&word)[NW])
         }
         h = h + h + __builtin_amdgcn_ubfe(wsel, h, 1u);  // bit (h mod 32) of the word
     }
-    return h - (1u << D);
+    return h;
+}
+
+// The same walk, returning the in-order leaf ordinal.
+template <int D, int NW>
+__device__ __forceinline__ uint32_t heap_walk(const uint32_t (&word)[NW])
+{
+    return heap_walk_pos<D, NW>(word) - (1u << D);
 }
 
 using KernelFn = void (*)(DevModel, const float *, int64_t, float *, int32_t *, int32_t *);

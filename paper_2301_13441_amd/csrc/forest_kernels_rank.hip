@@ -175,14 +175,20 @@ __device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NV
             for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
             pending_col = column;
         }
+        // wave-uniform base of the tree's leaf values, shifted so that the heap position the
+        // walk ends on indexes it directly: one vector instruction per gather address
+        const float *lv = m.leaf_value + ((t << D) - (1 << D));
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int leaf = (t << D) + static_cast<int>(heap_walk<D, NW>(word[r]));
+            const uint32_t pos = heap_walk_pos<D, NW>(word[r]);
+            if (MODE == MODE_SCALAR) {
+                pending[r] = lv[pos];
+                continue;
+            }
+            const int leaf = (t << D) + static_cast<int>(pos - (1u << D));
             if (MODE == MODE_LEAVES) {
                 const int64_t row = row0 + r * TILE + lane;
                 if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
-            } else if (MODE == MODE_SCALAR) {
-                pending[r] = m.leaf_value[leaf];
             } else {
                 accu.add(m, r, leaf);
             }
