@@ -96,6 +96,70 @@ struct RankStep<4> {
     }
 };
 
+// The eight comparisons alone; the outcomes (1.0 or 0.0 in each half) go to the matrix core.
+#define FOREST_RANK_CMP_ONLY(B)                                                                   \
+    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
+        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
+            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
+                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
+                    "s_set_gpr_idx_off"
+
+__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[2])
+{
+    asm volatile(FOREST_RANK_CMP_ONLY("v64")
+                 : [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]),
+                   [d5] "=&v"(d[5]), [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
+                 : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
+                   [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+}
+
+// Bit collection on the matrix core.  The eight outcome registers of a group are, read as
+// bytes, (0, a, 0, b) with a, b = 0x3c or 0 for the lane's two rows; 0x3c is 1.0 in bf8
+// (e5m2).  v_mfma_f32_16x16x128_f8f6f4 takes them as its B operand: a lane of 16-lane block q
+// supplies B[k][n] for n = lane % 16 and the 32 values of k that belong to block q, and
+// receives D[4q + i][n], i = 0..3.  With an A that is zero outside A[4q + i][k of block q],
+// D[4q + i][n] only sums the lane's own bytes: i = 0 weighs the row-a bytes by 2^(7 - v)
+// (register v of the group: first entry in bit 7), i = 1 the row-b bytes; a second matrix
+// weighs by 2^(15 - v).  Two chained MFMAs on top of a 2^23 addend therefore leave the 16
+// outcome bits of two groups in the low mantissa bits of D[..][0] and D[..][1]: exact, every
+// product and partial sum being an integer below 2^24.  The matrix core runs beside the
+// vector ALU, so the vector cost of a group drops from 16 instructions to 8 plus the MFMA issue.
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct BitCollector {
+    v8i a[2];  // weights 2^(7 - v) and 2^(15 - v)
+    v4f bias;
+
+    __device__ __forceinline__ void init(int lane)
+    {
+        const int m = lane & 15, q = lane >> 4;
+        const bool mine = (m >> 2) == q && (m & 3) < 2;
+        const int shift = (m & 3) == 0 ? 8 : 24;  // byte 1 = row a, byte 3 = row b
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const uint32_t bf8 = static_cast<uint32_t>(15 + 8 * j + 7 - v) << 2;  // 2^(8j + 7 - v)
+                a[j][v] = mine ? static_cast<int>(bf8 << shift) : 0;
+            }
+        bias = v4f{8388608.0f, 8388608.0f, 8388608.0f, 8388608.0f};
+        // keep the addend in registers instead of rebuilding it before every chain
+        asm volatile("" : "+v"(bias));
+    }
+    template <int J>
+    __device__ __forceinline__ v4f collect(const uint32_t (&d)[8], v4f c) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const v8i b = {static_cast<int>(d[0]), static_cast<int>(d[1]), static_cast<int>(d[2]), static_cast<int>(d[3]),
+                       static_cast<int>(d[4]), static_cast<int>(d[5]), static_cast<int>(d[6]), static_cast<int>(d[7])};
+        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[J], b, c, 1, 1, 0, 0, 0, 0);  // A, B: bf8, unscaled
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+        return c;
+    }
+};
+
 template <int N>
 struct Batch {
     Entry8 q[N / 8];
@@ -201,6 +265,127 @@ __device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NV
     }
 }
 
+// The same, with the outcome bits collected by the matrix core (64 rank registers only: the
+// wide kernel has no registers to spare for the weights).  A word's MFMAs are still running
+// when its last comparison has issued, so the word is read, and walked, one group later:
+// after the first comparisons of the next word, or of the next tree's first word, whose leaf
+// gather in turn is consumed one tree after that.
+template <int D, int MODE>
+__device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&x)[2], Accumulator<2> &accu, int wave,
+                                                int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
+{
+    constexpr int R = 2;
+    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);
+    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;
+    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;
+    constexpr int NB = GW * 8;
+    const int T = m.n_trees;
+    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
+    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    if (t_begin >= t_end) return;
+
+    BitCollector bits;
+    bits.init(lane);
+    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
+    MetaPtr meta = (MetaPtr)m.tree;
+    Batch<NB> cur = load_batch<NB>(p);
+    v4f lo = bits.bias, hi = bits.bias;
+    uint32_t pos[R], sel[R];
+    float pending[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, pending[r] = 0.0f;
+    int pending_col = 0, prev_column = 0, prev_caller = 0;
+
+    // reads the word the last four (or fewer) MFMAs produced and advances the walk by it
+    auto finish_word = [&](int w) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            // below 32 outcomes the bits above them are never indexed by the walk
+            const uint32_t word = GW == 4 ? __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u)
+                                          : __float_as_uint(lo[r]);
+            heap_walk_word<D>(w, word, pos[r], sel[r]);
+        }
+    };
+    // the walk of tree tp has ended on pos[]: consume the leaf
+    auto finish_tree = [&](int tp, int column, int caller_tree) {
+        if (MODE == MODE_SCALAR) {
+            accu.begin_tree(pending_col);
+#pragma unroll
+            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+            pending_col = column;
+        }
+        const float *lv = m.leaf_value + ((tp << D) - (1 << D));
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (MODE == MODE_SCALAR) {
+                pending[r] = lv[pos[r]];
+            } else {
+                const int leaf = (tp << D) + static_cast<int>(pos[r] - (1u << D));
+                if (MODE == MODE_LEAVES) {
+                    const int64_t row = row0 + r * TILE + lane;
+                    if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
+                } else {
+                    accu.add(m, r, leaf);
+                }
+            }
+            pos[r] = 1u;
+        }
+    };
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int column = meta[t].column;
+        const int caller_tree = meta[t].caller_tree;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            uint32_t d[8];
+            rank_compare(d, cur.q[0], x);
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);  // the reads of the previous word stay behind these comparisons
+#endif
+            if (w > 0) {
+                finish_word(w - 1);
+            } else if (t > t_begin) {
+                finish_word(NW - 1);
+                finish_tree(t - 1, prev_column, prev_caller);
+            }
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+            lo = bits.template collect<0>(d, bits.bias);
+            p += NB;
+            const Batch<NB> nxt = load_batch<NB>(p);
+            if (GW >= 2) {
+                rank_compare(d, cur.q[1 % GW], x);
+                lo = bits.template collect<1>(d, lo);
+            }
+            if (GW == 4) {
+                rank_compare(d, cur.q[2 % GW], x);
+                hi = bits.template collect<0>(d, bits.bias);
+                rank_compare(d, cur.q[3 % GW], x);
+                hi = bits.template collect<1>(d, hi);
+            }
+            cur = nxt;
+        }
+        prev_column = column;
+        prev_caller = caller_tree;
+    }
+    finish_word(NW - 1);
+    finish_tree(t_end - 1, prev_column, prev_caller);
+    if (MODE == MODE_SCALAR) {
+        accu.begin_tree(pending_col);
+#pragma unroll
+        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+    }
+}
+
+template <int D, int NVR, int MODE>
+__device__ __forceinline__ void run_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
+                                          int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
+{
+    if constexpr (NVR == 2) rank_trees_mfma<D, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+    else rank_trees<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+}
+
 // Register budget: 64 (NVR = 2) or 128 (NVR = 4) pinned rank registers plus the working set must
 // leave room for 4 resp. 3 waves per SIMD (128 resp. 168 VGPRs).
 template <int D, int NVR>
@@ -232,11 +417,11 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     Accumulator<R> accu;
     accu.init(acc, wave, lane, m);
     if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
-        rank_trees<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+        run_trees<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
         return;
     }
-    if (m.leaf_width == 1) rank_trees<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
-    else rank_trees<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    if (m.leaf_width == 1) run_trees<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    else run_trees<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
     accu.flush();
     __syncthreads();
     const int li = threadIdx.x;
