@@ -3,8 +3,10 @@
 
 Prints ONE JSON line.  `value` is rows/s with X already resident in HBM.  The `roofline`
 object prices the dominant (only) kernel against the vector-ALU peak: the method evaluates
-every internal node of every tree for every row, one float32 compare each, and the packed
-model stays on chip, so the arithmetic rate of the compare pipeline is what bounds it.
+every internal node of every tree for every row, one comparison each, and the packed model
+stays on chip, so the rate of the compare instruction is what bounds it.  The rank kernels
+compare two rows per lane with one packed-f16 instruction, so their peak is two comparisons
+per lane and clock; the fp32 kernels' peak is one.
 `cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -19,18 +21,19 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz; one (non-packed) vector compare
-# per lane per clock.  The fp32 vector peak of 157.3 TFLOP/s is this number x 2 (FMA) x 2
-# (packed fp32); a compare is neither fused nor packed.
+# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz vector instructions per second and
+# lane.  The fp32 vector peak of 157.3 TFLOP/s is this number x 2 (FMA) x 2 (packed fp32).  A
+# float32 compare is neither fused nor packed: one comparison per lane-op.  A packed-f16
+# compare (v_pk_add_f16 with clamp on exact integer ranks) is two comparisons per lane-op.
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 HBM_PEAK = 8.0e12
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC = {
-    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 62,991 x 2.000 (copy-kernel scale) KiB read,
+    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 63,965 x 2.000 (copy-kernel scale) KiB read,
     # WRITE_SIZE 7,812.5 x 1.000 KiB written
-    "c2": 129.0e6 + 8.0e6,
+    "c2": 131.0e6 + 8.0e6,
 }
 
 
@@ -102,17 +105,19 @@ def main() -> int:
     compares = float(info["n_internal"]) * n_rows          # one per (row, internal node)
     achieved = compares / kernel_s
     algo_bytes = n_rows * (4.0 * F) + f.out_bytes(n_rows)
+    packed = info["kernel_path"] in (2, 3)  # rank kernels: two comparisons per packed-f16 lane-op
+    peak = ALU_PEAK_LANE_OPS * (2 if packed else 1)
     roofline = {
         "bound": "alu",
         "kernel": "forest_predict (fused compare + leaf resolution + reduction)",
         "achieved": achieved / 1e12,
-        "peak": ALU_PEAK_LANE_OPS / 1e12,
+        "peak": peak / 1e12,
         "unit": "Tcompare/s",
-        "frac": achieved / ALU_PEAK_LANE_OPS,
-        "peak_basis": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one float32 compare per lane-op",
-        # the rank kernels evaluate two comparisons per packed-f16 lane-op: their own ceiling is 2x
-        "frac_vs_packed_f16_peak": (achieved / (2 * ALU_PEAK_LANE_OPS)
-                                    if info["kernel_path"] == 2 else None),
+        "frac": achieved / peak,
+        "peak_basis": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz x "
+                      + ("2 comparisons per packed-f16 lane-op" if packed else "1 float32 comparison per lane-op"),
+        # against one float32 compare per (row, node) and lane-op, the floor a plain fp32 kernel has
+        "frac_vs_fp32_compare_peak": achieved / ALU_PEAK_LANE_OPS,
         "kernel_ms_avg": kernel_s * 1e3,
         "kernel_ms_min": float(np.min(kernel_ms)),
         "algorithmic_bytes": algo_bytes,
