@@ -66,15 +66,15 @@ __device__ __forceinline__ Entry8 load_group(const uint32_t *__restrict__ p)
 #define FOREST_LDS_READ(n) "ds_read_b32 %[a" #n "], %[a" #n "]\n\t"
 #define FOREST_LDS_CMP(n) "v_pk_add_f16 %[a" #n "], %[a" #n "], %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
 
-// One group of 8 entries for the lane's two rows: returns 1024 + bits in each f16 half, i.e.
-// the low byte of each half holds the 8 outcome bits, first entry in bit 7.
+// One group of 8 entries for the lane's two rows: the eight comparison outcomes (1.0 or 0.0 in
+// each f16 half), which the matrix core then turns into one outcome byte per row (first entry
+// in bit 7).
 //
 // The entries arrive through the vector memory path (every lane loads the same words), not
 // through scalar loads: vector loads are counted in vmcnt, so waiting for the LDS reads
 // (lgkmcnt) never waits for the program stream, which is fetched two groups ahead.
-__device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, uint32_t l4)
+__device__ __forceinline__ void eval_group(uint32_t (&a)[8], const Entry8 &q, uint32_t mask, uint32_t l4)
 {
-    uint32_t acc, a0, a1, a2, a3, a4, a5, a6, a7;
     asm volatile(
         FOREST_LDS_ADDR(0) FOREST_LDS_ADDR(1) FOREST_LDS_ADDR(2) FOREST_LDS_ADDR(3)
         FOREST_LDS_ADDR(4) FOREST_LDS_ADDR(5) FOREST_LDS_ADDR(6) FOREST_LDS_ADDR(7)
@@ -86,21 +86,11 @@ __device__ __forceinline__ uint32_t eval_group(const Entry8 &q, uint32_t mask, u
         FOREST_LDS_CMP(0) FOREST_LDS_CMP(1) FOREST_LDS_CMP(2)
         "s_waitcnt lgkmcnt(0)\n\t"
         FOREST_LDS_CMP(3) FOREST_LDS_CMP(4) FOREST_LDS_CMP(5) FOREST_LDS_CMP(6) FOREST_LDS_CMP(7)
-        "v_pk_fma_f16 %[a0], %[a0], %[c2], %[a1]\n\t"
-        "v_pk_fma_f16 %[a2], %[a2], %[c2], %[a3]\n\t"
-        "v_pk_fma_f16 %[a4], %[a4], %[c2], %[a5]\n\t"
-        "v_pk_fma_f16 %[a6], %[a6], %[c2], %[a7]\n\t"
-        "v_pk_fma_f16 %[a0], %[a0], %[c4], %[a2]\n\t"
-        "v_pk_fma_f16 %[a4], %[a4], %[c4], %[a6]\n\t"
-        "v_pk_fma_f16 %[a0], %[a0], %[c16], %[a4]\n\t"
-        "v_pk_add_f16 %[acc], %[a0], %[c1024]"
-        : [acc] "=v"(acc), [a0] "=&v"(a0), [a1] "=&v"(a1), [a2] "=&v"(a2), [a3] "=&v"(a3), [a4] "=&v"(a4),
-          [a5] "=&v"(a5), [a6] "=&v"(a6), [a7] "=&v"(a7)
+        : [a0] "=&v"(a[0]), [a1] "=&v"(a[1]), [a2] "=&v"(a[2]), [a3] "=&v"(a[3]), [a4] "=&v"(a[4]),
+          [a5] "=&v"(a[5]), [a6] "=&v"(a[6]), [a7] "=&v"(a[7])
         : [e0] "v"(q.e[0]), [e1] "v"(q.e[1]), [e2] "v"(q.e[2]), [e3] "v"(q.e[3]), [e4] "v"(q.e[4]),
-          [e5] "v"(q.e[5]), [e6] "v"(q.e[6]), [e7] "v"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4),
-          [c2] "s"(0x40004000u), [c4] "s"(0x44004400u), [c16] "s"(0x4c004c00u), [c1024] "s"(0x64006400u)
+          [e5] "v"(q.e[5]), [e6] "v"(q.e[6]), [e7] "v"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4)
         : "memory");
-    return acc;
 }
 
 // Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
@@ -152,12 +142,11 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     ref[0] = ref[1] = meta[t].root_ref;
     pair[0] = pair[1] = ChildRef{0, 0};
     went_right[0] = went_right[1] = 0;
-    auto one_group = [&](const Entry8 &cur) {
-        const uint32_t flags = static_cast<uint32_t>(uniform(static_cast<int>(cur.e[0])));
-        const uint32_t g = eval_group(cur, mask, l4);
-        // outcome byte of row A (low half) and of row B (high half)
-        bytes[(gi * 2 + 0) * TILE + lane] = static_cast<uint8_t>(g);
-        bytes[(gi * 2 + 1) * TILE + lane] = static_cast<uint8_t>(g >> 16);
+    // what the walk does with a group once its outcome bytes are known
+    auto consume = [&](v4f g, uint32_t flags) {
+        // low mantissa byte = outcome byte, of row A in g[0] and of row B in g[1]
+        bytes[(gi * 2 + 0) * TILE + lane] = static_cast<uint8_t>(__float_as_uint(g[0]));
+        bytes[(gi * 2 + 1) * TILE + lane] = static_cast<uint8_t>(__float_as_uint(g[1]));
         ++gi;
         pos += 8;
         if (gi == CHUNK_GROUPS || (flags & 1u)) {  // chunk complete: lanes whose node is in it pick a child
@@ -211,6 +200,25 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             ref[0] = ref[1] = meta[t].root_ref;
         }
     };
+    // The matrix core is still collecting a group's bits when its comparisons have issued, so
+    // the walk consumes every group one group late: after the comparisons of the next one.
+    BitCollector bits;
+    bits.init(lane);
+    v4f prev_g = bits.bias;
+    uint32_t prev_flags = 0;
+    bool have_prev = false;  // wave-uniform
+    auto one_group = [&](const Entry8 &cur) {
+        const uint32_t flags = static_cast<uint32_t>(uniform(static_cast<int>(cur.e[0])));
+        uint32_t d[8];
+        eval_group(d, cur, mask, l4);
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+        if (have_prev) consume(prev_g, prev_flags);
+        prev_g = bits.template collect<0>(d, bits.bias);
+        prev_flags = flags;
+        have_prev = true;
+    };
     // The fetches are unconditional (past the end of the wave's stream they read the next
     // wave's groups or the padding at the end of the program), so that exactly two fetches are
     // issued between a buffer's fill and its use on every path.
@@ -223,6 +231,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         if (group + 2 < n_groups) one_group(buf2);
         p += 24;
     }
+    consume(prev_g, prev_flags);  // n_groups >= 1: the wave has at least one tree
 }
 
 __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, const float *__restrict__ X,

@@ -23,6 +23,54 @@ __device__ __forceinline__ uint16_t f16_bits(int v)
     return __builtin_bit_cast(uint16_t, h);
 }
 
+// Bit collection on the matrix core.  The eight outcome registers of a group are, read as
+// bytes, (0, a, 0, b) with a, b = 0x3c or 0 for the lane's two rows; 0x3c is 1.0 in bf8
+// (e5m2).  v_mfma_f32_16x16x128_f8f6f4 takes them as its B operand: a lane of 16-lane block q
+// supplies B[k][n] for n = lane % 16 and the 32 values of k that belong to block q, and
+// receives D[4q + i][n], i = 0..3.  With an A that is zero outside A[4q + i][k of block q],
+// D[4q + i][n] only sums the lane's own bytes: i = 0 weighs the row-a bytes by 2^(7 - v)
+// (register v of the group: first entry in bit 7), i = 1 the row-b bytes; a second matrix
+// weighs by 2^(15 - v).  Two chained MFMAs on top of a 2^23 addend therefore leave the 16
+// outcome bits of two groups in the low mantissa bits of D[..][0] and D[..][1]: exact, every
+// product and partial sum being an integer below 2^24.  The matrix core runs beside the
+// vector ALU, so collecting a group costs the vector ALU the MFMA's issue instead of the eight
+// instructions of a packed fused-multiply-add tree.
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct BitCollector {
+    v8i a[2];  // weights 2^(7 - v) and 2^(15 - v)
+    v4f bias;
+
+    __device__ __forceinline__ void init(int lane)
+    {
+        const int m = lane & 15, q = lane >> 4;
+        const bool mine = (m >> 2) == q && (m & 3) < 2;
+        const int shift = (m & 3) == 0 ? 8 : 24;  // byte 1 = row a, byte 3 = row b
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const uint32_t bf8 = static_cast<uint32_t>(15 + 8 * j + 7 - v) << 2;  // 2^(8j + 7 - v)
+                a[j][v] = mine ? static_cast<int>(bf8 << shift) : 0;
+            }
+        bias = v4f{8388608.0f, 8388608.0f, 8388608.0f, 8388608.0f};
+        // keep the addend in registers instead of rebuilding it before every chain
+        asm volatile("" : "+v"(bias));
+    }
+    template <int J>
+    __device__ __forceinline__ v4f collect(const uint32_t (&d)[8], v4f c) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const v8i b = {static_cast<int>(d[0]), static_cast<int>(d[1]), static_cast<int>(d[2]), static_cast<int>(d[3]),
+                       static_cast<int>(d[4]), static_cast<int>(d[5]), static_cast<int>(d[6]), static_cast<int>(d[7])};
+        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[J], b, c, 1, 1, 0, 0, 0, 0);  // A, B: bf8, unscaled
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+        return c;
+    }
+};
+
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) int32_t *RankTablePtr;
 #else
