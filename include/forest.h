@@ -91,7 +91,10 @@ typedef struct forest_info_t {
     int32_t kernel_path;        /* 0: features from the LDS tile; 1: float32 feature registers;
                                    2: packed f16 threshold-rank registers;
                                    3: packed f16 threshold ranks in LDS (any tree shape) */
-    int32_t rows_per_workgroup; /* rows one workgroup (4 wavefronts) owns */
+    int32_t rows_per_workgroup; /* rows one workgroup owns */
+    int64_t workspace_bytes;    /* device workspace the handle owns besides the packed model */
+    int64_t small_batch_rows;   /* batches below this many rows also cut the trees into shares
+                                   (more workgroups for few rows) and use the workspace */
 } forest_info_t;
 
 /*
@@ -125,7 +128,12 @@ int forest_out_layout(const forest *f, int64_t n_rows, int64_t *scores_offset, i
  *   stream  hipStream_t (NULL = default stream)
  * Asynchronous: enqueues kernels and returns; reports launch errors only.  n_rows == 0 is a
  * successful no-op.  The caller keeps X and out alive until the stream has run the work.
- * Allocates nothing.  Concurrent calls on one handle from different streams are allowed.
+ * Allocates nothing.
+ * Small batches (the latency regime of Table 6): below forest_info_t.small_batch_rows rows the
+ * trees are cut into shares that run in separate workgroups, their fp64 partial sums meet in
+ * the handle's workspace and a second kernel on the same stream finishes the rows.  Such calls
+ * on ONE handle must not overlap in time (same stream, or ordered by events); larger batches
+ * touch no shared state and may run concurrently from different streams.
  */
 int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream);
 

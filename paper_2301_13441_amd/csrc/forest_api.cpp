@@ -17,7 +17,8 @@ struct forest {
     PackedModel host;  // tables kept for forest_info; large arrays are released after upload
     DevModel dev{};
     void *blob = nullptr;  // one device allocation holding every table
-    int64_t blob_bytes = 0;
+    int64_t blob_bytes = 0;       // packed model
+    int64_t workspace_bytes = 0;  // partial sums of split launches, same allocation
     int device = 0;
 };
 
@@ -129,13 +130,20 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_fvf = place<int32_t>(cur, m.feat_vfirst.size());
     const size_t o_piv = place<float>(cur, m.pivots.size());
     const size_t o_fpb = place<int32_t>(cur, m.feat_pivot_base.size());
+    const size_t model_bytes = (cur + 255) & ~size_t{255};
+    const size_t n_partial = static_cast<size_t>(split_workspace_doubles(m.n_outputs));
+    const size_t o_part = place<double>(cur, n_partial);  // workspace of split launches, not uploaded
+    const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
+    const size_t n_rank_words = ranks ? static_cast<size_t>(SPLIT_BELOW_BLOCKS) * m.rank_regs * 64 : 0;
+    const size_t o_rtile = place<uint32_t>(cur, n_rank_words);
     cur = (cur + 255) & ~size_t{255};
     if (hipMalloc(&f->blob, cur) != hipSuccess) {
         (void)hipGetLastError();
         delete f;
         return FOREST_ENOMEM;
     }
-    f->blob_bytes = static_cast<int64_t>(cur);
+    f->blob_bytes = static_cast<int64_t>(model_bytes);
+    f->workspace_bytes = static_cast<int64_t>(cur - model_bytes);
     char *b = static_cast<char *>(f->blob);
     auto up = [&](size_t off, const void *src, size_t bytes) {
         return bytes == 0 || hipMemcpy(b + off, src, bytes, hipMemcpyHostToDevice) == hipSuccess;
@@ -189,6 +197,12 @@ int forest_load(const forest_desc *desc, forest **out)
     d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);
     d.feat_thr_base = reinterpret_cast<const int32_t *>(b + o_ftb);
     d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);
+    d.n_splits = 1;
+    d.n_entries = static_cast<int64_t>(m.prog32.size() > m.prog.size() ? m.prog32.size() : m.prog.size());
+    d.split_rows = 0;
+    d.partial = reinterpret_cast<double *>(b + o_part);
+    d.partial_capacity = static_cast<int64_t>(n_partial);
+    d.rank_tiles = reinterpret_cast<uint32_t *>(b + o_rtile);
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
     m.prog32 = {};
@@ -226,7 +240,9 @@ int forest_info(const forest *f, forest_info_t *info)
     info->packed_bytes = f->blob_bytes;
     info->x_in_registers = m.x_in_registers;
     info->kernel_path = m.path;
-    info->rows_per_workgroup = m.path == PATH_RANK_LDS ? 128 : m.x_in_registers ? 64 * m.reg_r : 64;
+    info->rows_per_workgroup = family_rows_per_block(f->dev);
+    info->workspace_bytes = f->workspace_bytes;
+    info->small_batch_rows = SPLIT_BELOW_BLOCKS * info->rows_per_workgroup;
     return FOREST_OK;
 }
 

@@ -30,7 +30,30 @@ struct DevModel {
     const float *thr_sorted;
     const int32_t *feat_thr_base;
     const int32_t *feat_vfirst;
+    // Tree splitting for small batches: with n_splits > 1 the grid's y index selects a share of
+    // the trees and the kernels store raw fp64 partial sums to partial[(split * split_rows + row)
+    // * n_outputs + k] instead of finishing the row; reduce_splits() finishes.  Set per launch.
+    int32_t n_splits;
+    int64_t split_rows;
+    double *partial;
+    int64_t partial_capacity;  // doubles available at `partial`
+    int64_t n_entries;         // entries of the split program, all trees (padding included)
+    // Rank families, split launches: the rank tiles ([tile][rank register][lane] packed f16 pairs)
+    // are computed once per row tile by forest_rank_tiles_kernel instead of by every workgroup.
+    uint32_t *rank_tiles;
 };
+
+// Batches below this many workgroups split the trees over several workgroups per row tile.
+constexpr int64_t SPLIT_BELOW_BLOCKS = 512;
+// A split launch aims at about this many workgroups in all and gives every wave whole trees of
+// at least this many program entries together.
+constexpr int64_t SPLIT_TARGET_BLOCKS = 1024;
+constexpr int64_t SPLIT_MIN_ENTRIES_PER_WAVE = 512;
+// Rows one workgroup of the model's kernel family owns, and its number of wavefronts.
+int family_rows_per_block(const DevModel &m);
+int family_waves_per_block(const DevModel &m);
+// Doubles of workspace a handle needs so that no split launch is limited by it (capped).
+int64_t split_workspace_doubles(int n_outputs);
 
 // Enqueues one pass over `n_rows` rows on `stream`.  `scores` / `labels` / `leaf_out` may be
 // null (that part is not written).  Returns the launch error, if any.
@@ -51,6 +74,13 @@ hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float 
 hipError_t init_ranklds_kernels(size_t lds_limit);
 hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream);
+
+// Sums the partial sums of a split launch over the splits and finishes every row.
+hipError_t launch_reduce_splits(const DevModel &m, int64_t n_rows, float *scores, int32_t *labels,
+                                hipStream_t stream);
+
+// Threshold ranks of every 128-row tile of the batch into m.rank_tiles (rank families).
+hipError_t launch_rank_tiles(const DevModel &m, const float *X, int64_t n_rows, hipStream_t stream);
 
 // Whether the kernels' LDS working set for this model fits a compute unit (host-only check).
 bool model_fits(const PackedModel &m);

@@ -35,26 +35,35 @@ __device__ __forceinline__ void stage_x_tile(float *xs, const float *X, int64_t 
     }
 }
 
-// Cross-wave reduction, aggregate, label, transform, store for tile row `li` (0 <= li < rows).
-// `acc` is [n_waves][K][rows]; wave 0's slice is overwritten with the raw values.
-__device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int rows, int li, int64_t row,
-                                           bool valid, float *scores, int32_t *labels, int n_waves = WAVES)
+// The trees of wave `wave` (of n_waves) in this workgroup: the trees are dealt, in contiguous
+// runs, over (split, wave) pairs; blockIdx.y is the split (0 when the launch is not split).
+__device__ __forceinline__ void tree_range(const DevModel &m, int wave, int n_waves, int &t_begin, int &t_end)
+{
+    const int64_t T = m.n_trees;
+    const int64_t unit = static_cast<int64_t>(blockIdx.y) * n_waves + wave;
+    const int64_t units = static_cast<int64_t>(m.n_splits) * n_waves;
+    t_begin = static_cast<int>((T * unit) / units);
+    t_end = static_cast<int>((T * (unit + 1)) / units);
+}
+
+// Aggregate, label, transform, store for one row whose K summed leaf values are raw[k * stride];
+// raw[] is overwritten with the aggregated values.
+__device__ __forceinline__ void finish_values(const DevModel &m, double *raw, int64_t stride, int64_t row,
+                                              float *scores, int32_t *labels)
 {
     const int K = m.n_outputs;
     double best = 0.0;
     int best_k = 0;
     for (int k = 0; k < K; ++k) {
-        double s = acc[(0 * K + k) * rows + li];
-        for (int w = 1; w < n_waves; ++w) s += acc[(w * K + k) * rows + li];
+        double s = raw[k * stride];
         if (m.aggregate == FOREST_AGG_MEAN) s = s / m.col_trees[k];
         s = static_cast<double>(m.base[k]) + s;
-        acc[k * rows + li] = s;
+        raw[k * stride] = s;
         if (k == 0 || s > best) {
             best = s;
             best_k = k;
         }
     }
-    if (!valid) return;
     if (labels) {
         int lab = best_k;
         if (K == 1) lab = (m.transform == FOREST_TRANSFORM_SIGMOID) ? (best > 0.0) : (best > 0.5);
@@ -64,13 +73,34 @@ __device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int r
     float *dst = scores + row * K;
     if (m.transform == FOREST_TRANSFORM_SOFTMAX) {
         double z = 0.0;
-        for (int k = 0; k < K; ++k) z += exp(acc[k * rows + li] - best);
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(exp(acc[k * rows + li] - best) / z);
+        for (int k = 0; k < K; ++k) z += exp(raw[k * stride] - best);
+        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(exp(raw[k * stride] - best) / z);
     } else if (m.transform == FOREST_TRANSFORM_SIGMOID) {
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(1.0 / (1.0 + exp(-acc[k * rows + li])));
+        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(1.0 / (1.0 + exp(-raw[k * stride])));
     } else {
-        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(acc[k * rows + li]);
+        for (int k = 0; k < K; ++k) dst[k] = static_cast<float>(raw[k * stride]);
     }
+}
+
+// Cross-wave reduction for tile row `li` (0 <= li < rows), then either the rest of the row
+// (aggregate, label, transform, store) or, in a split launch, the store of the partial sums.
+// `acc` is [n_waves][K][rows]; wave 0's slice is overwritten.
+__device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int rows, int li, int64_t row,
+                                           bool valid, float *scores, int32_t *labels, int n_waves = WAVES)
+{
+    const int K = m.n_outputs;
+    for (int k = 0; k < K; ++k) {
+        double s = acc[(0 * K + k) * rows + li];
+        for (int w = 1; w < n_waves; ++w) s += acc[(w * K + k) * rows + li];
+        acc[k * rows + li] = s;
+    }
+    if (!valid) return;
+    if (m.n_splits > 1) {
+        double *dst = m.partial + (static_cast<int64_t>(blockIdx.y) * m.split_rows + row) * K;
+        for (int k = 0; k < K; ++k) dst[k] = acc[k * rows + li];
+        return;
+    }
+    finish_values(m, acc + li, rows, row, scores, labels);
 }
 
 // Partial sums of one wave for R rows per lane.  Scalar leaves accumulate in a register per

@@ -74,8 +74,8 @@ __global__ __launch_bounds__(BLOCK) void forest_full_kernel(DevModel m, const fl
     constexpr int BLK = N_POS < 32 ? N_POS : 32;
     constexpr int NW = N_POS / BLK;
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
 
     for (int t = t_begin; t < t_end; ++t) {
         const SplitEntry *__restrict__ p = m.prog + (static_cast<size_t>(t) << D);
@@ -135,8 +135,8 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
     uint32_t *mybits = lds.bits + static_cast<size_t>(wave) * m.max_words * TILE;
 
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
 
     for (int t = t_begin; t < t_end; ++t) {
         const TreeMeta tm = m.tree[t];
@@ -244,10 +244,48 @@ hipError_t init_kernels()
     return init_ranklds_kernels(g_lds_limit);
 }
 
-hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
-                          int32_t *labels, int32_t *leaf_out, hipStream_t stream)
+int family_rows_per_block(const DevModel &m)
 {
-    if (n_rows <= 0) return hipSuccess;
+    if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) return 128;
+    if (m.path == PATH_REG) return TILE * m.reg_r;
+    return TILE;
+}
+
+int family_waves_per_block(const DevModel &m) { return m.path == PATH_RANK_LDS ? 8 : WAVES; }
+
+int64_t split_workspace_doubles(int n_outputs)
+{
+    // splits x rows stays below (SPLIT_TARGET_BLOCKS + SPLIT_BELOW_BLOCKS) workgroups x 128 rows
+    const int64_t want = (SPLIT_TARGET_BLOCKS + SPLIT_BELOW_BLOCKS) * 128 * n_outputs;
+    const int64_t cap = int64_t{4} << 20;  // 32 MB
+    return want < cap ? want : cap;
+}
+
+namespace {
+
+// How many shares the trees are cut into for a batch of n_rows rows (1 = no split).
+int choose_splits(const DevModel &m, int64_t n_rows, bool needs_workspace)
+{
+    const int64_t rb = family_rows_per_block(m);
+    const int64_t n_blocks = (n_rows + rb - 1) / rb;
+    if (n_blocks >= SPLIT_BELOW_BLOCKS) return 1;
+    const int64_t per_tree = m.n_trees > 0 ? (m.n_entries + m.n_trees - 1) / m.n_trees : 1;
+    const int64_t trees_per_wave = (SPLIT_MIN_ENTRIES_PER_WAVE + per_tree - 1) / (per_tree > 0 ? per_tree : 1);
+    int64_t s = m.n_trees / (family_waves_per_block(m) * (trees_per_wave > 0 ? trees_per_wave : 1));
+    const int64_t by_grid = (SPLIT_TARGET_BLOCKS + n_blocks - 1) / n_blocks;
+    if (by_grid < s) s = by_grid;
+    if (needs_workspace) {
+        const int64_t by_ws = m.partial_capacity / (n_rows * m.n_outputs);
+        if (by_ws < s) s = by_ws;
+    }
+    return s < 2 ? 1 : static_cast<int>(s);
+}
+
+}  // namespace
+
+static hipError_t launch_family(const DevModel &m, const float *X, int64_t n_rows, float *scores,
+                                int32_t *labels, int32_t *leaf_out, hipStream_t stream)
+{
     if (m.path == PATH_RANK) return launch_rank(m, X, n_rows, scores, labels, leaf_out, stream);
     if (m.path == PATH_RANK_LDS) return launch_ranklds(m, X, n_rows, scores, labels, leaf_out, g_lds_limit, stream);
     if (m.path == PATH_REG) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
@@ -258,9 +296,28 @@ hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, flo
     const int64_t n_blocks = (n_rows + TILE - 1) / TILE;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     KernelFn fn = pick(m.kind, leaf_out != nullptr, staged);
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks)), dim3(BLOCK), lds, stream, m, X, n_rows,
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), lds, stream, m, X, n_rows,
                        scores, labels, leaf_out);
     return hipGetLastError();
+}
+
+hipError_t launch_predict(const DevModel &model, const float *X, int64_t n_rows, float *scores,
+                          int32_t *labels, int32_t *leaf_out, hipStream_t stream)
+{
+    if (n_rows <= 0) return hipSuccess;
+    // Small batches: too few row tiles to fill the chip, so the trees are cut into shares as
+    // well (grid y) and a second kernel sums the shares.  The leaf-id output needs no sums.
+    DevModel m = model;
+    const bool sums = leaf_out == nullptr;
+    m.n_splits = choose_splits(m, n_rows, sums);
+    m.split_rows = n_rows;
+    if (m.n_splits > 1 && (m.path == PATH_RANK || m.path == PATH_RANK_LDS)) {
+        const hipError_t e = launch_rank_tiles(m, X, n_rows, stream);
+        if (e != hipSuccess) return e;
+    }
+    const hipError_t e = launch_family(m, X, n_rows, scores, labels, leaf_out, stream);
+    if (e != hipSuccess || m.n_splits == 1 || !sums) return e;
+    return launch_reduce_splits(m, n_rows, scores, labels, stream);
 }
 
 }  // namespace forest_impl

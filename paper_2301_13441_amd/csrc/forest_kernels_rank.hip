@@ -141,8 +141,8 @@ __device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NV
     constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups (outcome bytes) per word
     constexpr int NB = GW * 8;                          // entries per scalar load batch = one word
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
 
     // The wave's trees are one contiguous stream of entries; the batch after the last one
     // read here is padding the host appended to the program.
@@ -233,8 +233,8 @@ __device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&
     constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;
     constexpr int NB = GW * 8;
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
     if (t_begin >= t_end) return;
 
     BitCollector bits;
@@ -355,10 +355,14 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
-    float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
-    for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
-    __syncthreads();
-    rank_rows<WAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+    if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
+        load_rank_tile(rk, m, BLOCK);
+    } else {
+        float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
+        for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
+        __syncthreads();
+        rank_rows<WAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+    }
     __syncthreads();
     v32u x[NVR];
 #pragma unroll
@@ -428,7 +432,7 @@ hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float 
     KernelFn fn = pick_rank(nvr, m.kind);
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks)), dim3(BLOCK), rank_lds_bytes(m, nvr), stream, m,
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), rank_lds_bytes(m, nvr), stream, m,
                        X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }

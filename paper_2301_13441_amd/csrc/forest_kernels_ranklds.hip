@@ -106,8 +106,8 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
                                               int64_t n_rows, int32_t *leaf_out)
 {
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / LWAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / LWAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, LWAVES, t_begin, t_end);
     if (t_begin >= t_end) return;
     MetaPtr meta = (MetaPtr)m.tree;
     const uint32_t mask = 0xff00u;
@@ -255,11 +255,15 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
-    float *piv = reinterpret_cast<float *>(region2);
-    for (int i = threadIdx.x; i < m.n_pivots; i += LBLOCK) piv[i] = m.pivots[i];
     if (m.rank_regs == 0) rk[threadIdx.x & (TILE - 1)] = 0;  // the padding entries read row 0
-    __syncthreads();
-    rank_rows<LWAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+    if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
+        load_rank_tile(rk, m, LBLOCK);
+    } else {
+        float *piv = reinterpret_cast<float *>(region2);
+        for (int i = threadIdx.x; i < m.n_pivots; i += LBLOCK) piv[i] = m.pivots[i];
+        __syncthreads();
+        rank_rows<LWAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+    }
     __syncthreads();  // ranks complete; the pivots are dead, their space becomes the byte chunks
 
     uint8_t *bytes = reinterpret_cast<uint8_t *>(region2) + static_cast<size_t>(wave) * CHUNK_GROUPS * 2 * TILE;
@@ -310,7 +314,7 @@ hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, flo
     if (lds > lds_limit || m.rank_regs > RANKLDS_MAX_REGS) return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(forest_ranklds_kernel, dim3(static_cast<unsigned>(n_blocks)), dim3(LBLOCK), lds, stream, m,
+    hipLaunchKernelGGL(forest_ranklds_kernel, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(LBLOCK), lds, stream, m,
                        X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }

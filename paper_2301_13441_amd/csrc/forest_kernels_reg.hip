@@ -147,8 +147,8 @@ __global__ __launch_bounds__(BLOCK) void forest_reg_kernel(DevModel m, const flo
     constexpr int NW = N_POS / BLK;                // outcome words per tree
     constexpr int NB = BLK < 16 ? BLK : 16;        // entries per scalar load batch
     const int T = m.n_trees;
-    const int t_begin = static_cast<int>((static_cast<int64_t>(T) * wave) / WAVES);
-    const int t_end = static_cast<int>((static_cast<int64_t>(T) * (wave + 1)) / WAVES);
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
 
     // The wave's trees are one contiguous stream of entries; the batch after the last one
     // read here is padding the host appended to the program.
@@ -251,7 +251,7 @@ hipError_t launch_reg(const DevModel &m, const float *X, int64_t n_rows, float *
     const int rows = TILE * m.reg_r;
     const int64_t n_blocks = (n_rows + rows - 1) / rows;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks)), dim3(BLOCK), reg_lds_bytes(m), stream, m, X,
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), reg_lds_bytes(m), stream, m, X,
                        n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }

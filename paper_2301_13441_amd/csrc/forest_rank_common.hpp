@@ -77,6 +77,61 @@ typedef const __attribute__((address_space(4))) int32_t *RankTablePtr;
 typedef const int32_t *RankTablePtr;  // host pass: the kernel body is only parsed
 #endif
 
+// The same ranks for a tile with few valid rows (the tail of a batch, or a small batch): the
+// (row, feature) pairs are dealt to the threads, so the searches of one row run side by side
+// instead of one feature after the other; the rest of the tile gets rank 0.  Xt points at the
+// tile's first row.
+template <int NWAVES>
+__device__ __forceinline__ void rank_rows_few(uint32_t *rk, const float *piv, const DevModel &m,
+                                              const float *__restrict__ Xt, int n_valid)
+{
+    const int F = m.n_features;
+    const int n_threads = NWAVES * TILE;
+    const int block = 1 << m.pivot_shift;
+    for (int i = threadIdx.x; i < m.rank_regs * TILE; i += n_threads) rk[i] = 0;
+    __syncthreads();
+    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
+    for (int w = threadIdx.x; w < n_valid * F; w += n_threads) {
+        const int r = w / F, f = w - r * F;
+        const float x = Xt[w];
+        const int tb = m.feat_thr_base[f];
+        const int n_thr = m.feat_thr_base[f + 1] - tb;
+        const int pb = m.feat_pivot_base[f];
+        int lo = 0, hi = m.feat_pivot_base[f + 1] - pb;
+        while (lo < hi) {  // first block whose last threshold is not below x
+            const int mid = (lo + hi) >> 1;
+            if (piv[pb + mid] < x) lo = mid + 1;
+            else hi = mid;
+        }
+        lo = lo << m.pivot_shift;
+        hi = lo + block < n_thr ? lo + block : n_thr;
+        if (lo > hi) lo = hi;  // x is above every pivot: rank = n_thr
+        while (lo < hi) {      // position inside the block
+            const int mid = (lo + hi) >> 1;
+            if (m.thr_sorted[tb + mid] < x) lo = mid + 1;
+            else hi = mid;
+        }
+        const int rank = (x != x) ? n_thr : lo;  // NaN is right of every threshold
+        const int reg0 = m.feat_vfirst[f];
+        for (int sgm = 0, first = 0; first < n_thr; ++sgm, first += RANK_SEG) {
+            const int len = n_thr - first < RANK_SEG ? n_thr - first : RANK_SEG;
+            int rv = rank - first;
+            rv = rv < 0 ? 0 : (rv > len ? len : rv);
+            // tile row r lives in lane r % 64, low half for r < 64, high half above
+            rk16[((reg0 + sgm) * TILE + (r & (TILE - 1))) * 2 + (r >> 6)] = f16_bits(rv - RANK_BIAS);
+        }
+    }
+}
+
+// Split launches: the tile's ranks were computed by forest_rank_tiles_kernel; copy them from
+// global memory into the LDS tile (coalesced, n_threads threads).
+__device__ __forceinline__ void load_rank_tile(uint32_t *rk, const DevModel &m, int n_threads)
+{
+    const int words = m.rank_regs * TILE;
+    const uint32_t *__restrict__ src = m.rank_tiles + static_cast<size_t>(blockIdx.x) * words;
+    for (int i = threadIdx.x; i < words; i += n_threads) rk[i] = src[i];
+}
+
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
 // pairs into rk[reg * 64 + lane] (low half: row `lane` of the tile, high half: row lane + 64).
 // The features are dealt to the waves; inside a wave every lane searches the same feature for
@@ -92,6 +147,11 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const 
     constexpr int U = 2;  // features searched together (2 rows each: 4 searches in flight per lane)
     const int F = m.n_features;
     const int block = 1 << m.pivot_shift;
+    const int64_t left = n_rows - row0;
+    if (left * 4 <= RROWS) {  // workgroup-uniform
+        rank_rows_few<NWAVES>(rk, piv, m, X + row0 * F, static_cast<int>(left));
+        return;
+    }
     RankTablePtr thr_base = (RankTablePtr)m.feat_thr_base;
     RankTablePtr piv_base = (RankTablePtr)m.feat_pivot_base;
     RankTablePtr vfirst = (RankTablePtr)m.feat_vfirst;

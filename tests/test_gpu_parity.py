@@ -107,6 +107,37 @@ def test_empty_and_single_row_and_single_leaf_trees():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("name,trees", [
+    ("c2", 200),   # rank kernel, depth 8, one column
+    ("c3", 300),   # rank kernel, depth 6
+    ("c4", 200),   # wide rank kernel, 10 columns, softmax
+    ("c5", 128),   # LDS rank kernel, vector leaves, 8 waves
+])
+@pytest.mark.parametrize("rows", [1, 2, 65, 129, 1000])
+def test_small_batches_cut_the_trees_into_shares(name, trees, rows):
+    """Below forest_info.small_batch_rows rows a call also splits the trees over workgroups and
+    sums fp64 partial sums in a second kernel: same answers as the oracle at every batch size."""
+    w = wl.make_workload(name, n_rows=rows, n_trees=trees)
+    info = _check(w.forest, w.make_x(rows))
+    assert info["small_batch_rows"] == 512 * info["rows_per_workgroup"] > rows
+    assert info["workspace_bytes"] >= 8 * rows * w.forest.n_outputs * 2
+
+
+def test_small_batches_other_families():
+    # float32 register family (too many rank registers)
+    rng = np.random.default_rng(5)
+    f = _full_forest(3, 80, 8, 128, feature_bias=0.9)
+    for rows in (1, 100, 300):
+        info = _check(f, rng.standard_normal((rows, 128)).astype(np.float32))
+        assert info["kernel_path"] == 1
+    # plain LDS family: irregular trees with 20 output columns
+    g = wl.random_forest(901, n_trees=96, n_features=7, max_depth=7, stop_prob=0.15, n_outputs=20,
+                         leaf_width=20, transform=wl.TRANSFORM_SOFTMAX, aggregate=wl.AGG_MEAN)
+    for rows in (1, 70, 500):
+        info = _check(g, rng.standard_normal((rows, 7)).astype(np.float32))
+        assert info["kernel_path"] == 0
+
+
 def test_repeated_runs_are_bit_identical():
     import torch
     import paper_2301_13441_amd as pk
