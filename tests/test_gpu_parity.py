@@ -138,6 +138,63 @@ def test_small_batches_other_families():
         assert info["kernel_path"] == 0
 
 
+@pytest.mark.parametrize("rows", [300, 70000])   # a split launch (three kernels) and a plain one
+def test_predict_replays_from_a_captured_graph(rows):
+    """forest_predict allocates nothing and records only kernels, so a caller can capture it;
+    every replay, with eager work and synchronisations in between, must match the oracle."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c3", n_rows=rows, n_trees=100)
+    f = pk.forest_load(w.forest)
+    try:
+        rng = np.random.default_rng(rows)
+        xs = [w.make_x(rows)] + [rng.standard_normal((rows, w.forest.n_features)).astype(np.float32)
+                                 for _ in range(2)]
+        static_x = torch.zeros((rows, w.forest.n_features), dtype=torch.float32, device="cuda")
+        out = torch.zeros(max(f.out_bytes(rows), 4), dtype=torch.uint8, device="cuda")
+        static_x.copy_(torch.from_numpy(xs[0]))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            f.predict(static_x, out=out)          # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            scores, labels = f.predict(static_x, out=out)
+        for x in xs:
+            static_x.copy_(torch.from_numpy(x))
+            out.zero_()                           # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ref = oracle.predict(w.forest, x, want_leaves=False, n_threads=8)
+            np.testing.assert_allclose(scores.cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        f.close()
+
+
+def test_hand_off_from_torch_ops_on_the_same_stream():
+    """Hybrid use (Section 4.4): the features are the output of tensor ops on the device and
+    the forest consumes them on the same stream, without a host round trip in between."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c4", n_rows=2000, n_trees=60)
+    f = pk.forest_load(w.forest)
+    try:
+        torch.manual_seed(3)
+        a = torch.randn((2000, 32), device="cuda")
+        wgt = torch.randn((32, w.forest.n_features), device="cuda")
+        feats = torch.relu(a @ wgt).contiguous()      # stays on the device
+        scores, labels = f.predict(feats)             # enqueued behind the matmul, no sync
+        torch.cuda.synchronize()
+        ref = oracle.predict(w.forest, feats.cpu().numpy(), want_leaves=False, n_threads=8)
+        np.testing.assert_array_equal(labels.cpu().numpy(), ref.labels)
+        np.testing.assert_allclose(scores.cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        f.close()
+
+
 def test_repeated_runs_are_bit_identical():
     import torch
     import paper_2301_13441_amd as pk
