@@ -17,7 +17,7 @@
 // reference is either the child's ordinal in the next level or a leaf.  One pass over the
 // stream therefore resolves the leaf with a working set of one level.
 //
-// A workgroup is 8 wavefronts on 128 rows; the trees are split over the waves.
+// A workgroup is RANKLDS_WAVES wavefronts on 128 rows; the trees are split over the waves.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -29,7 +29,7 @@
 namespace forest_impl {
 namespace {
 
-constexpr int LWAVES = 8;
+constexpr int LWAVES = RANKLDS_WAVES;
 constexpr int LBLOCK = TILE * LWAVES;
 
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -47,7 +47,7 @@ struct Entry8 {
 __host__ __device__ inline size_t ranklds_region2_bytes(int n_pivots)
 {
     const size_t piv = sizeof(float) * static_cast<size_t>(n_pivots);
-    const size_t buf = static_cast<size_t>(8) * 8 * 2 * 64;
+    const size_t buf = static_cast<size_t>(LWAVES) * 8 * 2 * 64;
     return ((piv > buf ? piv : buf) + 15) / 16 * 16;
 }
 
@@ -62,35 +62,50 @@ __device__ __forceinline__ Entry8 load_group(const uint32_t *__restrict__ p)
     return q;
 }
 
-#define FOREST_LDS_ADDR(n) "v_and_or_b32 %[a" #n "], %[e" #n "], %[mask], %[l4]\n\t"
-#define FOREST_LDS_READ(n) "ds_read_b32 %[a" #n "], %[a" #n "]\n\t"
-#define FOREST_LDS_CMP(n) "v_pk_add_f16 %[a" #n "], %[a" #n "], %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+// One entry of a pair of groups: address of its rank row into a scratch register, the read, and
+// the comparison, which overwrites the entry with its outcome.
+#define FOREST_LDS_ADDR(t, e) "v_and_or_b32 " t ", %[" e "], %[mask], %[l4]\n\t"
+#define FOREST_LDS_READ(t) "ds_read_b32 " t ", " t "\n\t"
+#define FOREST_LDS_CMP(t, e) "v_pk_add_f16 %[" e "], " t ", %[" e "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
 
-// One group of 8 entries for the lane's two rows: the eight comparison outcomes (1.0 or 0.0 in
-// each f16 half), which the matrix core then turns into one outcome byte per row (first entry
-// in bit 7).
+// Two groups of 8 entries for the lane's two rows: every entry is replaced by its comparison
+// outcome (1.0 or 0.0 in each f16 half), which the matrix core then turns into one outcome byte
+// per group and row (first entry in bit 7).  All 16 LDS reads are issued before the first
+// comparison, so the LDS latency is paid once per pair; they land in v112..v127, which the
+// statement names as clobbered.  LDS operations complete in order, whatever scalar loads are
+// also outstanding: "at most 8 outstanding" means the first eight reads have returned.
 //
 // The entries arrive through the vector memory path (every lane loads the same words), not
 // through scalar loads: vector loads are counted in vmcnt, so waiting for the LDS reads
-// (lgkmcnt) never waits for the program stream, which is fetched two groups ahead.
-__device__ __forceinline__ void eval_group(uint32_t (&a)[8], const Entry8 &q, uint32_t mask, uint32_t l4)
+// (lgkmcnt) never waits for the program stream, which is fetched one pair ahead.
+__device__ __forceinline__ void eval_pair(Entry8 &q, Entry8 &r, uint32_t mask, uint32_t l4)
 {
     asm volatile(
-        FOREST_LDS_ADDR(0) FOREST_LDS_ADDR(1) FOREST_LDS_ADDR(2) FOREST_LDS_ADDR(3)
-        FOREST_LDS_ADDR(4) FOREST_LDS_ADDR(5) FOREST_LDS_ADDR(6) FOREST_LDS_ADDR(7)
-        FOREST_LDS_READ(0) FOREST_LDS_READ(1) FOREST_LDS_READ(2) FOREST_LDS_READ(3)
-        FOREST_LDS_READ(4) FOREST_LDS_READ(5) FOREST_LDS_READ(6) FOREST_LDS_READ(7)
-        // LDS operations complete in order; a scalar load of tree metadata may still be counted,
-        // so "at most 4 outstanding" guarantees at least the first three reads
-        "s_waitcnt lgkmcnt(4)\n\t"
-        FOREST_LDS_CMP(0) FOREST_LDS_CMP(1) FOREST_LDS_CMP(2)
+        FOREST_LDS_ADDR("v112", "e0") FOREST_LDS_ADDR("v113", "e1") FOREST_LDS_ADDR("v114", "e2")
+        FOREST_LDS_ADDR("v115", "e3") FOREST_LDS_ADDR("v116", "e4") FOREST_LDS_ADDR("v117", "e5")
+        FOREST_LDS_ADDR("v118", "e6") FOREST_LDS_ADDR("v119", "e7")
+        FOREST_LDS_READ("v112") FOREST_LDS_READ("v113") FOREST_LDS_READ("v114") FOREST_LDS_READ("v115")
+        FOREST_LDS_READ("v116") FOREST_LDS_READ("v117") FOREST_LDS_READ("v118") FOREST_LDS_READ("v119")
+        FOREST_LDS_ADDR("v120", "f0") FOREST_LDS_ADDR("v121", "f1") FOREST_LDS_ADDR("v122", "f2")
+        FOREST_LDS_ADDR("v123", "f3") FOREST_LDS_ADDR("v124", "f4") FOREST_LDS_ADDR("v125", "f5")
+        FOREST_LDS_ADDR("v126", "f6") FOREST_LDS_ADDR("v127", "f7")
+        FOREST_LDS_READ("v120") FOREST_LDS_READ("v121") FOREST_LDS_READ("v122") FOREST_LDS_READ("v123")
+        FOREST_LDS_READ("v124") FOREST_LDS_READ("v125") FOREST_LDS_READ("v126") FOREST_LDS_READ("v127")
+        "s_waitcnt lgkmcnt(8)\n\t"
+        FOREST_LDS_CMP("v112", "e0") FOREST_LDS_CMP("v113", "e1") FOREST_LDS_CMP("v114", "e2")
+        FOREST_LDS_CMP("v115", "e3") FOREST_LDS_CMP("v116", "e4") FOREST_LDS_CMP("v117", "e5")
+        FOREST_LDS_CMP("v118", "e6") FOREST_LDS_CMP("v119", "e7")
         "s_waitcnt lgkmcnt(0)\n\t"
-        FOREST_LDS_CMP(3) FOREST_LDS_CMP(4) FOREST_LDS_CMP(5) FOREST_LDS_CMP(6) FOREST_LDS_CMP(7)
-        : [a0] "=&v"(a[0]), [a1] "=&v"(a[1]), [a2] "=&v"(a[2]), [a3] "=&v"(a[3]), [a4] "=&v"(a[4]),
-          [a5] "=&v"(a[5]), [a6] "=&v"(a[6]), [a7] "=&v"(a[7])
-        : [e0] "v"(q.e[0]), [e1] "v"(q.e[1]), [e2] "v"(q.e[2]), [e3] "v"(q.e[3]), [e4] "v"(q.e[4]),
-          [e5] "v"(q.e[5]), [e6] "v"(q.e[6]), [e7] "v"(q.e[7]), [mask] "v"(mask), [l4] "v"(l4)
-        : "memory");
+        FOREST_LDS_CMP("v120", "f0") FOREST_LDS_CMP("v121", "f1") FOREST_LDS_CMP("v122", "f2")
+        FOREST_LDS_CMP("v123", "f3") FOREST_LDS_CMP("v124", "f4") FOREST_LDS_CMP("v125", "f5")
+        FOREST_LDS_CMP("v126", "f6") FOREST_LDS_CMP("v127", "f7")
+        : [e0] "+v"(q.e[0]), [e1] "+v"(q.e[1]), [e2] "+v"(q.e[2]), [e3] "+v"(q.e[3]), [e4] "+v"(q.e[4]),
+          [e5] "+v"(q.e[5]), [e6] "+v"(q.e[6]), [e7] "+v"(q.e[7]), [f0] "+v"(r.e[0]), [f1] "+v"(r.e[1]),
+          [f2] "+v"(r.e[2]), [f3] "+v"(r.e[3]), [f4] "+v"(r.e[4]), [f5] "+v"(r.e[5]), [f6] "+v"(r.e[6]),
+          [f7] "+v"(r.e[7])
+        : [mask] "v"(mask), [l4] "v"(l4)
+        : "memory", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122",
+          "v123", "v124", "v125", "v126", "v127");
 }
 
 // Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
@@ -119,13 +134,12 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     // number of groups of the wave's trees (n_words = number of groups of a tree); the last one
     // carries the closing flag of the last tree
     const int n_groups = (meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8 - pos) / 8;
-    // Three buffers in rotation, two groups in flight: group g uses buffer g mod 3 and, before it
-    // is evaluated, the fetch of group g + 2 into the buffer group g - 1 has just released is
-    // issued.  The loop is unrolled by three so that no buffer is ever copied.
+    // Three pairs of groups in rotation: while one pair is evaluated the fetches of the next two
+    // are in flight; a pair's registers are refilled as soon as the pair has been evaluated.
     const uint32_t *__restrict__ p = m.prog32 + pos;
-    Entry8 buf0 = load_group(p);
-    Entry8 buf1 = load_group(p + 8);
-    Entry8 buf2;
+    Entry8 pa0 = load_group(p), pa1 = load_group(p + 8);
+    Entry8 pb0 = load_group(p + 16), pb1 = load_group(p + 24);
+    Entry8 pc0 = load_group(p + 32), pc1 = load_group(p + 40);
     int t = t_begin;
     int level_start = pos;  // stream position of the current level's first entry
     int chunk = 0;          // chunk index inside the level
@@ -200,38 +214,46 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             ref[0] = ref[1] = meta[t].root_ref;
         }
     };
-    // The matrix core is still collecting a group's bits when its comparisons have issued, so
-    // the walk consumes every group one group late: after the comparisons of the next one.
+    // The matrix core is still collecting a pair's bits when its comparisons have issued, so
+    // the walk consumes every pair one pair late: after the comparisons of the next one.
     BitCollector bits;
     bits.init(lane);
-    v4f prev_g = bits.bias;
-    uint32_t prev_flags = 0;
-    bool have_prev = false;  // wave-uniform
-    auto one_group = [&](const Entry8 &cur) {
-        const uint32_t flags = static_cast<uint32_t>(uniform(static_cast<int>(cur.e[0])));
-        uint32_t d[8];
-        eval_group(d, cur, mask, l4);
+    v4f prev_g0 = bits.bias, prev_g1 = bits.bias;
+    uint32_t prev_f0 = 0, prev_f1 = 0;
+    int prev_count = 0;  // wave-uniform: groups of the previous pair that belong to the wave
+    auto one_pair = [&](Entry8 q, Entry8 r, int count) {
+        const uint32_t f0 = static_cast<uint32_t>(uniform(static_cast<int>(q.e[0])));
+        const uint32_t f1 = static_cast<uint32_t>(uniform(static_cast<int>(r.e[0])));
+        eval_pair(q, r, mask, l4);
 #if defined(__HIP_DEVICE_COMPILE__)
         __builtin_amdgcn_sched_barrier(0);
 #endif
-        if (have_prev) consume(prev_g, prev_flags);
-        prev_g = bits.template collect<0>(d, bits.bias);
-        prev_flags = flags;
-        have_prev = true;
+        if (prev_count > 0) consume(prev_g0, prev_f0);
+        if (prev_count > 1) consume(prev_g1, prev_f1);
+        prev_g0 = bits.template collect<0>(q.e, bits.bias);
+        prev_g1 = bits.template collect<0>(r.e, bits.bias);
+        prev_f0 = f0;
+        prev_f1 = f1;
+        prev_count = count;
     };
     // The fetches are unconditional (past the end of the wave's stream they read the next
-    // wave's groups or the padding at the end of the program), so that exactly two fetches are
-    // issued between a buffer's fill and its use on every path.
-    for (int group = 0; group < n_groups; group += 3) {
-        buf2 = load_group(p + 16);
-        one_group(buf0);
-        buf0 = load_group(p + 24);
-        if (group + 1 < n_groups) one_group(buf1);
-        buf1 = load_group(p + 32);
-        if (group + 2 < n_groups) one_group(buf2);
-        p += 24;
+    // wave's groups or the padding at the end of the program), so that the same number of
+    // fetches is issued between a buffer's fill and its use on every path.
+    static_assert(PROGRAM_PAD_ENTRIES >= 88, "the last fetches reach 87 entries past a wave's stream");
+    for (int group = 0; group < n_groups; group += 6) {
+        one_pair(pa0, pa1, n_groups - group);
+        pa0 = load_group(p + 48);
+        pa1 = load_group(p + 56);
+        if (group + 2 < n_groups) one_pair(pb0, pb1, n_groups - group - 2);
+        pb0 = load_group(p + 64);
+        pb1 = load_group(p + 72);
+        if (group + 4 < n_groups) one_pair(pc0, pc1, n_groups - group - 4);
+        pc0 = load_group(p + 80);
+        pc1 = load_group(p + 88);
+        p += 48;
     }
-    consume(prev_g, prev_flags);  // n_groups >= 1: the wave has at least one tree
+    if (prev_count > 0) consume(prev_g0, prev_f0);
+    if (prev_count > 1) consume(prev_g1, prev_f1);
 }
 
 __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, const float *__restrict__ X,

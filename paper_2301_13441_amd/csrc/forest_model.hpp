@@ -39,6 +39,8 @@ constexpr int RANK_MAX_PIVOTS = 4096;  // pivot thresholds staged in LDS by ever
 constexpr int RANKLDS_MAX_PIVOTS = 2048;       // smaller pivot budget: two workgroups share a CU's LDS
 constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
 constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel
+constexpr int PROGRAM_PAD_ENTRIES = 96;        // readable entries after the last tree's
+constexpr int RANKLDS_WAVES = 8;               // wavefronts per workgroup of that kernel
 
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {

@@ -249,13 +249,13 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
     }
     if (m.path == PATH_LDS && T > 0) {
-        // Rank family with the ranks held in LDS: any tree shape.  Needs, per workgroup of 8
-        // waves: the rank tile, the pivots (later one chunk of outcome bytes per wave) and, unless
+        // Rank family with the ranks held in LDS: any tree shape.  Needs, per workgroup of
+        // RANKLDS_WAVES waves: the rank tile, the pivots (later one chunk of outcome bytes per wave) and, unless
         // the partial sums can wait in registers, the partial sums.
         const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
         const size_t front = sizeof(uint32_t) * 64 * static_cast<size_t>(std::max<int64_t>(regs, 1)) +
-                             std::max(sizeof(float) * RANKLDS_MAX_PIVOTS, size_t{8} * 8 * 2 * 64);
-        const size_t sums = sizeof(double) * 8 * K * 128;
+                             std::max(sizeof(float) * RANKLDS_MAX_PIVOTS, size_t{RANKLDS_WAVES} * 8 * 2 * 64);
+        const size_t sums = sizeof(double) * RANKLDS_WAVES * K * 128;
         const size_t lds = deferred ? std::max(front, sums) : front + sums;
         if (regs <= RANKLDS_MAX_REGS && lds <= RANKLDS_MAX_LDS) {
             m.path = PATH_RANK_LDS;
@@ -401,8 +401,9 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         m.tree.push_back(tm);
     }
     m.tree.push_back(TreeMeta{});  // spare record: the stream kernels read the root of "the next tree"
-    // Padding: the kernels prefetch up to five groups past the entries they evaluate.
-    for (int j = 0; j < 64; ++j) m.prog.push_back(pad);
+    // Padding: the kernels prefetch (and may evaluate, without using the result) up to eleven
+    // groups past the entries of their trees.
+    for (int j = 0; j < PROGRAM_PAD_ENTRIES; ++j) m.prog.push_back(pad);
     if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
         // compact form: one dword per entry, f16(-j') in the high half.  RANK: rank register in
         // the low byte.  RANK_LDS: rank register in bits 8..15 (its LDS row offset is reg * 256),
