@@ -38,9 +38,13 @@ typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
 typedef const TreeMeta *MetaPtr;  // host pass: the kernel body is only parsed
 #endif
 
-struct Entry8 {
-    uint32_t e[8];
-};
+typedef uint32_t v16u __attribute__((ext_vector_type(16)));
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) uint32_t *StreamPtr;
+#else
+typedef const uint32_t *StreamPtr;  // host pass: the kernel body is only parsed
+#endif
 
 // LDS between the rank tile and the partial sums: the pivots during the prologue, then one
 // chunk of outcome bytes (8 groups x 2 rows x 64 lanes) per wave.
@@ -51,61 +55,75 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int n_pivots)
     return ((piv > buf ? piv : buf) + 15) / 16 * 16;
 }
 
-// Every lane loads the same eight words (one 32-byte piece of the stream).
-__device__ __forceinline__ Entry8 load_group(const uint32_t *__restrict__ p)
+// A pair of groups (16 entries) is evaluated from 16 scalar registers: s[36:51] for even pairs,
+// s[52:67] for odd pairs.  One entry: address of its rank row into a scratch register, the LDS
+// read, and the comparison, which leaves the outcome (1.0 or 0.0 in each f16 half) there.
+#define FOREST_LDS_ADDR(t, e) "v_and_or_b32 " t ", " e ", %[mask], %[l4]\n\t"
+#define FOREST_LDS_READ(t) "ds_read_b32 " t ", " t "\n\t"
+#define FOREST_LDS_CMP(t, e) "v_pk_add_f16 " t ", " t ", " e " op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)        \
+    "s_mov_b32 %[f0], " S0 "\n\t"                                                                              \
+    "s_mov_b32 %[f1], " S8 "\n\t"                                                                              \
+    FOREST_LDS_ADDR("v112", S0) FOREST_LDS_ADDR("v113", S1) FOREST_LDS_ADDR("v114", S2)                         \
+    FOREST_LDS_ADDR("v115", S3) FOREST_LDS_ADDR("v116", S4) FOREST_LDS_ADDR("v117", S5)                         \
+    FOREST_LDS_ADDR("v118", S6) FOREST_LDS_ADDR("v119", S7)                                                     \
+    FOREST_LDS_READ("v112") FOREST_LDS_READ("v113") FOREST_LDS_READ("v114") FOREST_LDS_READ("v115")             \
+    FOREST_LDS_READ("v116") FOREST_LDS_READ("v117") FOREST_LDS_READ("v118") FOREST_LDS_READ("v119")             \
+    FOREST_LDS_ADDR("v120", S8) FOREST_LDS_ADDR("v121", S9) FOREST_LDS_ADDR("v122", S10)                        \
+    FOREST_LDS_ADDR("v123", S11) FOREST_LDS_ADDR("v124", S12) FOREST_LDS_ADDR("v125", S13)                      \
+    FOREST_LDS_ADDR("v126", S14) FOREST_LDS_ADDR("v127", S15)                                                   \
+    FOREST_LDS_READ("v120") FOREST_LDS_READ("v121") FOREST_LDS_READ("v122") FOREST_LDS_READ("v123")             \
+    FOREST_LDS_READ("v124") FOREST_LDS_READ("v125") FOREST_LDS_READ("v126") FOREST_LDS_READ("v127")             \
+    "s_waitcnt lgkmcnt(8)\n\t"                                                                                 \
+    FOREST_LDS_CMP("v112", S0) FOREST_LDS_CMP("v113", S1) FOREST_LDS_CMP("v114", S2) FOREST_LDS_CMP("v115", S3) \
+    FOREST_LDS_CMP("v116", S4) FOREST_LDS_CMP("v117", S5) FOREST_LDS_CMP("v118", S6) FOREST_LDS_CMP("v119", S7) \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                 \
+    FOREST_LDS_CMP("v120", S8) FOREST_LDS_CMP("v121", S9) FOREST_LDS_CMP("v122", S10)                           \
+    FOREST_LDS_CMP("v123", S11) FOREST_LDS_CMP("v124", S12) FOREST_LDS_CMP("v125", S13)                         \
+    FOREST_LDS_CMP("v126", S14) FOREST_LDS_CMP("v127", S15)                                                     \
+    "s_load_dwordx16 " SET ", %[p], " NEXT
+
+// Two groups of 8 entries for the lane's two rows.  All 16 LDS reads are issued before the
+// first comparison, so the LDS latency is paid once per pair.  LDS operations complete in
+// order, whatever scalar loads are also outstanding, so "at most 8 outstanding" means the first
+// eight reads have returned; the closing "none outstanding" also completes the scalar load the
+// PREVIOUS pair issued, i.e. the entries of the NEXT pair.  The statement ends by fetching, into
+// the scalar registers it has just used, the entries of the pair after the next one (two pairs
+// = 128 bytes ahead); that load is in flight while the compiler's code between two statements
+// runs, which never touches those registers: they are carried from statement to statement as
+// one 16-register value pinned to s[36:51] resp. s[52:67].
+//
+// d0, d1: the outcomes of the two groups, the matrix core's B operands.  f0, f1: the first
+// entry of each group (its low byte holds the group's flags).
+__device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
+                                               StreamPtr p, uint32_t mask, uint32_t l4)
 {
-    const uint4 lo = *reinterpret_cast<const uint4 *>(p);
-    const uint4 hi = *reinterpret_cast<const uint4 *>(p + 4);
-    Entry8 q;
-    q.e[0] = lo.x; q.e[1] = lo.y; q.e[2] = lo.z; q.e[3] = lo.w;
-    q.e[4] = hi.x; q.e[5] = hi.y; q.e[6] = hi.z; q.e[7] = hi.w;
-    return q;
+    asm volatile(FOREST_LDS_PAIR("s36", "s37", "s38", "s39", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47",
+                                 "s48", "s49", "s50", "s51", "s[36:51]", "0x80")
+                 : "={v[112:119]}"(d0), "={v[120:127]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
+                 : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
+                 : "memory");
 }
 
-// One entry of a pair of groups: address of its rank row into a scratch register, the read, and
-// the comparison, which overwrites the entry with its outcome.
-#define FOREST_LDS_ADDR(t, e) "v_and_or_b32 " t ", %[" e "], %[mask], %[l4]\n\t"
-#define FOREST_LDS_READ(t) "ds_read_b32 " t ", " t "\n\t"
-#define FOREST_LDS_CMP(t, e) "v_pk_add_f16 %[" e "], " t ", %[" e "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
-
-// Two groups of 8 entries for the lane's two rows: every entry is replaced by its comparison
-// outcome (1.0 or 0.0 in each f16 half), which the matrix core then turns into one outcome byte
-// per group and row (first entry in bit 7).  All 16 LDS reads are issued before the first
-// comparison, so the LDS latency is paid once per pair; they land in v112..v127, which the
-// statement names as clobbered.  LDS operations complete in order, whatever scalar loads are
-// also outstanding: "at most 8 outstanding" means the first eight reads have returned.
-//
-// The entries arrive through the vector memory path (every lane loads the same words), not
-// through scalar loads: vector loads are counted in vmcnt, so waiting for the LDS reads
-// (lgkmcnt) never waits for the program stream, which is fetched one pair ahead.
-__device__ __forceinline__ void eval_pair(Entry8 &q, Entry8 &r, uint32_t mask, uint32_t l4)
+__device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
+                                              StreamPtr p, uint32_t mask, uint32_t l4)
 {
-    asm volatile(
-        FOREST_LDS_ADDR("v112", "e0") FOREST_LDS_ADDR("v113", "e1") FOREST_LDS_ADDR("v114", "e2")
-        FOREST_LDS_ADDR("v115", "e3") FOREST_LDS_ADDR("v116", "e4") FOREST_LDS_ADDR("v117", "e5")
-        FOREST_LDS_ADDR("v118", "e6") FOREST_LDS_ADDR("v119", "e7")
-        FOREST_LDS_READ("v112") FOREST_LDS_READ("v113") FOREST_LDS_READ("v114") FOREST_LDS_READ("v115")
-        FOREST_LDS_READ("v116") FOREST_LDS_READ("v117") FOREST_LDS_READ("v118") FOREST_LDS_READ("v119")
-        FOREST_LDS_ADDR("v120", "f0") FOREST_LDS_ADDR("v121", "f1") FOREST_LDS_ADDR("v122", "f2")
-        FOREST_LDS_ADDR("v123", "f3") FOREST_LDS_ADDR("v124", "f4") FOREST_LDS_ADDR("v125", "f5")
-        FOREST_LDS_ADDR("v126", "f6") FOREST_LDS_ADDR("v127", "f7")
-        FOREST_LDS_READ("v120") FOREST_LDS_READ("v121") FOREST_LDS_READ("v122") FOREST_LDS_READ("v123")
-        FOREST_LDS_READ("v124") FOREST_LDS_READ("v125") FOREST_LDS_READ("v126") FOREST_LDS_READ("v127")
-        "s_waitcnt lgkmcnt(8)\n\t"
-        FOREST_LDS_CMP("v112", "e0") FOREST_LDS_CMP("v113", "e1") FOREST_LDS_CMP("v114", "e2")
-        FOREST_LDS_CMP("v115", "e3") FOREST_LDS_CMP("v116", "e4") FOREST_LDS_CMP("v117", "e5")
-        FOREST_LDS_CMP("v118", "e6") FOREST_LDS_CMP("v119", "e7")
-        "s_waitcnt lgkmcnt(0)\n\t"
-        FOREST_LDS_CMP("v120", "f0") FOREST_LDS_CMP("v121", "f1") FOREST_LDS_CMP("v122", "f2")
-        FOREST_LDS_CMP("v123", "f3") FOREST_LDS_CMP("v124", "f4") FOREST_LDS_CMP("v125", "f5")
-        FOREST_LDS_CMP("v126", "f6") FOREST_LDS_CMP("v127", "f7")
-        : [e0] "+v"(q.e[0]), [e1] "+v"(q.e[1]), [e2] "+v"(q.e[2]), [e3] "+v"(q.e[3]), [e4] "+v"(q.e[4]),
-          [e5] "+v"(q.e[5]), [e6] "+v"(q.e[6]), [e7] "+v"(q.e[7]), [f0] "+v"(r.e[0]), [f1] "+v"(r.e[1]),
-          [f2] "+v"(r.e[2]), [f3] "+v"(r.e[3]), [f4] "+v"(r.e[4]), [f5] "+v"(r.e[5]), [f6] "+v"(r.e[6]),
-          [f7] "+v"(r.e[7])
-        : [mask] "v"(mask), [l4] "v"(l4)
-        : "memory", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122",
-          "v123", "v124", "v125", "v126", "v127");
+    asm volatile(FOREST_LDS_PAIR("s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63",
+                                 "s64", "s65", "s66", "s67", "s[52:67]", "0xc0")
+                 : "={v[112:119]}"(d0), "={v[120:127]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
+                 : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
+                 : "memory");
+}
+
+// The first two pairs of a wave's stream into the two register sets.
+__device__ __forceinline__ void load_first_pairs(v16u &even, v16u &odd, StreamPtr p)
+{
+    asm volatile("s_load_dwordx16 s[36:51], %[p], 0x0\n\t"
+                 "s_load_dwordx16 s[52:67], %[p], 0x40\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "={s[36:51]}"(even), "={s[52:67]}"(odd)
+                 : [p] "s"(p)
+                 : "memory");
 }
 
 // Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
@@ -134,12 +152,10 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     // number of groups of the wave's trees (n_words = number of groups of a tree); the last one
     // carries the closing flag of the last tree
     const int n_groups = (meta[t_end - 1].prog_base + meta[t_end - 1].n_words * 8 - pos) / 8;
-    // Three pairs of groups in rotation: while one pair is evaluated the fetches of the next two
-    // are in flight; a pair's registers are refilled as soon as the pair has been evaluated.
-    const uint32_t *__restrict__ p = m.prog32 + pos;
-    Entry8 pa0 = load_group(p), pa1 = load_group(p + 8);
-    Entry8 pb0 = load_group(p + 16), pb1 = load_group(p + 24);
-    Entry8 pc0 = load_group(p + 32), pc1 = load_group(p + 40);
+    // The stream lives in scalar registers, two pairs of groups (2 x 16 entries) at a time.
+    StreamPtr p = (StreamPtr)(m.prog32 + pos);
+    v16u set_even, set_odd;
+    load_first_pairs(set_even, set_odd, p);
     int t = t_begin;
     int level_start = pos;  // stream position of the current level's first entry
     int chunk = 0;          // chunk index inside the level
@@ -221,37 +237,35 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     v4f prev_g0 = bits.bias, prev_g1 = bits.bias;
     uint32_t prev_f0 = 0, prev_f1 = 0;
     int prev_count = 0;  // wave-uniform: groups of the previous pair that belong to the wave
-    auto one_pair = [&](Entry8 q, Entry8 r, int count) {
-        const uint32_t f0 = static_cast<uint32_t>(uniform(static_cast<int>(q.e[0])));
-        const uint32_t f1 = static_cast<uint32_t>(uniform(static_cast<int>(r.e[0])));
-        eval_pair(q, r, mask, l4);
+    auto after_pair = [&](const v8i &d0, const v8i &d1, uint32_t f0, uint32_t f1, int count) {
 #if defined(__HIP_DEVICE_COMPILE__)
         __builtin_amdgcn_sched_barrier(0);
 #endif
         if (prev_count > 0) consume(prev_g0, prev_f0);
         if (prev_count > 1) consume(prev_g1, prev_f1);
-        prev_g0 = bits.template collect<0>(q.e, bits.bias);
-        prev_g1 = bits.template collect<0>(r.e, bits.bias);
+        prev_g0 = bits.collect_b(d0, bits.bias);
+        prev_g1 = bits.collect_b(d1, bits.bias);
         prev_f0 = f0;
         prev_f1 = f1;
         prev_count = count;
     };
-    // The fetches are unconditional (past the end of the wave's stream they read the next
-    // wave's groups or the padding at the end of the program), so that the same number of
-    // fetches is issued between a buffer's fill and its use on every path.
-    static_assert(PROGRAM_PAD_ENTRIES >= 88, "the last fetches reach 87 entries past a wave's stream");
-    for (int group = 0; group < n_groups; group += 6) {
-        one_pair(pa0, pa1, n_groups - group);
-        pa0 = load_group(p + 48);
-        pa1 = load_group(p + 56);
-        if (group + 2 < n_groups) one_pair(pb0, pb1, n_groups - group - 2);
-        pb0 = load_group(p + 64);
-        pb1 = load_group(p + 72);
-        if (group + 4 < n_groups) one_pair(pc0, pc1, n_groups - group - 4);
-        pc0 = load_group(p + 80);
-        pc1 = load_group(p + 88);
-        p += 48;
+    // Every statement fetches two pairs ahead whatever the wave's own group count is (past the
+    // end of the wave's stream that is the next wave's groups or the padding at the end of the
+    // program), and a pair past the end is evaluated but not consumed.
+    static_assert(PROGRAM_PAD_ENTRIES >= 64, "the last fetch reaches 8 groups past a wave's stream");
+    for (int group = 0; group < n_groups; group += 4) {
+        v8i d0, d1;
+        uint32_t f0, f1;
+        eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
+        after_pair(d0, d1, f0, f1, n_groups - group);
+        if (group + 2 < n_groups) {
+            eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
+            after_pair(d0, d1, f0, f1, n_groups - group - 2);
+        }
+        p += 32;
     }
+    // the last statement's fetch is still in flight: let it land before the registers are reused
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+{s[36:51]}"(set_even), "+{s[52:67]}"(set_odd) : : "memory");
     if (prev_count > 0) consume(prev_g0, prev_f0);
     if (prev_count > 1) consume(prev_g1, prev_f1);
 }

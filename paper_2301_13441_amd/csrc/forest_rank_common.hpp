@@ -58,6 +58,15 @@ struct BitCollector {
         // keep the addend in registers instead of rebuilding it before every chain
         asm volatile("" : "+v"(bias));
     }
+    // the same with the eight outcome registers already in one tuple (weights 2^(7 - v))
+    __device__ __forceinline__ v4f collect_b(const v8i &b, v4f c) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[0], b, c, 1, 1, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+        return c;
+    }
     template <int J>
     __device__ __forceinline__ v4f collect(const uint32_t (&d)[8], v4f c) const
     {
