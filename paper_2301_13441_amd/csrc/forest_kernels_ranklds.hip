@@ -167,11 +167,11 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     constexpr int WAITING = static_cast<int>(0x80000000u);
     int ref[2];
     ChildRef pair[2];
-    uint32_t went_right[2];
+    uint32_t outcome[2], bit[2];  // the outcome byte that holds the lane's node, and the node's bit in it
     bool resolve = false;  // wave-uniform: a level has ended since the last resolution
     ref[0] = ref[1] = meta[t].root_ref;
     pair[0] = pair[1] = ChildRef{0, 0};
-    went_right[0] = went_right[1] = 0;
+    outcome[0] = outcome[1] = bit[0] = bit[1] = 0;
     // what the walk does with a group once its outcome bytes are known
     auto consume = [&](v4f g, uint32_t flags) {
         // low mantissa byte = outcome byte, of row A in g[0] and of row B in g[1]
@@ -183,15 +183,16 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             if (resolve) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
-                    if (ref[r] == WAITING) ref[r] = went_right[r] ? pair[r].right : pair[r].left;
+                    if (ref[r] == WAITING) ref[r] = ((outcome[r] >> bit[r]) & 1u) ? pair[r].right : pair[r].left;
                 resolve = false;
             }
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
-                    const uint32_t b = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
+                    // both fetches are only looked at when the child is picked, a group or more later
+                    outcome[r] = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
+                    bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
                     pair[r] = m.child[level_start + ref[r]];
-                    went_right[r] = (b >> (ref[r] & 7)) & 1u;
                     ref[r] = WAITING;
                 }
             }
@@ -206,7 +207,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         if (flags & 2u) {  // tree complete: every lane stands on a leaf
 #pragma unroll
             for (int r = 0; r < 2; ++r)
-                if (ref[r] == WAITING) ref[r] = went_right[r] ? pair[r].right : pair[r].left;
+                if (ref[r] == WAITING) ref[r] = ((outcome[r] >> bit[r]) & 1u) ? pair[r].right : pair[r].left;
             resolve = false;
             const TreeMeta tm = meta[t];
             if (MODE == MODE_GENERAL) accu.begin_tree(tm.column);
