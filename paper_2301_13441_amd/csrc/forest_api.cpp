@@ -128,8 +128,8 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_thrs = place<float>(cur, m.thr_sorted.size());
     const size_t o_ftb = place<int32_t>(cur, m.feat_thr_base.size());
     const size_t o_fvf = place<int32_t>(cur, m.feat_vfirst.size());
-    const size_t o_piv = place<float>(cur, m.pivots.size());
-    const size_t o_fpb = place<int32_t>(cur, m.feat_pivot_base.size());
+    const size_t o_fbk = place<FeatBucket>(cur, m.feat_bucket.size());
+    const size_t o_bst = place<int32_t>(cur, m.bucket_start.size());
     const size_t model_bytes = (cur + 255) & ~size_t{255};
     const size_t n_partial = static_cast<size_t>(split_workspace_doubles(m.n_outputs));
     const size_t o_part = place<double>(cur, n_partial);  // workspace of split launches, not uploaded
@@ -159,8 +159,8 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_thrs, m.thr_sorted.data(), m.thr_sorted.size() * sizeof(float)) &&
                     up(o_ftb, m.feat_thr_base.data(), m.feat_thr_base.size() * sizeof(int32_t)) &&
                     up(o_fvf, m.feat_vfirst.data(), m.feat_vfirst.size() * sizeof(int32_t)) &&
-                    up(o_piv, m.pivots.data(), m.pivots.size() * sizeof(float)) &&
-                    up(o_fpb, m.feat_pivot_base.data(), m.feat_pivot_base.size() * sizeof(int32_t));
+                    up(o_fbk, m.feat_bucket.data(), m.feat_bucket.size() * sizeof(FeatBucket)) &&
+                    up(o_bst, m.bucket_start.data(), m.bucket_start.size() * sizeof(int32_t));
     if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(f->blob);
@@ -189,11 +189,8 @@ int forest_load(const forest_desc *desc, forest **out)
     d.reg_nv = m.reg_nv;
     d.reg_r = m.reg_r;
     d.rank_regs = m.rank_regs;
-    d.rank_steps = m.rank_steps;
-    d.pivot_shift = m.pivot_shift;
-    d.n_pivots = static_cast<int32_t>(m.pivots.size());
-    d.pivots = reinterpret_cast<const float *>(b + o_piv);
-    d.feat_pivot_base = reinterpret_cast<const int32_t *>(b + o_fpb);
+    d.feat_bucket = reinterpret_cast<const FeatBucket *>(b + o_fbk);
+    d.bucket_start = reinterpret_cast<const int32_t *>(b + o_bst);
     d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);
     d.feat_thr_base = reinterpret_cast<const int32_t *>(b + o_ftb);
     d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);

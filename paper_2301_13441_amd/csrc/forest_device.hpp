@@ -24,9 +24,9 @@ struct DevModel {
     int32_t path;            // PATH_LDS / PATH_REG / PATH_RANK
     int32_t reg_nv, reg_r;   // REG family: 32 * reg_nv feature registers, reg_r rows per lane
     // RANK family
-    int32_t rank_regs, rank_steps, pivot_shift, n_pivots;
-    const float *pivots;
-    const int32_t *feat_pivot_base;
+    int32_t rank_regs;
+    const FeatBucket *feat_bucket;
+    const int32_t *bucket_start;
     const float *thr_sorted;
     const int32_t *feat_thr_base;
     const int32_t *feat_vfirst;

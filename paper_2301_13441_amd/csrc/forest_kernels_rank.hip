@@ -14,9 +14,8 @@
 // bit 7).  Four such bytes make one 32-bit heap-ordered outcome word, the same words the other
 // kernels use, and the walk, leaf gather and reduction are shared.
 //
-// Prologue: every workgroup computes the ranks of its 128 rows by a two-level binary search
-// (pivots staged in LDS, then one block of the sorted threshold table in global memory),
-// reading X coalesced.
+// Prologue: every workgroup computes the ranks of its 128 rows from per-feature bucket tables
+// (forest_rank_common.hpp).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -358,10 +357,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, BLOCK);
     } else {
-        float *piv = reinterpret_cast<float *>(smem + sizeof(uint32_t) * 32 * NVR * TILE);  // [n_pivots]
-        for (int i = threadIdx.x; i < m.n_pivots; i += BLOCK) piv[i] = m.pivots[i];
-        __syncthreads();
-        rank_rows<WAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+        rank_rows<WAVES>(rk, m, X, row0, n_rows, wave, lane);
     }
     __syncthreads();
     v32u x[NVR];
@@ -388,7 +384,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(
 size_t rank_lds_bytes(const DevModel &m, int nvr)
 {
     const size_t a = sizeof(double) * WAVES * m.n_outputs * RROWS;
-    const size_t b = sizeof(uint32_t) * 32 * nvr * TILE + sizeof(float) * m.n_pivots;
+    const size_t b = sizeof(uint32_t) * 32 * nvr * TILE;
     return a > b ? a : b;
 }
 

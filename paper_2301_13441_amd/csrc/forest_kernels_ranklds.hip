@@ -46,13 +46,11 @@ typedef const __attribute__((address_space(4))) uint32_t *StreamPtr;
 typedef const uint32_t *StreamPtr;  // host pass: the kernel body is only parsed
 #endif
 
-// LDS between the rank tile and the partial sums: the pivots during the prologue, then one
-// chunk of outcome bytes (8 groups x 2 rows x 64 lanes) per wave.
-__host__ __device__ inline size_t ranklds_region2_bytes(int n_pivots)
+// LDS between the rank tile and the partial sums: one chunk of outcome bytes (8 groups x 2 rows
+// x 64 lanes) per wave.
+__host__ __device__ inline size_t ranklds_region2_bytes()
 {
-    const size_t piv = sizeof(float) * static_cast<size_t>(n_pivots);
-    const size_t buf = static_cast<size_t>(LWAVES) * 8 * 2 * 64;
-    return ((piv > buf ? piv : buf) + 15) / 16 * 16;
+    return static_cast<size_t>(LWAVES) * 8 * 2 * 64;
 }
 
 // A pair of groups (16 entries) is evaluated from 16 scalar registers: s[36:51] for even pairs,
@@ -278,14 +276,14 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     extern __shared__ __align__(16) char smem[];
     const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
     const int K = m.n_outputs;
-    // LDS: [ rank tile | pivots, later one outcome-byte chunk per wave | partial sums (GENERAL) ].
+    // LDS: [ rank tile | one outcome-byte chunk per wave | partial sums (GENERAL) ].
     // The rank tile must start at LDS address 0: eval_group forms addresses as
     // (row offset | lane * 4).  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
     // every wave has finished.
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
     char *region2 = smem + sizeof(uint32_t) * TILE * regs;
     const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
-    const size_t r2_bytes = ranklds_region2_bytes(m.n_pivots);
+    const size_t r2_bytes = ranklds_region2_bytes();
     double *acc = deferred ? reinterpret_cast<double *>(smem) : reinterpret_cast<double *>(region2 + r2_bytes);
 
     const int lane = threadIdx.x & (TILE - 1);
@@ -296,12 +294,9 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, LBLOCK);
     } else {
-        float *piv = reinterpret_cast<float *>(region2);
-        for (int i = threadIdx.x; i < m.n_pivots; i += LBLOCK) piv[i] = m.pivots[i];
-        __syncthreads();
-        rank_rows<LWAVES>(rk, piv, m, X, row0, n_rows, wave, lane);
+        rank_rows<LWAVES>(rk, m, X, row0, n_rows, wave, lane);
     }
-    __syncthreads();  // ranks complete; the pivots are dead, their space becomes the byte chunks
+    __syncthreads();  // ranks complete
 
     uint8_t *bytes = reinterpret_cast<uint8_t *>(region2) + static_cast<size_t>(wave) * CHUNK_GROUPS * 2 * TILE;
     Accumulator<2> accu;
@@ -334,7 +329,7 @@ size_t ranklds_lds_bytes(const DevModel &m)
     const int K = m.n_outputs;
     const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
     const size_t sums = sizeof(double) * LWAVES * K * RROWS;
-    const size_t front = sizeof(uint32_t) * TILE * regs + ranklds_region2_bytes(m.n_pivots);
+    const size_t front = sizeof(uint32_t) * TILE * regs + ranklds_region2_bytes();
     return deferred ? (front > sums ? front : sums) : front + sums;
 }
 

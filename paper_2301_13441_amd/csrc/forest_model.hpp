@@ -35,12 +35,33 @@ constexpr int PATH_RANK_LDS = 3;  // any trees, packed f16 threshold ranks read 
 constexpr int RANK_SEG = 4095;
 constexpr int RANK_BIAS = 2048;
 constexpr int RANK_MAX_REGS = 128;
-constexpr int RANK_MAX_PIVOTS = 4096;  // pivot thresholds staged in LDS by every workgroup
-constexpr int RANKLDS_MAX_PIVOTS = 2048;       // smaller pivot budget: two workgroups share a CU's LDS
+constexpr int RANK_BUCKETS_PER_THRESHOLD = 2;  // resolution of the per-feature bucket tables
+constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature
 constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
 constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel
 constexpr int PROGRAM_PAD_ENTRIES = 96;        // readable entries after the last tree's
 constexpr int RANKLDS_WAVES = 8;               // wavefronts per workgroup of that kernel
+
+// Rank lookup of one feature: bucket(x) = trunc((x - lo) * scale) clamped to [0, n_buckets),
+// start[bucket] .. start[bucket + 1] bracket rank(x) in the feature's sorted thresholds.
+struct FeatBucket {
+    float lo, scale;
+    int32_t n_buckets;
+    int32_t start_base;  // offset of the feature's n_buckets + 1 entries in the start table
+};
+
+// The bucket of x; non-decreasing in x for every lo and scale >= 0 (float subtraction,
+// multiplication and truncation are monotone), NaN goes to bucket 0.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int32_t bucket_index(float x, float lo, float scale, int32_t n_buckets)
+{
+    const float t = (x - lo) * scale;
+    if (!(t > 0.0f)) return 0;
+    if (t >= static_cast<float>(n_buckets)) return n_buckets - 1;
+    return static_cast<int32_t>(t);
+}
 
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {
@@ -78,10 +99,8 @@ struct PackedModel {
     int32_t path = PATH_LDS;
     // rank family: X is rewritten, exactly, as per-feature threshold ranks (see forest_pack.cpp)
     int32_t rank_regs = 0;        // packed rank registers per lane (one per virtual feature)
-    int32_t rank_steps = 0;       // binary-search steps that cover the longest pivot list
-    int32_t pivot_shift = 0;      // every 2^pivot_shift-th threshold (the last of each block) is a pivot
-    std::vector<float> pivots;            // per feature: last threshold of each block, concatenated
-    std::vector<int32_t> feat_pivot_base; // [F + 1] offsets into pivots
+    std::vector<FeatBucket> feat_bucket;  // [F] bucket table of each feature
+    std::vector<int32_t> bucket_start;    // per feature: #thresholds in lower buckets, n_buckets + 1 entries
     std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
     std::vector<int32_t> feat_thr_base;   // [F + 1] offsets into thr_sorted
     std::vector<int32_t> feat_vfirst;     // [F] first rank register of the feature

@@ -197,7 +197,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         v.erase(std::unique(v.begin(), v.end()), v.end());  // -0 == +0: one threshold
         regs += static_cast<int64_t>((v.size() + RANK_SEG - 1) / RANK_SEG);
     }
-    auto build_rank_tables = [&](size_t max_pivots) {
+    auto build_rank_tables = [&]() {
         m.rank_regs = static_cast<int32_t>(regs);
         m.feat_thr_base.assign(1, 0);
         int32_t next_reg = 0;
@@ -207,33 +207,43 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
             m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
         }
-        // Two-level search: the last threshold of every block of 2^pivot_shift is a pivot; the
-        // pivots of all features fit RANK_MAX_PIVOTS and are searched in LDS, the block itself
-        // in global memory.
-        for (;; ++m.pivot_shift) {
-            size_t total = 0;
-            for (auto &v : per_feature) total += (v.size() + (size_t{1} << m.pivot_shift) - 1) >> m.pivot_shift;
-            if (total <= max_pivots) break;
-        }
-        const size_t block = size_t{1} << m.pivot_shift;
-        m.feat_pivot_base.assign(1, 0);
-        size_t most_pivots = 0;
+        // Bucket tables: a uniform grid over the feature's finite threshold range, about two
+        // buckets per threshold, and for every bucket the number of thresholds in lower buckets.
+        // bucket_index is monotone, so thresholds in lower buckets are below x and thresholds in
+        // higher buckets are not: start[b] <= rank(x) <= start[b + 1] for b = bucket(x).  The
+        // kernels check the bracket against the thresholds themselves before they trust it.
         for (auto &v : per_feature) {
-            for (size_t b = 0; b < v.size(); b += block) m.pivots.push_back(v[std::min(b + block, v.size()) - 1]);
-            most_pivots = std::max(most_pivots, (v.size() + block - 1) / block);
-            m.feat_pivot_base.push_back(static_cast<int32_t>(m.pivots.size()));
+            FeatBucket fb{0.0f, 0.0f, 1, static_cast<int32_t>(m.bucket_start.size())};
+            size_t a = 0, b = v.size();
+            while (a < b && !std::isfinite(v[a])) ++a;
+            while (b > a && !std::isfinite(v[b - 1])) --b;
+            if (b > a) {
+                fb.lo = v[a];
+                const float range = v[b - 1] - v[a];
+                const int64_t want = static_cast<int64_t>(v.size()) * RANK_BUCKETS_PER_THRESHOLD;
+                const int32_t nb = static_cast<int32_t>(std::min<int64_t>(want, RANK_MAX_BUCKETS));
+                const float scale = static_cast<float>(nb) / range;
+                if (range > 0.0f && std::isfinite(scale)) {
+                    fb.scale = scale;
+                    fb.n_buckets = nb;
+                }
+            }
+            size_t i = 0;
+            for (int32_t bk = 0; bk <= fb.n_buckets; ++bk) {
+                while (i < v.size() && bucket_index(v[i], fb.lo, fb.scale, fb.n_buckets) < bk) ++i;
+                m.bucket_start.push_back(static_cast<int32_t>(i));
+            }
+            m.feat_bucket.push_back(fb);
         }
-        while ((size_t{1} << m.rank_steps) < most_pivots + 1) ++m.rank_steps;
     };
     if (m.kind != KIND_GENERIC) {
         const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128,
-                                         sizeof(uint32_t) * 64 * static_cast<size_t>(regs > 64 ? 128 : 64) +
-                                             sizeof(float) * RANK_MAX_PIVOTS);
+                                         sizeof(uint32_t) * 64 * static_cast<size_t>(regs > 64 ? 128 : 64));
         if (regs <= RANK_MAX_REGS && rank_lds <= 64 * 1024) {
             m.path = PATH_RANK;
             m.x_in_registers = 1;
             m.reg_r = 2;
-            build_rank_tables(RANK_MAX_PIVOTS);
+            build_rank_tables();
         } else if (d.n_features <= 128) {
             // float32 features in vector registers
             m.reg_nv = d.n_features <= 32 ? 1 : d.n_features <= 64 ? 2 : 4;
@@ -250,16 +260,16 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     }
     if (m.path == PATH_LDS && T > 0) {
         // Rank family with the ranks held in LDS: any tree shape.  Needs, per workgroup of
-        // RANKLDS_WAVES waves: the rank tile, the pivots (later one chunk of outcome bytes per wave) and, unless
-        // the partial sums can wait in registers, the partial sums.
+        // RANKLDS_WAVES waves: the rank tile, one chunk of outcome bytes per wave and, unless the
+        // partial sums can wait in registers, the partial sums.
         const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
         const size_t front = sizeof(uint32_t) * 64 * static_cast<size_t>(std::max<int64_t>(regs, 1)) +
-                             std::max(sizeof(float) * RANKLDS_MAX_PIVOTS, size_t{RANKLDS_WAVES} * 8 * 2 * 64);
+                             size_t{RANKLDS_WAVES} * 8 * 2 * 64;
         const size_t sums = sizeof(double) * RANKLDS_WAVES * K * 128;
         const size_t lds = deferred ? std::max(front, sums) : front + sums;
         if (regs <= RANKLDS_MAX_REGS && lds <= RANKLDS_MAX_LDS) {
             m.path = PATH_RANK_LDS;
-            build_rank_tables(RANKLDS_MAX_PIVOTS);
+            build_rank_tables();
         }
     }
     const int32_t feature_scale = m.path == PATH_REG ? 1 : 64;

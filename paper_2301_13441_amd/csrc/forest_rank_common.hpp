@@ -82,53 +82,79 @@ struct BitCollector {
 
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) int32_t *RankTablePtr;
+typedef const __attribute__((address_space(4))) FeatBucket *BucketPtr;
 #else
 typedef const int32_t *RankTablePtr;  // host pass: the kernel body is only parsed
+typedef const FeatBucket *BucketPtr;
 #endif
 
-// The same ranks for a tile with few valid rows (the tail of a batch, or a small batch): the
-// (row, feature) pairs are dealt to the threads, so the searches of one row run side by side
-// instead of one feature after the other; the rest of the tile gets rank 0.  Xt points at the
-// tile's first row.
+// Bracket of rank(x) from the feature's bucket table; every candidate in [lo, hi] is a rank.
+struct RankBracket {
+    int lo, hi;
+};
+
+__device__ __forceinline__ RankBracket bucket_bracket(const FeatBucket &fb, const int32_t *__restrict__ start, float x)
+{
+    const int32_t *s = start + fb.start_base + bucket_index(x, fb.lo, fb.scale, fb.n_buckets);
+    return RankBracket{s[0], s[1]};
+}
+
+// Whether [lo, hi] really brackets rank(x) = #{i : thr[i] < x} in the n sorted thresholds.  It
+// does whenever the table was built with the arithmetic bucket_index runs here; checking it
+// against the thresholds makes the result independent of that.
+__device__ __forceinline__ bool bracket_holds(const float *__restrict__ thr, int n, RankBracket b, float x)
+{
+    const bool below = b.lo == 0 || thr[b.lo - 1] < x;
+    const bool above = b.hi == n || !(thr[b.hi] < x);
+    return below && above;
+}
+
+// One lane, one (row, feature): the rank of x among the feature's thresholds (all for NaN).
+__device__ __forceinline__ int rank_of(const DevModel &m, int f, float x)
+{
+    const int tb = m.feat_thr_base[f];
+    const int n = m.feat_thr_base[f + 1] - tb;
+    if (x != x) return n;  // NaN is right of every threshold
+    const float *__restrict__ thr = m.thr_sorted + tb;
+    RankBracket b = bucket_bracket(m.feat_bucket[f], m.bucket_start, x);
+    if (!bracket_holds(thr, n, b, x)) b = RankBracket{0, n};
+    while (b.lo < b.hi) {
+        const int mid = (b.lo + b.hi) >> 1;
+        if (thr[mid] < x) b.lo = mid + 1;
+        else b.hi = mid;
+    }
+    return b.lo;
+}
+
+// Writes the rank of tile row r for feature f into the packed tile: one f16 per rank register of
+// the feature; tile row r lives in lane r % 64, low half for r < 64, high half above.
+__device__ __forceinline__ void store_rank(uint16_t *tile16, const DevModel &m, int f, int r, int rank)
+{
+    const int n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
+    const int reg0 = m.feat_vfirst[f];
+    for (int sgm = 0, first = 0; first < n; ++sgm, first += RANK_SEG) {
+        const int len = n - first < RANK_SEG ? n - first : RANK_SEG;
+        int rv = rank - first;
+        rv = rv < 0 ? 0 : (rv > len ? len : rv);
+        tile16[((reg0 + sgm) * TILE + (r & (TILE - 1))) * 2 + (r >> 6)] = f16_bits(rv - RANK_BIAS);
+    }
+}
+
+// Ranks of a tile with few valid rows (the tail of a batch): the (row, feature) pairs are dealt
+// to the threads, so the searches of one row run side by side instead of one feature after the
+// other; the rest of the tile gets rank 0.  Xt points at the tile's first row.
 template <int NWAVES>
-__device__ __forceinline__ void rank_rows_few(uint32_t *rk, const float *piv, const DevModel &m,
-                                              const float *__restrict__ Xt, int n_valid)
+__device__ __forceinline__ void rank_rows_few(uint32_t *rk, const DevModel &m, const float *__restrict__ Xt,
+                                              int n_valid)
 {
     const int F = m.n_features;
     const int n_threads = NWAVES * TILE;
-    const int block = 1 << m.pivot_shift;
     for (int i = threadIdx.x; i < m.rank_regs * TILE; i += n_threads) rk[i] = 0;
     __syncthreads();
     uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
     for (int w = threadIdx.x; w < n_valid * F; w += n_threads) {
         const int r = w / F, f = w - r * F;
-        const float x = Xt[w];
-        const int tb = m.feat_thr_base[f];
-        const int n_thr = m.feat_thr_base[f + 1] - tb;
-        const int pb = m.feat_pivot_base[f];
-        int lo = 0, hi = m.feat_pivot_base[f + 1] - pb;
-        while (lo < hi) {  // first block whose last threshold is not below x
-            const int mid = (lo + hi) >> 1;
-            if (piv[pb + mid] < x) lo = mid + 1;
-            else hi = mid;
-        }
-        lo = lo << m.pivot_shift;
-        hi = lo + block < n_thr ? lo + block : n_thr;
-        if (lo > hi) lo = hi;  // x is above every pivot: rank = n_thr
-        while (lo < hi) {      // position inside the block
-            const int mid = (lo + hi) >> 1;
-            if (m.thr_sorted[tb + mid] < x) lo = mid + 1;
-            else hi = mid;
-        }
-        const int rank = (x != x) ? n_thr : lo;  // NaN is right of every threshold
-        const int reg0 = m.feat_vfirst[f];
-        for (int sgm = 0, first = 0; first < n_thr; ++sgm, first += RANK_SEG) {
-            const int len = n_thr - first < RANK_SEG ? n_thr - first : RANK_SEG;
-            int rv = rank - first;
-            rv = rv < 0 ? 0 : (rv > len ? len : rv);
-            // tile row r lives in lane r % 64, low half for r < 64, high half above
-            rk16[((reg0 + sgm) * TILE + (r & (TILE - 1))) * 2 + (r >> 6)] = f16_bits(rv - RANK_BIAS);
-        }
+        store_rank(rk16, m, f, r, rank_of(m, f, Xt[w]));
     }
 }
 
@@ -143,27 +169,26 @@ __device__ __forceinline__ void load_rank_tile(uint32_t *rk, const DevModel &m, 
 
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
 // pairs into rk[reg * 64 + lane] (low half: row `lane` of the tile, high half: row lane + 64).
-// The features are dealt to the waves; inside a wave every lane searches the same feature for
-// its own two rows, two features at a time, so the per-feature tables are read with scalar
-// loads and the 64 lanes' probes fall into one table.  Two-level search: first over the
-// feature's pivots (LDS: the last threshold of every block of 2^pivot_shift), then inside one
-// block of the sorted table (global memory).
+// The features are dealt to the waves; inside a wave every lane looks up the same feature for
+// its own two rows, two features at a time (four lookups in flight per lane), so the feature's
+// constants are read with scalar loads.  A lookup is a bucket (a subtraction, a multiplication,
+// a conversion), the bucket's bracket from the start table, the check of the bracket against
+// the two thresholds next to it, and a binary search inside the bracket, which is a step or
+// two for most inputs.
 template <int NWAVES>
-__device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const DevModel &m,
-                                          const float *__restrict__ X, int64_t row0, int64_t n_rows, int wave,
-                                          int lane)
+__device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
+                                          int64_t row0, int64_t n_rows, int wave, int lane)
 {
-    constexpr int U = 2;  // features searched together (2 rows each: 4 searches in flight per lane)
+    constexpr int U = 2;
     const int F = m.n_features;
-    const int block = 1 << m.pivot_shift;
     const int64_t left = n_rows - row0;
     if (left * 4 <= RROWS) {  // workgroup-uniform
-        rank_rows_few<NWAVES>(rk, piv, m, X + row0 * F, static_cast<int>(left));
+        rank_rows_few<NWAVES>(rk, m, X + row0 * F, static_cast<int>(left));
         return;
     }
     RankTablePtr thr_base = (RankTablePtr)m.feat_thr_base;
-    RankTablePtr piv_base = (RankTablePtr)m.feat_pivot_base;
     RankTablePtr vfirst = (RankTablePtr)m.feat_vfirst;
+    BucketPtr buckets = (BucketPtr)m.feat_bucket;
     const float *xrow[2];
     bool have[2];
 #pragma unroll
@@ -174,51 +199,41 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const 
     }
     for (int f0 = wave * U; f0 < F; f0 += NWAVES * U) {
         float x[U][2];
-        int lo[U][2], hi[U][2], tb[U], n_thr[U], pb[U];
+        RankBracket b[U][2];
+        int tb[U], n_thr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int f = f0 + u < F ? f0 + u : F - 1;  // wave-uniform; the duplicate is not stored
             tb[u] = thr_base[f];
             n_thr[u] = thr_base[f + 1] - tb[u];
-            pb[u] = piv_base[f];
-            const int n_piv = piv_base[f + 1] - pb[u];
+            FeatBucket fb;
+            fb.lo = buckets[f].lo;
+            fb.scale = buckets[f].scale;
+            fb.n_buckets = buckets[f].n_buckets;
+            fb.start_base = buckets[f].start_base;
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 x[u][r] = have[r] ? xrow[r][f] : 0.0f;
-                lo[u][r] = 0;
-                hi[u][r] = n_piv;
+                b[u][r] = bucket_bracket(fb, m.bucket_start, x[u][r]);
             }
-        }
-        // first block whose last threshold is not below x
-        for (int s = 0; s < m.rank_steps; ++s) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    if (lo[u][r] < hi[u][r]) {
-                        const int mid = (lo[u][r] + hi[u][r]) >> 1;
-                        if (piv[pb[u] + mid] < x[u][r]) lo[u][r] = mid + 1;
-                        else hi[u][r] = mid;
-                    }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                lo[u][r] = lo[u][r] << m.pivot_shift;
-                hi[u][r] = lo[u][r] + block < n_thr[u] ? lo[u][r] + block : n_thr[u];
-                if (lo[u][r] > hi[u][r]) lo[u][r] = hi[u][r];  // x is above every pivot: rank = n_thr
-            }
-        // position inside the block
-        for (int s = 0; s <= m.pivot_shift; ++s) {
+            for (int r = 0; r < 2; ++r)
+                if (!bracket_holds(m.thr_sorted + tb[u], n_thr[u], b[u][r], x[u][r])) b[u][r] = RankBracket{0, n_thr[u]};
+        bool more = true;
+        while (more) {
+            more = false;
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
-                    if (lo[u][r] < hi[u][r]) {
-                        const int mid = (lo[u][r] + hi[u][r]) >> 1;
-                        if (m.thr_sorted[tb[u] + mid] < x[u][r]) lo[u][r] = mid + 1;
-                        else hi[u][r] = mid;
+                    if (b[u][r].lo < b[u][r].hi) {
+                        const int mid = (b[u][r].lo + b[u][r].hi) >> 1;
+                        if (m.thr_sorted[tb[u] + mid] < x[u][r]) b[u][r].lo = mid + 1;
+                        else b[u][r].hi = mid;
+                        more = true;
                     }
         }
 #pragma unroll
@@ -227,7 +242,7 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const float *piv, const 
             int rank[2];
 #pragma unroll
             for (int r = 0; r < 2; ++r)
-                rank[r] = (x[u][r] != x[u][r]) ? n_thr[u] : lo[u][r];  // NaN is right of every threshold
+                rank[r] = (x[u][r] != x[u][r]) ? n_thr[u] : b[u][r].lo;  // NaN is right of every threshold
             const int reg0 = vfirst[f0 + u];
             for (int s = 0, first = 0; first < n_thr[u]; ++s, first += RANK_SEG) {
                 const int len = n_thr[u] - first < RANK_SEG ? n_thr[u] - first : RANK_SEG;
