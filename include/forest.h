@@ -150,6 +150,11 @@ int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32
  * compiles `desc` exactly as forest_load does, without uploading, and evaluates nothing.
  * The arrays below are HOST memory owned by the handle, valid until forest_pack_free.
  */
+struct forest_rank_bucket {
+    float lo, scale;
+    int32_t n_buckets, start_base;
+};
+
 typedef struct forest_packed_view {
     int32_t n_trees;
     int32_t kernel_kind;            /* common depth of a forest of full trees (1..8), else 0 */
@@ -166,6 +171,15 @@ typedef struct forest_packed_view {
     const int32_t *child_right;     /* [sum N_I] */
     const int32_t *leaf_node;       /* [sum N_L] caller's tree-local node index of L_j (in-order) */
     const float *leaf_value;        /* [sum N_L * leaf_width] the table E */
+    /* kernel_path 2 and 3 (else NULL): the tables that turn a feature value into its threshold
+     * rank.  rank_threshold[rank_threshold_base[f] .. rank_threshold_base[f + 1]) are the
+     * distinct thresholds of feature f, ascending.  rank_bucket[f] = (lo, scale, n_buckets,
+     * start_base): for b = min(max(trunc((x - lo) * scale), 0), n_buckets - 1), computed in
+     * float32, rank_bucket_start[start_base + b] <= rank(x) <= rank_bucket_start[start_base + b + 1]. */
+    const float *rank_threshold;
+    const int32_t *rank_threshold_base;        /* [n_features + 1] */
+    const struct forest_rank_bucket *rank_bucket; /* [n_features] */
+    const int32_t *rank_bucket_start;
 } forest_packed_view;
 
 typedef struct forest_packed forest_packed;

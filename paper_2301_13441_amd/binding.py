@@ -44,7 +44,8 @@ class _View(ctypes.Structure):
                 ("tree_n_internal", _p), ("tree_depth", _p),
                 ("tree_is_full", _p), ("node_base", _p), ("leaf_base", _p), ("split_feature", _p),
                 ("split_threshold", _p), ("child_left", _p), ("child_right", _p), ("leaf_node", _p),
-                ("leaf_value", _p)]
+                ("leaf_value", _p), ("rank_threshold", _p), ("rank_threshold_base", _p),
+                ("rank_bucket", _p), ("rank_bucket_start", _p)]
 
 
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
@@ -154,7 +155,20 @@ def forest_pack(forest) -> dict:
         node_base = get(v.node_base, T + 1, np.int64)
         leaf_base = get(v.leaf_base, T + 1, np.int64)
         ni, nl = int(node_base[-1]), int(leaf_base[-1])
+        rank = {}
+        if v.rank_threshold_base:
+            F = int(forest.n_features)
+            tbase = get(v.rank_threshold_base, F + 1, np.int32)
+            bucket = get(v.rank_bucket, 4 * F, np.int32).reshape(F, 4)  # lo, scale as raw bits
+            n_start = int((bucket[:, 2] + 1).sum()) if F else 0
+            rank = dict(rank_threshold=get(v.rank_threshold, int(tbase[-1]), np.float32),
+                        rank_threshold_base=tbase,
+                        rank_bucket_lo=bucket[:, 0].copy().view(np.float32),
+                        rank_bucket_scale=bucket[:, 1].copy().view(np.float32),
+                        rank_bucket_count=bucket[:, 2].copy(), rank_bucket_base=bucket[:, 3].copy(),
+                        rank_bucket_start=get(v.rank_bucket_start, n_start, np.int32))
         return dict(
+            **rank,
             n_trees=T, kernel_kind=v.kernel_kind, kernel_path=v.kernel_path,
             rank_registers=v.rank_registers,
             tree_n_internal=get(v.tree_n_internal, T, np.int32),

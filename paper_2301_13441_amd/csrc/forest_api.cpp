@@ -84,6 +84,12 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     v->child_right = m.v_right.data();
     v->leaf_node = m.v_leaf_node.data();
     v->leaf_value = m.v_leaf_value.data();
+    const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
+    static_assert(sizeof(forest_rank_bucket) == sizeof(FeatBucket), "same four fields");
+    v->rank_threshold = ranks ? m.thr_sorted.data() : nullptr;
+    v->rank_threshold_base = ranks ? m.feat_thr_base.data() : nullptr;
+    v->rank_bucket = ranks ? reinterpret_cast<const forest_rank_bucket *>(m.feat_bucket.data()) : nullptr;
+    v->rank_bucket_start = ranks ? m.bucket_start.data() : nullptr;
     return FOREST_OK;
 }
 

@@ -195,6 +195,31 @@ def test_hand_off_from_torch_ops_on_the_same_stream():
         f.close()
 
 
+@pytest.mark.parametrize("case", ["clustered", "one_threshold", "huge_range"])
+def test_rank_lookup_with_awkward_threshold_sets(case):
+    """Threshold sets that defeat a uniform bucket grid (one crowded bucket, a single threshold,
+    a range that overflows float32) must still rank every value exactly."""
+    rng = np.random.default_rng(21)
+    w = wl.make_workload("c2", n_rows=1, n_trees=40)
+    f = w.forest
+    thr = f.threshold.copy()
+    internal = np.flatnonzero(f.feature >= 0)
+    if case == "clustered":
+        thr[internal] = np.float32(1.0) + rng.integers(0, 300, internal.size).astype(np.float32) * np.float32(1e-6)
+        thr[internal[:3]] = np.float32([-1e30, 0.0, 1e30])
+    elif case == "one_threshold":
+        thr[internal] = np.float32(0.25)
+    else:
+        thr[internal[::2]] = np.float32(3e38)
+        thr[internal[1::2]] = np.float32(-3e38)
+    g = wl.Forest(**{**f.__dict__, "threshold": thr})
+    X = rng.standard_normal((700, f.n_features)).astype(np.float32)
+    X[:200] = np.float32(1.0) + rng.integers(-5, 305, (200, f.n_features)).astype(np.float32) * np.float32(1e-6)
+    X[200:230] = np.float32(0.25)
+    X[230:260] = rng.choice(np.float32([3e38, -3e38, np.inf, -np.inf, 0.0]), (30, f.n_features))
+    assert _check(g, X)["kernel_path"] == 2
+
+
 def test_repeated_runs_are_bit_identical():
     import torch
     import paper_2301_13441_amd as pk

@@ -141,3 +141,58 @@ def test_kernel_family_choice():
     w = wl.make_workload("c2", n_rows=1)
     v = pk.forest_pack(w.forest)
     assert v["kernel_path"] == 2 and v["rank_registers"] == 56       # ~4550 thresholds per feature
+
+
+def _bucket_of(x, lo, scale, count):
+    """bucket_index of the library, in float32 like the kernels."""
+    with np.errstate(all="ignore"):   # inf * 0 = NaN is a bucket-0 case, as in the library
+        t = (np.float32(x) - np.float32(lo)) * np.float32(scale)
+    if not t > 0:
+        return 0
+    if t >= np.float32(count):
+        return int(count) - 1
+    return int(t)
+
+
+@pytest.mark.parametrize("case", ["normal", "grid", "with_infinities", "one_threshold", "clustered"])
+def test_rank_bucket_tables_bracket_every_rank(case):
+    """The rank families turn x into #{thresholds < x} through a bucket table: for every feature
+    the table entry of x's bucket and the next one must bracket the true rank, for values between,
+    on and beyond the thresholds."""
+    rng = np.random.default_rng(11)
+    if case == "grid":
+        f = wl.make_workload("c3", n_rows=1, n_trees=60).forest
+    else:
+        f = wl.make_workload("c2", n_rows=1, n_trees=30).forest
+        thr = f.threshold.copy()
+        internal = np.flatnonzero(f.feature >= 0)
+        if case == "with_infinities":
+            thr[internal[::9]] = np.inf
+            thr[internal[4::13]] = -np.inf
+        elif case == "one_threshold":
+            thr[internal] = np.float32(0.25)
+        elif case == "clustered":   # almost every threshold in one bucket of the uniform grid
+            thr[internal] = (np.float32(1.0) + rng.integers(0, 50, internal.size).astype(np.float32) * np.float32(1e-6))
+            thr[internal[:3]] = np.float32([-1e30, 0.0, 1e30])
+        f = wl.Forest(**{**f.__dict__, "threshold": thr})
+    v = binding.forest_pack(f)
+    assert v["kernel_path"] in (2, 3)
+    tb = v["rank_threshold_base"]
+    for feat in range(f.n_features):
+        thr = v["rank_threshold"][tb[feat]:tb[feat + 1]]
+        want = np.unique(f.threshold[f.feature == feat])
+        np.testing.assert_array_equal(thr, want)      # distinct, ascending
+        lo, scale = v["rank_bucket_lo"][feat], v["rank_bucket_scale"][feat]
+        count, base = v["rank_bucket_count"][feat], v["rank_bucket_base"][feat]
+        start = v["rank_bucket_start"][base:base + count + 1]
+        assert count >= 1 and start[0] == 0 and start[-1] == len(thr)
+        assert np.all(np.diff(start) >= 0)
+        probes = [np.float32(x) for x in (-np.inf, np.inf, 0.0, -0.0, 1e-45, -3e38, 3e38)]
+        finite = thr[np.isfinite(thr)]
+        for t in finite[:: max(1, len(finite) // 40)]:
+            probes += [t, np.nextafter(t, np.float32(-np.inf)), np.nextafter(t, np.float32(np.inf))]
+        probes += list(rng.standard_normal(40).astype(np.float32) * np.float32(2.0))
+        for x in probes:
+            rank = int(np.sum(thr < x))
+            b = _bucket_of(x, lo, scale, count)
+            assert start[b] <= rank <= start[b + 1], (case, feat, float(x), b)
