@@ -37,12 +37,108 @@ MEASURED_TRAFFIC = {
 }
 
 
+def bench_linear(args) -> int:
+    """The linear-model family (one matmul + bias + transform + label): bound by reading X once
+    from HBM, so its roofline is the HBM one."""
+    import numpy as np
+    import torch
+
+    import paper_2301_13441_amd as pk
+    from workloads.linear import make_linear_workload
+
+    w = make_linear_workload(args.workload, n_rows=args.rows)
+    n_rows, F, K = w.n_rows, w.model.n_features, w.model.n_outputs
+    m = pk.linear_load(w.model)
+    xd = torch.empty((n_rows, F), dtype=torch.float32, device="cuda")
+    sample_rows = min(n_rows, 262144)
+    parts = []
+    pos = 0
+    for chunk in w.x_chunks(n_rows):
+        xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
+        if pos < sample_rows:
+            parts.append(chunk[:max(0, sample_rows - pos)].copy())
+        pos += len(chunk)
+    x_sample = np.concatenate(parts)[:sample_rows]
+    out = torch.empty(max(m.out_bytes(n_rows), 4), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        m.predict(xd, out=out)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record(stream)
+        m.predict(xd, out=out)
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+    kernel_s = float(np.mean(kernel_ms)) * 1e-3
+    scores, labels = m.predict(xd, out=out)
+    torch.cuda.synchronize()
+    algo_bytes = n_rows * 4.0 * F + m.out_bytes(n_rows)
+    roofline = {
+        "bound": "hbm",
+        "kernel": "linear_predict (matmul + bias + transform + label, one kernel)",
+        "achieved": algo_bytes / kernel_s / 1e9,
+        "peak": HBM_PEAK / 1e9,
+        "unit": "GB/s",
+        "frac": algo_bytes / kernel_s / HBM_PEAK,
+        "kernel_ms_avg": kernel_s * 1e3,
+        "kernel_ms_min": float(np.min(kernel_ms)),
+        "algorithmic_bytes": algo_bytes,
+        "flops": 2.0 * F * K * n_rows,
+        "traffic": None,
+    }
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle.linear_oracle import predict_linear
+        t1 = time.perf_counter()
+        ref = predict_linear(w.model, x_sample)
+        dt = time.perf_counter() - t1
+        cpu_baseline = {"value": sample_rows / dt, "unit": "rows/s", "cores": os.cpu_count() or 1,
+                        "kind": "oracle", "sample": f"first {sample_rows} rows of {args.workload}, one pass "
+                                                    "(numpy float64 matmul, its BLAS threads)"}
+        parity = {"rows_checked": sample_rows}
+        if scores is not None:
+            got = scores[:sample_rows].cpu().numpy()
+            err = np.abs(got - ref.scores)
+            parity["scores_within_tol"] = bool((err <= 1e-6 + 1e-5 * np.abs(ref.scores)).all())
+            parity["max_abs_err"] = float(err.max())
+        if labels is not None:
+            parity["labels_equal"] = bool((labels[:sample_rows].cpu().numpy() == ref.labels).all())
+    line = {
+        "metric": "rows/sec scored (fp32 X), 1 MI355X",
+        "value": n_rows * args.steps / wall,
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64 products and sums of f32 inputs, rounded to f32 once",
+        "data": "synthetic (seeded; stands in for the paper's linear models on YearPrediction)",
+        "config": {"workload": args.workload, "n_rows": n_rows, "n_features": F, "n_outputs": K},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+    print(json.dumps(line))
+    m.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "l1", "l2", "l3", "l4"],
+                    help="c1..c5: tree ensembles (c2 is the headline); l1..l4: linear models")
     ap.add_argument("--rows", type=int, default=None, help="override the row count (testing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -62,6 +158,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.workload.startswith("l"):
+        return bench_linear(args)
 
     w = wl.make_workload(args.workload, n_rows=args.rows)
     n_rows, F = w.n_rows, w.forest.n_features
@@ -158,7 +256,7 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": ("f16 threshold ranks (exact rewrite of the f32 compare), f64 accumulate"
-                  if info["kernel_path"] == 2 else "f32 compare, f64 accumulate"),
+                  if info["kernel_path"] in (2, 3) else "f32 compare, f64 accumulate"),
         "data": "synthetic (seeded; stands in for YearPrediction and the paper's unstated models)",
         "config": {"workload": args.workload, "n_rows": n_rows, "n_features": F,
                    "n_trees": info["n_trees"], "max_depth": info["max_depth"],
