@@ -22,14 +22,67 @@ namespace {
 
 constexpr int LANES = 64;
 constexpr int LWAVES = 4;
-constexpr int CHUNK = 32;              // features per pass
-constexpr int STRIDE = CHUNK + 1;      // odd row stride of the LDS tile: conflict-free column reads
+constexpr int CHUNK = 32;          // features per pass
+constexpr int STRIDE = CHUNK + 4;  // row pitch of the LDS tile in floats: 16-byte aligned rows, and the
+                                   // 8 lanes of a 128-bit read phase fall into 8 different bank groups
 
-template <int KP>
+// The lane's share of a 64 x 32 chunk, as V-float pieces: piece i is columns [V * (lane % (32 / V)),
+// +V) of row i * (64 * V / 32) + lane / (32 / V), so that 32 / V consecutive lanes read 128
+// contiguous bytes of one row.
+template <int V>
+struct Piece {
+    float v[V];
+};
+
+template <int V>
+__device__ __forceinline__ void load_chunk(Piece<V> (&pre)[CHUNK / V], const float *__restrict__ src, int F, int c0,
+                                           int fc, int rows_here, int lane)
+{
+    constexpr int LPR = CHUNK / V;       // lanes per row
+    constexpr int RPI = LANES / LPR;     // rows per instruction
+    const int c = (lane % LPR) * V;
+#pragma unroll
+    for (int i = 0; i < CHUNK / V; ++i) {
+        const int r = i * RPI + lane / LPR;
+        const float *q = src + static_cast<int64_t>(r) * F + c0 + c;
+        if (r < rows_here && c + V <= fc) {
+            if (V == 4) {
+                const float4 t = *reinterpret_cast<const float4 *>(q);
+                pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y, pre[i].v[2 % V] = t.z, pre[i].v[3 % V] = t.w;
+            } else if (V == 2) {
+                const float2 t = *reinterpret_cast<const float2 *>(q);
+                pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y;
+            } else {
+                pre[i].v[0] = *q;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) pre[i].v[j] = (r < rows_here && c + j < fc) ? q[j] : 0.0f;
+        }
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void park_chunk(float *xs, const Piece<V> (&pre)[CHUNK / V], int lane)
+{
+    constexpr int LPR = CHUNK / V;
+    constexpr int RPI = LANES / LPR;
+    const int c = (lane % LPR) * V;
+#pragma unroll
+    for (int i = 0; i < CHUNK / V; ++i) {
+        float *d = xs + (i * RPI + lane / LPR) * STRIDE + c;
+        if (V == 4) *reinterpret_cast<float4 *>(d) = make_float4(pre[i].v[0], pre[i].v[1 % V], pre[i].v[2 % V], pre[i].v[3 % V]);
+        else if (V == 2) *reinterpret_cast<float2 *>(d) = make_float2(pre[i].v[0], pre[i].v[1 % V]);
+        else *d = pre[i].v[0];
+    }
+}
+
+// V: floats per global load (4 when rows are 16-byte aligned, i.e. F % 4 == 0; else 2 or 1).
+template <int KP, int V>
 __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const float *__restrict__ X,
                                                                 int64_t n_rows, float *scores, int32_t *labels)
 {
-    __shared__ float tile[LWAVES][LANES * STRIDE];
+    __shared__ __align__(16) float tile[LWAVES][LANES * STRIDE];
     const int lane = threadIdx.x & (LANES - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float *xs = tile[wave];
@@ -44,20 +97,27 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
 #pragma unroll
     for (int k = 0; k < KP; ++k) acc[k] = m.bias[k];
 
+    // The next chunk is on its way from HBM (held in registers) while the current one is used.
+    Piece<V> pre[CHUNK / V];
+    load_chunk<V>(pre, src, F, 0, F < CHUNK ? F : CHUNK, rows_here, lane);
     for (int c0 = 0; c0 < F; c0 += CHUNK) {
         const int fc = F - c0 < CHUNK ? F - c0 : CHUNK;
-        // element e of the chunk: row e / 32, column e % 32
-#pragma unroll 8
-        for (int i = 0; i < CHUNK; ++i) {
-            const int r = 2 * i + (lane >> 5), c = lane & (CHUNK - 1);
-            const bool in = r < rows_here && c < fc;
-            xs[r * STRIDE + c] = in ? src[static_cast<int64_t>(r) * F + c0 + c] : 0.0f;
-        }
+        park_chunk<V>(xs, pre, lane);
+        const int n0 = c0 + CHUNK;
+        if (n0 < F) load_chunk<V>(pre, src, F, n0, F - n0 < CHUNK ? F - n0 : CHUNK, rows_here, lane);
         const double *__restrict__ w = m.weight + static_cast<int64_t>(c0) * KP;
-        for (int c = 0; c < fc; ++c) {
-            const double x = static_cast<double>(xs[lane * STRIDE + c]);
+        const float4 *row = reinterpret_cast<const float4 *>(xs + lane * STRIDE);
+        for (int c = 0; c < fc; c += 4) {  // columns past fc hold zeros and meet weights of the next rows or zeros
+            const float4 t = row[c >> 2];
+            const float x4[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-            for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[c * KP + k], acc[k]);
+            for (int j = 0; j < 4; ++j) {
+                if (c + j < fc) {
+                    const double x = static_cast<double>(x4[j]);
+#pragma unroll
+                    for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[(c + j) * KP + k], acc[k]);
+                }
+            }
         }
     }
 
@@ -103,23 +163,33 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
 
 using LinearFn = void (*)(LinDev, const float *, int64_t, float *, int32_t *);
 
-LinearFn pick(int kp)
+template <int V>
+LinearFn pick_k(int kp)
 {
     switch (kp) {
-        case 1: return linear_kernel<1>;
-        case 2: return linear_kernel<2>;
-        case 3: return linear_kernel<3>;
-        case 4: return linear_kernel<4>;
-        case 5: return linear_kernel<5>;
-        case 6: return linear_kernel<6>;
-        case 8: return linear_kernel<8>;
-        case 10: return linear_kernel<10>;
-        case 12: return linear_kernel<12>;
-        case 16: return linear_kernel<16>;
-        case 24: return linear_kernel<24>;
-        case 32: return linear_kernel<32>;
+        case 1: return linear_kernel<1, V>;
+        case 2: return linear_kernel<2, V>;
+        case 3: return linear_kernel<3, V>;
+        case 4: return linear_kernel<4, V>;
+        case 5: return linear_kernel<5, V>;
+        case 6: return linear_kernel<6, V>;
+        case 8: return linear_kernel<8, V>;
+        case 10: return linear_kernel<10, V>;
+        case 12: return linear_kernel<12, V>;
+        case 16: return linear_kernel<16, V>;
+        case 24: return linear_kernel<24, V>;
+        case 32: return linear_kernel<32, V>;
         default: return nullptr;
     }
+}
+
+// Widest load that every row start and every chunk start is aligned for.
+LinearFn pick(int kp, int n_features, const float *X)
+{
+    const bool a16 = (reinterpret_cast<uintptr_t>(X) & 15) == 0, a8 = (reinterpret_cast<uintptr_t>(X) & 7) == 0;
+    if (n_features % 4 == 0 && a16) return pick_k<4>(kp);
+    if (n_features % 2 == 0 && a8) return pick_k<2>(kp);
+    return pick_k<1>(kp);
 }
 
 }  // namespace
@@ -136,7 +206,7 @@ hipError_t launch_linear(const LinDev &m, const float *X, int64_t n_rows, float 
                          hipStream_t stream)
 {
     if (n_rows <= 0) return hipSuccess;
-    LinearFn fn = pick(m.kp);
+    LinearFn fn = pick(m.kp, m.n_features, X);
     if (!fn) return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + LANES * LWAVES - 1) / (LANES * LWAVES);
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
