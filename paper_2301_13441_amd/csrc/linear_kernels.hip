@@ -43,21 +43,22 @@ __device__ __forceinline__ void load_chunk(Piece<V> (&pre)[CHUNK / V], const flo
     const int c = (lane % LPR) * V;
 #pragma unroll
     for (int i = 0; i < CHUNK / V; ++i) {
+        // V divides F and the chunk start, so a piece is inside the matrix or outside as a whole;
+        // a piece outside reads the tile's first floats instead (always there) and becomes zero:
+        // no branch, every load of the chunk is issued back to back
         const int r = i * RPI + lane / LPR;
-        const float *q = src + static_cast<int64_t>(r) * F + c0 + c;
-        if (r < rows_here && c + V <= fc) {
-            if (V == 4) {
-                const float4 t = *reinterpret_cast<const float4 *>(q);
-                pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y, pre[i].v[2 % V] = t.z, pre[i].v[3 % V] = t.w;
-            } else if (V == 2) {
-                const float2 t = *reinterpret_cast<const float2 *>(q);
-                pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y;
-            } else {
-                pre[i].v[0] = *q;
-            }
+        const bool in = r < rows_here && c < fc;
+        const float *q = in ? src + static_cast<int64_t>(r) * F + c0 + c : src;
+        if (V == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(q);
+            pre[i].v[0] = in ? t.x : 0.0f, pre[i].v[1 % V] = in ? t.y : 0.0f;
+            pre[i].v[2 % V] = in ? t.z : 0.0f, pre[i].v[3 % V] = in ? t.w : 0.0f;
+        } else if (V == 2) {
+            const float2 t = *reinterpret_cast<const float2 *>(q);
+            pre[i].v[0] = in ? t.x : 0.0f, pre[i].v[1 % V] = in ? t.y : 0.0f;
         } else {
-#pragma unroll
-            for (int j = 0; j < V; ++j) pre[i].v[j] = (r < rows_here && c + j < fc) ? q[j] : 0.0f;
+            const float t = *q;
+            pre[i].v[0] = in ? t : 0.0f;
         }
     }
 }
@@ -97,17 +98,16 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
 #pragma unroll
     for (int k = 0; k < KP; ++k) acc[k] = m.bias[k];
 
-    // The next chunk is on its way from HBM (held in registers) while the current one is used.
-    Piece<V> pre[CHUNK / V];
-    load_chunk<V>(pre, src, F, 0, F < CHUNK ? F : CHUNK, rows_here, lane);
-    for (int c0 = 0; c0 < F; c0 += CHUNK) {
+    // The next two chunks are on their way from HBM (held in registers) while the current one is used.
+    Piece<V> pre0[CHUNK / V], pre1[CHUNK / V];
+    auto fetch = [&](Piece<V> (&pre)[CHUNK / V], int c) {
+        if (c < F) load_chunk<V>(pre, src, F, c, F - c < CHUNK ? F - c : CHUNK, rows_here, lane);
+    };
+    auto use = [&](int c0) {
         const int fc = F - c0 < CHUNK ? F - c0 : CHUNK;
-        park_chunk<V>(xs, pre, lane);
-        const int n0 = c0 + CHUNK;
-        if (n0 < F) load_chunk<V>(pre, src, F, n0, F - n0 < CHUNK ? F - n0 : CHUNK, rows_here, lane);
         const double *__restrict__ w = m.weight + static_cast<int64_t>(c0) * KP;
         const float4 *row = reinterpret_cast<const float4 *>(xs + lane * STRIDE);
-        for (int c = 0; c < fc; c += 4) {  // columns past fc hold zeros and meet weights of the next rows or zeros
+        for (int c = 0; c < fc; c += 4) {
             const float4 t = row[c >> 2];
             const float x4[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
@@ -118,6 +118,18 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
                     for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[(c + j) * KP + k], acc[k]);
                 }
             }
+        }
+    };
+    fetch(pre0, 0);
+    fetch(pre1, CHUNK);
+    for (int c0 = 0; c0 < F; c0 += 2 * CHUNK) {
+        park_chunk<V>(xs, pre0, lane);
+        fetch(pre0, c0 + 2 * CHUNK);
+        use(c0);
+        if (c0 + CHUNK < F) {
+            park_chunk<V>(xs, pre1, lane);
+            fetch(pre1, c0 + 3 * CHUNK);
+            use(c0 + CHUNK);
         }
     }
 
