@@ -20,11 +20,62 @@
 namespace linear_impl {
 namespace {
 
+// The weights are wave-uniform and never written: reading them through the constant address
+// space makes them scalar loads whatever else the kernel does to memory.
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) double *WeightPtr;
+#else
+typedef const double *WeightPtr;  // host pass: the kernel body is only parsed
+#endif
+
 constexpr int LANES = 64;
 constexpr int LWAVES = 4;
 constexpr int CHUNK = 32;          // features per pass
 constexpr int STRIDE = CHUNK + 4;  // row pitch of the LDS tile in floats: 16-byte aligned rows, and the
                                    // 8 lanes of a 128-bit read phase fall into 8 different bank groups
+
+// Label, transform and store of one row whose K raw values (bias included) are acc[0..K).
+template <int KP>
+__device__ __forceinline__ void finish_linear_row(const LinDev &m, double (&acc)[KP], int64_t row, float *scores,
+                                                  int32_t *labels)
+{
+    const int K = m.n_outputs;
+    double best = acc[0];
+    int best_k = 0;
+#pragma unroll
+    for (int k = 1; k < KP; ++k)
+        if (k < K && acc[k] > best) {
+            best = acc[k];
+            best_k = k;
+        }
+    if (labels) {
+        int lab = best_k;
+        if (K == 1) lab = (m.transform == LINEAR_TRANSFORM_SIGMOID) ? (best > 0.0) : (best > 0.5);
+        labels[row] = lab;
+    }
+    if (!scores) return;
+    float *dst = scores + row * K;
+    if (m.transform == LINEAR_TRANSFORM_SOFTMAX) {
+        double z = 0.0;
+#pragma unroll
+        for (int k = 0; k < KP; ++k)
+            if (k < K) {
+                acc[k] = exp(acc[k] - best);
+                z += acc[k];
+            }
+#pragma unroll
+        for (int k = 0; k < KP; ++k)
+            if (k < K) dst[k] = static_cast<float>(acc[k] / z);
+    } else if (m.transform == LINEAR_TRANSFORM_SIGMOID) {
+#pragma unroll
+        for (int k = 0; k < KP; ++k)
+            if (k < K) dst[k] = static_cast<float>(1.0 / (1.0 + exp(-acc[k])));
+    } else {
+#pragma unroll
+        for (int k = 0; k < KP; ++k)
+            if (k < K) dst[k] = static_cast<float>(acc[k]);
+    }
+}
 
 // The lane's share of a 64 x 32 chunk, as V-float pieces: piece i is columns [V * (lane % (32 / V)),
 // +V) of row i * (64 * V / 32) + lane / (32 / V), so that 32 / V consecutive lanes read 128
@@ -105,7 +156,7 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
     };
     auto use = [&](int c0) {
         const int fc = F - c0 < CHUNK ? F - c0 : CHUNK;
-        const double *__restrict__ w = m.weight + static_cast<int64_t>(c0) * KP;
+        WeightPtr w = (WeightPtr)(m.weight + static_cast<int64_t>(c0) * KP);
         const float4 *row = reinterpret_cast<const float4 *>(xs + lane * STRIDE);
         for (int c = 0; c < fc; c += 4) {
             const float4 t = row[c >> 2];
@@ -133,44 +184,56 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
         }
     }
 
-    if (lane >= rows_here) return;
-    const int64_t row = row0 + lane;
-    const int K = m.n_outputs;
-    double best = acc[0];
-    int best_k = 0;
-#pragma unroll
-    for (int k = 1; k < KP; ++k)
-        if (k < K && acc[k] > best) {
-            best = acc[k];
-            best_k = k;
-        }
-    if (labels) {
-        int lab = best_k;
-        if (K == 1) lab = (m.transform == LINEAR_TRANSFORM_SIGMOID) ? (best > 0.0) : (best > 0.5);
-        labels[row] = lab;
+    if (lane < rows_here) finish_linear_row<KP>(m, acc, row0 + lane, scores, labels);
+}
+
+// Narrow matrices (a 64-row tile of whole rows fits the wave's share of LDS): the tile is one
+// contiguous piece of X, copied to LDS as it lies in memory by loads that write LDS directly
+// (global_load_lds, 16 bytes per lane, no register staging): every byte of X is requested once,
+// in 1 KB pieces, and all of a tile's loads are in flight at once.  Rows whose size is not a
+// multiple of the 128-byte line would otherwise be fetched twice by the chunked kernel, once for
+// each chunk a line straddles.
+constexpr int ROWS_WAVES = 2;
+constexpr int ROWS_MAX_FEATURES = 96;
+
+template <int KP>
+__global__ __launch_bounds__(LANES *ROWS_WAVES) void linear_rows_kernel(LinDev m, const float *__restrict__ X,
+                                                                         int64_t n_rows, float *scores,
+                                                                         int32_t *labels)
+{
+    extern __shared__ __align__(16) float rows_tile[];  // [ROWS_WAVES][64 * F]
+    const int lane = threadIdx.x & (LANES - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int F = m.n_features;
+    float *xs = rows_tile + wave * LANES * F;
+    const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * ROWS_WAVES + wave) * LANES;
+    if (row0 >= n_rows) return;  // wave-uniform
+    const int64_t left = n_rows - row0;
+    const int rows_here = left < LANES ? static_cast<int>(left) : LANES;
+    const float *__restrict__ src = X + row0 * F;  // 16-byte aligned: 64 F floats per tile
+    const int n = rows_here * F, n4 = n >> 2;
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(1))) const void *GlobalPtr;
+    typedef __attribute__((address_space(3))) void *LdsPtr;
+    for (int i = 0; i * LANES < n4; ++i) {
+        if (i * LANES + lane < n4)  // the LDS address is the wave-uniform base plus 16 bytes per lane
+            __builtin_amdgcn_global_load_lds((GlobalPtr)(src + (i * LANES + lane) * 4), (LdsPtr)(xs + i * LANES * 4), 16, 0, 0);
     }
-    if (!scores) return;
-    float *dst = scores + row * K;
-    if (m.transform == LINEAR_TRANSFORM_SOFTMAX) {
-        double z = 0.0;
+#endif
+    for (int e = n4 * 4 + lane; e < n; e += LANES) xs[e] = src[e];  // at most three floats of a partial tile
+    double acc[KP];
 #pragma unroll
-        for (int k = 0; k < KP; ++k)
-            if (k < K) {
-                acc[k] = exp(acc[k] - best);
-                z += acc[k];
-            }
+    for (int k = 0; k < KP; ++k) acc[k] = ((WeightPtr)m.bias)[k];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const float *row = xs + (lane < rows_here ? lane : 0) * F;
+    WeightPtr w = (WeightPtr)m.weight;
+#pragma unroll 8
+    for (int f = 0; f < F; ++f) {
+        const double x = static_cast<double>(row[f]);
 #pragma unroll
-        for (int k = 0; k < KP; ++k)
-            if (k < K) dst[k] = static_cast<float>(acc[k] / z);
-    } else if (m.transform == LINEAR_TRANSFORM_SIGMOID) {
-#pragma unroll
-        for (int k = 0; k < KP; ++k)
-            if (k < K) dst[k] = static_cast<float>(1.0 / (1.0 + exp(-acc[k])));
-    } else {
-#pragma unroll
-        for (int k = 0; k < KP; ++k)
-            if (k < K) dst[k] = static_cast<float>(acc[k]);
+        for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[f * KP + k], acc[k]);
     }
+    if (lane < rows_here) finish_linear_row<KP>(m, acc, row0 + lane, scores, labels);
 }
 
 using LinearFn = void (*)(LinDev, const float *, int64_t, float *, int32_t *);
@@ -191,6 +254,25 @@ LinearFn pick_k(int kp)
         case 16: return linear_kernel<16, V>;
         case 24: return linear_kernel<24, V>;
         case 32: return linear_kernel<32, V>;
+        default: return nullptr;
+    }
+}
+
+LinearFn pick_rows(int kp)
+{
+    switch (kp) {
+        case 1: return linear_rows_kernel<1>;
+        case 2: return linear_rows_kernel<2>;
+        case 3: return linear_rows_kernel<3>;
+        case 4: return linear_rows_kernel<4>;
+        case 5: return linear_rows_kernel<5>;
+        case 6: return linear_rows_kernel<6>;
+        case 8: return linear_rows_kernel<8>;
+        case 10: return linear_rows_kernel<10>;
+        case 12: return linear_rows_kernel<12>;
+        case 16: return linear_rows_kernel<16>;
+        case 24: return linear_rows_kernel<24>;
+        case 32: return linear_rows_kernel<32>;
         default: return nullptr;
     }
 }
@@ -218,6 +300,17 @@ hipError_t launch_linear(const LinDev &m, const float *X, int64_t n_rows, float 
                          hipStream_t stream)
 {
     if (n_rows <= 0) return hipSuccess;
+    if (m.n_features <= ROWS_MAX_FEATURES && (reinterpret_cast<uintptr_t>(X) & 15) == 0) {
+        LinearFn fn = pick_rows(m.kp);
+        if (!fn) return hipErrorInvalidValue;
+        const int64_t rows_per_block = LANES * ROWS_WAVES;
+        const int64_t n_blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+        if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        const size_t lds = sizeof(float) * ROWS_WAVES * LANES * m.n_features;
+        hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks)), dim3(LANES * ROWS_WAVES), lds, stream, m, X,
+                           n_rows, scores, labels);
+        return hipGetLastError();
+    }
     LinearFn fn = pick(m.kp, m.n_features, X);
     if (!fn) return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + LANES * LWAVES - 1) / (LANES * LWAVES);

@@ -6,7 +6,7 @@ weights the paper does not give.
     l1  1 000 x 20,  3 classes, softmax + label      small case the oracle finishes at once
     l2  4 000 000 x 90, 1 output, no transform       regression at the paper's feature count
     l3  2 000 000 x 128, 10 classes, softmax + label multinomial logistic regression
-    l4  2 000 000 x 28, 1 output, sigmoid + label    binary logistic regression
+    l4  8 000 000 x 28, 1 output, sigmoid + label    binary logistic regression
 
 Weights ~ N(0, 1/sqrt(F)), bias ~ N(0, 0.1), X ~ N(0, 1) in chunks of 65 536 rows so that every
 row prefix is reproducible from the seed.
@@ -21,7 +21,7 @@ import numpy as np
 from . import OUT_BOTH, OUT_SCORES, TRANSFORM_NONE, TRANSFORM_SIGMOID, TRANSFORM_SOFTMAX, X_CHUNK_ROWS
 
 LINEAR_SEEDS = {"l1": 13441101, "l2": 13441102, "l3": 13441103, "l4": 13441104}
-LINEAR_ROWS = {"l1": 1_000, "l2": 4_000_000, "l3": 2_000_000, "l4": 2_000_000}
+LINEAR_ROWS = {"l1": 1_000, "l2": 4_000_000, "l3": 2_000_000, "l4": 8_000_000}
 _SHAPES = {  # n_features, n_outputs, transform, output
     "l1": (20, 3, TRANSFORM_SOFTMAX, OUT_BOTH),
     "l2": (90, 1, TRANSFORM_NONE, OUT_SCORES),
