@@ -34,6 +34,8 @@ MEASURED_TRAFFIC = {
     # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 63,965 x 2.000 (copy-kernel scale) KiB read,
     # WRITE_SIZE 7,812.5 x 1.000 KiB written
     "c2": 131.0e6 + 8.0e6,
+    # profiles/linear_kernels.md: FETCH_SIZE 703,161 x 2.000 KiB, WRITE_SIZE 15,625 x 1.000 KiB
+    "l2": 1440.0e6 + 16.0e6,
 }
 
 
@@ -89,7 +91,7 @@ def bench_linear(args) -> int:
         "kernel_ms_min": float(np.min(kernel_ms)),
         "algorithmic_bytes": algo_bytes,
         "flops": 2.0 * F * K * n_rows,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC.get(args.workload),
     }
     cpu_baseline = None
     parity = None
