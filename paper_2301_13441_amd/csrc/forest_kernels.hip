@@ -13,8 +13,11 @@
 //   workgroup, then the transform; labels are taken before the transform (Section 4.3.3).
 //
 // This file holds the kernels that read features from the LDS tile for every comparison
-// (any number of features, any tree shape) and the launcher.  forest_kernels_reg.hip holds
-// the kernels that keep the features in vector registers.
+// (any number of features, any tree shape), the choice of how many shares the trees of a small
+// batch are cut into, and the launcher.  The other families: forest_kernels_rank.hip (packed
+// f16 threshold ranks in vector registers, the headline path), forest_kernels_ranklds.hip (the
+// same with the ranks in LDS, any tree shape), forest_kernels_reg.hip (float32 features in
+// vector registers), forest_kernels_split.hip (what only split launches need).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

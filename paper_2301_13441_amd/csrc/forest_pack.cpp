@@ -26,10 +26,14 @@
 //     rv = clamp(rank - 4095 s, 0, L_s) - 2048,   j' = (j - 4095 s) - 2048,
 // and clamp_[0,1](rv - j') is the outcome bit (differences beyond +-2048 round, but keep
 // their sign and a magnitude above 1).  Two rows share a register (low / high half), so one
-// packed instruction compares two rows.  The kernel shifts outcomes into an f16 accumulator
-// that starts at 4.0: after 8 entries its value is 1024 + bits, whose low mantissa byte is
-// the 8 outcome bits, first entry in bit 7.  Entries are therefore stored in blocks of 8,
-// descending position inside a block.
+// packed instruction compares two rows.  The kernels turn the 8 outcomes of a block of 8
+// entries into one outcome byte per row, first entry in bit 7 (on the matrix core, or with a
+// tree of packed fused multiply-adds: forest_kernels_rank.hip).  Entries are therefore stored
+// in blocks of 8, descending position inside a block.
+//
+// Rank lookup tables: per feature a uniform bucket grid over the finite threshold range with,
+// per bucket, the number of thresholds in lower buckets (build_rank_tables below); the kernels
+// get a bracket of rank(x) from it and finish with a short search (forest_rank_common.hpp).
 #include <algorithm>
 #include <cassert>
 #include <cmath>
