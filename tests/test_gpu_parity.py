@@ -220,6 +220,58 @@ def test_rank_lookup_with_awkward_threshold_sets(case):
     assert _check(g, X)["kernel_path"] == 2
 
 
+def test_forest_without_trees_returns_the_base_scores():
+    f = wl.Forest(n_features=3, n_outputs=3, leaf_width=1, tree_offset=np.zeros(1, np.int64),
+                  feature=np.zeros(0, np.int32), threshold=np.zeros(0, np.float32), left=np.zeros(0, np.int32),
+                  right=np.zeros(0, np.int32), leaf_value=np.zeros((0, 1), np.float32),
+                  tree_output=np.zeros(0, np.int32), aggregate=wl.AGG_SUM,
+                  base_score=np.float32([0.25, 1.5, -2.0]), transform=wl.TRANSFORM_SOFTMAX, output=wl.OUT_BOTH)
+    X = np.random.default_rng(1).standard_normal((200, 3)).astype(np.float32)
+    scores, labels, _, info = _run(f, X, leaves=False)
+    ref = oracle.predict(f, X, want_leaves=False)
+    np.testing.assert_array_equal(labels, ref.labels)
+    np.testing.assert_allclose(scores, ref.scores, rtol=RTOL, atol=ATOL)
+    assert np.all(labels == 1) and info["n_trees"] == 0
+
+
+def test_large_batches_from_two_streams_at_once():
+    """Batches of small_batch_rows rows or more touch no state of the handle: two streams may
+    run them on one handle concurrently."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c3", n_rows=70000, n_trees=64)
+    f = pk.forest_load(w.forest)
+    try:
+        assert f.info["small_batch_rows"] <= 70000
+        rng = np.random.default_rng(4)
+        xs = [w.make_x(70000), rng.standard_normal((70000, w.forest.n_features)).astype(np.float32)]
+        xd = [torch.from_numpy(x).cuda() for x in xs]
+        outs = [torch.empty(f.out_bytes(70000), dtype=torch.uint8, device="cuda") for _ in xs]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        res = []
+        for _ in range(3):                      # interleave launches on the two streams
+            res = [f.predict(xd[i], out=outs[i], stream=streams[i]) for i in range(2)]
+        torch.cuda.synchronize()
+        for i in range(2):
+            ref = oracle.predict(w.forest, xs[i], want_leaves=False, n_threads=8)
+            np.testing.assert_allclose(res[i][0].cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        f.close()
+
+
+def test_null_pointers_are_refused_before_any_launch():
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c1", n_rows=10)
+    f = pk.forest_load(w.forest)
+    try:
+        with pytest.raises(pk.ForestError) as e:
+            f.predict_raw(0, 10, 0, 0)
+        assert e.value.code == -1
+    finally:
+        f.close()
+
+
 def test_repeated_runs_are_bit_identical():
     import torch
     import paper_2301_13441_amd as pk
