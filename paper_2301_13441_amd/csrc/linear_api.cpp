@@ -45,10 +45,12 @@ int linear_load(const linear_desc *desc, linear_model **out)
     if (int rc = check(*desc)) return rc;
     const int F = desc->n_features, K = desc->n_outputs;
     const int kp = padded_outputs(K);
+    const int f_pad = (F + 31) / 32 * 32;
     std::vector<double> host;
     linear_model *m = nullptr;
     try {
-        host.assign(static_cast<size_t>(F + 1) * kp, 0.0);  // weights [F][kp], then the bias [kp]
+        // weights [F rounded up to whole chunks of 32][kp] (zero rows past F), then the bias [kp]
+        host.assign(static_cast<size_t>(f_pad + 1) * kp, 0.0);
         m = new linear_model;
     } catch (const std::bad_alloc &) {
         return LINEAR_ENOMEM;
@@ -56,7 +58,7 @@ int linear_load(const linear_desc *desc, linear_model **out)
     for (int f = 0; f < F; ++f)
         for (int k = 0; k < K; ++k) host[static_cast<size_t>(f) * kp + k] = desc->weight[static_cast<size_t>(f) * K + k];
     if (desc->bias)
-        for (int k = 0; k < K; ++k) host[static_cast<size_t>(F) * kp + k] = desc->bias[k];
+        for (int k = 0; k < K; ++k) host[static_cast<size_t>(f_pad) * kp + k] = desc->bias[k];
     // Everything below needs a device.
     const size_t bytes = host.size() * sizeof(double);
     if (hipMalloc(&m->blob, bytes) != hipSuccess) {
@@ -75,7 +77,7 @@ int linear_load(const linear_desc *desc, linear_model **out)
     m->transform = desc->transform;
     m->output = desc->output;
     m->dev.weight = static_cast<const double *>(m->blob);
-    m->dev.bias = m->dev.weight + static_cast<size_t>(F) * kp;
+    m->dev.bias = m->dev.weight + static_cast<size_t>(f_pad) * kp;
     m->dev.n_features = F;
     m->dev.n_outputs = K;
     m->dev.kp = kp;

@@ -8,7 +8,7 @@
 namespace linear_impl {
 
 struct LinDev {
-    const double *weight;  // [n_features][kp]: float64, columns padded with zeros to kp
+    const double *weight;  // [n_features rounded up to a multiple of 32][kp]: float64, zero-padded
     const double *bias;    // [kp]
     int32_t n_features, n_outputs, kp;
     int32_t transform, output;

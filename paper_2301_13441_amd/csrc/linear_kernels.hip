@@ -155,19 +155,19 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
         if (c < F) load_chunk<V>(pre, src, F, c, F - c < CHUNK ? F - c : CHUNK, rows_here, lane);
     };
     auto use = [&](int c0) {
-        const int fc = F - c0 < CHUNK ? F - c0 : CHUNK;
+        // the tile holds zeros past the last feature and the weight matrix has zero rows there,
+        // so every chunk runs all 32 columns without a test
         WeightPtr w = (WeightPtr)(m.weight + static_cast<int64_t>(c0) * KP);
         const float4 *row = reinterpret_cast<const float4 *>(xs + lane * STRIDE);
-        for (int c = 0; c < fc; c += 4) {
+#pragma unroll 2
+        for (int c = 0; c < CHUNK; c += 4) {
             const float4 t = row[c >> 2];
             const float x4[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (c + j < fc) {
-                    const double x = static_cast<double>(x4[j]);
+                const double x = static_cast<double>(x4[j]);
 #pragma unroll
-                    for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[(c + j) * KP + k], acc[k]);
-                }
+                for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[(c + j) * KP + k], acc[k]);
             }
         }
     };
