@@ -39,6 +39,14 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    # the LDS rank kernel relies on the compiler leaving its pinned scalar registers alone
+    try:
+        from . import check_stream_registers
+    except ImportError:  # run as a script
+        import check_stream_registers
+    n = check_stream_registers.check(HIPCC, [*FLAGS, *extra], os.path.join(CSRC, "forest_kernels_ranklds.hip"), OBJ)
+    if verbose:
+        print(f"stream registers: {n} loops clean", flush=True)
     return LIB
 
 

@@ -196,3 +196,32 @@ def test_rank_bucket_tables_bracket_every_rank(case):
             rank = int(np.sum(thr < x))
             b = _bucket_of(x, lo, scale, count)
             assert start[b] <= rank <= start[b + 1], (case, feat, float(x), b)
+
+
+def test_pinned_stream_register_check_catches_a_violation():
+    """The build refuses a library whose LDS rank kernel lets compiler-generated code touch the
+    pinned stream registers between two evaluation statements; the checker itself is tested on
+    a miniature of the assembly's structure."""
+    from paper_2301_13441_amd import check_stream_registers as chk
+    clean = "\n".join([
+        ".LBB0_1:                                ; =>This Loop Header: Depth=1",
+        "\t;;#ASMSTART", "\tv_and_or_b32 v112, s36, v1, v2", "\ts_load_dwordx16 s[36:51], s[2:3], 0x80", "\t;;#ASMEND",
+        "\tv_add_u32 v3, v3, v4",
+        ".LBB0_2:                                ;   in Loop: Header=BB0_1 Depth=1",
+        "\ts_add_u32 s2, s2, 0x80", "\ts_cbranch_scc1 .LBB0_1",
+        ".LBB0_3:", "\ts_mov_b32 s40, 0", "\ts_endpgm"])
+    assert chk.check_assembly(clean) == 1
+    dirty = clean.replace("\ts_add_u32 s2, s2, 0x80", "\ts_add_u32 s2, s2, 0x80\n\ts_mov_b32 s44, s7")
+    with pytest.raises(RuntimeError, match="pinned stream register"):
+        chk.check_assembly(dirty)
+    with pytest.raises(RuntimeError, match="no stream loop"):
+        chk.check_assembly("\ts_endpgm")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
