@@ -31,9 +31,9 @@ HBM_PEAK = 8.0e12
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC = {
-    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 63,965 x 2.000 (copy-kernel scale) KiB read,
+    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 78,902 x 2.000 (copy-kernel scale) KiB read,
     # WRITE_SIZE 7,812.5 x 1.000 KiB written
-    "c2": 131.0e6 + 8.0e6,
+    "c2": 161.6e6 + 8.0e6,
     # profiles/linear_kernels.md: FETCH_SIZE 703,161 x 2.000 KiB, WRITE_SIZE 15,625 x 1.000 KiB
     "l2": 1440.0e6 + 16.0e6,
 }
