@@ -396,3 +396,35 @@ def _full_size(name, leaf_rows=4096):
 def test_full_size_sampled(name):
     info = _full_size(name)
     assert info["n_trees"] == {"c2": 500, "c3": 1000, "c4": 2000, "c5": 128}[name]
+
+
+def test_input_larger_than_2_to_31_elements():
+    """Row offsets past 2^31 elements (and 2^33 bytes) of X: 80,000,000 rows of 28 features,
+    drawn on the device; the oracle checks the first and last rows and seeded rows between,
+    most of them beyond the 2^31st element."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c2", n_rows=1, n_trees=8)
+    F = w.forest.n_features
+    n = 80_000_000
+    assert n * F > 2**31
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    xd = torch.empty((n, F), dtype=torch.float32, device="cuda")
+    step = 10_000_000
+    for pos in range(0, n, step):
+        xd[pos:pos + step].normal_(generator=gen)
+    rng = np.random.default_rng(99)
+    pick = np.unique(np.concatenate([np.arange(300), np.arange(n - 300, n), rng.integers(0, n, 4000),
+                                     rng.integers(2**31 // F, n, 4000)]))
+    idx = torch.from_numpy(pick).cuda()
+    xs = xd[idx].cpu().numpy()
+    f = pk.forest_load(w.forest)
+    try:
+        scores, labels = f.predict(xd)
+        torch.cuda.synchronize()
+        got_scores, got_labels = scores[idx].cpu().numpy(), labels[idx].cpu().numpy()
+    finally:
+        f.close()
+    ref = oracle.predict(w.forest, xs, n_threads=8)
+    np.testing.assert_array_equal(got_labels, ref.labels)
+    np.testing.assert_allclose(got_scores, ref.scores, rtol=RTOL, atol=ATOL)

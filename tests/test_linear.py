@@ -161,3 +161,34 @@ def test_full_size_sampled(name):
                 np.testing.assert_array_equal(labels[sel].cpu().numpy(), ref.labels)
     finally:
         m.close()
+
+
+@pytest.mark.gpu
+def test_input_larger_than_2_to_31_elements():
+    """Row offsets past 2^31 elements of X in both kernels (whole-row tiles: 30 features;
+    chunked: 130 features); the oracle checks the ends and seeded rows between."""
+    import torch
+    for F, K, n in ((30, 3, 75_000_000), (130, 2, 17_000_000)):
+        assert n * F > 2**31
+        model = _rand_model(F, F, K, TRANSFORM_SOFTMAX)
+        gen = torch.Generator(device="cuda").manual_seed(F)
+        xd = torch.empty((n, F), dtype=torch.float32, device="cuda")
+        step = 5_000_000
+        for pos in range(0, n, step):
+            xd[pos:pos + step].normal_(generator=gen)
+        rng = np.random.default_rng(F)
+        pick = np.unique(np.concatenate([np.arange(200), np.arange(n - 200, n), rng.integers(0, n, 3000),
+                                         rng.integers(2**31 // F, n, 3000)]))
+        idx = torch.from_numpy(pick).cuda()
+        xs = xd[idx].cpu().numpy()
+        m = lb.linear_load(model)
+        try:
+            scores, labels = m.predict(xd)
+            torch.cuda.synchronize()
+            got_scores, got_labels = scores[idx].cpu().numpy(), labels[idx].cpu().numpy()
+        finally:
+            m.close()
+        del xd, scores, labels
+        ref = predict_linear(model, xs)
+        np.testing.assert_array_equal(got_labels, ref.labels)
+        np.testing.assert_allclose(got_scores, ref.scores, rtol=RTOL, atol=ATOL)
