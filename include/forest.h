@@ -44,6 +44,8 @@ enum {
 #define FOREST_MAX_FEATURES 4096  /* n_features */
 #define FOREST_MAX_OUTPUTS 32     /* n_outputs (K) */
 #define FOREST_MAX_DEPTH 64       /* longest root-to-leaf path, in tests */
+/* Limit of one call (FOREST_ELIMIT from the predict and size calls): */
+#define FOREST_MAX_ROWS 1000000000 /* n_rows: keeps every launch inside HIP's 2^32 threads per grid axis */
 
 /*
  * A forest as the caller holds it: per-node arrays, trees concatenated.  All pointers are
@@ -103,6 +105,8 @@ typedef struct forest_info_t {
  * leaf table E).  Validates the description, packs it and copies it to the current HIP
  * device.  On success *out owns device memory until forest_free.  On error *out is untouched.
  * Validation happens before any HIP call, so malformed input is reported even without a GPU.
+ * The handle belongs to the device that was current at load: the predict calls return
+ * FOREST_EINVAL while another device is current.
  */
 int forest_load(const forest_desc *desc, forest **out);
 
@@ -111,7 +115,8 @@ void forest_free(forest *f);
 
 int forest_info(const forest *f, forest_info_t *info);
 
-/* Bytes forest_predict writes for n_rows rows; negative FOREST_E* on error. */
+/* Bytes forest_predict writes for n_rows rows (0 <= n_rows <= FOREST_MAX_ROWS); negative
+ * FOREST_E* on error. */
 int64_t forest_out_bytes(const forest *f, int64_t n_rows);
 
 /*

@@ -44,6 +44,8 @@ enum {
 
 #define LINEAR_MAX_FEATURES 65536 /* n_features */
 #define LINEAR_MAX_OUTPUTS 32     /* n_outputs (K) */
+/* Limit of one call (LINEAR_ELIMIT from the predict and size calls): */
+#define LINEAR_MAX_ROWS 1000000000 /* n_rows: keeps the launch inside HIP's 2^32 threads per grid axis */
 
 /* All pointers are HOST memory, borrowed for the duration of linear_load only. */
 typedef struct linear_desc {
@@ -59,13 +61,16 @@ typedef struct linear_desc {
  * Validates the description (before any HIP call, so malformed input is reported even
  * without a GPU), widens the weights to float64 and copies them to the current HIP device.
  * On success *out owns device memory until linear_free.  On error *out is untouched.
+ * The handle belongs to the device that was current at load: linear_predict returns
+ * LINEAR_EINVAL while another device is current.
  */
 int linear_load(const linear_desc *desc, linear_model **out);
 
 /* Releases host and device memory. linear_free(NULL) is a no-op. */
 void linear_free(linear_model *m);
 
-/* Bytes linear_predict writes for n_rows rows; negative LINEAR_E* on error. */
+/* Bytes linear_predict writes for n_rows rows (0 <= n_rows <= LINEAR_MAX_ROWS); negative
+ * LINEAR_E* on error. */
 int64_t linear_out_bytes(const linear_model *m, int64_t n_rows);
 
 /*

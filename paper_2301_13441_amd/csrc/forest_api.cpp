@@ -24,8 +24,23 @@ struct forest {
 
 namespace {
 
-std::once_flag g_init_once;
-hipError_t g_init_status = hipSuccess;
+// Kernel attributes (dynamic LDS sizes) are per device: set once for every device a model is
+// loaded on.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_init_mutex;
+bool g_init_done[MAX_DEVICES] = {};
+hipError_t g_init_status[MAX_DEVICES] = {};
+
+hipError_t init_device(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_init_mutex);
+    if (!g_init_done[device]) {
+        g_init_status[device] = init_kernels();
+        g_init_done[device] = true;
+    }
+    return g_init_status[device];
+}
 
 template <class T>
 size_t place(size_t &cursor, size_t count)
@@ -39,7 +54,19 @@ size_t place(size_t &cursor, size_t count)
 int check_out_args(const forest *f, int64_t n_rows)
 {
     if (!f || n_rows < 0) return FOREST_EINVAL;
+    if (n_rows > FOREST_MAX_ROWS) return FOREST_ELIMIT;
     return FOREST_OK;
+}
+
+// The handle's tables live on the device it was loaded on.
+int check_device(const forest *f)
+{
+    int current = -1;
+    if (hipGetDevice(&current) != hipSuccess) {
+        (void)hipGetLastError();
+        return FOREST_EHIP;
+    }
+    return current == f->device ? FOREST_OK : FOREST_EINVAL;
 }
 
 }  // namespace
@@ -115,8 +142,7 @@ int forest_load(const forest_desc *desc, forest **out)
         return FOREST_ELIMIT;
     }
     // Everything below needs a device.
-    std::call_once(g_init_once, [] { g_init_status = init_kernels(); });
-    if (g_init_status != hipSuccess || hipGetDevice(&f->device) != hipSuccess) {
+    if (hipGetDevice(&f->device) != hipSuccess || init_device(f->device) != hipSuccess) {
         (void)hipGetLastError();
         delete f;
         return FOREST_EHIP;
@@ -281,6 +307,7 @@ int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, v
     if (int rc = check_out_args(f, n_rows)) return rc;
     if (n_rows == 0) return FOREST_OK;
     if (!X || !out) return FOREST_EINVAL;
+    if (int rc = check_device(f)) return rc;
     int64_t so, lo;
     forest_out_layout(f, n_rows, &so, &lo);
     char *o = static_cast<char *>(out);
@@ -297,6 +324,7 @@ int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32
     if (int rc = check_out_args(f, n_rows)) return rc;
     if (n_rows == 0 || f->host.n_trees == 0) return FOREST_OK;
     if (!X || !leaf_node_id) return FOREST_EINVAL;
+    if (int rc = check_device(f)) return rc;
     const hipError_t e = launch_predict(f->dev, X, n_rows, nullptr, nullptr, leaf_node_id,
                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FOREST_OK : FOREST_EHIP;

@@ -15,6 +15,7 @@ struct linear_model {
     LinDev dev{};
     void *blob = nullptr;
     int32_t n_features = 0, n_outputs = 0, transform = 0, output = 0;
+    int device = 0;  // the device the weights live on
 };
 
 namespace {
@@ -60,6 +61,11 @@ int linear_load(const linear_desc *desc, linear_model **out)
     if (desc->bias)
         for (int k = 0; k < K; ++k) host[static_cast<size_t>(f_pad) * kp + k] = desc->bias[k];
     // Everything below needs a device.
+    if (hipGetDevice(&m->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete m;
+        return LINEAR_EHIP;
+    }
     const size_t bytes = host.size() * sizeof(double);
     if (hipMalloc(&m->blob, bytes) != hipSuccess) {
         const hipError_t e = hipGetLastError();
@@ -97,6 +103,7 @@ void linear_free(linear_model *m)
 int linear_out_layout(const linear_model *m, int64_t n_rows, int64_t *scores_offset, int64_t *labels_offset)
 {
     if (!m || n_rows < 0) return LINEAR_EINVAL;
+    if (n_rows > LINEAR_MAX_ROWS) return LINEAR_ELIMIT;
     const int64_t score_bytes = n_rows * m->n_outputs * static_cast<int64_t>(sizeof(float));
     int64_t so = -1, lo = -1;
     switch (m->output) {
@@ -112,6 +119,7 @@ int linear_out_layout(const linear_model *m, int64_t n_rows, int64_t *scores_off
 int64_t linear_out_bytes(const linear_model *m, int64_t n_rows)
 {
     if (!m || n_rows < 0) return LINEAR_EINVAL;
+    if (n_rows > LINEAR_MAX_ROWS) return LINEAR_ELIMIT;
     int64_t bytes = 0;
     if (m->output != LINEAR_OUT_LABELS) bytes += n_rows * m->n_outputs * static_cast<int64_t>(sizeof(float));
     if (m->output != LINEAR_OUT_SCORES) bytes += n_rows * static_cast<int64_t>(sizeof(int32_t));
@@ -121,8 +129,15 @@ int64_t linear_out_bytes(const linear_model *m, int64_t n_rows)
 int linear_predict(const linear_model *m, const float *X, int64_t n_rows, void *out, void *stream)
 {
     if (!m || n_rows < 0) return LINEAR_EINVAL;
+    if (n_rows > LINEAR_MAX_ROWS) return LINEAR_ELIMIT;
     if (n_rows == 0) return LINEAR_OK;
     if (!X || !out) return LINEAR_EINVAL;
+    int current = -1;
+    if (hipGetDevice(&current) != hipSuccess) {
+        (void)hipGetLastError();
+        return LINEAR_EHIP;
+    }
+    if (current != m->device) return LINEAR_EINVAL;
     int64_t so = -1, lo = -1;
     (void)linear_out_layout(m, n_rows, &so, &lo);
     char *base = static_cast<char *>(out);

@@ -268,6 +268,13 @@ def test_null_pointers_are_refused_before_any_launch():
         with pytest.raises(pk.ForestError) as e:
             f.predict_raw(0, 10, 0, 0)
         assert e.value.code == -1
+        # more rows than one call takes: refused by the size calls and by predict, nothing runs
+        for call in (lambda: f.out_bytes(10**9 + 1), lambda: f.out_layout(2**40),
+                     lambda: f.predict_raw(256, 10**9 + 1, 256, 0)):
+            with pytest.raises(pk.ForestError) as e:
+                call()
+            assert e.value.code == -7
+        assert f.out_bytes(10**9) == 10**9 * 8
     finally:
         f.close()
 

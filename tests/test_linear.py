@@ -114,6 +114,9 @@ def test_output_kinds_ties_and_empty_batch():
     _check(tie, X)
     m = lb.linear_load(tie)
     m.predict_raw(0, 0, 0, 0)   # n_rows == 0 is a successful no-op
+    with pytest.raises(lb.LinearError) as e:   # more rows than one call takes
+        m.predict_raw(256, 10**9 + 1, 256, 0)
+    assert e.value.code == -7
     m.close()
     torch.cuda.synchronize()
 
