@@ -6,9 +6,12 @@
 // sit in LDS and every entry of the split program reads its row
 //     v_and_or_b32  a, entry, 0xff00, lane * 4          -- LDS address of the row, no scalar op
 //     ds_read_b32   x, a
-//     v_pk_add_f16  d, x, entry.hi  clamp               -- step (2) of Fig. 2 for two rows
-//     v_pk_fma_f16  ...                                 -- 8 outcomes -> one outcome byte
-// i.e. three vector instructions and one LDS read per (node, two rows).
+//     v_pk_add_f16  x, x, entry.hi  clamp               -- step (2) of Fig. 2 for two rows
+// i.e. two vector instructions and one LDS read per (node, two rows); the matrix core then
+// turns the 8 outcome registers of a group into one outcome byte per row
+// (forest_rank_common.hpp).  (Forming the address on the scalar side instead -- row offset to
+// M0, ds_read_addtid_b32 -- takes the address instruction off the vector ALU but costs the wave
+// two more instruction issues per entry, and measured 4 % slower.)
 //
 // Trees are stored level by level (internal nodes in level order, Section 3.1.2; every level
 // padded to whole groups of 8 entries).  After the last group of a level the wave has that
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
     const int K = m.n_outputs;
     // LDS: [ rank tile | one outcome-byte chunk per wave | partial sums (GENERAL) ].
-    // The rank tile must start at LDS address 0: eval_group forms addresses as
+    // The rank tile must start at LDS address 0: the entries' reads form addresses as
     // (row offset | lane * 4).  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
     // every wave has finished.
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
