@@ -104,6 +104,18 @@ def test_shapes_ragged_in_every_direction(F, K, transform):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("F", [4, 8, 28, 100, 124, 128])
+def test_rows_of_whole_16_byte_pieces(F):
+    """Feature counts that are multiples of 4 on both sides of the whole-row / chunked kernel
+    boundary, full and partial tiles."""
+    for K, transform in ((1, TRANSFORM_SIGMOID), (10, TRANSFORM_SOFTMAX)):
+        model = _rand_model(7 * F + K, F, K, transform)
+        rng = np.random.default_rng(F * K)
+        for rows in (1, 63, 64, 65, 129, 1000):
+            _check(model, rng.standard_normal((rows, F)).astype(np.float32))
+
+
+@pytest.mark.gpu
 def test_output_kinds_ties_and_empty_batch():
     import torch
     X = np.random.default_rng(5).standard_normal((130, 6)).astype(np.float32)
