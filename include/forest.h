@@ -97,6 +97,7 @@ typedef struct forest_info_t {
     int64_t workspace_bytes;    /* device workspace the handle owns besides the packed model */
     int64_t small_batch_rows;   /* batches below this many rows also cut the trees into shares
                                    (more workgroups for few rows) and use the workspace */
+    int32_t workgroup_waves;    /* wavefronts per workgroup of the kernel the model runs */
 } forest_info_t;
 
 /*

@@ -36,7 +36,7 @@ class _Info(ctypes.Structure):
     _fields_ = [("n_trees", _i32), ("n_features", _i32), ("n_outputs", _i32), ("leaf_width", _i32),
                 ("n_internal", _i64), ("n_leaves", _i64), ("max_depth", _i32), ("kernel_kind", _i32),
                 ("packed_bytes", _i64), ("x_in_registers", _i32), ("kernel_path", _i32), ("rows_per_workgroup", _i32),
-                ("workspace_bytes", _i64), ("small_batch_rows", _i64)]
+                ("workspace_bytes", _i64), ("small_batch_rows", _i64), ("workgroup_waves", _i32)]
 
 
 class _View(ctypes.Structure):

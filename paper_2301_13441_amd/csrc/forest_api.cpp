@@ -221,6 +221,7 @@ int forest_load(const forest_desc *desc, forest **out)
     d.reg_nv = m.reg_nv;
     d.reg_r = m.reg_r;
     d.rank_regs = m.rank_regs;
+    d.lds_waves = m.lds_waves;
     d.feat_bucket = reinterpret_cast<const FeatBucket *>(b + o_fbk);
     d.bucket_start = reinterpret_cast<const int32_t *>(b + o_bst);
     d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);
@@ -272,6 +273,7 @@ int forest_info(const forest *f, forest_info_t *info)
     info->rows_per_workgroup = family_rows_per_block(f->dev);
     info->workspace_bytes = f->workspace_bytes;
     info->small_batch_rows = SPLIT_BELOW_BLOCKS * info->rows_per_workgroup;
+    info->workgroup_waves = family_waves_per_block(f->dev);
     return FOREST_OK;
 }
 

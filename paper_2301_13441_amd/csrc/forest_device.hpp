@@ -25,6 +25,7 @@ struct DevModel {
     int32_t reg_nv, reg_r;   // REG family: 32 * reg_nv feature registers, reg_r rows per lane
     // RANK family
     int32_t rank_regs;
+    int32_t lds_waves;  // LDS rank family: wavefronts per workgroup
     const FeatBucket *feat_bucket;
     const int32_t *bucket_start;
     const float *thr_sorted;

@@ -254,7 +254,7 @@ int family_rows_per_block(const DevModel &m)
     return TILE;
 }
 
-int family_waves_per_block(const DevModel &m) { return m.path == PATH_RANK_LDS ? RANKLDS_WAVES : WAVES; }
+int family_waves_per_block(const DevModel &m) { return m.path == PATH_RANK_LDS ? m.lds_waves : WAVES; }
 
 int64_t split_workspace_doubles(int n_outputs)
 {

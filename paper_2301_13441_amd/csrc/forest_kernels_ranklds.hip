@@ -20,7 +20,9 @@
 // reference is either the child's ordinal in the next level or a leaf.  One pass over the
 // stream therefore resolves the leaf with a working set of one level.
 //
-// A workgroup is RANKLDS_WAVES wavefronts on 128 rows; the trees are split over the waves.
+// A workgroup is 12 or 8 wavefronts on 128 rows (the host compiler chooses: 12 where two
+// workgroups fit a CU's LDS, which with 80 vector registers per lane gives 6 waves per SIMD);
+// the trees are split over the waves.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -32,8 +34,6 @@
 namespace forest_impl {
 namespace {
 
-constexpr int LWAVES = RANKLDS_WAVES;
-constexpr int LBLOCK = TILE * LWAVES;
 
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
@@ -51,9 +51,9 @@ typedef const uint32_t *StreamPtr;  // host pass: the kernel body is only parsed
 
 // LDS between the rank tile and the partial sums: one chunk of outcome bytes (8 groups x 2 rows
 // x 64 lanes) per wave.
-__host__ __device__ inline size_t ranklds_region2_bytes()
+__host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 {
-    return static_cast<size_t>(LWAVES) * 8 * 2 * 64;
+    return static_cast<size_t>(waves) * 8 * 2 * 64;
 }
 
 // A pair of groups (16 entries) is evaluated from 16 scalar registers: s[36:51] for even pairs,
@@ -65,23 +65,23 @@ __host__ __device__ inline size_t ranklds_region2_bytes()
 #define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)        \
     "s_mov_b32 %[f0], " S0 "\n\t"                                                                              \
     "s_mov_b32 %[f1], " S8 "\n\t"                                                                              \
-    FOREST_LDS_ADDR("v112", S0) FOREST_LDS_ADDR("v113", S1) FOREST_LDS_ADDR("v114", S2)                         \
-    FOREST_LDS_ADDR("v115", S3) FOREST_LDS_ADDR("v116", S4) FOREST_LDS_ADDR("v117", S5)                         \
-    FOREST_LDS_ADDR("v118", S6) FOREST_LDS_ADDR("v119", S7)                                                     \
-    FOREST_LDS_READ("v112") FOREST_LDS_READ("v113") FOREST_LDS_READ("v114") FOREST_LDS_READ("v115")             \
-    FOREST_LDS_READ("v116") FOREST_LDS_READ("v117") FOREST_LDS_READ("v118") FOREST_LDS_READ("v119")             \
-    FOREST_LDS_ADDR("v120", S8) FOREST_LDS_ADDR("v121", S9) FOREST_LDS_ADDR("v122", S10)                        \
-    FOREST_LDS_ADDR("v123", S11) FOREST_LDS_ADDR("v124", S12) FOREST_LDS_ADDR("v125", S13)                      \
-    FOREST_LDS_ADDR("v126", S14) FOREST_LDS_ADDR("v127", S15)                                                   \
-    FOREST_LDS_READ("v120") FOREST_LDS_READ("v121") FOREST_LDS_READ("v122") FOREST_LDS_READ("v123")             \
-    FOREST_LDS_READ("v124") FOREST_LDS_READ("v125") FOREST_LDS_READ("v126") FOREST_LDS_READ("v127")             \
+    FOREST_LDS_ADDR("v64", S0) FOREST_LDS_ADDR("v65", S1) FOREST_LDS_ADDR("v66", S2)                         \
+    FOREST_LDS_ADDR("v67", S3) FOREST_LDS_ADDR("v68", S4) FOREST_LDS_ADDR("v69", S5)                         \
+    FOREST_LDS_ADDR("v70", S6) FOREST_LDS_ADDR("v71", S7)                                                     \
+    FOREST_LDS_READ("v64") FOREST_LDS_READ("v65") FOREST_LDS_READ("v66") FOREST_LDS_READ("v67")             \
+    FOREST_LDS_READ("v68") FOREST_LDS_READ("v69") FOREST_LDS_READ("v70") FOREST_LDS_READ("v71")             \
+    FOREST_LDS_ADDR("v72", S8) FOREST_LDS_ADDR("v73", S9) FOREST_LDS_ADDR("v74", S10)                        \
+    FOREST_LDS_ADDR("v75", S11) FOREST_LDS_ADDR("v76", S12) FOREST_LDS_ADDR("v77", S13)                      \
+    FOREST_LDS_ADDR("v78", S14) FOREST_LDS_ADDR("v79", S15)                                                   \
+    FOREST_LDS_READ("v72") FOREST_LDS_READ("v73") FOREST_LDS_READ("v74") FOREST_LDS_READ("v75")             \
+    FOREST_LDS_READ("v76") FOREST_LDS_READ("v77") FOREST_LDS_READ("v78") FOREST_LDS_READ("v79")             \
     "s_waitcnt lgkmcnt(8)\n\t"                                                                                 \
-    FOREST_LDS_CMP("v112", S0) FOREST_LDS_CMP("v113", S1) FOREST_LDS_CMP("v114", S2) FOREST_LDS_CMP("v115", S3) \
-    FOREST_LDS_CMP("v116", S4) FOREST_LDS_CMP("v117", S5) FOREST_LDS_CMP("v118", S6) FOREST_LDS_CMP("v119", S7) \
+    FOREST_LDS_CMP("v64", S0) FOREST_LDS_CMP("v65", S1) FOREST_LDS_CMP("v66", S2) FOREST_LDS_CMP("v67", S3) \
+    FOREST_LDS_CMP("v68", S4) FOREST_LDS_CMP("v69", S5) FOREST_LDS_CMP("v70", S6) FOREST_LDS_CMP("v71", S7) \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                 \
-    FOREST_LDS_CMP("v120", S8) FOREST_LDS_CMP("v121", S9) FOREST_LDS_CMP("v122", S10)                           \
-    FOREST_LDS_CMP("v123", S11) FOREST_LDS_CMP("v124", S12) FOREST_LDS_CMP("v125", S13)                         \
-    FOREST_LDS_CMP("v126", S14) FOREST_LDS_CMP("v127", S15)                                                     \
+    FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10)                           \
+    FOREST_LDS_CMP("v75", S11) FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13)                         \
+    FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15)                                                     \
     "s_load_dwordx16 " SET ", %[p], " NEXT
 
 // Two groups of 8 entries for the lane's two rows.  All 16 LDS reads are issued before the
@@ -101,7 +101,7 @@ __device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, u
 {
     asm volatile(FOREST_LDS_PAIR("s36", "s37", "s38", "s39", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47",
                                  "s48", "s49", "s50", "s51", "s[36:51]", "0x80")
-                 : "={v[112:119]}"(d0), "={v[120:127]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
+                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
                  : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
                  : "memory");
 }
@@ -111,7 +111,7 @@ __device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, ui
 {
     asm volatile(FOREST_LDS_PAIR("s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63",
                                  "s64", "s65", "s66", "s67", "s[52:67]", "0xc0")
-                 : "={v[112:119]}"(d0), "={v[120:127]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
+                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
                  : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
                  : "memory");
 }
@@ -134,7 +134,7 @@ enum { MODE_SCALAR1 = 0, MODE_VECTOR2 = 1, MODE_GENERAL = 2, MODE_LEAVES = 3 };
 
 constexpr int CHUNK_GROUPS = 8;  // a level is walked in chunks of 8 groups = 64 nodes
 
-template <int MODE>
+template <int MODE, int LWAVES>
 __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes, Accumulator<2> &accu,
                                               double (&sum)[2][2], int wave, int lane, int64_t row0,
                                               int64_t n_rows, int32_t *leaf_out)
@@ -272,10 +272,12 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     if (prev_count > 1) consume(prev_g1, prev_f1);
 }
 
-__global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, const float *__restrict__ X,
-                                                                int64_t n_rows, float *scores,
-                                                                int32_t *labels, int32_t *leaf_out)
+// 80 vector registers per lane in either size: six waves per SIMD.
+template <int LWAVES>
+__global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6, 6))) void forest_ranklds_kernel(
+    DevModel m, const float *__restrict__ X, int64_t n_rows, float *scores, int32_t *labels, int32_t *leaf_out)
 {
+    constexpr int LBLOCK = TILE * LWAVES;
     extern __shared__ __align__(16) char smem[];
     const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
     const int K = m.n_outputs;
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
     char *region2 = smem + sizeof(uint32_t) * TILE * regs;
     const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
-    const size_t r2_bytes = ranklds_region2_bytes();
+    const size_t r2_bytes = ranklds_region2_bytes(LWAVES);
     double *acc = deferred ? reinterpret_cast<double *>(smem) : reinterpret_cast<double *>(region2 + r2_bytes);
 
     const int lane = threadIdx.x & (TILE - 1);
@@ -305,18 +307,18 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
     Accumulator<2> accu;
     double sum[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
     if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
-        ranklds_trees<MODE_LEAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, leaf_out);
+        ranklds_trees<MODE_LEAVES, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, leaf_out);
         return;
     }
     if (deferred) {
-        if (m.leaf_width == 1) ranklds_trees<MODE_SCALAR1>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
-        else ranklds_trees<MODE_VECTOR2>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        if (m.leaf_width == 1) ranklds_trees<MODE_SCALAR1, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        else ranklds_trees<MODE_VECTOR2, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
         __syncthreads();  // no wave reads the rank tile any more
         for (int r = 0; r < 2; ++r)
             for (int k = 0; k < K; ++k) acc[(wave * K + k) * RROWS + r * TILE + lane] = sum[r][k];
     } else {
         accu.init(acc, wave, lane, m);
-        ranklds_trees<MODE_GENERAL>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        ranklds_trees<MODE_GENERAL, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
         accu.flush();
     }
     __syncthreads();
@@ -326,31 +328,31 @@ __global__ __launch_bounds__(LBLOCK) void forest_ranklds_kernel(DevModel m, cons
 
 }  // namespace
 
-size_t ranklds_lds_bytes(const DevModel &m)
-{
-    const size_t regs = m.rank_regs > 0 ? m.rank_regs : 1;
-    const int K = m.n_outputs;
-    const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
-    const size_t sums = sizeof(double) * LWAVES * K * RROWS;
-    const size_t front = sizeof(uint32_t) * TILE * regs + ranklds_region2_bytes();
-    return deferred ? (front > sums ? front : sums) : front + sums;
-}
-
 hipError_t init_ranklds_kernels(size_t lds_limit)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel<RANKLDS_WAVES_WIDE>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel<RANKLDS_WAVES_NARROW>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
 }
 
 hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream)
 {
-    const size_t lds = ranklds_lds_bytes(m);
+    const bool wide = m.lds_waves == RANKLDS_WAVES_WIDE;
+    if (!wide && m.lds_waves != RANKLDS_WAVES_NARROW) return hipErrorInvalidValue;
+    const size_t lds = ranklds_lds_bytes(m.rank_regs, m.n_outputs, m.leaf_width, m.lds_waves);
     if (lds > lds_limit || m.rank_regs > RANKLDS_MAX_REGS) return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(forest_ranklds_kernel, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(LBLOCK), lds, stream, m,
-                       X, n_rows, scores, labels, leaf_out);
+    const dim3 grid(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits));
+    if (wide)
+        hipLaunchKernelGGL(forest_ranklds_kernel<RANKLDS_WAVES_WIDE>, grid, dim3(TILE * RANKLDS_WAVES_WIDE), lds, stream,
+                           m, X, n_rows, scores, labels, leaf_out);
+    else
+        hipLaunchKernelGGL(forest_ranklds_kernel<RANKLDS_WAVES_NARROW>, grid, dim3(TILE * RANKLDS_WAVES_NARROW), lds,
+                           stream, m, X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }
 

@@ -40,7 +40,9 @@ constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature
 constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
 constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel
 constexpr int PROGRAM_PAD_ENTRIES = 96;        // readable entries after the last tree's
-constexpr int RANKLDS_WAVES = 8;               // wavefronts per workgroup of that kernel
+constexpr int RANKLDS_WAVES_WIDE = 12;         // wavefronts per workgroup of that kernel: 12 where two
+constexpr int RANKLDS_WAVES_NARROW = 8;        // workgroups of 12 share a CU's LDS (6 per SIMD), else 8
+constexpr size_t CU_LDS_BYTES = 160 * 1024;
 
 // Rank lookup of one feature: bucket(x) = trunc((x - lo) * scale) clamped to [0, n_buckets),
 // start[bucket] .. start[bucket + 1] bracket rank(x) in the feature's sorted thresholds.
@@ -99,6 +101,7 @@ struct PackedModel {
     int32_t path = PATH_LDS;
     // rank family: X is rewritten, exactly, as per-feature threshold ranks (see forest_pack.cpp)
     int32_t rank_regs = 0;        // packed rank registers per lane (one per virtual feature)
+    int32_t lds_waves = 0;        // LDS rank family: wavefronts per workgroup
     std::vector<FeatBucket> feat_bucket;  // [F] bucket table of each feature
     std::vector<int32_t> bucket_start;    // per feature: #thresholds in lower buckets, n_buckets + 1 entries
     std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
@@ -121,6 +124,19 @@ struct PackedModel {
     std::vector<int32_t> v_feature, v_left, v_right, v_leaf_node;
     std::vector<float> v_threshold, v_leaf_value;
 };
+
+// LDS of one workgroup of the LDS rank kernel with `waves` wavefronts: the rank tile, one chunk
+// of outcome bytes (8 groups x 2 rows x 64 lanes) per wave and the float64 partial sums, which
+// reuse the front part when they can wait in registers until every wave is done.
+inline size_t ranklds_lds_bytes(int rank_regs, int n_outputs, int leaf_width, int waves)
+{
+    const size_t regs = rank_regs > 0 ? static_cast<size_t>(rank_regs) : 1;
+    const int K = n_outputs, W = leaf_width;
+    const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
+    const size_t front = sizeof(uint32_t) * 64 * regs + static_cast<size_t>(waves) * 8 * 2 * 64;
+    const size_t sums = sizeof(double) * static_cast<size_t>(waves) * K * 128;
+    return deferred ? (front > sums ? front : sums) : front + sums;
+}
 
 // Validates `d` and fills `out`.  Returns FOREST_OK or a negative FOREST_E* code.
 int compile_forest(const forest_desc &d, PackedModel &out);

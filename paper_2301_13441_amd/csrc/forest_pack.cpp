@@ -263,16 +263,23 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
     }
     if (m.path == PATH_LDS && T > 0) {
-        // Rank family with the ranks held in LDS: any tree shape.  Needs, per workgroup of
-        // RANKLDS_WAVES waves: the rank tile, one chunk of outcome bytes per wave and, unless the
-        // partial sums can wait in registers, the partial sums.
-        const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
-        const size_t front = sizeof(uint32_t) * 64 * static_cast<size_t>(std::max<int64_t>(regs, 1)) +
-                             size_t{RANKLDS_WAVES} * 8 * 2 * 64;
-        const size_t sums = sizeof(double) * RANKLDS_WAVES * K * 128;
-        const size_t lds = deferred ? std::max(front, sums) : front + sums;
-        if (regs <= RANKLDS_MAX_REGS && lds <= RANKLDS_MAX_LDS) {
+        // Rank family with the ranks held in LDS: any tree shape.  The workgroup size that puts
+        // the most wavefronts on a CU wins (two workgroups of 12 waves when their LDS allows).
+        int best_waves = 0;
+        size_t best_per_cu = 0;
+        for (int waves : {RANKLDS_WAVES_WIDE, RANKLDS_WAVES_NARROW}) {
+            const size_t lds = ranklds_lds_bytes(regs, K, W, waves);
+            if (lds > RANKLDS_MAX_LDS) continue;
+            // 80 vector registers per lane: at most 6 waves per SIMD, 24 per CU
+            const size_t per_cu = std::min<size_t>((CU_LDS_BYTES / lds) * static_cast<size_t>(waves), 24);
+            if (per_cu > best_per_cu) {
+                best_per_cu = per_cu;
+                best_waves = waves;
+            }
+        }
+        if (regs <= RANKLDS_MAX_REGS && best_waves > 0) {
             m.path = PATH_RANK_LDS;
+            m.lds_waves = best_waves;
             build_rank_tables();
         }
     }

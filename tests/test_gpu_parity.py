@@ -314,6 +314,7 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
     ("reg_fallback", 1),          # too many rank registers -> float32 feature registers
     ("ranklds_full_wide", 3),     # full trees over > 128 features: ranks in LDS
     ("ranklds_irregular", 3),     # irregular trees, 3 output columns
+    ("ranklds_narrow", 3),        # 10 output columns over 64 features: workgroups of 8 waves
     ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the rank kernels
     ("lds_generic_many_outputs", 0),
 ])
@@ -330,6 +331,9 @@ def test_kernel_families(what, path):
     elif what == "ranklds_irregular":
         f = wl.random_forest(6, n_trees=37, n_features=11, max_depth=10, stop_prob=0.12, n_outputs=3,
                              transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "ranklds_narrow":
+        f = wl.random_forest(8, n_trees=45, n_features=64, max_depth=9, stop_prob=0.15, n_outputs=10,
+                             transform=wl.TRANSFORM_SOFTMAX)
     elif what == "lds_many_outputs":
         f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
     else:
@@ -341,6 +345,8 @@ def test_kernel_families(what, path):
     X[:64, 0] = np.resize(thr, 64)
     info = _check(f, X)
     assert info["kernel_path"] == path, info
+    if what.startswith("ranklds"):
+        assert info["workgroup_waves"] == (8 if what == "ranklds_narrow" else 12), info
 
 
 def test_duplicate_thresholds_and_unused_features():
