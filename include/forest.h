@@ -186,6 +186,12 @@ typedef struct forest_packed_view {
     const int32_t *rank_threshold_base;        /* [n_features + 1] */
     const struct forest_rank_bucket *rank_bucket; /* [n_features] */
     const int32_t *rank_bucket_start;
+    /* kernel_path 3: wavefronts per workgroup, the trees of each wavefront (processing order:
+     * wave w takes trees wave_tree[w] .. wave_tree[w + 1] - 1, workgroup_waves + 1 entries) and
+     * the program length of every tree in that order, in groups of 8 entries; else 0 / NULL. */
+    int32_t workgroup_waves;
+    const int32_t *wave_tree;
+    const int32_t *program_groups; /* [n_trees] */
 } forest_packed_view;
 
 typedef struct forest_packed forest_packed;

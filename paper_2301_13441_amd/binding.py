@@ -45,7 +45,8 @@ class _View(ctypes.Structure):
                 ("tree_is_full", _p), ("node_base", _p), ("leaf_base", _p), ("split_feature", _p),
                 ("split_threshold", _p), ("child_left", _p), ("child_right", _p), ("leaf_node", _p),
                 ("leaf_value", _p), ("rank_threshold", _p), ("rank_threshold_base", _p),
-                ("rank_bucket", _p), ("rank_bucket_start", _p)]
+                ("rank_bucket", _p), ("rank_bucket_start", _p),
+                ("workgroup_waves", _i32), ("wave_tree", _p), ("program_groups", _p)]
 
 
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
@@ -167,6 +168,10 @@ def forest_pack(forest) -> dict:
                         rank_bucket_scale=bucket[:, 1].copy().view(np.float32),
                         rank_bucket_count=bucket[:, 2].copy(), rank_bucket_base=bucket[:, 3].copy(),
                         rank_bucket_start=get(v.rank_bucket_start, n_start, np.int32))
+        if v.wave_tree:
+            rank["workgroup_waves"] = int(v.workgroup_waves)
+            rank["wave_tree"] = get(v.wave_tree, int(v.workgroup_waves) + 1, np.int32)
+            rank["program_groups"] = get(v.program_groups, T, np.int32)
         return dict(
             **rank,
             n_trees=T, kernel_kind=v.kernel_kind, kernel_path=v.kernel_path,

@@ -117,6 +117,9 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     v->rank_threshold_base = ranks ? m.feat_thr_base.data() : nullptr;
     v->rank_bucket = ranks ? reinterpret_cast<const forest_rank_bucket *>(m.feat_bucket.data()) : nullptr;
     v->rank_bucket_start = ranks ? m.bucket_start.data() : nullptr;
+    v->workgroup_waves = m.path == PATH_RANK_LDS ? m.lds_waves : 0;
+    v->wave_tree = m.path == PATH_RANK_LDS ? m.wave_tree : nullptr;
+    v->program_groups = m.path == PATH_RANK_LDS ? m.v_program_groups.data() : nullptr;
     return FOREST_OK;
 }
 
@@ -222,6 +225,7 @@ int forest_load(const forest_desc *desc, forest **out)
     d.reg_r = m.reg_r;
     d.rank_regs = m.rank_regs;
     d.lds_waves = m.lds_waves;
+    for (int w = 0; w <= RANKLDS_WAVES_WIDE; ++w) d.wave_tree[w] = m.wave_tree[w];
     d.feat_bucket = reinterpret_cast<const FeatBucket *>(b + o_fbk);
     d.bucket_start = reinterpret_cast<const int32_t *>(b + o_bst);
     d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);

@@ -26,6 +26,7 @@ struct DevModel {
     // RANK family
     int32_t rank_regs;
     int32_t lds_waves;  // LDS rank family: wavefronts per workgroup
+    int32_t wave_tree[RANKLDS_WAVES_WIDE + 1];  // and the trees of each wave when the launch is not split
     const FeatBucket *feat_bucket;
     const int32_t *bucket_start;
     const float *thr_sorted;

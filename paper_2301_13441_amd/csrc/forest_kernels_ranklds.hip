@@ -141,7 +141,12 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
 {
     const int T = m.n_trees;
     int t_begin, t_end;
-    tree_range(m, wave, LWAVES, t_begin, t_end);
+    if (m.n_splits == 1) {  // launch-uniform: runs of about equal program length, cut at load time
+        t_begin = m.wave_tree[wave];
+        t_end = m.wave_tree[wave + 1];
+    } else {
+        tree_range(m, wave, LWAVES, t_begin, t_end);
+    }
     if (t_begin >= t_end) return;
     MetaPtr meta = (MetaPtr)m.tree;
     const uint32_t mask = 0xff00u;

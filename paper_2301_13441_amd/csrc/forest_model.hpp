@@ -102,6 +102,9 @@ struct PackedModel {
     // rank family: X is rewritten, exactly, as per-feature threshold ranks (see forest_pack.cpp)
     int32_t rank_regs = 0;        // packed rank registers per lane (one per virtual feature)
     int32_t lds_waves = 0;        // LDS rank family: wavefronts per workgroup
+    // LDS rank family: wave w of a workgroup evaluates trees wave_tree[w] .. wave_tree[w + 1]
+    // (processing order) -- contiguous runs of about equal program length
+    int32_t wave_tree[RANKLDS_WAVES_WIDE + 1] = {};
     std::vector<FeatBucket> feat_bucket;  // [F] bucket table of each feature
     std::vector<int32_t> bucket_start;    // per feature: #thresholds in lower buckets, n_buckets + 1 entries
     std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
@@ -119,7 +122,7 @@ struct PackedModel {
     std::vector<float> base;         // [K]
 
     // caller-order views used only by forest_pack_view
-    std::vector<int32_t> v_n_internal, v_depth, v_is_full;
+    std::vector<int32_t> v_n_internal, v_depth, v_is_full, v_program_groups;
     std::vector<int64_t> v_node_base, v_leaf_base;
     std::vector<int32_t> v_feature, v_left, v_right, v_leaf_node;
     std::vector<float> v_threshold, v_leaf_value;

@@ -154,6 +154,43 @@ int check_desc(const forest_desc &d)
 
 }  // namespace
 
+// Trees of irregular shape differ in program length, and a workgroup ends with its slowest
+// wave: cut the trees (processing order) into lds_waves contiguous runs whose longest is as
+// short as possible.  Cost of a tree: its groups plus two for the work at its end.
+static void balance_waves(PackedModel &m)
+{
+    const int waves = m.lds_waves;
+    const int32_t T = m.n_trees;
+    auto cost = [&](int32_t t) { return static_cast<int64_t>(m.tree[t].n_words) + 2; };
+    int64_t lo = 0, hi = 0;  // the answer lies in [largest tree, all trees]
+    for (int32_t t = 0; t < T; ++t) {
+        lo = std::max(lo, cost(t));
+        hi += cost(t);
+    }
+    // greedy cut under a cap; returns the number of runs and fills `cut` when asked
+    auto runs = [&](int64_t cap, int32_t *cut) {
+        int n = 0;
+        int64_t sum = 0;
+        for (int32_t t = 0; t < T; ++t) {
+            if (t == 0 || sum + cost(t) > cap) {
+                if (cut && n <= waves) cut[n] = t;
+                ++n;
+                sum = 0;
+            }
+            sum += cost(t);
+        }
+        return n;
+    };
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (runs(mid, nullptr) <= waves) hi = mid;
+        else lo = mid + 1;
+    }
+    int32_t cut[RANKLDS_WAVES_WIDE + 2] = {};
+    const int n = T > 0 ? runs(lo, cut) : 0;
+    for (int w = 0; w <= waves; ++w) m.wave_tree[w] = w < n ? cut[w] : T;  // spare waves get no trees
+}
+
 int compile_forest(const forest_desc &d, PackedModel &m)
 {
     if (int rc = check_desc(d)) return rc;
@@ -421,6 +458,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
         m.tree.push_back(tm);
     }
+    if (m.path == PATH_RANK_LDS) balance_waves(m);
+    for (const TreeMeta &tm : m.tree) m.v_program_groups.push_back(tm.n_words);
     m.tree.push_back(TreeMeta{});  // spare record: the stream kernels read the root of "the next tree"
     // Padding: the kernels prefetch (and may evaluate, without using the result) up to eleven
     // groups past the entries of their trees.

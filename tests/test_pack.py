@@ -143,6 +143,32 @@ def test_kernel_family_choice():
     assert v["kernel_path"] == 2 and v["rank_registers"] == 56       # ~4550 thresholds per feature
 
 
+def test_lds_rank_family_cuts_the_trees_into_balanced_runs():
+    """Irregular trees: each wave of a workgroup gets a contiguous run of trees, the runs cover
+    every tree once, and the longest run is the shortest any contiguous cut allows (brute force
+    over all cuts on a small forest; never longer than the equal-count cut on c5)."""
+    import itertools
+    small = wl.random_forest(21, n_trees=9, n_features=6, max_depth=9, stop_prob=0.1, n_outputs=3)
+    for forest in (small, wl.make_workload("c5", n_rows=1).forest):
+        v = pk.forest_pack(forest)
+        assert v["kernel_path"] == 3
+        waves, cut, groups = v["workgroup_waves"], v["wave_tree"], v["program_groups"].astype(np.int64)
+        T = forest.n_trees
+        assert waves in (8, 12) and len(cut) == waves + 1
+        assert cut[0] == 0 and cut[-1] == T and (np.diff(cut) >= 0).all()
+        cost = groups + 2
+        run = lambda a, b: int(cost[a:b].sum())
+        longest = max(run(cut[w], cut[w + 1]) for w in range(waves))
+        equal = max(run(T * w // waves, T * (w + 1) // waves) for w in range(waves))
+        assert longest <= equal
+        if T <= 9:
+            best = min(max(run(a, b) for a, b in zip((0,) + c, c + (T,)))
+                       for c in itertools.combinations_with_replacement(range(T + 1), waves - 1))
+            assert longest == best
+        else:
+            print("c5: longest run", longest, "equal-count cut", equal, "mean", cost.sum() / waves)
+
+
 def _bucket_of(x, lo, scale, count):
     """bucket_index of the library, in float32 like the kernels."""
     with np.errstate(all="ignore"):   # inf * 0 = NaN is a bucket-0 case, as in the library
