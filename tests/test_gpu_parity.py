@@ -75,6 +75,36 @@ def test_irregular_forests_with_ties(seed):
     assert info["kernel_kind"] == 0 and info["kernel_path"] == 3
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_models_and_batches(seed):
+    """Everything drawn at once: full or irregular trees, feature and tree counts, depth, output
+    columns, scalar or vector leaves, aggregate, base scores, transform, output kind, batch size
+    (single rows, ragged tiles, batches that cut the trees into shares and batches that do not)."""
+    rng = np.random.default_rng(7000 + seed)
+    K = int(rng.choice([1, 1, 2, 3, 5, 12]))
+    vector = bool(K > 1 and rng.random() < 0.4)
+    transform = int(rng.choice([wl.TRANSFORM_NONE, wl.TRANSFORM_SIGMOID] if K == 1 else
+                               [wl.TRANSFORM_NONE, wl.TRANSFORM_SIGMOID, wl.TRANSFORM_SOFTMAX]))
+    kw = dict(n_outputs=K, transform=transform, aggregate=int(rng.choice([wl.AGG_SUM, wl.AGG_MEAN])),
+              output=int(rng.choice([wl.OUT_SCORES, wl.OUT_LABELS, wl.OUT_BOTH])))
+    F = int(rng.choice([1, 2, 7, 28, 60, 130, 260]))
+    T = int(rng.integers(1, 70))
+    if rng.random() < 0.5 and not vector:
+        f = _full_forest(8000 + seed, T, int(rng.integers(1, 9)), F, **{k: v for k, v in kw.items() if k != "n_outputs"},
+                         n_outputs=K)
+    else:
+        f = wl.random_forest(8000 + seed, n_trees=T, n_features=F, max_depth=int(rng.integers(1, 12)),
+                             stop_prob=float(rng.choice([0.05, 0.2, 0.4])), leaf_width=(K if vector else 1),
+                             grid_thresholds=bool(rng.random() < 0.3), **kw)
+    if rng.random() < 0.5:
+        f = wl.Forest(**{**f.__dict__, "base_score": rng.standard_normal(K).astype(np.float32)})
+    rows = int(rng.choice([1, 2, 63, 64, 65, 127, 128, 129, 500, 1111, 70000]))
+    X = rng.standard_normal((rows, F)).astype(np.float32)
+    if rng.random() < 0.3:
+        X = np.round(X * 2) / 2          # many x == threshold cases on grid thresholds
+    _check(f, X, leaves=rows <= 2000)
+
+
 def test_special_values_nan_inf_signed_zero():
     w = wl.make_workload("c1", n_rows=256)
     X = w.make_x(256).copy()
@@ -305,7 +335,7 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
         arrs["feature"] = np.where(hit, 0, arrs["feature"]).astype(np.int32)
     out = (rng.integers(0, n_outputs, size=n_trees).astype(np.int32))
     return wl.Forest(n_features=n_features, n_outputs=n_outputs, leaf_width=1, tree_output=out,
-                     aggregate=wl.AGG_SUM, **arrs, **kw)
+                     **arrs, **{"aggregate": wl.AGG_SUM, **kw})
 
 
 @pytest.mark.parametrize("what,path", [
