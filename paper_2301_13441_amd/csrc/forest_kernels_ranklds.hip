@@ -132,7 +132,7 @@ __device__ __forceinline__ void load_first_pairs(v16u &even, v16u &odd, StreamPt
 // sums can reuse the LDS of the rank tile; GENERAL keeps them in an LDS region of its own.
 enum { MODE_SCALAR1 = 0, MODE_VECTOR2 = 1, MODE_GENERAL = 2, MODE_LEAVES = 3 };
 
-constexpr int CHUNK_GROUPS = 8;  // a level is walked in chunks of 8 groups = 64 nodes
+constexpr int CHUNK_GROUPS = RANKLDS_CHUNK_GROUPS;  // a level is walked in chunks of 8 groups = 64 nodes
 
 template <int MODE, int LWAVES>
 __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes, Accumulator<2> &accu,
@@ -185,26 +185,28 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         bytes[(gi * 2 + 1) * TILE + lane] = static_cast<uint8_t>(__float_as_uint(g[1]));
         ++gi;
         pos += 8;
-        if (gi == CHUNK_GROUPS || (flags & 1u)) {  // chunk complete: lanes whose node is in it pick a child
-            if (resolve) {
+        // flag bit 2: last group of a chunk (set at load time: every eighth group of a level and
+        // its last).  Level and tree ends are chunk ends too, so the common group tests one bit.
+        if (!(flags & 4u)) return;
+        // chunk complete: lanes whose node is in it pick a child
+        if (resolve) {
 #pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    if (ref[r] == WAITING) ref[r] = ((outcome[r] >> bit[r]) & 1u) ? pair[r].right : pair[r].left;
-                resolve = false;
-            }
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
-                    // both fetches are only looked at when the child is picked, a group or more later
-                    outcome[r] = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
-                    bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
-                    pair[r] = m.child[level_start + ref[r]];
-                    ref[r] = WAITING;
-                }
-            }
-            ++chunk;
-            gi = 0;
+            for (int r = 0; r < 2; ++r)
+                if (ref[r] == WAITING) ref[r] = ((outcome[r] >> bit[r]) & 1u) ? pair[r].right : pair[r].left;
+            resolve = false;
         }
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
+                // both fetches are only looked at when the child is picked, a group or more later
+                outcome[r] = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
+                bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
+                pair[r] = m.child[level_start + ref[r]];
+                ref[r] = WAITING;
+            }
+        }
+        ++chunk;
+        gi = 0;
         if (flags & 1u) {  // level complete: every lane that was on a node has picked its child
             resolve = true;
             level_start = pos;

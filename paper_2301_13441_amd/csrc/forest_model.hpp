@@ -43,6 +43,7 @@ constexpr int PROGRAM_PAD_ENTRIES = 96;        // readable entries after the las
 constexpr int RANKLDS_WAVES_WIDE = 12;         // wavefronts per workgroup of that kernel: 12 where two
 constexpr int RANKLDS_WAVES_NARROW = 8;        // workgroups of 12 share a CU's LDS (6 per SIMD), else 8
 constexpr size_t CU_LDS_BYTES = 160 * 1024;
+constexpr int RANKLDS_CHUNK_GROUPS = 8;        // that kernel walks a level in chunks of 8 groups = 64 nodes
 
 // Rank lookup of one feature: bucket(x) = trunc((x - lo) * scale) clamped to [0, n_buckets),
 // start[bucket] .. start[bucket + 1] bracket rank(x) in the feature's sorted thresholds.

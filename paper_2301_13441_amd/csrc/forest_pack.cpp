@@ -393,25 +393,30 @@ int compile_forest(const forest_desc &d, PackedModel &m)
 
         if (m.path == PATH_RANK_LDS) {
             // Stream of 8-entry groups, level by level (each level padded to whole groups).  The
-            // first entry of a group carries two flags in its low byte: bit 0 = last group of
-            // its level, bit 1 = last group of the tree.  The child-reference table is indexed
-            // like the stream; a reference >= 0 is the node's ordinal inside the next level.
+            // first entry of a group carries three flags in its low byte: bit 0 = last group of
+            // its level, bit 1 = last group of the tree, bit 2 = last group of a chunk (every
+            // eighth group of a level, and its last: the walk looks at its nodes chunk by
+            // chunk).  The child-reference table is indexed like the stream; a reference >= 0 is
+            // the node's ordinal inside the next level.
             const size_t n_levels = s.level_begin.size() - 1;
             if (n_levels == 0) {  // the root is a leaf: one group of padding closes the tree
                 for (int j = 0; j < 8; ++j) {
                     m.prog.push_back(pad);
                     m.child.push_back(ChildRef{~0, ~0});
                 }
-                m.prog[m.prog.size() - 8].feature_slot |= 3 << 16;
+                m.prog[m.prog.size() - 8].feature_slot |= 7 << 16;
             }
             for (size_t l = 0; l < n_levels; ++l) {
                 const int32_t lb = s.level_begin[l], le = s.level_begin[l + 1];
                 const int32_t next_begin = le;  // ordinals of the next level start here
                 // entries: groups of 8 in descending ordinal (the first entry of a group becomes
                 // bit 7 of the outcome byte); child references: ascending ordinal
-                for (int32_t g0 = lb; g0 < le; g0 += 8)
+                for (int32_t g0 = lb; g0 < le; g0 += 8) {
                     for (int32_t k = 7; k >= 0; --k)
                         m.prog.push_back(g0 + k < le ? entry_of(t, s.internal[g0 + k]) : pad);
+                    if ((g0 - lb) / 8 % RANKLDS_CHUNK_GROUPS == RANKLDS_CHUNK_GROUPS - 1)
+                        m.prog[m.prog.size() - 8].feature_slot |= 4 << 16;
+                }
                 for (int32_t i = lb; i < le; ++i) {
                     const int32_t v = s.internal[i];
                     auto ref_of = [&](int32_t c) {
@@ -422,7 +427,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 }
                 while (m.child.size() < m.prog.size()) m.child.push_back(ChildRef{~0, ~0});
                 const size_t last_group = m.prog.size() - 8;
-                m.prog[last_group].feature_slot |= (l + 1 == n_levels ? 3 : 1) << 16;
+                m.prog[last_group].feature_slot |= (l + 1 == n_levels ? 7 : 5) << 16;
             }
             tm.n_words = static_cast<int32_t>((m.prog.size() - tm.prog_base) / 8);
             for (int32_t v : s.leaves) {
