@@ -245,38 +245,51 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     bits.init(lane);
     v4f prev_g0 = bits.bias, prev_g1 = bits.bias;
     uint32_t prev_f0 = 0, prev_f1 = 0;
-    int prev_count = 0;  // wave-uniform: groups of the previous pair that belong to the wave
-    auto after_pair = [&](const v8i &d0, const v8i &d1, uint32_t f0, uint32_t f1, int count) {
+    auto consume_previous = [&]() {
 #if defined(__HIP_DEVICE_COMPILE__)
         __builtin_amdgcn_sched_barrier(0);
 #endif
-        if (prev_count > 0) consume(prev_g0, prev_f0);
-        if (prev_count > 1) consume(prev_g1, prev_f1);
+        consume(prev_g0, prev_f0);
+        consume(prev_g1, prev_f1);
+    };
+    auto collect = [&](const v8i &d0, const v8i &d1, uint32_t f0, uint32_t f1) {
         prev_g0 = bits.collect_b(d0, bits.bias);
         prev_g1 = bits.collect_b(d1, bits.bias);
         prev_f0 = f0;
         prev_f1 = f1;
-        prev_count = count;
     };
-    // Every statement fetches two pairs ahead whatever the wave's own group count is (past the
-    // end of the wave's stream that is the next wave's groups or the padding at the end of the
-    // program), and a pair past the end is evaluated but not consumed.
-    static_assert(PROGRAM_PAD_ENTRIES >= 64, "the last fetch reaches 8 groups past a wave's stream");
-    for (int group = 0; group < n_groups; group += 4) {
-        v8i d0, d1;
-        uint32_t f0, f1;
-        eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
-        after_pair(d0, d1, f0, f1, n_groups - group);
-        if (group + 2 < n_groups) {
-            eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
-            after_pair(d0, d1, f0, f1, n_groups - group - 2);
-        }
+    // Pair k of the wave's stream is evaluated from the even register set when k is even.  Every
+    // statement fetches two pairs ahead whatever the wave's own group count is (past the end
+    // of the wave's stream that is the next wave's groups or the padding at the end of the
+    // program).  Every pair but the last has two groups of the wave's own.
+    static_assert(PROGRAM_PAD_ENTRIES >= 64, "the last fetches reach 4 pairs past a wave's stream");
+    const int n_pairs = (n_groups + 1) >> 1;
+    v8i d0, d1;
+    uint32_t f0, f1;
+    eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+    collect(d0, d1, f0, f1);
+    int k = 1;
+    for (; k + 1 < n_pairs; k += 2) {
+        eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
+        consume_previous();
+        collect(d0, d1, f0, f1);
         p += 32;
+        eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
+        consume_previous();
+        collect(d0, d1, f0, f1);
     }
-    // the last statement's fetch is still in flight: let it land before the registers are reused
+    if (k < n_pairs) {
+        eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
+        consume_previous();
+        collect(d0, d1, f0, f1);
+    }
+    // the last statements' fetches are still in flight: let them land before the registers are reused
     asm volatile("s_waitcnt lgkmcnt(0)" : "+{s[36:51]}"(set_even), "+{s[52:67]}"(set_odd) : : "memory");
-    if (prev_count > 0) consume(prev_g0, prev_f0);
-    if (prev_count > 1) consume(prev_g1, prev_f1);
+    consume(prev_g0, prev_f0);
+    if (!(n_groups & 1)) consume(prev_g1, prev_f1);
 }
 
 // 80 vector registers per lane in either size: six waves per SIMD.
