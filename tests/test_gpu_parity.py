@@ -105,6 +105,21 @@ def test_random_models_and_batches(seed):
     _check(f, X, leaves=rows <= 2000)
 
 
+@pytest.mark.parametrize("what", ["depth", "features", "outputs", "all"])
+def test_models_at_the_documented_limits(what):
+    """64 tests on the longest path, 4096 features, 32 output columns: each alone and together."""
+    from test_pack import _chain_forest
+    depth, F, K = {"depth": (64, 5, 1), "features": (6, 4096, 2), "outputs": (6, 9, 32), "all": (64, 4096, 32)}[what]
+    n_trees = 700 if what == "features" else 7     # 4200 nodes: most of the 4096 features are tested somewhere
+    for vector in (False, True):
+        if vector and K == 1:
+            continue
+        f = _chain_forest(depth, F, n_trees=n_trees, n_outputs=K, leaf_width=(K if vector else 1), seed=depth + F + K,
+                          transform=(wl.TRANSFORM_SOFTMAX if K > 1 else wl.TRANSFORM_SIGMOID))
+        rng = np.random.default_rng(F)
+        _check(f, rng.standard_normal((300, F)).astype(np.float32))
+
+
 def test_special_values_nan_inf_signed_zero():
     w = wl.make_workload("c1", n_rows=256)
     X = w.make_x(256).copy()

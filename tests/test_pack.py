@@ -109,6 +109,40 @@ def test_error_paths_need_no_gpu():
     lib.forest_pack_free(None)
 
 
+def _chain_forest(depth, n_features, n_trees=3, n_outputs=1, leaf_width=1, seed=0, **kw):
+    """Trees that are one long path: internal node i has a leaf on one side (which side is
+    drawn) and node i + 1 on the other; `depth` tests on the longest path."""
+    rng = np.random.default_rng(seed)
+    n = 2 * depth + 1
+    feature, threshold, left, right = [], [], [], []
+    for _ in range(n_trees):
+        f = np.full(n, -1, np.int32); t = np.zeros(n, np.float32)
+        l = np.full(n, -1, np.int32); r = np.full(n, -1, np.int32)
+        for i in range(depth):                      # internal nodes 0..depth-1, leaves depth..2*depth
+            f[i] = rng.integers(0, n_features); t[i] = rng.standard_normal()
+            nxt, leaf = (i + 1 if i + 1 < depth else 2 * depth), depth + i
+            l[i], r[i] = (nxt, leaf) if rng.random() < 0.5 else (leaf, nxt)
+        feature.append(f); threshold.append(t); left.append(l); right.append(r)
+    vals = rng.standard_normal((n_trees * n, leaf_width)).astype(np.float32)
+    feat = np.concatenate(feature)
+    vals[feat >= 0] = 0
+    return wl.Forest(n_features=n_features, n_outputs=n_outputs, leaf_width=leaf_width,
+                     tree_offset=np.arange(n_trees + 1, dtype=np.int64) * n, feature=feat,
+                     threshold=np.concatenate(threshold), left=np.concatenate(left), right=np.concatenate(right),
+                     leaf_value=vals, tree_output=(rng.integers(0, n_outputs, n_trees).astype(np.int32)
+                                                   if leaf_width == 1 else np.zeros(n_trees, np.int32)), **kw)
+
+
+def test_documented_limits_are_the_limits():
+    """Just inside every documented limit packs; just outside is refused with the limit code."""
+    pk.forest_pack(_chain_forest(64, 5))
+    _bad(_chain_forest(65, 5), -7)                          # FOREST_MAX_DEPTH
+    pk.forest_pack(_chain_forest(3, 4096))
+    _bad(_chain_forest(3, 4097), -7)                        # FOREST_MAX_FEATURES
+    pk.forest_pack(_chain_forest(3, 6, n_outputs=32))
+    _bad(_chain_forest(3, 6, n_outputs=33), -7)             # FOREST_MAX_OUTPUTS
+
+
 def test_load_without_device_reports_hip_error_not_crash():
     import torch
     if torch.cuda.is_available():
