@@ -44,6 +44,8 @@ enum {
 #define FOREST_MAX_FEATURES 4096  /* n_features */
 #define FOREST_MAX_OUTPUTS 32     /* n_outputs (K) */
 #define FOREST_MAX_DEPTH 64       /* longest root-to-leaf path, in tests */
+#define FOREST_MAX_NODES (1 << 27) /* internal nodes, and leaves, summed over the trees: the split
+                                      program pads levels to groups of 8 and indexes entries with int32 */
 /* Limit of one call (FOREST_ELIMIT from the predict and size calls): */
 #define FOREST_MAX_ROWS 1000000000 /* n_rows: keeps every launch inside HIP's 2^32 threads per grid axis */
 

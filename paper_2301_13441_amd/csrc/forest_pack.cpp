@@ -223,7 +223,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         if (W == 1) m.col_trees[d.tree_output ? d.tree_output[t] : 0] += 1.0;
         else for (int32_t k = 0; k < K; ++k) m.col_trees[k] += 1.0;
     }
-    if (m.n_internal > (int64_t{1} << 30) || m.n_leaves > (int64_t{1} << 30)) return FOREST_ELIMIT;
+    if (m.n_internal > FOREST_MAX_NODES || m.n_leaves > FOREST_MAX_NODES) return FOREST_ELIMIT;
     m.kind = (all_full && common_depth >= 1 && common_depth <= FULL_MAX_DEPTH) ? common_depth
                                                                               : KIND_GENERIC;
 
