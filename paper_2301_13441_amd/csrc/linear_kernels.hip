@@ -63,9 +63,11 @@ __device__ __forceinline__ void finish_linear_row(const LinDev &m, double (&acc)
                 acc[k] = exp(acc[k] - best);
                 z += acc[k];
             }
+        const double inv = 1.0 / z;  // one division per row; the product differs from the quotient by
+                                     // at most an ulp of float64, far below the float32 rounding
 #pragma unroll
         for (int k = 0; k < KP; ++k)
-            if (k < K) dst[k] = static_cast<float>(acc[k] / z);
+            if (k < K) dst[k] = static_cast<float>(acc[k] * inv);
     } else if (m.transform == LINEAR_TRANSFORM_SIGMOID) {
 #pragma unroll
         for (int k = 0; k < KP; ++k)
