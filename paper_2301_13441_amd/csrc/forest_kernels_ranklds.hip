@@ -4,14 +4,13 @@
 // !(x <= tau_j), two rows per 32-bit word, v_pk_add_f16 with clamp as the comparison), for
 // models whose rank tile does not fit the vector registers: up to 256 rank rows of 64 words
 // sit in LDS and every entry of the split program reads its row
-//     v_and_or_b32  a, entry, 0xff00, lane * 4          -- LDS address of the row, no scalar op
-//     ds_read_b32   x, a
-//     v_pk_add_f16  x, x, entry.hi  clamp               -- step (2) of Fig. 2 for two rows
-// i.e. two vector instructions and one LDS read per (node, two rows); the matrix core then
-// turns the 8 outcome registers of a group into one outcome byte per row
-// (forest_rank_common.hpp).  (Forming the address on the scalar side instead -- row offset to
-// M0, ds_read_addtid_b32 -- takes the address instruction off the vector ALU but costs the wave
-// two more instruction issues per entry, and measured 4 % slower.)
+//     s_and_b32           m0, entry, 0xff00             -- byte offset of the row (64 words each)
+//     ds_read_addtid_b32  x                             -- LDS[m0 + lane * 4]
+//     v_pk_add_f16        x, x, entry.hi  clamp         -- step (2) of Fig. 2 for two rows
+// i.e. one vector instruction and one LDS read per (node, two rows); the matrix core then turns
+// the 8 outcome registers of a group into one outcome byte per row (forest_rank_common.hpp).
+// The address is formed on the scalar side because the vector ALU is what the kernel is short
+// of (about 80 % busy); the write of M0 needs one wait state before the read that uses it.
 //
 // Trees are stored level by level (internal nodes in level order, Section 3.1.2; every level
 // padded to whole groups of 8 entries).  After the last group of a level the wave has that
@@ -57,31 +56,19 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 }
 
 // A pair of groups (16 entries) is evaluated from 16 scalar registers: s[36:51] for even pairs,
-// s[52:67] for odd pairs.  One entry: address of its rank row into a scratch register, the LDS
-// read, and the comparison, which leaves the outcome (1.0 or 0.0 in each f16 half) there.
-#define FOREST_LDS_ADDR(t, e) "v_and_or_b32 " t ", " e ", %[mask], %[l4]\n\t"
-#define FOREST_LDS_READ(t) "ds_read_b32 " t ", " t "\n\t"
+// s[52:67] for odd pairs.  One entry: the byte offset of its rank row (bits 8..15 of the entry)
+// goes to M0, the LDS read adds lane * 4 by itself, and the comparison leaves the outcome (1.0 or
+// 0.0 in each f16 half) in the register the read filled.
+#define FOREST_LDS_FETCH(t, e) "s_and_b32 m0, " e ", 0xff00\n\ts_nop 0\n\tds_read_addtid_b32 " t "\n\t"
 #define FOREST_LDS_CMP(t, e) "v_pk_add_f16 " t ", " t ", " e " op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
-#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)        \
-    "s_mov_b32 %[f0], " S0 "\n\t"                                                                              \
-    "s_mov_b32 %[f1], " S8 "\n\t"                                                                              \
-    FOREST_LDS_ADDR("v64", S0) FOREST_LDS_ADDR("v65", S1) FOREST_LDS_ADDR("v66", S2)                         \
-    FOREST_LDS_ADDR("v67", S3) FOREST_LDS_ADDR("v68", S4) FOREST_LDS_ADDR("v69", S5)                         \
-    FOREST_LDS_ADDR("v70", S6) FOREST_LDS_ADDR("v71", S7)                                                     \
-    FOREST_LDS_READ("v64") FOREST_LDS_READ("v65") FOREST_LDS_READ("v66") FOREST_LDS_READ("v67")             \
-    FOREST_LDS_READ("v68") FOREST_LDS_READ("v69") FOREST_LDS_READ("v70") FOREST_LDS_READ("v71")             \
-    FOREST_LDS_ADDR("v72", S8) FOREST_LDS_ADDR("v73", S9) FOREST_LDS_ADDR("v74", S10)                        \
-    FOREST_LDS_ADDR("v75", S11) FOREST_LDS_ADDR("v76", S12) FOREST_LDS_ADDR("v77", S13)                      \
-    FOREST_LDS_ADDR("v78", S14) FOREST_LDS_ADDR("v79", S15)                                                   \
-    FOREST_LDS_READ("v72") FOREST_LDS_READ("v73") FOREST_LDS_READ("v74") FOREST_LDS_READ("v75")             \
-    FOREST_LDS_READ("v76") FOREST_LDS_READ("v77") FOREST_LDS_READ("v78") FOREST_LDS_READ("v79")             \
-    "s_waitcnt lgkmcnt(8)\n\t"                                                                                 \
-    FOREST_LDS_CMP("v64", S0) FOREST_LDS_CMP("v65", S1) FOREST_LDS_CMP("v66", S2) FOREST_LDS_CMP("v67", S3) \
-    FOREST_LDS_CMP("v68", S4) FOREST_LDS_CMP("v69", S5) FOREST_LDS_CMP("v70", S6) FOREST_LDS_CMP("v71", S7) \
-    "s_waitcnt lgkmcnt(0)\n\t"                                                                                 \
-    FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10)                           \
-    FOREST_LDS_CMP("v75", S11) FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13)                         \
-    FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15)                                                     \
+#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT) \
+    "s_mov_b32 %[f0], " S0 "\n\t" \
+    "s_mov_b32 %[f1], " S8 "\n\t" \
+    FOREST_LDS_FETCH("v64", S0) FOREST_LDS_FETCH("v65", S1) FOREST_LDS_FETCH("v66", S2) FOREST_LDS_FETCH("v67", S3) FOREST_LDS_FETCH("v68", S4) FOREST_LDS_FETCH("v69", S5) FOREST_LDS_FETCH("v70", S6) FOREST_LDS_FETCH("v71", S7) FOREST_LDS_FETCH("v72", S8) FOREST_LDS_FETCH("v73", S9) FOREST_LDS_FETCH("v74", S10) FOREST_LDS_FETCH("v75", S11) FOREST_LDS_FETCH("v76", S12) FOREST_LDS_FETCH("v77", S13) FOREST_LDS_FETCH("v78", S14) FOREST_LDS_FETCH("v79", S15) \
+    "s_waitcnt lgkmcnt(8)\n\t" \
+    FOREST_LDS_CMP("v64", S0) FOREST_LDS_CMP("v65", S1) FOREST_LDS_CMP("v66", S2) FOREST_LDS_CMP("v67", S3) FOREST_LDS_CMP("v68", S4) FOREST_LDS_CMP("v69", S5) FOREST_LDS_CMP("v70", S6) FOREST_LDS_CMP("v71", S7) \
+    "s_waitcnt lgkmcnt(0)\n\t" \
+    FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10) FOREST_LDS_CMP("v75", S11) FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13) FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15) \
     "s_load_dwordx16 " SET ", %[p], " NEXT
 
 // Two groups of 8 entries for the lane's two rows.  All 16 LDS reads are issued before the
@@ -97,23 +84,23 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // d0, d1: the outcomes of the two groups, the matrix core's B operands.  f0, f1: the first
 // entry of each group (its low byte holds the group's flags).
 __device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
-                                               StreamPtr p, uint32_t mask, uint32_t l4)
+                                               StreamPtr p)
 {
     asm volatile(FOREST_LDS_PAIR("s36", "s37", "s38", "s39", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47",
                                  "s48", "s49", "s50", "s51", "s[36:51]", "0x80")
                  : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
-                 : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
-                 : "memory");
+                 : [p] "s"(p)
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
-                                              StreamPtr p, uint32_t mask, uint32_t l4)
+                                              StreamPtr p)
 {
     asm volatile(FOREST_LDS_PAIR("s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63",
                                  "s64", "s65", "s66", "s67", "s[52:67]", "0xc0")
                  : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
-                 : [p] "s"(p), [mask] "v"(mask), [l4] "v"(l4)
-                 : "memory");
+                 : [p] "s"(p)
+                 : "memory", "m0");
 }
 
 // The first two pairs of a wave's stream into the two register sets.
@@ -149,8 +136,6 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     }
     if (t_begin >= t_end) return;
     MetaPtr meta = (MetaPtr)m.tree;
-    const uint32_t mask = 0xff00u;
-    const uint32_t l4 = static_cast<uint32_t>(lane) * 4u;
 
     // The wave's trees are one contiguous stream of groups; the group after the last one read
     // here is padding the host appended to the program.
@@ -266,23 +251,23 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     const int n_pairs = (n_groups + 1) >> 1;
     v8i d0, d1;
     uint32_t f0, f1;
-    eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
+    eval_pair_even(d0, d1, f0, f1, set_even, p);
 #if defined(__HIP_DEVICE_COMPILE__)
     __builtin_amdgcn_sched_barrier(0);
 #endif
     collect(d0, d1, f0, f1);
     int k = 1;
     for (; k + 1 < n_pairs; k += 2) {
-        eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
+        eval_pair_odd(d0, d1, f0, f1, set_odd, p);
         consume_previous();
         collect(d0, d1, f0, f1);
         p += 32;
-        eval_pair_even(d0, d1, f0, f1, set_even, p, mask, l4);
+        eval_pair_even(d0, d1, f0, f1, set_even, p);
         consume_previous();
         collect(d0, d1, f0, f1);
     }
     if (k < n_pairs) {
-        eval_pair_odd(d0, d1, f0, f1, set_odd, p, mask, l4);
+        eval_pair_odd(d0, d1, f0, f1, set_odd, p);
         consume_previous();
         collect(d0, d1, f0, f1);
     }
@@ -302,8 +287,8 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
     const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
     const int K = m.n_outputs;
     // LDS: [ rank tile | one outcome-byte chunk per wave | partial sums (GENERAL) ].
-    // The rank tile must start at LDS address 0: the entries' reads form addresses as
-    // (row offset | lane * 4).  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
+    // The rank tile must start at LDS address 0: the entries' reads address it as
+    // row offset + lane * 4.  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
     // every wave has finished.
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
     char *region2 = smem + sizeof(uint32_t) * TILE * regs;
