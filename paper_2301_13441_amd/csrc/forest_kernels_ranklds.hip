@@ -182,9 +182,11 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         }
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            if (ref[r] >= 0 && (ref[r] >> 6) == chunk) {
+            // the lane stands on node ref[r] of this chunk: 64 * chunk <= ref[r] < 64 * chunk + 64
+            // (leaves and WAITING have the top bit set and fail the unsigned test)
+            if ((static_cast<uint32_t>(ref[r]) ^ (static_cast<uint32_t>(chunk) << 6)) < 64u) {
                 // both fetches are only looked at when the child is picked, a group or more later
-                outcome[r] = bytes[(((ref[r] >> 3) & 7) * 2 + r) * TILE + lane];
+                outcome[r] = bytes[__builtin_amdgcn_ubfe(static_cast<uint32_t>(ref[r]), 3, 3) * (2 * TILE) + (r * TILE + lane)];
                 bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
                 pair[r] = m.child[level_start + ref[r]];
                 ref[r] = WAITING;
