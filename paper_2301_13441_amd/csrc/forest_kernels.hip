@@ -299,8 +299,8 @@ static hipError_t launch_family(const DevModel &m, const float *X, int64_t n_row
     const int64_t n_blocks = (n_rows + TILE - 1) / TILE;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     KernelFn fn = pick(m.kind, leaf_out != nullptr, staged);
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), lds, stream, m, X, n_rows,
-                       scores, labels, leaf_out);
+    const dim3 grid(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits));
+    hipLaunchKernelGGL(fn, grid, dim3(BLOCK), lds, stream, m, X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }
 

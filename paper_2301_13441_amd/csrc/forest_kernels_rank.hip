@@ -428,8 +428,8 @@ hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float 
     KernelFn fn = pick_rank(nvr, m.kind);
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), rank_lds_bytes(m, nvr), stream, m,
-                       X, n_rows, scores, labels, leaf_out);
+    const dim3 grid(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits));
+    hipLaunchKernelGGL(fn, grid, dim3(BLOCK), rank_lds_bytes(m, nvr), stream, m, X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }
 

@@ -33,7 +33,6 @@
 namespace forest_impl {
 namespace {
 
-
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
 #else
@@ -61,14 +60,20 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // 0.0 in each f16 half) in the register the read filled.
 #define FOREST_LDS_FETCH(t, e) "s_and_b32 m0, " e ", 0xff00\n\ts_nop 0\n\tds_read_addtid_b32 " t "\n\t"
 #define FOREST_LDS_CMP(t, e) "v_pk_add_f16 " t ", " t ", " e " op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
-#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT) \
-    "s_mov_b32 %[f0], " S0 "\n\t" \
-    "s_mov_b32 %[f1], " S8 "\n\t" \
-    FOREST_LDS_FETCH("v64", S0) FOREST_LDS_FETCH("v65", S1) FOREST_LDS_FETCH("v66", S2) FOREST_LDS_FETCH("v67", S3) FOREST_LDS_FETCH("v68", S4) FOREST_LDS_FETCH("v69", S5) FOREST_LDS_FETCH("v70", S6) FOREST_LDS_FETCH("v71", S7) FOREST_LDS_FETCH("v72", S8) FOREST_LDS_FETCH("v73", S9) FOREST_LDS_FETCH("v74", S10) FOREST_LDS_FETCH("v75", S11) FOREST_LDS_FETCH("v76", S12) FOREST_LDS_FETCH("v77", S13) FOREST_LDS_FETCH("v78", S14) FOREST_LDS_FETCH("v79", S15) \
-    "s_waitcnt lgkmcnt(8)\n\t" \
-    FOREST_LDS_CMP("v64", S0) FOREST_LDS_CMP("v65", S1) FOREST_LDS_CMP("v66", S2) FOREST_LDS_CMP("v67", S3) FOREST_LDS_CMP("v68", S4) FOREST_LDS_CMP("v69", S5) FOREST_LDS_CMP("v70", S6) FOREST_LDS_CMP("v71", S7) \
-    "s_waitcnt lgkmcnt(0)\n\t" \
-    FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10) FOREST_LDS_CMP("v75", S11) FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13) FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15) \
+#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)           \
+    "s_mov_b32 %[f0], " S0 "\n\t"                                                                                \
+    "s_mov_b32 %[f1], " S8 "\n\t"                                                                                \
+    FOREST_LDS_FETCH("v64", S0) FOREST_LDS_FETCH("v65", S1) FOREST_LDS_FETCH("v66", S2) FOREST_LDS_FETCH("v67", S3)  \
+    FOREST_LDS_FETCH("v68", S4) FOREST_LDS_FETCH("v69", S5) FOREST_LDS_FETCH("v70", S6) FOREST_LDS_FETCH("v71", S7)  \
+    FOREST_LDS_FETCH("v72", S8) FOREST_LDS_FETCH("v73", S9) FOREST_LDS_FETCH("v74", S10)                            \
+    FOREST_LDS_FETCH("v75", S11) FOREST_LDS_FETCH("v76", S12) FOREST_LDS_FETCH("v77", S13)                          \
+    FOREST_LDS_FETCH("v78", S14) FOREST_LDS_FETCH("v79", S15)                                                       \
+    "s_waitcnt lgkmcnt(8)\n\t"                                                                                    \
+    FOREST_LDS_CMP("v64", S0) FOREST_LDS_CMP("v65", S1) FOREST_LDS_CMP("v66", S2) FOREST_LDS_CMP("v67", S3)          \
+    FOREST_LDS_CMP("v68", S4) FOREST_LDS_CMP("v69", S5) FOREST_LDS_CMP("v70", S6) FOREST_LDS_CMP("v71", S7)          \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                    \
+    FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10) FOREST_LDS_CMP("v75", S11)        \
+    FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13) FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15)      \
     "s_load_dwordx16 " SET ", %[p], " NEXT
 
 // Two groups of 8 entries for the lane's two rows.  All 16 LDS reads are issued before the
@@ -186,7 +191,8 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             // (leaves and WAITING have the top bit set and fail the unsigned test)
             if ((static_cast<uint32_t>(ref[r]) ^ (static_cast<uint32_t>(chunk) << 6)) < 64u) {
                 // both fetches are only looked at when the child is picked, a group or more later
-                outcome[r] = bytes[__builtin_amdgcn_ubfe(static_cast<uint32_t>(ref[r]), 3, 3) * (2 * TILE) + (r * TILE + lane)];
+                const uint32_t group_in_chunk = __builtin_amdgcn_ubfe(static_cast<uint32_t>(ref[r]), 3, 3);
+                outcome[r] = bytes[group_in_chunk * (2 * TILE) + (r * TILE + lane)];
                 bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
                 pair[r] = m.child[level_start + ref[r]];
                 ref[r] = WAITING;

@@ -251,8 +251,8 @@ hipError_t launch_reg(const DevModel &m, const float *X, int64_t n_rows, float *
     const int rows = TILE * m.reg_r;
     const int64_t n_blocks = (n_rows + rows - 1) / rows;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits)), dim3(BLOCK), reg_lds_bytes(m), stream, m, X,
-                       n_rows, scores, labels, leaf_out);
+    const dim3 grid(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits));
+    hipLaunchKernelGGL(fn, grid, dim3(BLOCK), reg_lds_bytes(m), stream, m, X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }
 
