@@ -71,6 +71,15 @@ def linear_desc(model):
     return d, keep
 
 
+def _check_x(X, n_features: int) -> None:
+    """The kernels trust the shape they are given: refuse anything but a contiguous float32
+    [n_rows, n_features] tensor in device memory before a pointer reaches them."""
+    import torch
+    if not (isinstance(X, torch.Tensor) and X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+            and X.shape[1] == n_features and X.is_contiguous()):
+        raise ValueError(f"X must be a contiguous float32 CUDA tensor of shape [n_rows, {n_features}]")
+
+
 class Linear:
     """Owner of a loaded linear model handle.  predict() takes torch CUDA tensors."""
 
@@ -112,13 +121,14 @@ class Linear:
         """X: torch float32 CUDA tensor [n_rows, F], contiguous.  Returns (scores, labels) views
         into one uint8 output buffer (either may be None, per the model's output kind)."""
         import torch
-        assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous()
-        assert X.dim() == 2 and X.shape[1] == self.n_features
+        _check_x(X, self.n_features)
         n = X.shape[0]
         nbytes = self.out_bytes(n)
         if out is None:
             out = torch.empty(max(nbytes, 4), dtype=torch.uint8, device=X.device)
-        assert out.is_cuda and out.numel() * out.element_size() >= nbytes
+        if not (out.is_cuda and out.device == X.device and out.is_contiguous()
+                and out.numel() * out.element_size() >= nbytes):
+            raise ValueError(f"out must be a contiguous tensor of at least {nbytes} bytes on {X.device}")
         s = torch.cuda.current_stream(X.device) if stream is None else stream
         self.predict_raw(X.data_ptr(), n, out.data_ptr(), s.cuda_stream)
         so, lo = self.out_layout(n)

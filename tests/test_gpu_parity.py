@@ -320,6 +320,22 @@ def test_null_pointers_are_refused_before_any_launch():
                 call()
             assert e.value.code == -7
         assert f.out_bytes(10**9) == 10**9 * 8
+        # the binding refuses tensors the kernels would read out of bounds or misinterpret
+        import torch
+        F = w.forest.n_features
+        good = torch.zeros((10, F), dtype=torch.float32, device="cuda")
+        for bad in (torch.zeros((10, F - 1), dtype=torch.float32, device="cuda"),       # too few columns
+                    torch.zeros((10, F), dtype=torch.float64, device="cuda"),           # wrong dtype
+                    torch.zeros((10, F), dtype=torch.float32),                          # host memory
+                    torch.zeros((10, 2 * F), dtype=torch.float32, device="cuda")[:, ::2],  # strided
+                    torch.zeros((10 * F,), dtype=torch.float32, device="cuda")):        # not a matrix
+            with pytest.raises(ValueError):
+                f.predict(bad)
+            with pytest.raises(ValueError):
+                f.predict_leaves(bad)
+        with pytest.raises(ValueError):
+            f.predict(good, out=torch.empty(8, dtype=torch.uint8, device="cuda"))      # output too small
+        f.predict(good)
     finally:
         f.close()
 

@@ -129,6 +129,11 @@ def test_output_kinds_ties_and_empty_batch():
     with pytest.raises(lb.LinearError) as e:   # more rows than one call takes
         m.predict_raw(256, 10**9 + 1, 256, 0)
     assert e.value.code == -7
+    for bad in (torch.zeros((10, 5), dtype=torch.float32, device="cuda"),      # wrong feature count
+                torch.zeros((10, 6), dtype=torch.float32),                     # host memory
+                torch.zeros((10, 6), dtype=torch.float16, device="cuda")):     # wrong dtype
+        with pytest.raises(ValueError):
+            m.predict(bad)
     m.close()
     torch.cuda.synchronize()
 
