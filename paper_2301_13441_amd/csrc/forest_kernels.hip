@@ -183,12 +183,10 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
 constexpr size_t LDS_LIMIT = 160 * 1024;  // LDS of one gfx950 compute unit
 size_t g_lds_limit = LDS_LIMIT;            // replaced by the device's per-workgroup limit at init
 
+static_assert(WAVES == 4 && TILE == 64, "plain_lds_bytes assumes this workgroup shape");
 size_t lds_bytes(int kind, int n_features, int n_outputs, int max_words, bool staged)
 {
-    size_t b = sizeof(double) * WAVES * n_outputs * TILE;
-    if (staged) b += sizeof(float) * n_features * TILE;
-    if (kind == KIND_GENERIC) b += sizeof(uint32_t) * WAVES * max_words * TILE;
-    return b;
+    return plain_lds_bytes(kind, n_features, n_outputs, max_words, staged);
 }
 
 size_t lds_bytes(const DevModel &m, bool staged)

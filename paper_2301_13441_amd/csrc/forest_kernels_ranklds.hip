@@ -339,33 +339,42 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
     if (li < RROWS) finish_row(m, acc, RROWS, li, row0 + li, row0 + li < n_rows, scores, labels, LWAVES);
 }
 
+using RankLdsFn = void (*)(DevModel, const float *, int64_t, float *, int32_t *, int32_t *);
+
+RankLdsFn ranklds_kernel_for(int waves)
+{
+    switch (waves) {
+        case 12: return forest_ranklds_kernel<12>;
+        case 8: return forest_ranklds_kernel<8>;
+        case 4: return forest_ranklds_kernel<4>;
+        case 2: return forest_ranklds_kernel<2>;
+        default: return nullptr;
+    }
+}
+
 }  // namespace
 
 hipError_t init_ranklds_kernels(size_t lds_limit)
 {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel<RANKLDS_WAVES_WIDE>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(forest_ranklds_kernel<RANKLDS_WAVES_NARROW>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+    for (int waves : RANKLDS_WAVE_CHOICES) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ranklds_kernel_for(waves)),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream)
 {
-    const bool wide = m.lds_waves == RANKLDS_WAVES_WIDE;
-    if (!wide && m.lds_waves != RANKLDS_WAVES_NARROW) return hipErrorInvalidValue;
+    RankLdsFn fn = ranklds_kernel_for(m.lds_waves);
+    if (!fn) return hipErrorInvalidValue;
     const size_t lds = ranklds_lds_bytes(m.rank_regs, m.n_outputs, m.leaf_width, m.lds_waves);
     if (lds > lds_limit || m.rank_regs > RANKLDS_MAX_REGS) return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid(static_cast<unsigned>(n_blocks), static_cast<unsigned>(m.n_splits));
-    if (wide)
-        hipLaunchKernelGGL(forest_ranklds_kernel<RANKLDS_WAVES_WIDE>, grid, dim3(TILE * RANKLDS_WAVES_WIDE), lds, stream,
-                           m, X, n_rows, scores, labels, leaf_out);
-    else
-        hipLaunchKernelGGL(forest_ranklds_kernel<RANKLDS_WAVES_NARROW>, grid, dim3(TILE * RANKLDS_WAVES_NARROW), lds,
-                           stream, m, X, n_rows, scores, labels, leaf_out);
+    hipLaunchKernelGGL(fn, grid, dim3(TILE * m.lds_waves), lds, stream, m, X, n_rows, scores, labels, leaf_out);
     return hipGetLastError();
 }
 

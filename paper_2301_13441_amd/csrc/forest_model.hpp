@@ -40,8 +40,10 @@ constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature
 constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
 constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel
 constexpr int PROGRAM_PAD_ENTRIES = 96;        // readable entries after the last tree's
-constexpr int RANKLDS_WAVES_WIDE = 12;         // wavefronts per workgroup of that kernel: 12 where two
-constexpr int RANKLDS_WAVES_NARROW = 8;        // workgroups of 12 share a CU's LDS (6 per SIMD), else 8
+constexpr int RANKLDS_WAVES_WIDE = 12;         // most wavefronts per workgroup of that kernel
+// Workgroup sizes the kernel is built for, in waves: 12 where two workgroups share a CU's LDS
+// (6 waves per SIMD), fewer where the model's LDS need per wave is larger.
+constexpr int RANKLDS_WAVE_CHOICES[] = {12, 8, 4, 2};
 constexpr size_t CU_LDS_BYTES = 160 * 1024;
 constexpr int RANKLDS_CHUNK_GROUPS = 8;        // that kernel walks a level in chunks of 8 groups = 64 nodes
 
@@ -140,6 +142,17 @@ inline size_t ranklds_lds_bytes(int rank_regs, int n_outputs, int leaf_width, in
     const size_t front = sizeof(uint32_t) * 64 * regs + static_cast<size_t>(waves) * 8 * 2 * 64;
     const size_t sums = sizeof(double) * static_cast<size_t>(waves) * K * 128;
     return deferred ? (front > sums ? front : sums) : front + sums;
+}
+
+// LDS of one workgroup (4 waves, 64 rows) of the plain LDS family: float64 partial sums, the
+// transposed X tile when it is staged, and for trees of irregular shape the outcome words of one
+// tree per wave.
+inline size_t plain_lds_bytes(int kind, int n_features, int n_outputs, int max_words, bool staged)
+{
+    size_t b = sizeof(double) * 4 * static_cast<size_t>(n_outputs) * 64;
+    if (staged) b += sizeof(float) * static_cast<size_t>(n_features) * 64;
+    if (kind == KIND_GENERIC) b += sizeof(uint32_t) * 4 * static_cast<size_t>(max_words) * 64;
+    return b;
 }
 
 // Validates `d` and fills `out`.  Returns FOREST_OK or a negative FOREST_E* code.

@@ -301,11 +301,21 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     }
     if (m.path == PATH_LDS && T > 0) {
         // Rank family with the ranks held in LDS: any tree shape.  The workgroup size that puts
-        // the most wavefronts on a CU wins (two workgroups of 12 waves when their LDS allows).
+        // the most wavefronts on a CU wins (two workgroups of 12 waves when their LDS allows; the
+        // small sizes are for many output columns, whose partial sums take 1 KB per wave and
+        // column: two waves fit whatever the model).
+        // Does the plain LDS family take the model?  (Its irregular-tree kernel holds the outcome
+        // words of a whole tree per wave.)  If it does, the small workgroups are not tried: the
+        // plain family is the better fallback for many output columns.
+        int plain_words = 1;
+        for (int32_t t = 0; t < T; ++t)
+            plain_words = std::max(plain_words, static_cast<int>((shape[t].internal.size() + 31) / 32));
+        const bool plain_fits = plain_lds_bytes(m.kind, d.n_features, K, plain_words, false) <= CU_LDS_BYTES;
         int best_waves = 0;
         size_t best_per_cu = 0;
-        for (int waves : {RANKLDS_WAVES_WIDE, RANKLDS_WAVES_NARROW}) {
-            const size_t lds = ranklds_lds_bytes(regs, K, W, waves);
+        for (int waves : RANKLDS_WAVE_CHOICES) {
+            if (plain_fits && waves < 8) continue;
+            const size_t lds = ranklds_lds_bytes(static_cast<int>(std::min<int64_t>(regs, RANKLDS_MAX_REGS)), K, W, waves);
             if (lds > RANKLDS_MAX_LDS) continue;
             // 80 vector registers per lane: at most 6 waves per SIMD, 24 per CU
             const size_t per_cu = std::min<size_t>((CU_LDS_BYTES / lds) * static_cast<size_t>(waves), 24);

@@ -376,6 +376,8 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
     ("ranklds_full_wide", 3),     # full trees over > 128 features: ranks in LDS
     ("ranklds_irregular", 3),     # irregular trees, 3 output columns
     ("ranklds_narrow", 3),        # 10 output columns over 64 features: workgroups of 8 waves
+    ("ranklds_four_waves", 3),    # 12 columns, trees too large for the plain kernels: 4 waves
+    ("ranklds_two_waves", 3),     # 32-wide vector leaves on such trees: 2 waves
     ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the rank kernels
     ("lds_generic_many_outputs", 0),
 ])
@@ -395,6 +397,12 @@ def test_kernel_families(what, path):
     elif what == "ranklds_narrow":
         f = wl.random_forest(8, n_trees=45, n_features=64, max_depth=9, stop_prob=0.15, n_outputs=10,
                              transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "ranklds_four_waves":
+        f = wl.random_forest(9, n_trees=9, n_features=256, max_depth=13, stop_prob=0.02, n_outputs=12,
+                             transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "ranklds_two_waves":
+        f = wl.random_forest(10, n_trees=5, n_features=130, max_depth=13, stop_prob=0.02, n_outputs=32, leaf_width=32,
+                             transform=wl.TRANSFORM_SOFTMAX)
     elif what == "lds_many_outputs":
         f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
     else:
@@ -407,7 +415,8 @@ def test_kernel_families(what, path):
     info = _check(f, X)
     assert info["kernel_path"] == path, info
     if what.startswith("ranklds"):
-        assert info["workgroup_waves"] == (8 if what == "ranklds_narrow" else 12), info
+        waves = {"ranklds_narrow": 8, "ranklds_four_waves": 4, "ranklds_two_waves": 2}.get(what, 12)
+        assert info["workgroup_waves"] == waves, info
 
 
 def test_duplicate_thresholds_and_unused_features():
