@@ -46,11 +46,6 @@ enum {
 #define FOREST_MAX_DEPTH 64       /* longest root-to-leaf path, in tests */
 #define FOREST_MAX_NODES (1 << 27) /* internal nodes, and leaves, summed over the trees: the split
                                       program pads levels to groups of 8 and indexes entries with int32 */
-/* One combination inside these limits is refused as well (FOREST_ELIMIT at load): a model that
- * needs more than 256 threshold-rank rows (the sum over the features of ceil(distinct thresholds
- * of the feature / 4095)) AND has a tree of irregular shape with more than
- * 32 * (160 - 2 * n_outputs) internal nodes (5056 for one output column).  Such a model runs in
- * the plain kernels, which keep the outcome bits of a whole tree per wavefront in LDS. */
 /* Limit of one call (FOREST_ELIMIT from the predict and size calls): */
 #define FOREST_MAX_ROWS 1000000000 /* n_rows: keeps every launch inside HIP's 2^32 threads per grid axis */
 

@@ -31,7 +31,6 @@ namespace {
 struct Lds {
     double *acc;     // [WAVES][K][64]     per-wave partial sums
     float *xs;       // [F][64]            (staged X tile; unused when !STAGED)
-    uint32_t *bits;  // [WAVES][max_words][64] outcome words (generic kernel only)
 };
 
 __device__ __forceinline__ Lds carve_lds(char *smem, const DevModel &m, bool staged)
@@ -41,8 +40,6 @@ __device__ __forceinline__ Lds carve_lds(char *smem, const DevModel &m, bool sta
     l.acc = reinterpret_cast<double *>(smem + off);
     off += sizeof(double) * WAVES * m.n_outputs * TILE;
     l.xs = reinterpret_cast<float *>(smem + off);
-    if (staged) off += sizeof(float) * m.n_features * TILE;
-    l.bits = reinterpret_cast<uint32_t *>(smem + off);
     return l;
 }
 
@@ -110,8 +107,10 @@ __global__ __launch_bounds__(BLOCK) void forest_full_kernel(DevModel m, const fl
 }
 
 // ---------------------------------------------------------------------------------------
-// Generic trees: any shape.  Outcome words are written to LDS (one word per 32 internal
-// nodes, level order), the walk follows child references.
+// Generic trees: any shape and size.  The internal nodes are evaluated 32 at a time in level
+// order; after each outcome word the lanes whose node is among its 32 follow their child
+// reference.  A child comes later in level order than its parent, so one pass over the words
+// ends on the leaf, and nothing but the current word is kept.
 // ---------------------------------------------------------------------------------------
 template <bool LEAVES, bool STAGED>
 __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const float *__restrict__ X,
@@ -135,7 +134,6 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
 
     Accumulator<1> accu;
     accu.init(lds.acc, wave, lane, m);
-    uint32_t *mybits = lds.bits + static_cast<size_t>(wave) * m.max_words * TILE;
 
     const int T = m.n_trees;
     int t_begin, t_end;
@@ -144,6 +142,8 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
     for (int t = t_begin; t < t_end; ++t) {
         const TreeMeta tm = m.tree[t];
         const SplitEntry *__restrict__ p = m.prog + tm.prog_base;
+        const ChildRef *__restrict__ ch = m.child + tm.child_base;
+        int ref = tm.root_ref;  // level-order ordinal of the lane's node, or ~leaf
         for (int w = 0; w < tm.n_words; ++w) {
             uint32_t b = 0;
 #pragma unroll
@@ -152,18 +152,16 @@ __global__ __launch_bounds__(BLOCK) void forest_generic_kernel(DevModel m, const
                 const float x = STAGED ? lds.xs[e.feature_slot + lane] : xrow[e.feature_slot >> 6];
                 b = b + b + (!(x <= e.threshold) ? 1u : 0u);
             }
-            mybits[w * TILE + lane] = b;
-        }
-        // walk over child references; a validated tree ends within FOREST_MAX_DEPTH steps
-        int ref = tm.root_ref;
-        const ChildRef *__restrict__ ch = m.child + tm.child_base;
-        for (int step = 0; step <= FOREST_MAX_DEPTH; ++step) {
-            const bool inside = ref >= 0;
-            if (!__any(inside)) break;
-            if (inside) {
-                const uint32_t wv = mybits[(ref >> 5) * TILE + lane];
-                const ChildRef c = ch[ref];
-                ref = ((wv >> (ref & 31)) & 1u) ? c.right : c.left;
+            // lanes standing on one of these 32 nodes move on; at the top of a tree the child
+            // can be in the same word, so repeat until no lane is left in it (a validated tree
+            // has no cycles: every move goes to a later ordinal or to a leaf)
+            for (;;) {
+                const bool here = ref >= 0 && (ref >> 5) == w;
+                if (!__any(here)) break;
+                if (here) {
+                    const ChildRef c = ch[ref];
+                    ref = ((b >> (ref & 31)) & 1u) ? c.right : c.left;
+                }
             }
         }
         const int leaf = tm.leaf_base + (ref < 0 ? ~ref : 0);
@@ -184,15 +182,7 @@ constexpr size_t LDS_LIMIT = 160 * 1024;  // LDS of one gfx950 compute unit
 size_t g_lds_limit = LDS_LIMIT;            // replaced by the device's per-workgroup limit at init
 
 static_assert(WAVES == 4 && TILE == 64, "plain_lds_bytes assumes this workgroup shape");
-size_t lds_bytes(int kind, int n_features, int n_outputs, int max_words, bool staged)
-{
-    return plain_lds_bytes(kind, n_features, n_outputs, max_words, staged);
-}
-
-size_t lds_bytes(const DevModel &m, bool staged)
-{
-    return lds_bytes(m.kind, m.n_features, m.n_outputs, m.max_words, staged);
-}
+size_t lds_bytes(const DevModel &m, bool staged) { return plain_lds_bytes(m.n_features, m.n_outputs, staged); }
 
 template <bool LEAVES, bool STAGED>
 KernelFn pick_kernel(int kind)
@@ -221,7 +211,7 @@ KernelFn pick(int kind, bool leaves, bool staged)
 bool model_fits(const PackedModel &m)
 {
     if (m.path != PATH_LDS) return true;  // their LDS need is bounded at pack time
-    return lds_bytes(m.kind, m.n_features, m.n_outputs, m.max_words, false) <= LDS_LIMIT;
+    return plain_lds_bytes(m.n_features, m.n_outputs, false) <= LDS_LIMIT;  // 2 KB per output column
 }
 
 hipError_t init_kernels()

@@ -144,14 +144,12 @@ inline size_t ranklds_lds_bytes(int rank_regs, int n_outputs, int leaf_width, in
     return deferred ? (front > sums ? front : sums) : front + sums;
 }
 
-// LDS of one workgroup (4 waves, 64 rows) of the plain LDS family: float64 partial sums, the
-// transposed X tile when it is staged, and for trees of irregular shape the outcome words of one
-// tree per wave.
-inline size_t plain_lds_bytes(int kind, int n_features, int n_outputs, int max_words, bool staged)
+// LDS of one workgroup (4 waves, 64 rows) of the plain LDS family: float64 partial sums and the
+// transposed X tile when it is staged.
+inline size_t plain_lds_bytes(int n_features, int n_outputs, bool staged)
 {
     size_t b = sizeof(double) * 4 * static_cast<size_t>(n_outputs) * 64;
     if (staged) b += sizeof(float) * static_cast<size_t>(n_features) * 64;
-    if (kind == KIND_GENERIC) b += sizeof(uint32_t) * 4 * static_cast<size_t>(max_words) * 64;
     return b;
 }
 

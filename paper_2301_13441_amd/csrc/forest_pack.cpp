@@ -303,18 +303,16 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         // Rank family with the ranks held in LDS: any tree shape.  The workgroup size that puts
         // the most wavefronts on a CU wins (two workgroups of 12 waves when their LDS allows; the
         // small sizes are for many output columns, whose partial sums take 1 KB per wave and
-        // column: two waves fit whatever the model).
-        // Does the plain LDS family take the model?  (Its irregular-tree kernel holds the outcome
-        // words of a whole tree per wave.)  If it does, the small workgroups are not tried: the
-        // plain family is the better fallback for many output columns.
-        int plain_words = 1;
-        for (int32_t t = 0; t < T; ++t)
-            plain_words = std::max(plain_words, static_cast<int>((shape[t].internal.size() + 31) / 32));
-        const bool plain_fits = plain_lds_bytes(m.kind, d.n_features, K, plain_words, false) <= CU_LDS_BYTES;
+        // column: two waves fit whatever the model).  Models that need more than 256 rank rows
+        // stay in the plain family, whose kernels take any model.
+        // The small workgroups (4 and 2 waves) are for irregular trees only: measured faster than
+        // the plain family's irregular-tree kernel on models with 12 to 32 output columns, while
+        // shallow full trees with many columns run faster in the plain full-tree kernels.
+        const bool small_workgroups = m.kind == KIND_GENERIC;
         int best_waves = 0;
         size_t best_per_cu = 0;
         for (int waves : RANKLDS_WAVE_CHOICES) {
-            if (plain_fits && waves < 8) continue;
+            if (!small_workgroups && waves < 8) continue;
             const size_t lds = ranklds_lds_bytes(static_cast<int>(std::min<int64_t>(regs, RANKLDS_MAX_REGS)), K, W, waves);
             if (lds > RANKLDS_MAX_LDS) continue;
             // 80 vector registers per lane: at most 6 waves per SIMD, 24 per CU

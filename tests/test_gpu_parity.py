@@ -175,11 +175,17 @@ def test_small_batches_other_families():
     for rows in (1, 100, 300):
         info = _check(f, rng.standard_normal((rows, 128)).astype(np.float32))
         assert info["kernel_path"] == 1
-    # plain LDS family: irregular trees with 20 output columns
+    # LDS rank family in small workgroups: irregular trees with 20 output columns
     g = wl.random_forest(901, n_trees=96, n_features=7, max_depth=7, stop_prob=0.15, n_outputs=20,
                          leaf_width=20, transform=wl.TRANSFORM_SOFTMAX, aggregate=wl.AGG_MEAN)
     for rows in (1, 70, 500):
         info = _check(g, rng.standard_normal((rows, 7)).astype(np.float32))
+        assert info["kernel_path"] == 3 and info["workgroup_waves"] == 2
+    # plain LDS family: irregular trees over more features than the rank tile has rows
+    g = wl.random_forest(902, n_trees=96, n_features=300, max_depth=7, stop_prob=0.1, n_outputs=20,
+                         leaf_width=20, transform=wl.TRANSFORM_SOFTMAX, aggregate=wl.AGG_MEAN)
+    for rows in (1, 70, 500):
+        info = _check(g, rng.standard_normal((rows, 300)).astype(np.float32))
         assert info["kernel_path"] == 0
 
 
@@ -380,6 +386,7 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
     ("ranklds_two_waves", 3),     # 32-wide vector leaves on such trees: 2 waves
     ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the rank kernels
     ("lds_generic_many_outputs", 0),
+    ("lds_generic_large_trees", 0),   # more than 256 rank rows and trees of ~7000 nodes: plain family, any size
 ])
 def test_kernel_families(what, path):
     rng = np.random.default_rng(42)
@@ -405,8 +412,11 @@ def test_kernel_families(what, path):
                              transform=wl.TRANSFORM_SOFTMAX)
     elif what == "lds_many_outputs":
         f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
+    elif what == "lds_generic_large_trees":
+        f = wl.random_forest(11, n_trees=6, n_features=300, max_depth=13, stop_prob=0.02, n_outputs=5, leaf_width=5,
+                             transform=wl.TRANSFORM_SOFTMAX)
     else:
-        f = wl.random_forest(7, n_trees=21, n_features=7, max_depth=8, stop_prob=0.2, n_outputs=20,
+        f = wl.random_forest(7, n_trees=41, n_features=300, max_depth=8, stop_prob=0.1, n_outputs=20,
                              transform=wl.TRANSFORM_SOFTMAX)
     X = rng.standard_normal((517, f.n_features)).astype(np.float32)
     # rows that sit exactly on thresholds of their feature

@@ -168,7 +168,10 @@ def test_kernel_family_choice():
     irregular = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7)
     assert pk.forest_pack(irregular)["kernel_path"] == 3
     many = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7, n_outputs=20)
-    assert pk.forest_pack(many)["kernel_path"] == 0
+    v = pk.forest_pack(many)
+    assert v["kernel_path"] == 3 and v["workgroup_waves"] == 2        # 20 columns: three workgroups of 2 waves per CU
+    wide = wl.random_forest(9, n_trees=40, n_features=300, max_depth=9, stop_prob=0.05)
+    assert pk.forest_pack(wide)["kernel_path"] == 0                   # more than 256 rank rows: plain family
     w = wl.make_workload("c5", n_rows=1, n_trees=4)
     v = pk.forest_pack(w.forest)
     assert v["kernel_path"] == 3 and v["rank_registers"] == 256
