@@ -120,6 +120,18 @@ def test_models_at_the_documented_limits(what):
         _check(f, rng.standard_normal((300, F)).astype(np.float32))
 
 
+@pytest.mark.parametrize("n_features,path", [(20, 3), (300, 0)])
+def test_very_large_trees(n_features, path):
+    """Two trees of about 100,000 internal nodes each (depth 17): the streaming walks of the LDS
+    rank kernel and of the plain irregular-tree kernel keep nothing per tree but one chunk."""
+    f = wl.random_forest(1700 + n_features, n_trees=2, n_features=n_features, max_depth=17, stop_prob=0.004,
+                         n_outputs=2, leaf_width=2, transform=wl.TRANSFORM_SOFTMAX)
+    assert f.n_nodes > 150_000
+    rng = np.random.default_rng(n_features)
+    info = _check(f, rng.standard_normal((200, n_features)).astype(np.float32))
+    assert info["kernel_path"] == path, info
+
+
 def test_special_values_nan_inf_signed_zero():
     w = wl.make_workload("c1", n_rows=256)
     X = w.make_x(256).copy()
