@@ -31,7 +31,9 @@ def predict_linear(model, X: np.ndarray) -> LinearResult:
     X = np.asarray(X, dtype=np.float32)
     assert X.ndim == 2 and X.shape[1] == model.n_features
     w = np.asarray(model.weight, dtype=np.float64).reshape(model.n_features, model.n_outputs)
-    b = np.asarray(model.bias, dtype=np.float64).reshape(model.n_outputs)
+    # an absent bias is a zero bias (the description's bias pointer may be NULL)
+    b = (np.zeros(model.n_outputs) if model.bias is None
+         else np.asarray(model.bias, dtype=np.float64).reshape(model.n_outputs))
     with np.errstate(all="ignore"):
         raw = X.astype(np.float64) @ w + b
         if model.transform == TRANSFORM_SOFTMAX:
