@@ -116,6 +116,32 @@ def test_rows_of_whole_16_byte_pieces(F):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("F", [28, 64, 90, 130])
+def test_x_that_starts_off_a_16_byte_boundary_and_absent_bias(F):
+    """X may start at any float: 4, 8 or 12 bytes past a 16-byte boundary the kernels fall back
+    to narrower loads.  The bias pointer may be NULL (zeros)."""
+    import torch
+    rng = np.random.default_rng(F)
+    model = LinearModel(F, 3, rng.standard_normal((F, 3)).astype(np.float32), None, TRANSFORM_SOFTMAX, OUT_BOTH)
+    m = lb.linear_load(model)
+    try:
+        for off in (0, 1, 2, 3):
+            for rows in (1, 65, 300):
+                X = rng.standard_normal((rows, F)).astype(np.float32)
+                buf = torch.empty(rows * F + 4, dtype=torch.float32, device="cuda")
+                xd = buf[off:off + rows * F].view(rows, F)
+                xd.copy_(torch.from_numpy(X))
+                assert xd.data_ptr() % 16 == 4 * off
+                scores, labels = m.predict(xd)
+                torch.cuda.synchronize()
+                ref = predict_linear(model, X)
+                np.testing.assert_array_equal(labels.cpu().numpy(), ref.labels)
+                np.testing.assert_allclose(scores.cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        m.close()
+
+
+@pytest.mark.gpu
 def test_output_kinds_ties_and_empty_batch():
     import torch
     X = np.random.default_rng(5).standard_normal((130, 6)).astype(np.float32)
