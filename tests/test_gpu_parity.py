@@ -75,7 +75,7 @@ def test_irregular_forests_with_ties(seed):
     assert info["kernel_kind"] == 0 and info["kernel_path"] == 3
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_models_and_batches(seed):
     """Everything drawn at once: full or irregular trees, feature and tree counts, depth, output
     columns, scalar or vector leaves, aggregate, base scores, transform, output kind, batch size
