@@ -82,9 +82,23 @@ __device__ __forceinline__ void finish_values(const DevModel &m, double *raw, in
     }
 }
 
-// Cross-wave reduction for tile row `li` (0 <= li < rows), then either the rest of the row
-// (aggregate, label, transform, store) or, in a split launch, the store of the partial sums.
-// `acc` is [n_waves][K][rows]; wave 0's slice is overwritten.
+// Tile row `li` (0 <= li < rows) once its K column sums are in acc[k * rows + li]: the rest of
+// the row (aggregate, label, transform, store) or, in a split launch, the store of the sums.
+__device__ __forceinline__ void finish_summed_row(const DevModel &m, double *acc, int rows, int li, int64_t row,
+                                                  bool valid, float *scores, int32_t *labels)
+{
+    const int K = m.n_outputs;
+    if (!valid) return;
+    if (m.n_splits > 1) {
+        double *dst = m.partial + (static_cast<int64_t>(blockIdx.y) * m.split_rows + row) * K;
+        for (int k = 0; k < K; ++k) dst[k] = acc[k * rows + li];
+        return;
+    }
+    finish_values(m, acc + li, rows, row, scores, labels);
+}
+
+// Cross-wave reduction for tile row `li`, then finish_summed_row.  `acc` is [n_waves][K][rows];
+// wave 0's slice is overwritten.
 __device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int rows, int li, int64_t row,
                                            bool valid, float *scores, int32_t *labels, int n_waves = WAVES)
 {
@@ -94,13 +108,7 @@ __device__ __forceinline__ void finish_row(const DevModel &m, double *acc, int r
         for (int w = 1; w < n_waves; ++w) s += acc[(w * K + k) * rows + li];
         acc[k * rows + li] = s;
     }
-    if (!valid) return;
-    if (m.n_splits > 1) {
-        double *dst = m.partial + (static_cast<int64_t>(blockIdx.y) * m.split_rows + row) * K;
-        for (int k = 0; k < K; ++k) dst[k] = acc[k * rows + li];
-        return;
-    }
-    finish_values(m, acc + li, rows, row, scores, labels);
+    finish_summed_row(m, acc, rows, li, row, valid, scores, labels);
 }
 
 // Partial sums of one wave for R rows per lane.  Scalar leaves accumulate in a register per

@@ -121,24 +121,63 @@ __device__ __forceinline__ void load_first_pairs(v16u &even, v16u &odd, StreamPt
 
 // Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
 // two columns) keep their partial sums in registers until every wave is done, so the partial
-// sums can reuse the LDS of the rank tile; GENERAL keeps them in an LDS region of its own.
-enum { MODE_SCALAR1 = 0, MODE_VECTOR2 = 1, MODE_GENERAL = 2, MODE_LEAVES = 3 };
+// sums can reuse the LDS of the rank tile; GENERAL (wider vector leaves) keeps a [K][rows] slice
+// per wave in an LDS region of its own; SCALARK (scalar leaves, several columns) keeps one sum per
+// (wave, column the wave's trees feed).
+enum { MODE_SCALAR1 = 0, MODE_VECTOR2 = 1, MODE_GENERAL = 2, MODE_LEAVES = 3, MODE_SCALARK = 4 };
+
+// SCALARK: the trees are sorted by output column, so the run of trees a wave evaluates feeds the
+// consecutive columns first .. last, and the sum of a column is complete when the next column
+// begins.  The wave keeps the running sums of its current column in registers and stores them,
+// once, to its own slot of that column: mine[(column - first) * 128 + row in tile].
+struct ColumnRuns {
+    double run[2];
+    double *mine;
+    int first, current;
+
+    __device__ __forceinline__ void start(double *slots, int first_column)
+    {
+        mine = slots;
+        first = current = first_column;
+        run[0] = run[1] = 0.0;
+    }
+    __device__ __forceinline__ void store(int lane) const
+    {
+        mine[(current - first) * RROWS + lane] = run[0];
+        mine[(current - first) * RROWS + TILE + lane] = run[1];
+    }
+    // `column` is wave-uniform and never decreases
+    __device__ __forceinline__ void begin_tree(int column, int lane)
+    {
+        if (column == current) return;
+        store(lane);
+        run[0] = run[1] = 0.0;
+        for (++current; current < column; ++current) store(lane);  // columns no tree of the forest feeds
+    }
+};
 
 constexpr int CHUNK_GROUPS = RANKLDS_CHUNK_GROUPS;  // a level is walked in chunks of 8 groups = 64 nodes
 
-template <int MODE, int LWAVES>
-__device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes, Accumulator<2> &accu,
-                                              double (&sum)[2][2], int wave, int lane, int64_t row0,
-                                              int64_t n_rows, int32_t *leaf_out)
+// The trees (processing order) of wave `wave` of the workgroup.
+template <int LWAVES>
+__device__ __forceinline__ void wave_trees(const DevModel &m, int wave, int &t_begin, int &t_end)
 {
-    const int T = m.n_trees;
-    int t_begin, t_end;
     if (m.n_splits == 1) {  // launch-uniform: runs of about equal program length, cut at load time
         t_begin = m.wave_tree[wave];
         t_end = m.wave_tree[wave + 1];
     } else {
         tree_range(m, wave, LWAVES, t_begin, t_end);
     }
+}
+
+template <int MODE, int LWAVES>
+__device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes, Accumulator<2> &accu,
+                                              ColumnRuns &runs, double (&sum)[2][2], int wave, int lane,
+                                              int64_t row0, int64_t n_rows, int32_t *leaf_out)
+{
+    const int T = m.n_trees;
+    int t_begin, t_end;
+    wave_trees<LWAVES>(m, wave, t_begin, t_end);
     if (t_begin >= t_end) return;
     MetaPtr meta = (MetaPtr)m.tree;
 
@@ -212,6 +251,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             resolve = false;
             const TreeMeta tm = meta[t];
             if (MODE == MODE_GENERAL) accu.begin_tree(tm.column);
+            if (MODE == MODE_SCALARK) runs.begin_tree(tm.column, lane);
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 const int leaf = tm.leaf_base + (ref[r] < 0 ? ~ref[r] : 0);
@@ -220,6 +260,8 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
                     if (row < n_rows) leaf_out[row * T + tm.caller_tree] = m.leaf_node[leaf];
                 } else if (MODE == MODE_SCALAR1) {
                     sum[r][0] += static_cast<double>(m.leaf_value[leaf]);
+                } else if (MODE == MODE_SCALARK) {
+                    runs.run[r] += static_cast<double>(m.leaf_value[leaf]);
                 } else if (MODE == MODE_VECTOR2) {
                     const float *v = m.leaf_value + static_cast<size_t>(leaf) * m.n_outputs;
                     sum[r][0] += static_cast<double>(v[0]);
@@ -294,20 +336,35 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
     extern __shared__ __align__(16) char smem[];
     const int regs = m.rank_regs > 0 ? m.rank_regs : 1;
     const int K = m.n_outputs;
-    // LDS: [ rank tile | one outcome-byte chunk per wave | partial sums (GENERAL) ].
+    // LDS: [ rank tile | one outcome-byte chunk per wave | partial sums (GENERAL, SCALARK) ].
     // The rank tile must start at LDS address 0: the entries' reads address it as
     // row offset + lane * 4.  SCALAR1 / VECTOR2 put their partial sums over the rank tile once
     // every wave has finished.
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
     char *region2 = smem + sizeof(uint32_t) * TILE * regs;
     const bool deferred = (m.leaf_width == 1 && K == 1) || (m.leaf_width == K && K <= 2 && m.leaf_width != 1);
+    const bool column_runs = m.leaf_width == 1 && K > 1;
     const size_t r2_bytes = ranklds_region2_bytes(LWAVES);
     double *acc = deferred ? reinterpret_cast<double *>(smem) : reinterpret_cast<double *>(region2 + r2_bytes);
+    // SCALARK: (wave, column) sums [LWAVES + K - 1][128], summed columns [K][128], then per wave its
+    // first column, its number of columns and its first slot
+    double *slots = acc;
+    double *summed = slots + static_cast<size_t>(LWAVES + K - 1) * RROWS;
+    int *wave_first = reinterpret_cast<int *>(summed + static_cast<size_t>(K) * RROWS);
+    int *wave_count = wave_first + LWAVES;
+    int *wave_slot = wave_count + LWAVES;
 
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
+    if (column_runs && leaf_out == nullptr && lane == 0) {  // which columns the wave's trees feed
+        int t_begin, t_end;
+        wave_trees<LWAVES>(m, wave, t_begin, t_end);
+        const bool any = t_begin < t_end;
+        wave_first[wave] = any ? m.tree[t_begin].column : 0;
+        wave_count[wave] = any ? m.tree[t_end - 1].column - m.tree[t_begin].column + 1 : 0;
+    }
     if (m.rank_regs == 0) rk[threadIdx.x & (TILE - 1)] = 0;  // the padding entries read row 0
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, LBLOCK);
@@ -318,20 +375,45 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
 
     uint8_t *bytes = reinterpret_cast<uint8_t *>(region2) + static_cast<size_t>(wave) * CHUNK_GROUPS * 2 * TILE;
     Accumulator<2> accu;
+    ColumnRuns runs;
     double sum[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
     if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
-        ranklds_trees<MODE_LEAVES, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, leaf_out);
+        ranklds_trees<MODE_LEAVES, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, leaf_out);
         return;
     }
     if (deferred) {
-        if (m.leaf_width == 1) ranklds_trees<MODE_SCALAR1, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
-        else ranklds_trees<MODE_VECTOR2, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        if (m.leaf_width == 1)
+            ranklds_trees<MODE_SCALAR1, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, nullptr);
+        else
+            ranklds_trees<MODE_VECTOR2, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, nullptr);
         __syncthreads();  // no wave reads the rank tile any more
         for (int r = 0; r < 2; ++r)
             for (int k = 0; k < K; ++k) acc[(wave * K + k) * RROWS + r * TILE + lane] = sum[r][k];
+    } else if (column_runs) {
+        int slot = 0;  // the slots of the waves before this one come first
+        for (int v = 0; v < wave; ++v) slot += wave_count[v];
+        if (lane == 0) wave_slot[wave] = slot;
+        runs.start(slots + static_cast<size_t>(slot) * RROWS, wave_first[wave]);
+        ranklds_trees<MODE_SCALARK, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, nullptr);
+        if (wave_count[wave] > 0) runs.store(lane);  // the last column of the run
+        __syncthreads();
+        // column k of a row: the slots of the waves whose run covers k, in wave order
+        const int li = threadIdx.x;
+        if (li < RROWS) {
+            for (int k = 0; k < K; ++k) {
+                double s = 0.0;
+                for (int v = 0; v < LWAVES; ++v) {
+                    const int j = k - wave_first[v];
+                    if (j >= 0 && j < wave_count[v]) s += slots[static_cast<size_t>(wave_slot[v] + j) * RROWS + li];
+                }
+                summed[k * RROWS + li] = s;
+            }
+            finish_summed_row(m, summed, RROWS, li, row0 + li, row0 + li < n_rows, scores, labels);
+        }
+        return;
     } else {
         accu.init(acc, wave, lane, m);
-        ranklds_trees<MODE_GENERAL, LWAVES>(m, bytes, accu, sum, wave, lane, row0, n_rows, nullptr);
+        ranklds_trees<MODE_GENERAL, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, nullptr);
         accu.flush();
     }
     __syncthreads();

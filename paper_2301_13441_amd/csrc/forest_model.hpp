@@ -140,6 +140,12 @@ inline size_t ranklds_lds_bytes(int rank_regs, int n_outputs, int leaf_width, in
     const int K = n_outputs, W = leaf_width;
     const bool deferred = (W == 1 && K == 1) || (W == K && K <= 2 && W != 1);
     const size_t front = sizeof(uint32_t) * 64 * regs + static_cast<size_t>(waves) * 8 * 2 * 64;
+    if (W == 1 && K > 1) {
+        // scalar leaves, several columns: the trees are sorted by column, so a wave's run of trees
+        // feeds consecutive columns and the workgroup has at most waves + K - 1 (wave, column)
+        // sums of 128 rows; then K summed columns, and three small integers per wave
+        return front + sizeof(double) * 128 * static_cast<size_t>(waves + 2 * K - 1) + 256;
+    }
     const size_t sums = sizeof(double) * static_cast<size_t>(waves) * K * 128;
     return deferred ? (front > sums ? front : sums) : front + sums;
 }

@@ -306,8 +306,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         // column: two waves fit whatever the model).  Models that need more than 256 rank rows
         // stay in the plain family, whose kernels take any model.
         // The small workgroups (4 and 2 waves) are for irregular trees only: measured faster than
-        // the plain family's irregular-tree kernel on models with 12 to 32 output columns, while
-        // shallow full trees with many columns run faster in the plain full-tree kernels.
+        // the plain family's irregular-tree kernel on models with 12- to 32-wide leaves, while
+        // shallow full trees with such leaves run faster in the plain full-tree kernels.
         const bool small_workgroups = m.kind == KIND_GENERIC;
         int best_waves = 0;
         size_t best_per_cu = 0;

@@ -393,10 +393,11 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
     ("reg_fallback", 1),          # too many rank registers -> float32 feature registers
     ("ranklds_full_wide", 3),     # full trees over > 128 features: ranks in LDS
     ("ranklds_irregular", 3),     # irregular trees, 3 output columns
-    ("ranklds_narrow", 3),        # 10 output columns over 64 features: workgroups of 8 waves
-    ("ranklds_four_waves", 3),    # 12 columns, trees too large for the plain kernels: 4 waves
-    ("ranklds_two_waves", 3),     # 32-wide vector leaves on such trees: 2 waves
-    ("lds_many_outputs", 0),      # 20 output columns: partial sums too large for the rank kernels
+    ("ranklds_scalar_columns", 3),  # 10 output columns, scalar leaves: one sum per (wave, column), 12 waves
+    ("ranklds_narrow", 3),        # 10-wide vector leaves over 64 features: workgroups of 8 waves
+    ("ranklds_four_waves", 3),    # 12-wide vector leaves over 256 features: 4 waves
+    ("ranklds_two_waves", 3),     # 32-wide vector leaves: 2 waves
+    ("lds_many_outputs", 0),      # full trees over 300 features, 20 columns: more rank rows than the tile holds
     ("lds_generic_many_outputs", 0),
     ("lds_generic_large_trees", 0),   # more than 256 rank rows and trees of ~7000 nodes: plain family, any size
 ])
@@ -413,17 +414,21 @@ def test_kernel_families(what, path):
     elif what == "ranklds_irregular":
         f = wl.random_forest(6, n_trees=37, n_features=11, max_depth=10, stop_prob=0.12, n_outputs=3,
                              transform=wl.TRANSFORM_SOFTMAX)
-    elif what == "ranklds_narrow":
+    elif what == "ranklds_scalar_columns":
         f = wl.random_forest(8, n_trees=45, n_features=64, max_depth=9, stop_prob=0.15, n_outputs=10,
                              transform=wl.TRANSFORM_SOFTMAX)
+        f.tree_output[f.tree_output == 4] = 5      # a column no tree feeds, inside the waves' runs
+    elif what == "ranklds_narrow":
+        f = wl.random_forest(8, n_trees=45, n_features=64, max_depth=9, stop_prob=0.15, n_outputs=10, leaf_width=10,
+                             transform=wl.TRANSFORM_SOFTMAX)
     elif what == "ranklds_four_waves":
-        f = wl.random_forest(9, n_trees=9, n_features=256, max_depth=13, stop_prob=0.02, n_outputs=12,
+        f = wl.random_forest(9, n_trees=9, n_features=256, max_depth=13, stop_prob=0.02, n_outputs=12, leaf_width=12,
                              transform=wl.TRANSFORM_SOFTMAX)
     elif what == "ranklds_two_waves":
         f = wl.random_forest(10, n_trees=5, n_features=130, max_depth=13, stop_prob=0.02, n_outputs=32, leaf_width=32,
                              transform=wl.TRANSFORM_SOFTMAX)
     elif what == "lds_many_outputs":
-        f = _full_forest(5, 60, 4, 9, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
+        f = _full_forest(5, 60, 4, 300, n_outputs=20, transform=wl.TRANSFORM_SOFTMAX)
     elif what == "lds_generic_large_trees":
         f = wl.random_forest(11, n_trees=6, n_features=300, max_depth=13, stop_prob=0.02, n_outputs=5, leaf_width=5,
                              transform=wl.TRANSFORM_SOFTMAX)

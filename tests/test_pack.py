@@ -164,12 +164,16 @@ def test_kernel_family_choice():
     v = pk.forest_pack(_full_forest(3, 40, 8, 128, feature_bias=0.9))
     assert v["kernel_path"] == 1                                     # 130 rank registers would be needed
     assert pk.forest_pack(_full_forest(4, 12, 5, 200))["kernel_path"] == 3      # too wide for registers
-    assert pk.forest_pack(_full_forest(5, 60, 4, 9, n_outputs=20))["kernel_path"] == 0
+    assert pk.forest_pack(_full_forest(5, 60, 4, 9, n_outputs=20))["kernel_path"] == 3     # 20 columns of scalar leaves
+    assert pk.forest_pack(_full_forest(5, 60, 4, 300, n_outputs=20))["kernel_path"] == 0   # more than 256 rank rows
     irregular = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7)
     assert pk.forest_pack(irregular)["kernel_path"] == 3
     many = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7, n_outputs=20)
     v = pk.forest_pack(many)
-    assert v["kernel_path"] == 3 and v["workgroup_waves"] == 2        # 20 columns: three workgroups of 2 waves per CU
+    assert v["kernel_path"] == 3 and v["workgroup_waves"] == 12       # scalar leaves: one sum per (wave, column)
+    many = wl.random_forest(9, n_trees=5, n_features=6, max_depth=7, n_outputs=20, leaf_width=20)
+    v = pk.forest_pack(many)
+    assert v["kernel_path"] == 3 and v["workgroup_waves"] == 2        # 20-wide leaves: three workgroups of 2 waves per CU
     wide = wl.random_forest(9, n_trees=40, n_features=300, max_depth=9, stop_prob=0.05)
     assert pk.forest_pack(wide)["kernel_path"] == 0                   # more than 256 rank rows: plain family
     w = wl.make_workload("c5", n_rows=1, n_trees=4)
