@@ -270,7 +270,11 @@ __device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (MODE == MODE_SCALAR) {
-                pending[r] = lv[pos[r]];
+                // wave-uniform base + 32-bit byte offset: the gather takes its base from scalar
+                // registers and needs one vector instruction for the address (a tree's leaves
+                // are within 1 KB of the base)
+                const uint32_t off = pos[r] << 2;
+                pending[r] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lv) + off);
             } else {
                 const int leaf = (tp << D) + static_cast<int>(pos[r] - (1u << D));
                 if (MODE == MODE_LEAVES) {
