@@ -38,6 +38,17 @@ MEASURED_TRAFFIC = {
     "l2": 1440.0e6 + 16.0e6,
 }
 
+# Busy fractions of the units the forest kernels use, from rocprofv3 --pmc runs of this script
+# (SQ_INSTS_VALU x 4 cycles, SQ_VALU_MFMA_BUSY_CYCLES, SQ_LDS_IDX_ACTIVE over the SIMD / CU cycles
+# of the launch); see the profile named.  They are measurements of the committed kernels, not
+# taken live, and are reported next to the live roofline fraction.
+MEASURED_UNIT_BUSY = {
+    "c2": {"valu_issue": 0.77, "mfma": 0.52, "profile": "profiles/forest_rank_kernel_c2.md"},
+    "c3": {"valu_issue": 0.78, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
+    "c4": {"valu_issue": 0.73, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
+    "c5": {"valu_issue": 0.53, "lds": 0.64, "profile": "profiles/forest_ranklds_kernel_c5.md"},
+}
+
 
 def bench_linear(args) -> int:
     """The linear-model family (one matmul + bias + transform + label): bound by reading X once
@@ -224,6 +235,7 @@ def main() -> int:
         "hbm_GBps": algo_bytes / kernel_s / 1e9,
         "hbm_frac": algo_bytes / kernel_s / HBM_PEAK,
         "traffic": MEASURED_TRAFFIC.get(args.workload),
+        "unit_busy_measured": MEASURED_UNIT_BUSY.get(args.workload),
     }
 
     cpu_baseline = None
