@@ -87,7 +87,9 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // one 16-register value pinned to s[36:51] resp. s[52:67].
 //
 // d0, d1: the outcomes of the two groups, the matrix core's B operands.  f0, f1: the first
-// entry of each group (its low byte holds the group's flags).
+// entry of each group (its low byte holds the group's flags).  M0 is not on the clobber list:
+// the compiler reserves it and loads it immediately before each of its own uses, so nothing of
+// its making is live in M0 across a statement.
 __device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
                                                StreamPtr p)
 {
@@ -95,7 +97,7 @@ __device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, u
                                  "s48", "s49", "s50", "s51", "s[36:51]", "0x80")
                  : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
                  : [p] "s"(p)
-                 : "memory", "m0");
+                 : "memory");
 }
 
 __device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
@@ -105,7 +107,7 @@ __device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, ui
                                  "s64", "s65", "s66", "s67", "s[52:67]", "0xc0")
                  : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
                  : [p] "s"(p)
-                 : "memory", "m0");
+                 : "memory");
 }
 
 // The first two pairs of a wave's stream into the two register sets.
