@@ -281,6 +281,8 @@ def test_pinned_stream_register_check_catches_a_violation():
     dirty = clean.replace("\ts_add_u32 s2, s2, 0x80", "\ts_add_u32 s2, s2, 0x80\n\ts_mov_b32 s44, s7")
     with pytest.raises(RuntimeError, match="pinned stream register"):
         chk.check_assembly(dirty)
+    with pytest.raises(RuntimeError, match="use of m0"):
+        chk.check_assembly(clean.replace("\ts_endpgm", "\ts_mov_b32 m0, -1\n\ts_endpgm"))
     with pytest.raises(RuntimeError, match="no stream loop"):
         chk.check_assembly("\ts_endpgm")
 
