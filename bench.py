@@ -24,16 +24,16 @@ if ROOT not in sys.path:
 # MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz vector instructions per second and
 # lane.  The fp32 vector peak of 157.3 TFLOP/s is this number x 2 (FMA) x 2 (packed fp32).  A
 # float32 compare is neither fused nor packed: one comparison per lane-op.  A packed-f16
-# compare (v_pk_add_f16 with clamp on exact integer ranks) is two comparisons per lane-op.
+# compare (v_pk_fma_f16 with clamp on exactly coded ranks) is two comparisons per lane-op.
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 HBM_PEAK = 8.0e12
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC = {
-    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 78,902 x 2.000 (copy-kernel scale) KiB read,
+    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 81,670 x 2.000 (copy-kernel scale) KiB read,
     # WRITE_SIZE 7,812.5 x 1.000 KiB written
-    "c2": 161.6e6 + 8.0e6,
+    "c2": 167.3e6 + 8.0e6,
     # profiles/linear_kernels.md: FETCH_SIZE 703,161 x 2.000 KiB, WRITE_SIZE 15,625 x 1.000 KiB
     "l2": 1440.0e6 + 16.0e6,
 }
@@ -43,7 +43,7 @@ MEASURED_TRAFFIC = {
 # of the launch); see the profile named.  They are measurements of the committed kernels, not
 # taken live, and are reported next to the live roofline fraction.
 MEASURED_UNIT_BUSY = {
-    "c2": {"valu_issue": 0.77, "mfma": 0.52, "profile": "profiles/forest_rank_kernel_c2.md"},
+    "c2": {"valu_issue": 0.79, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
     "c3": {"valu_issue": 0.78, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
     "c4": {"valu_issue": 0.73, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
     "c5": {"valu_issue": 0.53, "lds": 0.64, "profile": "profiles/forest_ranklds_kernel_c5.md"},

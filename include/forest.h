@@ -201,6 +201,17 @@ int forest_pack(const forest_desc *desc, forest_packed **out);
 int forest_pack_view(const forest_packed *p, forest_packed_view *view);
 void forest_pack_free(forest_packed *p);
 
+/*
+ * Host-only view of the rank coding of kernel_path 2 and 3 (the input's dtype rewriting,
+ * Section 4.3.1; no GPU needed): a rank register stores the local rank q of a row among the
+ * thresholds of its segment as the f16 bit pattern *code, and a split on the segment's j-th
+ * threshold carries the f16 bit pattern *entry (for q = j); the kernels take
+ * clamp_[0,1](fma(code(q), 4, entry(j))), in f16 with one rounding, as the outcome bit q > j.
+ * Returns the number of codes (q must be in [0, that number); one register covers one
+ * threshold fewer), or FOREST_EINVAL for q out of range or a null pointer.
+ */
+int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry);
+
 const char *forest_strerror(int code);
 
 #ifdef __cplusplus

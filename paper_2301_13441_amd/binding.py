@@ -51,7 +51,7 @@ class _View(ctypes.Structure):
 
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
            "forest_predict", "forest_predict_leaves", "forest_pack", "forest_pack_view",
-           "forest_pack_free", "forest_strerror"]
+           "forest_pack_free", "forest_rank_code", "forest_strerror"]
 
 
 def lib_path() -> str:
@@ -88,6 +88,8 @@ def load_library():
     lib.forest_pack_view.argtypes = [_p, ctypes.POINTER(_View)]
     lib.forest_pack_free.restype = None
     lib.forest_pack_free.argtypes = [_p]
+    lib.forest_rank_code.restype = ctypes.c_int
+    lib.forest_rank_code.argtypes = [_i32, ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_uint16)]
     lib.forest_strerror.restype = ctypes.c_char_p
     lib.forest_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -189,6 +191,15 @@ def forest_pack(forest) -> dict:
         )
     finally:
         lib.forest_pack_free(h)
+
+
+def forest_rank_code(q: int) -> tuple[int, int, int]:
+    """(number of codes, f16 bits of code(q), f16 bits of the split entry for threshold q)."""
+    code, entry = ctypes.c_uint16(), ctypes.c_uint16()
+    n = load_library().forest_rank_code(int(q), ctypes.byref(code), ctypes.byref(entry))
+    if n < 0:
+        raise ForestError(n, _strerror(n))
+    return n, code.value, entry.value
 
 
 def _check_x(X, n_features: int) -> None:

@@ -92,6 +92,14 @@ int forest_pack(const forest_desc *desc, forest_packed **out)
     return FOREST_OK;
 }
 
+int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry)
+{
+    if (!code || !entry || q < 0 || q >= RANK_CODES) return FOREST_EINVAL;
+    *code = rank_code_bits(q);
+    *entry = rank_entry_bits(q);
+    return RANK_CODES;
+}
+
 int forest_pack_view(const forest_packed *p, forest_packed_view *v)
 {
     if (!p || !v) return FOREST_EINVAL;

@@ -5,7 +5,8 @@
 // feature f sorted, rank(x) = #{i : tau_i < x}, and a node holding tau_j sends x right iff
 // rank(x) > j.  Ranks and node indices are small integers, exact in f16, and two rows share
 // one register (low / high half), so one packed instruction handles two rows:
-//     v_pk_add_f16  d,   rank[reg], (-j', -j')  clamp   -- d = 1.0 iff rank > j  (step (2) of Fig. 2)
+//     v_pk_fma_f16  d, rank[reg], 4.0, (-4 j', -4 j')  clamp   -- d = 1.0 iff rank > j  (step (2) of Fig. 2)
+// (rank and j' as f16 codes, forest_model.hpp).
 // The register is selected with the VGPR index mode (s_set_gpr_idx_on / _idx: M0 = wave-uniform
 // register index), so step (1), the feature selection matmul(X, W1), costs no vector
 // instruction.  The outcomes of 8 nodes are turned into 8 bits per row either by the matrix
@@ -38,9 +39,10 @@ typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
 typedef const TreeMeta *MetaPtr;
 #endif
 
-// One entry of the compact split program is one scalar register: f16(-j') in the high half,
+// One entry of the compact split program is one scalar register: -4 code(j') in the high half,
 // the rank register's index in the low byte.  s_set_gpr_idx_* reads only the low byte; the
-// packed add reads the high half for both rows (op_sel:[0,1] op_sel_hi:[1,1]).
+// packed multiply-add reads the high half for both rows (op_sel / op_sel_hi of the addend) and
+// the inline constant's low half for both (op_sel_hi 0: a packed inline constant fills only it).
 struct Entry8 {
     uint32_t e[8];
 };
@@ -49,7 +51,8 @@ struct Entry8 {
 template <int NVR>
 struct RankStep;
 
-#define FOREST_RANK_CMP(B, n) "v_pk_add_f16 %[d" #n "], " B ", %[e" #n "] op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+#define FOREST_RANK_CMP(B, n) \
+    "v_pk_fma_f16 %[d" #n "], " B ", 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
 #define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
 #define FOREST_RANK_ASM(B)                                                                       \
     "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
@@ -103,13 +106,23 @@ struct RankStep<4> {
                 FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
                     "s_set_gpr_idx_off"
 
+#define FOREST_RANK_CMP_OUTS                                                                                  \
+    [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]), [d5] "=&v"(d[5]), \
+        [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
+#define FOREST_RANK_CMP_INS                                                                                \
+    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]), [e5] "s"(q.e[5]), \
+        [e6] "s"(q.e[6]), [e7] "s"(q.e[7])
+
+__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[1])
+{
+    asm volatile(FOREST_RANK_CMP_ONLY("v64") : FOREST_RANK_CMP_OUTS : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]));
+}
+
 __device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[2])
 {
     asm volatile(FOREST_RANK_CMP_ONLY("v64")
-                 : [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]),
-                   [d5] "=&v"(d[5]), [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
-                 : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
-                   [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+                 : FOREST_RANK_CMP_OUTS
+                 : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
 }
 
 template <int N>
@@ -217,13 +230,13 @@ __device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NV
     }
 }
 
-// The same, with the outcome bits collected by the matrix core (64 rank registers only: the
+// The same, with the outcome bits collected by the matrix core (32 or 64 rank registers: the
 // wide kernel has no registers to spare for the weights).  A word's MFMAs are still running
 // when its last comparison has issued, so the word is read, and walked, one group later:
 // after the first comparisons of the next word, or of the next tree's first word, whose leaf
 // gather in turn is consumed one tree after that.
-template <int D, int MODE>
-__device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&x)[2], Accumulator<2> &accu, int wave,
+template <int D, int NVR, int MODE>
+__device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
                                                 int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
 {
     constexpr int R = 2;
@@ -338,14 +351,14 @@ template <int D, int NVR, int MODE>
 __device__ __forceinline__ void run_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
                                           int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
 {
-    if constexpr (NVR == 2) rank_trees_mfma<D, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+    if constexpr (NVR <= 2) rank_trees_mfma<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
     else rank_trees<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
 }
 
-// Register budget: 64 (NVR = 2) or 128 (NVR = 4) pinned rank registers plus the working set must
-// leave room for 4 resp. 3 waves per SIMD (128 resp. 168 VGPRs).
+// Register budget: 32, 64 or 128 pinned rank registers (NVR = 1, 2, 4) plus the working set must
+// leave room for 5, 4 resp. 3 waves per SIMD (96, 128 resp. 168 VGPRs).
 template <int D, int NVR>
-__global__ __launch_bounds__(BLOCK, (NVR == 2 ? 4 : 3)) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
+__global__ __launch_bounds__(BLOCK, (NVR == 1 ? 5 : NVR == 2 ? 4 : 3)) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
                                                             int64_t n_rows, float *scores,
                                                             int32_t *labels, int32_t *leaf_out)
 {
@@ -408,13 +421,15 @@ KernelFn pick_depth(int d)
     }
 }
 
-KernelFn pick_rank(int nvr, int d) { return nvr == 2 ? pick_depth<2>(d) : pick_depth<4>(d); }
+KernelFn pick_rank(int nvr, int d) { return nvr == 1 ? pick_depth<1>(d) : nvr == 2 ? pick_depth<2>(d) : pick_depth<4>(d); }
+
+int rank_nvr(const DevModel &m) { return m.rank_regs <= 32 ? 1 : m.rank_regs <= 64 ? 2 : 4; }
 
 }  // namespace
 
 hipError_t init_rank_kernels(size_t lds_limit)
 {
-    for (int nvr = 2; nvr <= 4; nvr += 2)
+    for (int nvr = 1; nvr <= 4; nvr *= 2)
         for (int d = 1; d <= FULL_MAX_DEPTH; ++d) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_rank(nvr, d)),
                                                hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -428,7 +443,7 @@ hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float 
                        int32_t *leaf_out, hipStream_t stream)
 {
     if (m.rank_regs > RANK_MAX_REGS || m.kind < 1 || m.kind > FULL_MAX_DEPTH) return hipErrorInvalidValue;
-    const int nvr = m.rank_regs <= 64 ? 2 : 4;
+    const int nvr = rank_nvr(m);
     KernelFn fn = pick_rank(nvr, m.kind);
     const int64_t n_blocks = (n_rows + RROWS - 1) / RROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;

@@ -6,7 +6,7 @@
 // sit in LDS and every entry of the split program reads its row
 //     s_and_b32           m0, entry, 0xff00             -- byte offset of the row (64 words each)
 //     ds_read_addtid_b32  x                             -- LDS[m0 + lane * 4]
-//     v_pk_add_f16        x, x, entry.hi  clamp         -- step (2) of Fig. 2 for two rows
+//     v_pk_fma_f16        x, x, 4.0, entry.hi  clamp    -- step (2) of Fig. 2 for two rows
 // i.e. one vector instruction and one LDS read per (node, two rows); the matrix core then turns
 // the 8 outcome registers of a group into one outcome byte per row (forest_rank_common.hpp).
 // The address is formed on the scalar side because the vector ALU is what the kernel is short
@@ -59,7 +59,7 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // goes to M0, the LDS read adds lane * 4 by itself, and the comparison leaves the outcome (1.0 or
 // 0.0 in each f16 half) in the register the read filled.
 #define FOREST_LDS_FETCH(t, e) "s_and_b32 m0, " e ", 0xff00\n\ts_nop 0\n\tds_read_addtid_b32 " t "\n\t"
-#define FOREST_LDS_CMP(t, e) "v_pk_add_f16 " t ", " t ", " e " op_sel:[0,1] op_sel_hi:[1,1] clamp\n\t"
+#define FOREST_LDS_CMP(t, e) "v_pk_fma_f16 " t ", " t ", 4.0, " e " op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
 #define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)           \
     "s_mov_b32 %[f0], " S0 "\n\t"                                                                                \
     "s_mov_b32 %[f1], " S8 "\n\t"                                                                                \

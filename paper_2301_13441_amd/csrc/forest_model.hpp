@@ -31,9 +31,33 @@ constexpr int PATH_REG = 1;   // full trees, float32 features in vector register
 constexpr int PATH_RANK = 2;  // full trees, features rewritten as packed f16 threshold ranks
 constexpr int PATH_RANK_LDS = 3;  // any trees, packed f16 threshold ranks read from LDS
 
-// Rank family: one rank register covers RANK_SEG consecutive thresholds of a feature.
-constexpr int RANK_SEG = 4095;
-constexpr int RANK_BIAS = 2048;
+// Rank family.  Local ranks 0 .. RANK_SEG of a segment of RANK_SEG consecutive thresholds are
+// stored as f16 CODES: code(q) is the q-th smallest f16 value with magnitude in [256, 16384)
+// (6144 negative ones, then 6144 positive ones), so codes are strictly increasing in q, two
+// different codes differ by at least 1/4, and 4 * code is finite in f16.  A node with local
+// threshold index j' holds -4 * code(j'), and
+//     clamp_[0,1]( fma(code(rank), 4, -4 code(j')) )          (one v_pk_fma_f16, two rows)
+// is exactly 1.0 iff rank > j': the fused multiply-add rounds 4 (code(rank) - code(j')) once,
+// which is 0 for equal codes and at least 1 in magnitude otherwise (overflow to +-Inf included),
+// with the sign of the difference.  4.0 is an inline constant of the instruction.
+constexpr int RANK_CODES = 12288;
+constexpr int RANK_SEG = RANK_CODES - 1;  // thresholds one rank register covers
+
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline uint16_t rank_code_bits(int q)  // f16 bit pattern of code(q), 0 <= q < RANK_CODES
+{
+    return q < RANK_CODES / 2 ? static_cast<uint16_t>(0x8000u | (0x5c00u + (RANK_CODES / 2 - 1 - q)))
+                              : static_cast<uint16_t>(0x5c00u + (q - RANK_CODES / 2));
+}
+
+// f16 bit pattern of -4 * code(q): sign flipped, exponent field + 2
+inline uint16_t rank_entry_bits(int q)
+{
+    const uint16_t c = rank_code_bits(q);
+    return static_cast<uint16_t>(((c ^ 0x8000u) & 0x8000u) | ((c & 0x7fffu) + (2u << 10)));
+}
 constexpr int RANK_MAX_REGS = 128;
 constexpr int RANK_BUCKETS_PER_THRESHOLD = 2;  // resolution of the per-feature bucket tables
 constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature

@@ -20,12 +20,12 @@
 // For feature f let tau_0 < tau_1 < ... < tau_{m-1} be the distinct thresholds of all nodes
 // that test f, and rank(x) = #{i : tau_i < x} (m for NaN).  A node with threshold tau_j sends
 // x right iff !(x <= tau_j) iff rank(x) > j: an integer comparison with exactly the float
-// comparison's result for every x, including NaN, infinities and signed zeros.  Ranks and
-// node indices are stored as f16, which is exact for integers in [-2048, 2047]; one rank
-// register therefore covers a segment of RANK_SEG = 4095 consecutive thresholds:
-//     rv = clamp(rank - 4095 s, 0, L_s) - 2048,   j' = (j - 4095 s) - 2048,
-// and clamp_[0,1](rv - j') is the outcome bit (differences beyond +-2048 round, but keep
-// their sign and a magnitude above 1).  Two rows share a register (low / high half), so one
+// comparison's result for every x, including NaN, infinities and signed zeros.  One rank
+// register covers a segment of RANK_SEG = 12287 consecutive thresholds; local ranks and node
+// indices,
+//     rv = clamp(rank - RANK_SEG s, 0, L_s),   j' = j - RANK_SEG s,
+// are stored as f16 codes (forest_model.hpp) such that one packed fused multiply-add with clamp
+// gives the outcome bit rv > j' exactly.  Two rows share a register (low / high half), so one
 // packed instruction compares two rows.  The kernels turn the 8 outcomes of a block of 8
 // entries into one outcome byte per row, first entry in bit 7 (on the matrix core, or with a
 // tree of packed fused multiply-adds: forest_kernels_rank.hip).  Entries are therefore stored
@@ -119,14 +119,6 @@ int analyse_tree(const forest_desc &d, int64_t base, int64_t n, TreeShape &s)
     return FOREST_OK;
 }
 
-uint16_t f16_bits_of_small_int(int v)
-{
-    // exact for |v| <= 2048
-    const _Float16 h = static_cast<_Float16>(static_cast<float>(v));
-    uint16_t u;
-    std::memcpy(&u, &h, sizeof(u));
-    return u;
-}
 
 int check_desc(const forest_desc &d)
 {
@@ -339,7 +331,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         const int32_t j = static_cast<int32_t>(std::lower_bound(lo, hi, d.threshold[n]) - lo);
         assert(lo + j < hi && lo[j] == d.threshold[n]);
         const int32_t seg = j / RANK_SEG;
-        const uint32_t h = f16_bits_of_small_int(-((j - seg * RANK_SEG) - RANK_BIAS));
+        const uint32_t h = rank_entry_bits(j - seg * RANK_SEG);
         const uint32_t pair = h | (h << 16);
         SplitEntry e;
         e.feature_slot = m.feat_vfirst[f] + seg;
@@ -381,8 +373,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     const float inf = std::numeric_limits<float>::infinity();
     SplitEntry pad{0, inf};
     if (m.path == PATH_RANK || m.path == PATH_RANK_LDS) {
-        // register 0 against j' = 2047: rv - 2047 <= 0 for every rank, the outcome bit is 0
-        const uint32_t h = f16_bits_of_small_int(-2047);
+        // register 0 against the largest code: no local rank exceeds it, the outcome bit is 0
+        const uint32_t h = rank_entry_bits(RANK_SEG);
         const uint32_t pair = h | (h << 16);
         std::memcpy(&pad.threshold, &pair, sizeof(pair));
     }

@@ -17,12 +17,6 @@ namespace forest_impl {
 
 constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half) and l + 64 (high half)
 
-__device__ __forceinline__ uint16_t f16_bits(int v)
-{
-    const _Float16 h = static_cast<_Float16>(static_cast<float>(v));  // exact for |v| <= 2048
-    return __builtin_bit_cast(uint16_t, h);
-}
-
 // Bit collection on the matrix core.  The eight outcome registers of a group are, read as
 // bytes, (0, a, 0, b) with a, b = 0x3c or 0 for the lane's two rows; 0x3c is 1.0 in bf8
 // (e5m2).  v_mfma_f32_16x16x128_f8f6f4 takes them as its B operand: a lane of 16-lane block q
@@ -136,7 +130,7 @@ __device__ __forceinline__ void store_rank(uint16_t *tile16, const DevModel &m, 
         const int len = n - first < RANK_SEG ? n - first : RANK_SEG;
         int rv = rank - first;
         rv = rv < 0 ? 0 : (rv > len ? len : rv);
-        tile16[((reg0 + sgm) * TILE + (r & (TILE - 1))) * 2 + (r >> 6)] = f16_bits(rv - RANK_BIAS);
+        tile16[((reg0 + sgm) * TILE + (r & (TILE - 1))) * 2 + (r >> 6)] = rank_code_bits(rv);
     }
 }
 
@@ -251,7 +245,7 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
                 for (int r = 0; r < 2; ++r) {
                     int rv = rank[r] - first;
                     rv = rv < 0 ? 0 : (rv > len ? len : rv);
-                    packed |= static_cast<uint32_t>(f16_bits(rv - RANK_BIAS)) << (16 * r);
+                    packed |= static_cast<uint32_t>(rank_code_bits(rv)) << (16 * r);
                 }
                 rk[(reg0 + s) * TILE + lane] = packed;
             }

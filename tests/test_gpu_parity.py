@@ -388,7 +388,7 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
 
 
 @pytest.mark.parametrize("what,path", [
-    ("rank_three_segments", 2),   # > 2 * 4095 distinct thresholds on one feature
+    ("rank_three_segments", 2),   # > 2 * 12287 distinct thresholds on one feature
     ("rank_wide", 2),             # 128 features -> 128 rank registers (the 3-waves variant)
     ("reg_fallback", 1),          # too many rank registers -> float32 feature registers
     ("ranklds_full_wide", 3),     # full trees over > 128 features: ranks in LDS
@@ -404,11 +404,11 @@ def _full_forest(seed, n_trees, depth, n_features, feature_bias=None, n_outputs=
 def test_kernel_families(what, path):
     rng = np.random.default_rng(42)
     if what == "rank_three_segments":
-        f = _full_forest(1, 40, 8, 2)
+        f = _full_forest(1, 100, 8, 1)
     elif what == "rank_wide":
         f = _full_forest(2, 30, 7, 128, n_outputs=3, transform=wl.TRANSFORM_SOFTMAX)
     elif what == "reg_fallback":
-        f = _full_forest(3, 40, 8, 128, feature_bias=0.9)
+        f = _full_forest(3, 100, 8, 128, feature_bias=0.9)
     elif what == "ranklds_full_wide":
         f = _full_forest(4, 12, 5, 200)
     elif what == "ranklds_irregular":
@@ -444,6 +444,26 @@ def test_kernel_families(what, path):
     if what.startswith("ranklds"):
         waves = {"ranklds_narrow": 8, "ranklds_four_waves": 4, "ranklds_two_waves": 2}.get(what, 12)
         assert info["workgroup_waves"] == waves, info
+
+
+@pytest.mark.parametrize("full", [True, False])
+def test_every_rank_code_against_every_neighbouring_threshold(full):
+    """One feature with integer thresholds 0 .. n - 1 spread over more than two rank registers,
+    and rows at every threshold and halfway between neighbours: every code of a register is
+    compared with the entries next to it, and with entries far away through the other nodes of
+    the row's trees.  Register and LDS rank kernels."""
+    rng = np.random.default_rng(5)
+    if full:
+        f = _full_forest(12, 3600, 3, 1)
+    else:
+        f = wl.random_forest(12, n_trees=900, n_features=1, max_depth=6, stop_prob=0.05)
+    internal = np.flatnonzero(f.feature >= 0)
+    n = internal.size
+    assert n > 2 * 12287
+    f.threshold[internal] = rng.permutation(n).astype(np.float32)
+    X = np.arange(-1.0, n + 0.5, 0.5, dtype=np.float32).reshape(-1, 1)
+    info = _check(f, X)
+    assert info["kernel_path"] == (2 if full else 3), info
 
 
 def test_duplicate_thresholds_and_unused_features():

@@ -157,11 +157,13 @@ def test_kernel_family_choice():
     import sys, os
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from test_gpu_parity import _full_forest
+    v = pk.forest_pack(_full_forest(1, 100, 8, 1))
+    assert v["kernel_path"] == 2 and v["rank_registers"] == 3       # 25500 thresholds on one feature: 3 segments
     v = pk.forest_pack(_full_forest(1, 40, 8, 2))
-    assert v["kernel_path"] == 2 and v["rank_registers"] == 4       # 5096 and 5104 thresholds: 2 + 2 segments
+    assert v["kernel_path"] == 2 and v["rank_registers"] == 2       # 5096 and 5104 thresholds: one segment each
     v = pk.forest_pack(_full_forest(2, 30, 7, 128))
     assert v["kernel_path"] == 2 and v["rank_registers"] == 128
-    v = pk.forest_pack(_full_forest(3, 40, 8, 128, feature_bias=0.9))
+    v = pk.forest_pack(_full_forest(3, 100, 8, 128, feature_bias=0.9))
     assert v["kernel_path"] == 1                                     # 130 rank registers would be needed
     assert pk.forest_pack(_full_forest(4, 12, 5, 200))["kernel_path"] == 3      # too wide for registers
     assert pk.forest_pack(_full_forest(5, 60, 4, 9, n_outputs=20))["kernel_path"] == 3     # 20 columns of scalar leaves
@@ -181,7 +183,7 @@ def test_kernel_family_choice():
     assert v["kernel_path"] == 3 and v["rank_registers"] == 256
     w = wl.make_workload("c2", n_rows=1)
     v = pk.forest_pack(w.forest)
-    assert v["kernel_path"] == 2 and v["rank_registers"] == 56       # ~4550 thresholds per feature
+    assert v["kernel_path"] == 2 and v["rank_registers"] == 28       # ~4550 thresholds per feature
 
 
 def test_lds_rank_family_cuts_the_trees_into_balanced_runs():
@@ -294,3 +296,40 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_rank_codes_compare_exactly():
+    """The rank families replace x <= tau by a comparison of f16 codes (dtype rewriting,
+    Section 4.3.1): for every local rank q and threshold index j of a rank register,
+    clamp(fma(code(q), 4, entry(j))) rounded once to f16 must be 1 iff q > j and 0 otherwise.
+    Checked for all pairs, with the fused multiply-add taken exactly in float64 (the operands are
+    f16 values, so 4 * code + entry is exact there) and rounded to f16 by numpy."""
+    n, _, _ = binding.forest_rank_code(0)
+    codes = np.empty(n, np.uint16)
+    entries = np.empty(n, np.uint16)
+    for q in range(n):
+        _, codes[q], entries[q] = binding.forest_rank_code(q)
+    c = codes.view(np.float16).astype(np.float64)
+    e = entries.view(np.float16).astype(np.float64)
+    assert np.isfinite(c).all() and np.isfinite(e).all()
+    assert (np.diff(c) > 0).all()                       # strictly increasing in q
+    assert np.array_equal(e, -4.0 * c)
+    with pytest.raises(binding.ForestError):
+        binding.forest_rank_code(n)
+    with pytest.raises(binding.ForestError):
+        binding.forest_rank_code(-1)
+    q = np.arange(n)
+    with np.errstate(over="ignore"):
+        for j0 in range(0, n, 512):
+            j = np.arange(j0, min(j0 + 512, n))
+            fused = (4.0 * c[:, None] + e[None, j]).astype(np.float16)      # one rounding, +-Inf on overflow
+            bit = np.clip(fused.astype(np.float64), 0.0, 1.0)
+            assert np.array_equal(bit, (q[:, None] > j[None, :]).astype(np.float64)), j0
+    # one register covers one threshold fewer than there are codes
+    f = _chain_forest(3, 1, n_trees=n // 3 + 1)
+    internal = np.flatnonzero(f.feature >= 0)
+    assert internal.size >= n
+    f.threshold[internal] = np.minimum(np.arange(internal.size), n - 2).astype(np.float32)   # n - 1 distinct
+    assert pk.forest_pack(f)["rank_registers"] == 1
+    f.threshold[internal] = np.minimum(np.arange(internal.size), n - 1).astype(np.float32)   # n distinct
+    assert pk.forest_pack(f)["rank_registers"] == 2
