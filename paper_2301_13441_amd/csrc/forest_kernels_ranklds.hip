@@ -1,7 +1,7 @@
 // Rank kernel for trees of any shape (gfx950): packed f16 threshold ranks held in LDS.
 //
 // Same exact rewrite of the comparison as forest_kernels_rank.hip (rank(x) > j instead of
-// !(x <= tau_j), two rows per 32-bit word, v_pk_add_f16 with clamp as the comparison), for
+// !(x <= tau_j), two rows per 32-bit word, v_pk_fma_f16 with clamp as the comparison), for
 // models whose rank tile does not fit the vector registers: up to 256 rank rows of 64 words
 // sit in LDS and every entry of the split program reads its row
 //     s_and_b32           m0, entry, 0xff00             -- byte offset of the row (64 words each)
