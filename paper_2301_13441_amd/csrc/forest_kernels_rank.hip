@@ -3,14 +3,14 @@
 // A comparison x <= tau only needs to know where x falls among the thresholds it can meet
 // (Section 4.3.1, dtype rewriting, applied to the input): with the distinct thresholds of
 // feature f sorted, rank(x) = #{i : tau_i < x}, and a node holding tau_j sends x right iff
-// rank(x) > j.  Ranks and node indices are small integers, exact in f16, and two rows share
-// one register (low / high half), so one packed instruction handles two rows:
+// rank(x) > j.  Ranks and node indices are small integers, stored as f16 codes, and two rows
+// share one register (low / high half), so one packed instruction handles two rows:
 //     v_pk_fma_f16  d, rank[reg], 4.0, (-4 j', -4 j')  clamp   -- d = 1.0 iff rank > j  (step (2) of Fig. 2)
 // (rank and j' as f16 codes, forest_model.hpp).
 // The register is selected with the VGPR index mode (s_set_gpr_idx_on / _idx: M0 = wave-uniform
 // register index), so step (1), the feature selection matmul(X, W1), costs no vector
 // instruction.  The outcomes of 8 nodes are turned into 8 bits per row either by the matrix
-// core (64 rank registers: BitCollector, one MFMA per 8 nodes) or by a tree of packed
+// core (up to 64 rank registers: BitCollector, one MFMA per 8 nodes) or by a tree of packed
 // fused multiply-adds (128 rank registers: RankStep, 1024 + bits in each half, first entry in
 // bit 7).  Four such bytes make one 32-bit heap-ordered outcome word, the same words the other
 // kernels use, and the walk, leaf gather and reduction are shared.
