@@ -240,6 +240,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             m.thr_sorted.insert(m.thr_sorted.end(), v.begin(), v.end());
             m.feat_thr_base.push_back(static_cast<int32_t>(m.thr_sorted.size()));
         }
+        // one spare element: the kernels read a feature's threshold 0 even if it has none
+        m.thr_sorted.push_back(std::numeric_limits<float>::infinity());
         // Bucket tables: a uniform grid over the feature's finite threshold range, about two
         // buckets per threshold, and for every bucket the number of thresholds in lower buckets.
         // bucket_index is monotone, so thresholds in lower buckets are below x and thresholds in

@@ -98,9 +98,16 @@ __device__ __forceinline__ RankBracket bucket_bracket(const FeatBucket &fb, cons
 // against the thresholds makes the result independent of that.
 __device__ __forceinline__ bool bracket_holds(const float *__restrict__ thr, int n, RankBracket b, float x)
 {
-    const bool below = b.lo == 0 || thr[b.lo - 1] < x;
-    const bool above = b.hi == n || !(thr[b.hi] < x);
-    return below && above;
+    // Both neighbours are read whatever the bracket is (indices clamped into the feature's
+    // thresholds; the table has one spare element, so index 0 exists for a feature without
+    // thresholds too): loads that do not hang on a condition can be in flight together.
+    const int last = n > 0 ? n - 1 : 0;
+    const int il = b.lo > 0 ? b.lo - 1 : 0;
+    const int ih = b.hi < last ? b.hi : last;
+    const float tl = thr[il], th = thr[ih];
+    const bool below = (b.lo == 0) | (tl < x);
+    const bool above = (b.hi == n) | !(th < x);
+    return below & above;
 }
 
 // One lane, one (row, feature): the rank of x among the feature's thresholds (all for NaN).
@@ -195,40 +202,61 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         float x[U][2];
         RankBracket b[U][2];
         int tb[U], n_thr[U];
+        FeatBucket fb[U];
+        // all feature values first, then all bucket reads: the loads of one kind go out together
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int f = f0 + u < F ? f0 + u : F - 1;  // wave-uniform; the duplicate is not stored
             tb[u] = thr_base[f];
             n_thr[u] = thr_base[f + 1] - tb[u];
-            FeatBucket fb;
-            fb.lo = buckets[f].lo;
-            fb.scale = buckets[f].scale;
-            fb.n_buckets = buckets[f].n_buckets;
-            fb.start_base = buckets[f].start_base;
+            fb[u].lo = buckets[f].lo;
+            fb[u].scale = buckets[f].scale;
+            fb[u].n_buckets = buckets[f].n_buckets;
+            fb[u].start_base = buckets[f].start_base;
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                x[u][r] = have[r] ? xrow[r][f] : 0.0f;
-                b[u][r] = bucket_bracket(fb, m.bucket_start, x[u][r]);
-            }
+            for (int r = 0; r < 2; ++r)
+                x[u][r] = xrow[r][f];  // a row past the batch reads the tile's first row; its rank is not used
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
-                if (!bracket_holds(m.thr_sorted + tb[u], n_thr[u], b[u][r], x[u][r])) b[u][r] = RankBracket{0, n_thr[u]};
-        bool more = true;
-        while (more) {
-            more = false;
+            for (int r = 0; r < 2; ++r) b[u][r] = bucket_bracket(fb[u], m.bucket_start, x[u][r]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const bool ok = bracket_holds(m.thr_sorted + tb[u], n_thr[u], b[u][r], x[u][r]);
+                b[u][r].lo = ok ? b[u][r].lo : 0;
+                b[u][r].hi = ok ? b[u][r].hi : n_thr[u];
+            }
+        // binary search inside the brackets: every step reads one threshold per lookup, whether
+        // the lookup is still open or not (index clamped), so the four loads go out together
+        for (;;) {
+            bool more = false;
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    if (b[u][r].lo < b[u][r].hi) {
-                        const int mid = (b[u][r].lo + b[u][r].hi) >> 1;
-                        if (m.thr_sorted[tb[u] + mid] < x[u][r]) b[u][r].lo = mid + 1;
-                        else b[u][r].hi = mid;
-                        more = true;
-                    }
+                for (int r = 0; r < 2; ++r) more |= b[u][r].lo < b[u][r].hi;
+            if (!more) break;
+            float t[U][2];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const int last = n_thr[u] > 0 ? n_thr[u] - 1 : 0;
+                    const int mid = (b[u][r].lo + b[u][r].hi) >> 1;
+                    t[u][r] = m.thr_sorted[tb[u] + (mid < last ? mid : last)];
+                }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const bool open = b[u][r].lo < b[u][r].hi;
+                    const int mid = (b[u][r].lo + b[u][r].hi) >> 1;
+                    const bool right = t[u][r] < x[u][r];
+                    b[u][r].lo = (open & right) ? mid + 1 : b[u][r].lo;
+                    b[u][r].hi = (open & !right) ? mid : b[u][r].hi;
+                }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
