@@ -371,7 +371,8 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, LBLOCK);
     } else {
-        rank_rows<LWAVES>(rk, m, X, row0, n_rows, wave, lane);
+        // many features: four at a time per wave (8 lookups in flight per lane)
+        rank_rows<LWAVES, 4>(rk, m, X, row0, n_rows, wave, lane);
     }
     __syncthreads();  // ranks complete
 

@@ -171,16 +171,15 @@ __device__ __forceinline__ void load_rank_tile(uint32_t *rk, const DevModel &m, 
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
 // pairs into rk[reg * 64 + lane] (low half: row `lane` of the tile, high half: row lane + 64).
 // The features are dealt to the waves; inside a wave every lane looks up the same feature for
-// its own two rows, two features at a time (four lookups in flight per lane), so the feature's
+// its own two rows, U features at a time (2 U lookups in flight per lane), so the feature's
 // constants are read with scalar loads.  A lookup is a bucket (a subtraction, a multiplication,
 // a conversion), the bucket's bracket from the start table, the check of the bracket against
 // the two thresholds next to it, and a binary search inside the bracket, which is a step or
 // two for most inputs.
-template <int NWAVES>
+template <int NWAVES, int U = 2>
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
                                           int64_t row0, int64_t n_rows, int wave, int lane)
 {
-    constexpr int U = 2;
     const int F = m.n_features;
     const int64_t left = n_rows - row0;
     if (left * 4 <= RROWS) {  // workgroup-uniform
