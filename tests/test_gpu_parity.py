@@ -466,6 +466,30 @@ def test_every_rank_code_against_every_neighbouring_threshold(full):
     assert info["kernel_path"] == (2 if full else 3), info
 
 
+@pytest.mark.parametrize("full", [True, False])
+def test_x_at_a_four_byte_aligned_address(full):
+    """X is only promised to be float32-aligned: rows of 13 floats starting one float into an
+    allocation (the kernels read neighbouring features of a row with wider loads)."""
+    import torch
+    import paper_2301_13441_amd as pk
+    F, n = 13, 700
+    f = _full_forest(31, 20, 5, F) if full else wl.random_forest(31, n_trees=20, n_features=F, max_depth=9, stop_prob=0.1)
+    X = np.random.default_rng(8).standard_normal((n, F)).astype(np.float32)
+    buf = torch.zeros(n * F + 1, dtype=torch.float32, device="cuda")
+    xd = buf[1:].view(n, F)
+    xd.copy_(torch.from_numpy(X))
+    assert xd.data_ptr() % 8 == 4 and xd.is_contiguous()
+    ref = oracle.predict(f, X, n_threads=8)
+    h = pk.forest_load(f)
+    try:
+        scores, labels = h.predict(xd)
+        torch.cuda.synchronize()
+        assert h.info["kernel_path"] == (2 if full else 3)
+        np.testing.assert_allclose(scores.cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        h.close()
+
+
 def test_duplicate_thresholds_and_unused_features():
     w = wl.make_workload("c3", n_rows=700, n_trees=60)      # thresholds from a 255-value grid
     f = w.forest
