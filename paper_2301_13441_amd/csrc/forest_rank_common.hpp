@@ -168,9 +168,10 @@ __device__ __forceinline__ void load_rank_tile(uint32_t *rk, const DevModel &m, 
     for (int i = threadIdx.x; i < words; i += n_threads) rk[i] = src[i];
 }
 
-// Four floats read with one load; X is only known to be 4-byte aligned.
-struct __attribute__((aligned(4))) Float4 {
-    float v[4];
+// N floats read with one load; X is only known to be 4-byte aligned.
+template <int N>
+struct __attribute__((aligned(4))) FloatRun {
+    float v[N];
 };
 
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
@@ -217,18 +218,18 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
             fb[u].scale = buckets[f].scale;
             fb[u].n_buckets = buckets[f].n_buckets;
             fb[u].start_base = buckets[f].start_base;
-            if (U != 4 || f0 + 3 >= F) {
+            if (f0 + U > F) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
                     x[u][r] = xrow[r][f];  // a row past the batch reads the tile's first row; its rank is not used
             }
         }
-        if (U == 4 && f0 + 3 < F) {  // wave-uniform: four neighbouring features of a row in one load
+        if (f0 + U <= F) {  // wave-uniform: the U neighbouring features of a row in one load
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                const Float4 v = *reinterpret_cast<const Float4 *>(xrow[r] + f0);
+                const FloatRun<U> v = *reinterpret_cast<const FloatRun<U> *>(xrow[r] + f0);
 #pragma unroll
-                for (int u = 0; u < U; ++u) x[u][r] = v.v[u % 4];
+                for (int u = 0; u < U; ++u) x[u][r] = v.v[u];
             }
         }
 #pragma unroll
