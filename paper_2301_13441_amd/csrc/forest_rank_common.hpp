@@ -168,6 +168,15 @@ __device__ __forceinline__ void load_rank_tile(uint32_t *rk, const DevModel &m, 
     for (int i = threadIdx.x; i < words; i += n_threads) rk[i] = src[i];
 }
 
+// A table element at a wave-uniform base plus a per-lane 32-bit byte offset: the load takes the
+// base from scalar registers and one vector register for the offset (the tables are far below
+// 4 GB), instead of a 64-bit address built on the vector ALU.
+template <typename T>
+__device__ __forceinline__ T load_at(const void *__restrict__ base, uint32_t byte_offset)
+{
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_offset);
+}
+
 // N floats read with one load; X is only known to be 4-byte aligned.
 template <int N>
 struct __attribute__((aligned(4))) FloatRun {
@@ -236,14 +245,49 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < 2; ++r) b[u][r] = bucket_bracket(fb[u], m.bucket_start, x[u][r]);
+        // Check of the bracket and the rank inside it.  A feature with 8 thresholds or more
+        // (wave-uniform) reads, besides the two neighbours of the check, the 8 thresholds from
+        // start = min(lo, n - 8) on: if the bracket holds, every threshold below lo is < x and
+        // none from hi on is, so rank = start + #{i < 8 : thr[start + i] < x} whenever hi <= start + 8
+        // -- no search.  What is left open (a bracket that does not hold, or a wider one, or a
+        // feature with fewer thresholds) goes through the binary search below.
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            const float *thr = m.thr_sorted + tb[u];
+            const int n = n_thr[u];
+            if (n >= 8) {
+                float tl[2], th[2];
+                FloatRun<8> w[2];
+                int start[2];
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const bool ok = bracket_holds(m.thr_sorted + tb[u], n_thr[u], b[u][r], x[u][r]);
-                b[u][r].lo = ok ? b[u][r].lo : 0;
-                b[u][r].hi = ok ? b[u][r].hi : n_thr[u];
+                for (int r = 0; r < 2; ++r) {
+                    const RankBracket c = b[u][r];
+                    start[r] = c.lo < n - 8 ? c.lo : n - 8;
+                    tl[r] = load_at<float>(thr, static_cast<uint32_t>(c.lo > 0 ? c.lo - 1 : 0) << 2);
+                    th[r] = load_at<float>(thr, static_cast<uint32_t>(c.hi < n - 1 ? c.hi : n - 1) << 2);
+                    w[r] = load_at<FloatRun<8>>(thr, static_cast<uint32_t>(start[r]) << 2);
+                }
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const RankBracket c = b[u][r];
+                    const float xv = x[u][r];
+                    const bool ok = ((c.lo == 0) | (tl[r] < xv)) & ((c.hi == n) | !(th[r] < xv));
+                    int rank = start[r];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) rank += (w[r].v[i] < xv) ? 1 : 0;
+                    const bool closed = ok & (c.hi <= start[r] + 8);
+                    b[u][r].lo = closed ? rank : (ok ? c.lo : 0);
+                    b[u][r].hi = closed ? rank : (ok ? c.hi : n);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const bool ok = bracket_holds(thr, n, b[u][r], x[u][r]);
+                    b[u][r].lo = ok ? b[u][r].lo : 0;
+                    b[u][r].hi = ok ? b[u][r].hi : n;
+                }
             }
+        }
         // binary search inside the brackets: every step reads one threshold per lookup, whether
         // the lookup is still open or not (index clamped), so the four loads go out together
         for (;;) {
