@@ -189,8 +189,8 @@ struct __attribute__((aligned(4))) FloatRun {
 // its own two rows, U features at a time (2 U lookups in flight per lane), so the feature's
 // constants are read with scalar loads.  A lookup is a bucket (a subtraction, a multiplication,
 // a conversion), the bucket's bracket from the start table, the check of the bracket against
-// the two thresholds next to it, and a binary search inside the bracket, which is a step or
-// two for most inputs.
+// the two thresholds next to it, and the rank inside the bracket (a count over 8 thresholds, or
+// a binary search).
 template <int NWAVES, int U = 2>
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
                                           int64_t row0, int64_t n_rows, int wave, int lane)
