@@ -374,7 +374,7 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 5 : NVR == 2 ? 4 : 3)) void fore
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, BLOCK);
     } else {
-        rank_rows<WAVES>(rk, m, X, row0, n_rows, wave, lane);
+        rank_rows<WAVES, (NVR == 4 ? 4 : 2)>(rk, m, X, row0, n_rows, wave, lane);
     }
     __syncthreads();
     v32u x[NVR];
