@@ -44,9 +44,9 @@ MEASURED_TRAFFIC = {
 # taken live, and are reported next to the live roofline fraction.
 MEASURED_UNIT_BUSY = {
     "c2": {"valu_issue": 0.79, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
-    "c3": {"valu_issue": 0.79, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c4": {"valu_issue": 0.78, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c5": {"valu_issue": 0.57, "lds": 0.66, "profile": "profiles/forest_ranklds_kernel_c5.md"},
+    "c3": {"valu_issue": 0.80, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
+    "c4": {"valu_issue": 0.79, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
+    "c5": {"valu_issue": 0.55, "lds": 0.66, "profile": "profiles/forest_ranklds_kernel_c5.md"},
 }
 
 
