@@ -147,24 +147,32 @@ int check_desc(const forest_desc &d)
 }  // namespace
 
 // Trees of irregular shape differ in program length, and a workgroup ends with its slowest
-// wave: cut the trees (processing order) into lds_waves contiguous runs whose longest is as
-// short as possible.  Cost of a tree: its groups plus two for the work at its end.
+// wave: cut the trees (processing order) into lds_waves contiguous runs so that the wave that
+// finishes last finishes as early as possible.  Cost of a tree: its groups plus two for the work
+// at its end.  The waves of a workgroup do not run equally fast: wave w sits on SIMD w mod 4, and
+// of the waves a workgroup has on one SIMD the one launched first is served first.  Measured on
+// 12-wave workgroups (two per CU, 128 trees of ~124 groups): 540, 610 and 700 clock ticks per
+// group for waves 0-3, 4-7 and 8-11.  A run's length is therefore weighed by its wave's pace.
+static int wave_pace_permille(int waves, int w)
+{
+    if (waves != 12) return 1000;  // one or two waves per SIMD: not measured, taken as equal
+    return w < 4 ? 876 : (w < 8 ? 989 : 1135);  // ticks per group relative to their mean of 617
+}
+
 static void balance_waves(PackedModel &m)
 {
     const int waves = m.lds_waves;
     const int32_t T = m.n_trees;
     auto cost = [&](int32_t t) { return static_cast<int64_t>(m.tree[t].n_words) + 2; };
-    int64_t lo = 0, hi = 0;  // the answer lies in [largest tree, all trees]
-    for (int32_t t = 0; t < T; ++t) {
-        lo = std::max(lo, cost(t));
-        hi += cost(t);
-    }
-    // greedy cut under a cap; returns the number of runs and fills `cut` when asked
+    int64_t lo = 0, hi = 0;  // time of the last wave, in cost x permille: between 0 and all trees on the slowest
+    for (int32_t t = 0; t < T; ++t) hi += cost(t) * 1135;
+    // greedy cut under a time cap; returns the number of runs and fills `cut` when asked
     auto runs = [&](int64_t cap, int32_t *cut) {
         int n = 0;
         int64_t sum = 0;
         for (int32_t t = 0; t < T; ++t) {
-            if (t == 0 || sum + cost(t) > cap) {
+            const int pace = wave_pace_permille(waves, n > 0 ? std::min(n - 1, waves - 1) : 0);
+            if (t == 0 || (sum + cost(t)) * pace > cap) {
                 if (cut && n <= waves) cut[n] = t;
                 ++n;
                 sum = 0;
@@ -173,6 +181,8 @@ static void balance_waves(PackedModel &m)
         }
         return n;
     };
+    // a cap below a single tree's time on its wave makes that wave's run empty and the count
+    // exceed `waves`, so the search settles on a feasible cap
     while (lo < hi) {
         const int64_t mid = lo + (hi - lo) / 2;
         if (runs(mid, nullptr) <= waves) hi = mid;
