@@ -374,7 +374,9 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 5 : NVR == 2 ? 4 : 3)) void fore
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, BLOCK);
     } else {
-        rank_rows<WAVES, (NVR == 4 ? 4 : 2)>(rk, m, X, row0, n_rows, wave, lane);
+        // 128 rank registers: four features per wave and iteration, 16 per workgroup, so a line
+        // of X is used up in two iterations and can be streamed past the L2
+        rank_rows<WAVES, (NVR == 4 ? 4 : 2), NVR == 4>(rk, m, X, row0, n_rows, wave, lane);
     }
     __syncthreads();
     v32u x[NVR];

@@ -177,7 +177,7 @@ __device__ __forceinline__ T load_at(const void *__restrict__ base, uint32_t byt
     return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_offset);
 }
 
-// N floats read with one load; X is only known to be 4-byte aligned.
+// N floats read with one load; the tables are only known to be 4-byte aligned.
 template <int N>
 struct __attribute__((aligned(4))) FloatRun {
     float v[N];
@@ -191,7 +191,7 @@ struct __attribute__((aligned(4))) FloatRun {
 // a conversion), the bucket's bracket from the start table, the check of the bracket against
 // the two thresholds next to it, and the rank inside the bracket (a count over 8 thresholds, or
 // a binary search).
-template <int NWAVES, int U = 2>
+template <int NWAVES, int U = 2, bool STREAM_X = false>
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
                                           int64_t row0, int64_t n_rows, int wave, int lane)
 {
@@ -236,9 +236,14 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         if (f0 + U <= F) {  // wave-uniform: the U neighbouring features of a row in one load
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                const FloatRun<U> v = *reinterpret_cast<const FloatRun<U> *>(xrow[r] + f0);
+                // STREAM_X: a non-temporal load, so that X, read once, does not push the model's
+                // tables out of the L2.  Only where the waves of a workgroup use up a 128-byte
+                // line within an iteration or two; else the line would be fetched again.
+                typedef float XRun __attribute__((ext_vector_type(U), aligned(4)));
+                const XRun *p = reinterpret_cast<const XRun *>(xrow[r] + f0);
+                const XRun v = STREAM_X ? __builtin_nontemporal_load(p) : *p;
 #pragma unroll
-                for (int u = 0; u < U; ++u) x[u][r] = v.v[u];
+                for (int u = 0; u < U; ++u) x[u][r] = v[u];
             }
         }
 #pragma unroll
