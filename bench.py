@@ -45,7 +45,7 @@ MEASURED_TRAFFIC = {
 MEASURED_UNIT_BUSY = {
     "c2": {"valu_issue": 0.79, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
     "c3": {"valu_issue": 0.80, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c4": {"valu_issue": 0.79, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
+    "c4": {"valu_issue": 0.82, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
     "c5": {"valu_issue": 0.55, "lds": 0.66, "profile": "profiles/forest_ranklds_kernel_c5.md"},
 }
 
