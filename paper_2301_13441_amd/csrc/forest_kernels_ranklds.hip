@@ -390,8 +390,13 @@ __global__ __launch_bounds__(TILE *LWAVES) __attribute__((amdgpu_waves_per_eu(6,
         else
             ranklds_trees<MODE_VECTOR2, LWAVES>(m, bytes, accu, runs, sum, wave, lane, row0, n_rows, nullptr);
         __syncthreads();  // no wave reads the rank tile any more
+        // constant indices into `sum` (K <= 2 here): indexed by a run-time k the array would
+        // live in scratch memory and every tree would end with stores to it
+#pragma unroll
         for (int r = 0; r < 2; ++r)
-            for (int k = 0; k < K; ++k) acc[(wave * K + k) * RROWS + r * TILE + lane] = sum[r][k];
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+                if (k < K) acc[(wave * K + k) * RROWS + r * TILE + lane] = sum[r][k];
     } else if (column_runs) {
         int slot = 0;  // the slots of the waves before this one come first
         for (int v = 0; v < wave; ++v) slot += wave_count[v];
