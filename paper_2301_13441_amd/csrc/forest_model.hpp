@@ -59,7 +59,7 @@ inline uint16_t rank_entry_bits(int q)
     return static_cast<uint16_t>(((c ^ 0x8000u) & 0x8000u) | ((c & 0x7fffu) + (2u << 10)));
 }
 constexpr int RANK_MAX_REGS = 128;
-constexpr int RANK_BUCKETS_PER_THRESHOLD = 2;  // resolution of the per-feature bucket tables
+constexpr int RANK_BUCKETS_PER_THRESHOLD = 1;  // resolution of the per-feature bucket tables
 constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature
 constexpr int RANKLDS_MAX_REGS = 256;          // rank register index is 8 bits of an entry
 constexpr size_t RANKLDS_MAX_LDS = 144 * 1024; // LDS budget of the LDS-resident rank kernel

@@ -252,8 +252,10 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         }
         // one spare element: the kernels read a feature's threshold 0 even if it has none
         m.thr_sorted.push_back(std::numeric_limits<float>::infinity());
-        // Bucket tables: a uniform grid over the feature's finite threshold range, about two
-        // buckets per threshold, and for every bucket the number of thresholds in lower buckets.
+        // Bucket tables: a uniform grid over the feature's finite threshold range, one bucket
+        // per threshold (the kernels resolve brackets of up to 8 thresholds in one step, and a
+        // finer grid would only take L2 from the other tables), and for every bucket the number
+        // of thresholds in lower buckets.
         // bucket_index is monotone, so thresholds in lower buckets are below x and thresholds in
         // higher buckets are not: start[b] <= rank(x) <= start[b + 1] for b = bucket(x).  The
         // kernels check the bracket against the thresholds themselves before they trust it.
