@@ -31,9 +31,9 @@ HBM_PEAK = 8.0e12
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC = {
-    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 77,803 x 2.000 (copy-kernel scale) KiB read,
+    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 66,233 x 2.000 (copy-kernel scale) KiB read,
     # WRITE_SIZE 7,812.5 x 1.000 KiB written
-    "c2": 159.3e6 + 8.0e6,
+    "c2": 135.6e6 + 8.0e6,
     # profiles/linear_kernels.md: FETCH_SIZE 703,161 x 2.000 KiB, WRITE_SIZE 15,625 x 1.000 KiB
     "l2": 1440.0e6 + 16.0e6,
 }
@@ -43,10 +43,10 @@ MEASURED_TRAFFIC = {
 # of the launch); see the profile named.  They are measurements of the committed kernels, not
 # taken live, and are reported next to the live roofline fraction.
 MEASURED_UNIT_BUSY = {
-    "c2": {"valu_issue": 0.79, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
+    "c2": {"valu_issue": 0.81, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
     "c3": {"valu_issue": 0.80, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
     "c4": {"valu_issue": 0.82, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c5": {"valu_issue": 0.55, "lds": 0.66, "profile": "profiles/forest_ranklds_kernel_c5.md"},
+    "c5": {"valu_issue": 0.56, "lds": 0.67, "profile": "profiles/forest_ranklds_kernel_c5.md"},
 }
 
 
