@@ -235,7 +235,10 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
                 const uint32_t group_in_chunk = __builtin_amdgcn_ubfe(static_cast<uint32_t>(ref[r]), 3, 3);
                 outcome[r] = bytes[group_in_chunk * (2 * TILE) + (r * TILE + lane)];
                 bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
-                pair[r] = m.child[level_start + ref[r]];
+                // wave-uniform base + 32-bit byte offset (the table is far below 4 GB): one
+                // vector instruction for the address instead of a 64-bit sum
+                pair[r] = *reinterpret_cast<const ChildRef *>(
+                    reinterpret_cast<const char *>(m.child) + (static_cast<uint32_t>(level_start + ref[r]) << 3));
                 ref[r] = WAITING;
             }
         }
