@@ -63,7 +63,7 @@ enum {
  * leaf_value[node * n_outputs + k] into every column k.
  *
  * Per column: raw = base_score[k] + (aggregate == MEAN ? sum / #trees feeding k : sum),
- * accumulated in double and rounded once.  scores = transform(raw).  label (n_outputs >= 2)
+ * accumulated in double and rounded once; a column no tree feeds is its base score.  scores = transform(raw).  label (n_outputs >= 2)
  * = smallest k with maximal raw; n_outputs == 1: raw > 0.5 (no transform) or raw > 0 (sigmoid).
  */
 typedef struct forest_desc {

@@ -18,7 +18,8 @@
  *   - a row goes LEFT iff x[feature] <= threshold, both float32, IEEE ordered compare;
  *     a NaN feature therefore goes RIGHT;
  *   - sums are accumulated in double, trees in ascending index, one rounding to float32;
- *   - MEAN divides a column's sum by the number of trees that feed that column;
+ *   - MEAN divides a column's sum by the number of trees that feed that column; a column no
+ *     tree feeds has an empty sum, which adds nothing to its base score;
  *   - sigmoid / softmax are evaluated in double from the unrounded value;
  *   - label, K >= 2: the smallest column index that attains the maximum unrounded raw value;
  *     K == 1: raw > 0.5 without transform, raw > 0 under sigmoid (the same decision, taken
@@ -94,7 +95,7 @@ static void *run_rows(void *arg)
         }
         for (int32_t k = 0; k < K; ++k) {
             double s = acc[k];
-            if (m->aggregate == ORACLE_MEAN) s = s / j->col_trees[k];
+            if (m->aggregate == ORACLE_MEAN && j->col_trees[k] > 0.0) s = s / j->col_trees[k];
             acc[k] = (m->base_score ? (double)m->base_score[k] : 0.0) + s;
             if (j->raw_out) j->raw_out[r * K + k] = acc[k];
         }

@@ -146,7 +146,7 @@ def forest_raw_scores(forest, X: np.ndarray, use: str = "path") -> np.ndarray:
             acc += contrib
             cnt += 1
     if forest.aggregate == 1:
-        acc = acc / cnt[None, :]
+        acc = acc / np.where(cnt > 0, cnt, 1.0)[None, :]   # a column no tree feeds stays an empty sum
     if forest.base_score is not None:
         acc = forest.base_score.astype(np.float64)[None, :] + acc
     return acc

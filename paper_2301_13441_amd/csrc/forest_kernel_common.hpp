@@ -56,7 +56,8 @@ __device__ __forceinline__ void finish_values(const DevModel &m, double *raw, in
     int best_k = 0;
     for (int k = 0; k < K; ++k) {
         double s = raw[k * stride];
-        if (m.aggregate == FOREST_AGG_MEAN) s = s / m.col_trees[k];
+        // a column no tree feeds: the mean over no trees adds nothing to the base score
+        if (m.aggregate == FOREST_AGG_MEAN && m.col_trees[k] > 0.0) s = s / m.col_trees[k];
         s = static_cast<double>(m.base[k]) + s;
         raw[k * stride] = s;
         if (k == 0 || s > best) {

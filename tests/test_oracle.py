@@ -191,6 +191,53 @@ def test_against_sklearn_gradient_boosting_regressor():
     np.testing.assert_allclose(oracle.predict(f, Xt).scores[:, 0], gb.predict(Xt), rtol=2e-6, atol=2e-6)
 
 
+def test_against_sklearn_gradient_boosting_classifier_binary():
+    """Per-class sums + sigmoid + label of a boosted binary classifier: probability of class 1
+    is sigmoid(raw), raw = log-odds of the prior + learning rate x sum of the trees' leaf values."""
+    ske = pytest.importorskip("sklearn.ensemble")
+    X, rng = _grid_data(11, 900, 5)
+    y = ((X[:, 0] + X[:, 3] > 11) ^ (X[:, 1] > 9)).astype(int)
+    gb = ske.GradientBoostingClassifier(n_estimators=25, max_depth=3, learning_rate=0.2,
+                                        random_state=0).fit(X, y)
+    prior = gb.init_.class_prior_
+    f = _sk_forest([e[0] for e in gb.estimators_], 5, 1, 1, scale=gb.learning_rate, aggregate=wl.AGG_SUM,
+                   base_score=np.asarray([np.log(prior[1] / prior[0])], np.float32),
+                   transform=wl.TRANSFORM_SIGMOID)
+    Xt, _ = _grid_data(12, 500, 5)
+    res = oracle.predict(f, Xt)
+    proba = gb.predict_proba(Xt)[:, 1]
+    np.testing.assert_allclose(res.scores[:, 0], proba, rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(res.raw[:, 0], gb.decision_function(Xt), rtol=2e-6, atol=2e-6)
+    clear = np.abs(proba - 0.5) > 1e-6
+    assert clear.sum() > 400
+    assert (res.labels[clear] == gb.predict(Xt)[clear]).all()
+
+
+def test_against_sklearn_gradient_boosting_classifier_multiclass():
+    """Three classes: one scalar-leaf tree per class and round feeding its class's column, base
+    score = log prior, softmax over the per-class sums, label = argmax of the raw sums."""
+    ske = pytest.importorskip("sklearn.ensemble")
+    X, rng = _grid_data(13, 900, 5)
+    y = (X[:, 0] + X[:, 1] > 11).astype(int) + (X[:, 2] > 8).astype(int)
+    gb = ske.GradientBoostingClassifier(n_estimators=12, max_depth=3, learning_rate=0.3,
+                                        random_state=0).fit(X, y)
+    n_rounds, K = gb.estimators_.shape
+    assert K == 3
+    ests = [gb.estimators_[i, k] for i in range(n_rounds) for k in range(K)]   # round-major
+    f = _sk_forest(ests, 5, K, 1, scale=gb.learning_rate, aggregate=wl.AGG_SUM,
+                   base_score=np.log(gb.init_.class_prior_).astype(np.float32),
+                   transform=wl.TRANSFORM_SOFTMAX)
+    f.tree_output = np.asarray([k for _ in range(n_rounds) for k in range(K)], np.int32)
+    Xt, _ = _grid_data(14, 500, 5)
+    res = oracle.predict(f, Xt)
+    proba = gb.predict_proba(Xt)
+    np.testing.assert_allclose(res.scores, proba, rtol=5e-6, atol=2e-6)
+    srt = np.sort(proba, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 1e-5
+    assert clear.sum() > 400
+    assert (res.labels[clear] == gb.predict(Xt)[clear]).all()
+
+
 # ----------------------------------------------------------------------------- matrix formulation
 
 @pytest.mark.parametrize("seed", range(8))
@@ -264,6 +311,63 @@ def test_constant_leaves_closed_form():
     summed = wl.Forest(**{**f.__dict__, "leaf_value": const, "aggregate": wl.AGG_SUM,
                           "base_score": np.asarray([0.5], np.float32)})
     assert (oracle.predict(summed, X).scores == np.float32(0.5 + 10 * 0.375)).all()
+
+
+def _constant_leaf_trees(columns, c, K, **kw):
+    """Single-split trees (x0 <= 0) whose two leaves both hold c; tree t feeds columns[t]."""
+    T = len(columns)
+    return wl.Forest(n_features=1, n_outputs=K, leaf_width=1,
+                     tree_offset=np.arange(0, 3 * T + 1, 3, dtype=np.int64),
+                     feature=np.tile(np.asarray([0, -1, -1], np.int32), T),
+                     threshold=np.zeros(3 * T, np.float32),
+                     left=np.tile(np.asarray([1, -1, -1], np.int32), T),
+                     right=np.tile(np.asarray([2, -1, -1], np.int32), T),
+                     leaf_value=np.tile(np.asarray([[0.0], [c], [c]], np.float32), (T, 1)),
+                     tree_output=np.asarray(columns, np.int32), **kw)
+
+
+def test_mean_divides_by_the_trees_that_feed_a_column():
+    """Closed form: eleven scalar-leaf trees with constant leaves c feed three of four columns
+    unevenly (3 / 4 / 4 trees).  MEAN gives base + c in every fed column -- dividing by all eleven
+    trees would give 3c/11 and 4c/11 -- and a column no tree feeds is its base score: the mean
+    over no trees adds nothing."""
+    c = 0.375
+    columns = [0, 1, 2, 1, 2, 0, 1, 2, 2, 1, 0]
+    base = np.asarray([0.25, -1.0, 2.0, 0.5], np.float32)
+    X = np.asarray([[-1.0], [0.0], [3.0], [np.nan]], np.float32)
+    f = _constant_leaf_trees(columns, c, 4, aggregate=wl.AGG_MEAN, base_score=base)
+    res = oracle.predict(f, X)
+    want = np.asarray([0.25 + c, -1.0 + c, 2.0 + c, 0.5], np.float32)
+    assert (res.scores == want[None, :]).all()
+    assert res.labels.tolist() == [2, 2, 2, 2]
+    # SUM of the same forest: base + (trees feeding the column) * c
+    g = _constant_leaf_trees(columns, c, 4, aggregate=wl.AGG_SUM, base_score=base)
+    want_sum = np.asarray([0.25 + 3 * c, -1.0 + 4 * c, 2.0 + 4 * c, 0.5], np.float32)
+    assert (oracle.predict(g, X).scores == want_sum[None, :]).all()
+    # without base scores the unfed column is exactly 0, never 0/0
+    h = _constant_leaf_trees(columns, c, 4, aggregate=wl.AGG_MEAN)
+    assert (oracle.predict(h, X).scores == np.asarray([c, c, c, 0.0], np.float32)[None, :]).all()
+
+
+def test_single_output_labels_follow_the_transformed_score():
+    """K = 1: the label is taken before the monotone transform (Section 4.3.3) and must agree with
+    thresholding the transformed score at one half wherever the score is not within rounding of
+    it: sigmoid(raw) > 0.5 iff raw > 0; without transform, raw > 0.5."""
+    X = np.random.default_rng(5).standard_normal((4000, 6)).astype(np.float32)
+    g = wl.random_forest(34, n_trees=9, n_features=6, max_depth=4, transform=wl.TRANSFORM_SIGMOID)
+    centre = np.float32(-np.median(oracle.predict(g, X).raw))      # both classes occur
+    g = wl.Forest(**{**g.__dict__, "base_score": np.asarray([centre], np.float32)})
+    rs = oracle.predict(g, X)
+    off = np.abs(rs.scores[:, 0].astype(np.float64) - 0.5) > 1e-6
+    assert off.sum() > 3900 and 0.2 < rs.labels.mean() < 0.8
+    assert (rs.labels[off] == (rs.scores[off, 0] > 0.5)).all()
+    # a raw value of exactly zero is class 0 under sigmoid, and exactly one half is class 0 without
+    for transform, value in ((wl.TRANSFORM_SIGMOID, 0.0), (wl.TRANSFORM_NONE, 0.5)):
+        z = _constant_leaf_trees([0], value, 1, transform=transform)
+        assert oracle.predict(z, X[:4, :1]).labels.tolist() == [0, 0, 0, 0]
+        nxt = float(np.nextafter(np.float32(value), np.float32(1)))
+        z = _constant_leaf_trees([0], nxt, 1, transform=transform)
+        assert oracle.predict(z, X[:4, :1]).labels.tolist() == [1, 1, 1, 1]
 
 
 def test_tree_order_and_forest_doubling():
