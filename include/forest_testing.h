@@ -1,0 +1,84 @@
+/*
+ * forest_testing.h -- host-only views into the model compiler of the tree-ensemble library,
+ * for its tests.  Not part of the inference ABI (include/forest.h): the layouts shown here are
+ * internals of the packed model and may change with the kernels.  Same conventions: extern "C",
+ * plain pointers and sizes, 0 or a negative FOREST_E* code, no GPU needed.
+ *
+ * What the views let a test check: the numbering of Section 3.1.2 (internal nodes in level order,
+ * leaves in in-order), the weights of Table 2 as the packed model stores them (split features W1,
+ * thresholds W2, child references standing for W3, the leaf table E), and the exact rewriting of
+ * the float32 comparison as a comparison of small-integer threshold ranks (Section 4.3.1, dtype
+ * rewriting, applied to the input).
+ */
+#ifndef FOREST_TESTING_H_
+#define FOREST_TESTING_H_
+
+#include "forest.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Host-only view of the packed model for tests of the model compiler (no GPU needed):
+ * compiles `desc` exactly as forest_load does, without uploading, and evaluates nothing.
+ * The arrays below are HOST memory owned by the handle, valid until forest_pack_free.
+ */
+struct forest_rank_bucket {
+    float lo, scale;
+    int32_t n_buckets, start_base;
+};
+
+typedef struct forest_packed_view {
+    int32_t n_trees;
+    int32_t kernel_kind;            /* common depth of a forest of full trees (1..8), else 0 */
+    int32_t kernel_path;            /* as forest_info_t.kernel_path */
+    int32_t rank_registers;         /* kernel_path 2: rank registers per lane (virtual features) */
+    const int32_t *tree_n_internal; /* [n_trees] N_I */
+    const int32_t *tree_depth;      /* [n_trees] longest path; full trees: every path */
+    const int32_t *tree_is_full;    /* [n_trees] 1 if every leaf sits at tree_depth */
+    const int64_t *node_base;       /* [n_trees + 1] offsets into the per-internal-node arrays */
+    const int64_t *leaf_base;       /* [n_trees + 1] offsets into the per-leaf arrays */
+    const int32_t *split_feature;   /* [sum N_I] level order (I_0, I_1, ...) */
+    const float *split_threshold;   /* [sum N_I] */
+    const int32_t *child_left;      /* [sum N_I] >= 0: internal ordinal; < 0: ~leaf ordinal */
+    const int32_t *child_right;     /* [sum N_I] */
+    const int32_t *leaf_node;       /* [sum N_L] caller's tree-local node index of L_j (in-order) */
+    const float *leaf_value;        /* [sum N_L * leaf_width] the table E */
+    /* kernel_path 2 and 3 (else NULL): the tables that turn a feature value into its threshold
+     * rank.  rank_threshold[rank_threshold_base[f] .. rank_threshold_base[f + 1]) are the
+     * distinct thresholds of feature f, ascending.  rank_bucket[f] = (lo, scale, n_buckets,
+     * start_base): for b = min(max(trunc((x - lo) * scale), 0), n_buckets - 1), computed in
+     * float32, rank_bucket_start[start_base + b] <= rank(x) <= rank_bucket_start[start_base + b + 1]. */
+    const float *rank_threshold;
+    const int32_t *rank_threshold_base;        /* [n_features + 1] */
+    const struct forest_rank_bucket *rank_bucket; /* [n_features] */
+    const int32_t *rank_bucket_start;
+    /* kernel_path 3: wavefronts per workgroup, the trees of each wavefront (processing order:
+     * wave w takes trees wave_tree[w] .. wave_tree[w + 1] - 1, workgroup_waves + 1 entries) and
+     * the program length of every tree in that order, in groups of 8 entries; else 0 / NULL. */
+    int32_t workgroup_waves;
+    const int32_t *wave_tree;
+    const int32_t *program_groups; /* [n_trees] */
+} forest_packed_view;
+
+typedef struct forest_packed forest_packed;
+int forest_pack(const forest_desc *desc, forest_packed **out);
+int forest_pack_view(const forest_packed *p, forest_packed_view *view);
+void forest_pack_free(forest_packed *p);
+
+/*
+ * Host-only view of the rank coding of kernel_path 2 and 3 (the input's dtype rewriting,
+ * Section 4.3.1; no GPU needed): a rank register stores the local rank q of a row among the
+ * thresholds of its segment as the f16 bit pattern *code, and a split on the segment's j-th
+ * threshold carries the f16 bit pattern *entry (for q = j); the kernels take
+ * clamp_[0,1](fma(code(q), 4, entry(j))), in f16 with one rounding, as the outcome bit q > j.
+ * Returns the number of codes (q must be in [0, that number); one register covers one
+ * threshold fewer), or FOREST_EINVAL for q out of range or a null pointer.
+ */
+int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOREST_TESTING_H_ */

@@ -1,7 +1,7 @@
 /*
  * linear.h -- C ABI of the linear-model family of the MI355X (gfx950) inference library.
  *
- * The linear classifiers and regressors the paper lists (Section 4.1, Table 3:
+ * The linear classifiers and regressors the paper lists (Section 3.3, Table 4:
  * LogisticRegression, SGDClassifier, RidgeClassifier, LinearRegression, LinearSVC, ...) are
  * one matmul with the weight matrix plus the bias, optionally followed by a monotone
  * transform (sigmoid, softmax) and an index operator (argmax).  Redundant elimination

@@ -1,6 +1,6 @@
 """CPU oracle for the linear-model family.  TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
-The paper's linear classifiers and regressors (Section 4.1, Table 3: LogisticRegression,
+The paper's linear classifiers and regressors (Section 3.3, Table 4: LogisticRegression,
 SGDClassifier, RidgeClassifier, LinearRegression, LinearSVC, ...) are one matmul plus bias,
 optionally followed by a monotone transform and an index operator; redundant elimination
 (Section 4.3.3) takes the label from the values before the transform.  This is that definition

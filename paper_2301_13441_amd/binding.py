@@ -49,9 +49,11 @@ class _View(ctypes.Structure):
                 ("workgroup_waves", _i32), ("wave_tree", _p), ("program_groups", _p)]
 
 
+# include/forest.h: the inference ABI
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
-           "forest_predict", "forest_predict_leaves", "forest_pack", "forest_pack_view",
-           "forest_pack_free", "forest_rank_code", "forest_strerror"]
+           "forest_predict", "forest_predict_leaves", "forest_strerror"]
+# include/forest_testing.h: host-only views into the model compiler, for its tests
+TESTING_EXPORTS = ["forest_pack", "forest_pack_view", "forest_pack_free", "forest_rank_code"]
 
 
 def lib_path() -> str:

@@ -1,4 +1,5 @@
-// C ABI of the library (see include/forest.h): validation, packing, upload, launch.
+// C ABI of the library (see include/forest.h): validation, packing, upload, launch.  The entry
+// points that need no device are in forest_api_host.cpp.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -8,10 +9,6 @@
 #include "forest_device.hpp"
 
 using namespace forest_impl;
-
-struct forest_packed {
-    PackedModel m;
-};
 
 struct forest {
     PackedModel host;  // tables kept for forest_info; large arrays are released after upload
@@ -72,66 +69,6 @@ int check_device(const forest *f)
 }  // namespace
 
 extern "C" {
-
-int forest_pack(const forest_desc *desc, forest_packed **out)
-{
-    if (!desc || !out) return FOREST_EINVAL;
-    forest_packed *p = new (std::nothrow) forest_packed;
-    if (!p) return FOREST_ENOMEM;
-    int rc;
-    try {
-        rc = compile_forest(*desc, p->m);
-    } catch (const std::bad_alloc &) {
-        rc = FOREST_ENOMEM;
-    }
-    if (rc != FOREST_OK) {
-        delete p;
-        return rc;
-    }
-    *out = p;
-    return FOREST_OK;
-}
-
-int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry)
-{
-    if (!code || !entry || q < 0 || q >= RANK_CODES) return FOREST_EINVAL;
-    *code = rank_code_bits(q);
-    *entry = rank_entry_bits(q);
-    return RANK_CODES;
-}
-
-int forest_pack_view(const forest_packed *p, forest_packed_view *v)
-{
-    if (!p || !v) return FOREST_EINVAL;
-    const PackedModel &m = p->m;
-    v->n_trees = m.n_trees;
-    v->kernel_kind = m.kind;
-    v->kernel_path = m.path;
-    v->rank_registers = m.rank_regs;
-    v->tree_n_internal = m.v_n_internal.data();
-    v->tree_depth = m.v_depth.data();
-    v->tree_is_full = m.v_is_full.data();
-    v->node_base = m.v_node_base.data();
-    v->leaf_base = m.v_leaf_base.data();
-    v->split_feature = m.v_feature.data();
-    v->split_threshold = m.v_threshold.data();
-    v->child_left = m.v_left.data();
-    v->child_right = m.v_right.data();
-    v->leaf_node = m.v_leaf_node.data();
-    v->leaf_value = m.v_leaf_value.data();
-    const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
-    static_assert(sizeof(forest_rank_bucket) == sizeof(FeatBucket), "same four fields");
-    v->rank_threshold = ranks ? m.thr_sorted.data() : nullptr;
-    v->rank_threshold_base = ranks ? m.feat_thr_base.data() : nullptr;
-    v->rank_bucket = ranks ? reinterpret_cast<const forest_rank_bucket *>(m.feat_bucket.data()) : nullptr;
-    v->rank_bucket_start = ranks ? m.bucket_start.data() : nullptr;
-    v->workgroup_waves = m.path == PATH_RANK_LDS ? m.lds_waves : 0;
-    v->wave_tree = m.path == PATH_RANK_LDS ? m.wave_tree : nullptr;
-    v->program_groups = m.path == PATH_RANK_LDS ? m.v_program_groups.data() : nullptr;
-    return FOREST_OK;
-}
-
-void forest_pack_free(forest_packed *p) { delete p; }
 
 int forest_load(const forest_desc *desc, forest **out)
 {
@@ -342,21 +279,6 @@ int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32
     const hipError_t e = launch_predict(f->dev, X, n_rows, nullptr, nullptr, leaf_node_id,
                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
-}
-
-const char *forest_strerror(int code)
-{
-    switch (code) {
-        case FOREST_OK: return "ok";
-        case FOREST_EINVAL: return "invalid argument";
-        case FOREST_ETREE: return "malformed tree";
-        case FOREST_EFEATURE: return "split feature out of range";
-        case FOREST_ENONFINITE: return "NaN threshold or base score";
-        case FOREST_ENOMEM: return "out of memory";
-        case FOREST_EHIP: return "HIP runtime error";
-        case FOREST_ELIMIT: return "model exceeds a kernel limit";
-        default: return "unknown error";
-    }
 }
 
 }  // extern "C"

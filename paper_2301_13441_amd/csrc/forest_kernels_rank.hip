@@ -43,6 +43,10 @@ typedef const TreeMeta *MetaPtr;
 // the rank register's index in the low byte.  s_set_gpr_idx_* reads only the low byte; the
 // packed multiply-add reads the high half for both rows (op_sel / op_sel_hi of the addend) and
 // the inline constant's low half for both (op_sel_hi 0: a packed inline constant fills only it).
+// The index mode lives in M0.  M0 is a register the compiler reserves: it never keeps a value of
+// its own in it across an inline-assembly statement (it sets M0 immediately before each use it
+// generates, and rejects M0 on a clobber list as having no effect), so the statements below may
+// write it freely.
 struct Entry8 {
     uint32_t e[8];
 };
@@ -81,7 +85,9 @@ struct RankStep<2> {
     static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, const v32u (&x)[2])
     {
         uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
-        asm volatile(FOREST_RANK_ASM("v64") : FOREST_RANK_OUTS : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+        asm volatile(FOREST_RANK_ASM("v64")
+                     : FOREST_RANK_OUTS
+                     : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
     }
 };
 

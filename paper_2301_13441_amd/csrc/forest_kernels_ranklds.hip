@@ -60,7 +60,19 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // 0.0 in each f16 half) in the register the read filled.
 #define FOREST_LDS_FETCH(t, e) "s_and_b32 m0, " e ", 0xff00\n\ts_nop 0\n\tds_read_addtid_b32 " t "\n\t"
 #define FOREST_LDS_CMP(t, e) "v_pk_fma_f16 " t ", " t ", 4.0, " e " op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
-#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, NEXT)           \
+#if !defined(FOREST_RANKLDS_CONSERVATIVE)
+// Streaming form: the statement ends by fetching, into the register set it has just used, the pair
+// after the next one (NEXT); the fetch lands while the code between two statements runs.
+#define FOREST_LDS_PAIR_HEAD(SET, CUR) ""
+#define FOREST_LDS_PAIR_TAIL(SET, NEXT) "s_load_dwordx16 " SET ", %[p], " NEXT
+#else
+// Conservative form: the statement fetches its own 16 entries (CUR) and waits for them; nothing
+// is in flight when it ends, and the register set is an ordinary scratch of the statement.
+#define FOREST_LDS_PAIR_HEAD(SET, CUR) "s_load_dwordx16 " SET ", %[p], " CUR "\n\ts_waitcnt lgkmcnt(0)\n\t"
+#define FOREST_LDS_PAIR_TAIL(SET, NEXT) ""
+#endif
+#define FOREST_LDS_PAIR(S0, S1, S2, S3, S4, S5, S6, S7, S8, S9, S10, S11, S12, S13, S14, S15, SET, CUR, NEXT)      \
+    FOREST_LDS_PAIR_HEAD(SET, CUR)                                                                                 \
     "s_mov_b32 %[f0], " S0 "\n\t"                                                                                \
     "s_mov_b32 %[f1], " S8 "\n\t"                                                                                \
     FOREST_LDS_FETCH("v64", S0) FOREST_LDS_FETCH("v65", S1) FOREST_LDS_FETCH("v66", S2) FOREST_LDS_FETCH("v67", S3)  \
@@ -74,7 +86,7 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                    \
     FOREST_LDS_CMP("v72", S8) FOREST_LDS_CMP("v73", S9) FOREST_LDS_CMP("v74", S10) FOREST_LDS_CMP("v75", S11)        \
     FOREST_LDS_CMP("v76", S12) FOREST_LDS_CMP("v77", S13) FOREST_LDS_CMP("v78", S14) FOREST_LDS_CMP("v79", S15)      \
-    "s_load_dwordx16 " SET ", %[p], " NEXT
+    FOREST_LDS_PAIR_TAIL(SET, NEXT)
 
 // Two groups of 8 entries for the lane's two rows.  All 16 LDS reads are issued before the
 // first comparison, so the LDS latency is paid once per pair.  LDS operations complete in
@@ -87,38 +99,69 @@ __host__ __device__ inline size_t ranklds_region2_bytes(int waves)
 // one 16-register value pinned to s[36:51] resp. s[52:67].
 //
 // d0, d1: the outcomes of the two groups, the matrix core's B operands.  f0, f1: the first
-// entry of each group (its low byte holds the group's flags).  M0 is not on the clobber list:
-// the compiler reserves it and loads it immediately before each of its own uses, so nothing of
-// its making is live in M0 across a statement.
+// entry of each group (its low byte holds the group's flags).  M0 is written by every entry; it is a
+// register the compiler reserves -- it keeps nothing of its own in M0 across an inline-assembly
+// statement, sets it immediately before each use it generates, and rejects it on a clobber list as
+// having no effect -- so the statements may write it freely.
+//
+// The streaming form is sound only if the compiler's own code between two statements leaves
+// s[36:67] alone; the build checks that on the generated assembly before it links and otherwise
+// builds the conservative form (FOREST_RANKLDS_CONSERVATIVE), which needs no such promise.
+#if !defined(FOREST_RANKLDS_CONSERVATIVE)
+#define FOREST_LDS_OUTS_EVEN(set) , "+{s[36:51]}"(set)
+#define FOREST_LDS_OUTS_ODD(set) , "+{s[52:67]}"(set)
+#define FOREST_LDS_CLOBBERS_EVEN "memory"
+#define FOREST_LDS_CLOBBERS_ODD "memory"
+#else
+#define FOREST_LDS_OUTS_EVEN(set)
+#define FOREST_LDS_OUTS_ODD(set)
+#define FOREST_LDS_CLOBBERS_EVEN                                                                              \
+    "memory", "s36", "s37", "s38", "s39", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", \
+        "s50", "s51"
+#define FOREST_LDS_CLOBBERS_ODD                                                                               \
+    "memory", "s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", \
+        "s66", "s67"
+#endif
 __device__ __forceinline__ void eval_pair_even(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
                                                StreamPtr p)
 {
     asm volatile(FOREST_LDS_PAIR("s36", "s37", "s38", "s39", "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47",
-                                 "s48", "s49", "s50", "s51", "s[36:51]", "0x80")
-                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[36:51]}"(set)
+                                 "s48", "s49", "s50", "s51", "s[36:51]", "0x0", "0x80")
+                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1) FOREST_LDS_OUTS_EVEN(set)
                  : [p] "s"(p)
-                 : "memory");
+                 : FOREST_LDS_CLOBBERS_EVEN);
 }
 
 __device__ __forceinline__ void eval_pair_odd(v8i &d0, v8i &d1, uint32_t &f0, uint32_t &f1, v16u &set,
                                               StreamPtr p)
 {
     asm volatile(FOREST_LDS_PAIR("s52", "s53", "s54", "s55", "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63",
-                                 "s64", "s65", "s66", "s67", "s[52:67]", "0xc0")
-                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1), "+{s[52:67]}"(set)
+                                 "s64", "s65", "s66", "s67", "s[52:67]", "0x40", "0xc0")
+                 : "={v[64:71]}"(d0), "={v[72:79]}"(d1), [f0] "=&s"(f0), [f1] "=&s"(f1) FOREST_LDS_OUTS_ODD(set)
                  : [p] "s"(p)
-                 : "memory");
+                 : FOREST_LDS_CLOBBERS_ODD);
 }
 
-// The first two pairs of a wave's stream into the two register sets.
+// The first two pairs of a wave's stream into the two register sets (streaming form only).
 __device__ __forceinline__ void load_first_pairs(v16u &even, v16u &odd, StreamPtr p)
 {
+#if !defined(FOREST_RANKLDS_CONSERVATIVE)
     asm volatile("s_load_dwordx16 s[36:51], %[p], 0x0\n\t"
                  "s_load_dwordx16 s[52:67], %[p], 0x40\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "={s[36:51]}"(even), "={s[52:67]}"(odd)
                  : [p] "s"(p)
                  : "memory");
+#endif
+}
+
+// The last statements' fetches are still in flight: let them land before the registers are reused
+// (streaming form only).
+__device__ __forceinline__ void finish_stream(v16u &even, v16u &odd)
+{
+#if !defined(FOREST_RANKLDS_CONSERVATIVE)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+{s[36:51]}"(even), "+{s[52:67]}"(odd) : : "memory");
+#endif
 }
 
 // Output modes.  SCALAR1 (one output column, scalar leaves) and VECTOR2 (vector leaves, at most
@@ -194,7 +237,13 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
     v16u set_even, set_odd;
     load_first_pairs(set_even, set_odd, p);
     int t = t_begin;
-    int level_start = pos;  // stream position of the current level's first entry
+    // The child references are addressed relative to the current tree: wave-uniform table base of
+    // the tree + a per-lane 32-bit byte offset.  A tree's stream is its internal nodes plus at most
+    // 7 entries of padding per level (at most 64 levels), far below the 2^29 entries the offset
+    // can span, whatever the length of the whole program.
+    const ChildRef *tree_child = m.child + pos;
+    int level_start = 0;    // position of the current level's first entry inside the tree's stream
+    int tree_start = pos;   // stream position of the tree's first entry
     int chunk = 0;          // chunk index inside the level
     int gi = 0;             // group index inside the chunk
     // ref: ordinal of the lane's node inside the current level; ~leaf once a leaf is reached;
@@ -235,10 +284,10 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
                 const uint32_t group_in_chunk = __builtin_amdgcn_ubfe(static_cast<uint32_t>(ref[r]), 3, 3);
                 outcome[r] = bytes[group_in_chunk * (2 * TILE) + (r * TILE + lane)];
                 bit[r] = static_cast<uint32_t>(ref[r]) & 7u;
-                // wave-uniform base + 32-bit byte offset (the table is far below 4 GB): one
-                // vector instruction for the address instead of a 64-bit sum
+                // wave-uniform base of the tree + 32-bit byte offset: one vector instruction for
+                // the address instead of a 64-bit sum
                 pair[r] = *reinterpret_cast<const ChildRef *>(
-                    reinterpret_cast<const char *>(m.child) + (static_cast<uint32_t>(level_start + ref[r]) << 3));
+                    reinterpret_cast<const char *>(tree_child) + (static_cast<uint32_t>(level_start + ref[r]) << 3));
                 ref[r] = WAITING;
             }
         }
@@ -246,7 +295,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         gi = 0;
         if (flags & 1u) {  // level complete: every lane that was on a node has picked its child
             resolve = true;
-            level_start = pos;
+            level_start = pos - tree_start;
             chunk = 0;
         }
         if (flags & 2u) {  // tree complete: every lane stands on a leaf
@@ -277,6 +326,9 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
             }
             ++t;  // the metadata table has one spare record after the last tree
             ref[0] = ref[1] = meta[t].root_ref;
+            tree_start = pos;
+            tree_child = m.child + pos;
+            level_start = 0;
         }
     };
     // The matrix core is still collecting a pair's bits when its comparisons have issued, so
@@ -326,8 +378,7 @@ __device__ __forceinline__ void ranklds_trees(const DevModel &m, uint8_t *bytes,
         consume_previous();
         collect(d0, d1, f0, f1);
     }
-    // the last statements' fetches are still in flight: let them land before the registers are reused
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+{s[36:51]}"(set_even), "+{s[52:67]}"(set_odd) : : "memory");
+    finish_stream(set_even, set_odd);
     consume(prev_g0, prev_f0);
     if (!(n_groups & 1)) consume(prev_g1, prev_f1);
 }

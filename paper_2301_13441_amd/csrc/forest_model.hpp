@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "../../include/forest.h"
+#include "../../include/forest_testing.h"
 
 namespace forest_impl {
 

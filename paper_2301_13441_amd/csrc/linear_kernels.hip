@@ -1,4 +1,4 @@
-// Linear models on gfx950: raw = X . W + b, transform, label (Section 4.1, Table 3; the label
+// Linear models on gfx950: raw = X . W + b, transform, label (Section 3.3, Table 4; the label
 // comes from the values before the transform, Section 4.3.3).
 //
 // The path is bound by reading X once from HBM (4 F bytes per row against 2 F K flops), so the

@@ -238,7 +238,7 @@ def test_predict_replays_from_a_captured_graph(rows):
 
 
 def test_hand_off_from_torch_ops_on_the_same_stream():
-    """Hybrid use (Section 4.4): the features are the output of tensor ops on the device and
+    """Hybrid use (Section 4.5): the features are the output of tensor ops on the device and
     the forest consumes them on the same stream, without a host round trip in between."""
     import torch
     import paper_2301_13441_amd as pk

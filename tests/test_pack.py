@@ -18,13 +18,13 @@ def _lib():
 def test_library_exports_every_declared_symbol():
     import os
     import re
-    header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
-                               "include", "forest.h")).read()
-    declared = set(re.findall(r"\b(forest_[a-z_]+)\s*\(", header))
-    assert declared == set(binding.EXPORTS)
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
     lib = _lib()
-    for name in declared:
-        assert getattr(lib, name) is not None
+    for header, names in (("forest.h", binding.EXPORTS), ("forest_testing.h", binding.TESTING_EXPORTS)):
+        declared = set(re.findall(r"\b(forest_[a-z_]+)\s*\(", open(os.path.join(inc, header)).read()))
+        assert declared == set(names), header
+        for name in declared:
+            assert getattr(lib, name) is not None
     assert lib.forest_strerror(-2) == b"malformed tree"
 
 
@@ -268,9 +268,10 @@ def test_rank_bucket_tables_bracket_every_rank(case):
 
 
 def test_pinned_stream_register_check_catches_a_violation():
-    """The build refuses a library whose LDS rank kernel lets compiler-generated code touch the
-    pinned stream registers between two evaluation statements; the checker itself is tested on
-    a miniature of the assembly's structure."""
+    """The build does not ship the streaming form of the LDS rank kernel when compiler-generated
+    code touches the pinned stream registers between two evaluation statements (it builds the
+    conservative form instead, tests/test_build.py); the checker itself is tested here on a
+    miniature of the assembly's structure."""
     from paper_2301_13441_amd import check_stream_registers as chk
     clean = "\n".join([
         ".LBB0_1:                                ; =>This Loop Header: Depth=1",
@@ -283,8 +284,6 @@ def test_pinned_stream_register_check_catches_a_violation():
     dirty = clean.replace("\ts_add_u32 s2, s2, 0x80", "\ts_add_u32 s2, s2, 0x80\n\ts_mov_b32 s44, s7")
     with pytest.raises(RuntimeError, match="pinned stream register"):
         chk.check_assembly(dirty)
-    with pytest.raises(RuntimeError, match="use of m0"):
-        chk.check_assembly(clean.replace("\ts_endpgm", "\ts_mov_b32 m0, -1\n\ts_endpgm"))
     with pytest.raises(RuntimeError, match="no stream loop"):
         chk.check_assembly("\ts_endpgm")
 
