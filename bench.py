@@ -1,13 +1,16 @@
-#!/usr/bin/env python3
 """Benchmark of the whole hot path: one step = forest_predict over one batch of synthetic rows.
 
-Prints ONE JSON line.  `value` is rows/s with X already resident in HBM.  The `roofline`
-object prices the dominant (only) kernel against the vector-ALU peak: the method evaluates
-every internal node of every tree for every row, one comparison each, and the packed model
-stays on chip, so the rate of the compare instruction is what bounds it.  The rank kernels
-compare two rows per lane with one packed-f16 instruction, so their peak is two comparisons
-per lane and clock; the fp32 kernels' peak is one.
-`cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded sample.
+Prints ONE JSON line.  With no --workload it measures every configuration: the headline fields
+(`value`, `config`, `roofline`, `cpu_baseline`, `parity`) are those of c5, the largest one, and
+`per_config` holds the same fields for c4, c3, c2 and, as a latency, c1.  `value` is rows/s with
+X already resident in HBM.  The `roofline` object prices the dominant (only) kernel against the
+vector-ALU peak: the method evaluates every internal node of every tree for every row, one
+comparison each, and the packed model stays on chip, so the rate of the compare instruction is
+what bounds it.  The rank kernels compare two rows per lane with one packed-f16 instruction, so
+their peak is two comparisons per lane and clock; the fp32 kernels' peak is one.
+`cpu_baseline` is the CPU oracle timed on this machine's host cores over all rows of the
+configuration (one warm-up pass, median of three timed passes), and `parity` compares every row
+of the timed output with it.
 """
 from __future__ import annotations
 
@@ -27,26 +30,13 @@ if ROOT not in sys.path:
 # compare (v_pk_fma_f16 with clamp on exactly coded ranks) is two comparisons per lane-op.
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 HBM_PEAK = 8.0e12
+ORACLE_THREADS_MAX = 16   # the share of host cores one GPU's job may use on the bench machine
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy kernel of known size); see profiles/.  None until measured for a workload.
+# HBM bytes per launch from rocprofv3 --pmc runs of this script (FETCH_SIZE and WRITE_SIZE, each
+# scaled by what the same counter reads for a plain copy of known size).  Not taken live: every
+# entry names the summary under profiles/ it comes from and the commit whose kernels were
+# measured; a workload without an entry reports null.
 MEASURED_TRAFFIC = {
-    # profiles/forest_rank_kernel_c2.md: FETCH_SIZE 66,233 x 2.000 (copy-kernel scale) KiB read,
-    # WRITE_SIZE 7,812.5 x 1.000 KiB written
-    "c2": 135.6e6 + 8.0e6,
-    # profiles/linear_kernels.md: FETCH_SIZE 703,161 x 2.000 KiB, WRITE_SIZE 15,625 x 1.000 KiB
-    "l2": 1440.0e6 + 16.0e6,
-}
-
-# Busy fractions of the units the forest kernels use, from rocprofv3 --pmc runs of this script
-# (SQ_INSTS_VALU x 4 cycles, SQ_VALU_MFMA_BUSY_CYCLES, SQ_LDS_IDX_ACTIVE over the SIMD / CU cycles
-# of the launch); see the profile named.  They are measurements of the committed kernels, not
-# taken live, and are reported next to the live roofline fraction.
-MEASURED_UNIT_BUSY = {
-    "c2": {"valu_issue": 0.81, "mfma": 0.54, "profile": "profiles/forest_rank_kernel_c2.md"},
-    "c3": {"valu_issue": 0.80, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c4": {"valu_issue": 0.82, "profile": "profiles/forest_rank_kernel_c3_c4.md"},
-    "c5": {"valu_issue": 0.56, "lds": 0.67, "profile": "profiles/forest_ranklds_kernel_c5.md"},
 }
 
 
@@ -102,7 +92,9 @@ def bench_linear(args) -> int:
         "kernel_ms_min": float(np.min(kernel_ms)),
         "algorithmic_bytes": algo_bytes,
         "flops": 2.0 * F * K * n_rows,
-        "traffic": MEASURED_TRAFFIC.get(args.workload),
+        "traffic": (MEASURED_TRAFFIC.get(args.workload) or {}).get("bytes"),
+        "traffic_source": ({k: MEASURED_TRAFFIC[args.workload][k] for k in ("profile", "commit")}
+                           if args.workload in MEASURED_TRAFFIC else None),
     }
     cpu_baseline = None
     parity = None
@@ -145,59 +137,73 @@ def bench_linear(args) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "l1", "l2", "l3", "l4"],
-                    help="c1..c5: tree ensembles (c2 is the headline); l1..l4: linear models")
-    ap.add_argument("--rows", type=int, default=None, help="override the row count (testing)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 "
-              "(rows are independent: more GPUs = shard X by rows, replicate the packed model)",
-              file=sys.stderr)
-        return 2
+def _host_threads() -> int:
+    return max(1, min(os.cpu_count() or 1, ORACLE_THREADS_MAX))
 
+
+def _time_oracle(forest, X, threads: int, passes: int = 3):
+    """One warm-up pass, then `passes` timed passes over all of X; returns (median seconds, result)."""
+    import oracle
+    ref = oracle.predict(forest, X, n_threads=threads)
+    times = []
+    for _ in range(passes):
+        t0 = time.perf_counter()
+        ref = oracle.predict(forest, X, n_threads=threads)
+        times.append(time.perf_counter() - t0)
+    return sorted(times)[len(times) // 2], ref
+
+
+def hbm_copy_rate() -> float:
+    """Bytes moved per second by a plain device-to-device copy of 1 GiB (read + write), the memory
+    system's own rate for a streaming kernel on this machine; reported next to the nominal peak."""
+    import torch
+    n = 1 << 28
+    a = torch.empty(n, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    a.fill_(1.0)
+    for _ in range(2):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(5):
+        b.copy_(a)
+    stop.record()
+    torch.cuda.synchronize()
+    return 5 * 2 * 4.0 * n / (start.elapsed_time(stop) * 1e-3)
+
+
+def bench_forest(name: str, args) -> dict:
+    """All fields of one tree-ensemble configuration."""
     import numpy as np
     import torch
 
     import paper_2301_13441_amd as pk
     import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    torch.cuda.set_device(0)
-    if args.workload.startswith("l"):
-        return bench_linear(args)
-
-    w = wl.make_workload(args.workload, n_rows=args.rows)
+    w = wl.make_workload(name, n_rows=args.rows)
     n_rows, F = w.n_rows, w.forest.n_features
     f = pk.forest_load(w.forest)
     info = f.info
 
-    # X: generated on the host in chunks, copied to HBM before the timed region
+    # X: generated on the host in chunks, copied to HBM before the timed region; the host copy is
+    # kept for the oracle
+    want_host = not args.no_cpu_baseline
     xd = torch.empty((n_rows, F), dtype=torch.float32, device="cuda")
-    sample_rows = min(n_rows, 262144)
-    parts = []
+    xh = np.empty((n_rows, F), dtype=np.float32) if want_host else None
     pos = 0
     for chunk in w.x_chunks(n_rows):
         xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
-        if pos < sample_rows:
-            parts.append(chunk[:max(0, sample_rows - pos)].copy())
+        if want_host:
+            xh[pos:pos + len(chunk)] = chunk
         pos += len(chunk)
-    x_sample = np.concatenate(parts)[:sample_rows]
     out = torch.empty(max(f.out_bytes(n_rows), 4), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
 
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.current_stream()   # forest_predict is enqueued on this stream
     for _ in range(args.warmup):
         f.predict(xd, out=out)
     torch.cuda.synchronize()
-
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     t0 = time.perf_counter()
@@ -209,15 +215,15 @@ def main() -> int:
     wall = time.perf_counter() - t0
     kernel_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
     kernel_s = float(np.mean(kernel_ms)) * 1e-3
-
     scores, labels = f.predict(xd, out=out)
     torch.cuda.synchronize()
 
     compares = float(info["n_internal"]) * n_rows          # one per (row, internal node)
     achieved = compares / kernel_s
     algo_bytes = n_rows * (4.0 * F) + f.out_bytes(n_rows)
-    packed = info["kernel_path"] in (2, 3)  # rank kernels: two comparisons per packed-f16 lane-op
+    packed = info["kernel_path"] in (2, 3, 4)  # rank kernels: two comparisons per packed-f16 lane-op
     peak = ALU_PEAK_LANE_OPS * (2 if packed else 1)
+    traffic = MEASURED_TRAFFIC.get(name) if args.rows is None else None
     roofline = {
         "bound": "alu",
         "kernel": "forest_predict (fused compare + leaf resolution + reduction)",
@@ -234,45 +240,37 @@ def main() -> int:
         "algorithmic_bytes": algo_bytes,
         "hbm_GBps": algo_bytes / kernel_s / 1e9,
         "hbm_frac": algo_bytes / kernel_s / HBM_PEAK,
-        "traffic": MEASURED_TRAFFIC.get(args.workload),
-        "unit_busy_measured": MEASURED_UNIT_BUSY.get(args.workload),
+        "traffic": traffic["bytes"] if traffic else None,
+        "traffic_source": ({k: traffic[k] for k in ("profile", "commit")} if traffic else None),
     }
 
     cpu_baseline = None
     parity = None
-    if not args.no_cpu_baseline:
-        import oracle
-        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
-        t1 = time.perf_counter()
-        ref = oracle.predict(w.forest, x_sample, n_threads=cores)
-        dt = time.perf_counter() - t1
-        cpu_baseline = {"value": sample_rows / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
-                        "sample": f"first {sample_rows} rows of {args.workload}, one pass, "
-                                  f"{cores} threads over contiguous row blocks"}
-        parity = {"rows_checked": sample_rows}
+    if want_host:
+        threads = _host_threads()
+        dt, ref = _time_oracle(w.forest, xh, threads)
+        cpu_baseline = {"value": n_rows / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
+                        "host_cpu_count": os.cpu_count(),
+                        "sample": f"all {n_rows} rows of {name}: one warm-up pass, median of 3 timed passes, "
+                                  f"{threads} threads over contiguous row blocks"}
+        parity = {"rows_checked": n_rows}
         if scores is not None:
-            got = scores[:sample_rows].cpu().numpy()
+            got = scores.cpu().numpy()
             err = np.abs(got - ref.scores)
             parity["scores_within_tol"] = bool((err <= 1e-6 + 1e-5 * np.abs(ref.scores)).all())
             parity["max_abs_err"] = float(err.max())
         if labels is not None:
-            parity["labels_equal"] = bool((labels[:sample_rows].cpu().numpy() == ref.labels).all())
+            parity["labels_equal"] = bool((labels.cpu().numpy() == ref.labels).all())
+        if name == "c1":   # the small configuration also on one thread
+            dt1, _ = _time_oracle(w.forest, xh, 1)
+            cpu_baseline["one_thread_value"] = n_rows / dt1
 
-    line = {
-        "metric": "rows/sec scored (fp32 X), 1 MI355X",
+    res = {
         "value": n_rows * args.steps / wall,
-        "unit": "rows/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
         "dtype": ("f16 threshold ranks (exact rewrite of the f32 compare), f64 accumulate"
-                  if info["kernel_path"] in (2, 3) else "f32 compare, f64 accumulate"),
-        "data": "synthetic (seeded; stands in for YearPrediction and the paper's unstated models)",
-        "config": {"workload": args.workload, "n_rows": n_rows, "n_features": F,
+                  if packed else "f32 compare, f64 accumulate"),
+        "config": {"workload": name, "n_rows": n_rows, "n_features": F,
                    "n_trees": info["n_trees"], "max_depth": info["max_depth"],
                    "n_internal_nodes": info["n_internal"], "n_outputs": info["n_outputs"],
                    "kernel_kind": info["kernel_kind"], "kernel_path": info["kernel_path"],
@@ -281,8 +279,80 @@ def main() -> int:
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
-    print(json.dumps(line))
     f.close()
+    del xd, out, scores, labels
+    torch.cuda.empty_cache()
+    return res
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, choices=["c1", "c2", "c3", "c4", "c5", "l1", "l2", "l3", "l4"],
+                    help="one configuration only (c1..c5: tree ensembles; l1..l4: linear models); "
+                         "default: c5 as the headline and c4, c3, c2, c1 under per_config")
+    ap.add_argument("--rows", type=int, default=None, help="override the row count (testing)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(rows are independent: more GPUs = shard X by rows, replicate the packed model)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.workload is not None and args.workload.startswith("l"):
+        return bench_linear(args)
+
+    names = [args.workload] if args.workload else ["c5", "c4", "c3", "c2", "c1"]
+    results = {}
+    for name in names:
+        print(f"bench: {name} ...", file=sys.stderr, flush=True)
+        results[name] = bench_forest(name, args)
+    head = results[names[0]]
+    line = {
+        "metric": "rows/sec scored (fp32 X), 1 MI355X",
+        "value": head["value"],
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head["dtype"],
+        "data": "synthetic (seeded; stands in for YearPrediction and the paper's unstated models)",
+        "config": head["config"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"],
+        "parity": head["parity"],
+    }
+    if len(names) > 1:
+        per = {}
+        for name in names[1:]:
+            r = results[name]
+            if name == "c1":
+                # 1,000 rows: bound by the launch, so a latency and no roofline claim
+                per[name] = {"latency_us_per_call": r["roofline"]["kernel_ms_avg"] * 1e3,
+                             "latency_us_min": r["roofline"]["kernel_ms_min"] * 1e3,
+                             "value": r["value"], "unit": "rows/s", "config": r["config"],
+                             "cpu_baseline": r["cpu_baseline"], "parity": r["parity"]}
+            else:
+                per[name] = {k: r[k] for k in ("value", "ms_per_step", "dtype", "config", "roofline",
+                                               "cpu_baseline", "parity")}
+                per[name]["unit"] = "rows/s"
+        line["per_config"] = per
+        line["measured_peaks"] = {"hbm_copy_GBps": hbm_copy_rate() / 1e9,
+                                  "note": "device-to-device copy of 1 GiB, bytes read + written"}
+    print(json.dumps(line))
     return 0
 
 

@@ -503,51 +503,59 @@ def test_duplicate_thresholds_and_unused_features():
 
 # ----------------------------------------------------------------------------- full-size runs
 
-def _full_size(name, leaf_rows=4096):
-    """The bench's launch configuration (full row count, device-resident X); outputs of the
-    first 65 536 rows and of 65 536 seeded random rows are compared with the oracle."""
+def _full_size(name):
+    """The bench's launch configuration (full row count, device-resident X): scores and labels of
+    EVERY row are compared with the oracle, and the leaf ids of every tree on the first 65 536
+    rows plus 65 536 seeded random rows.  X is drawn chunk by chunk; each chunk goes to the device
+    and through the oracle, so the host never holds more than one chunk and the sampled rows."""
+    import os
     import torch
     import paper_2301_13441_amd as pk
     w = wl.make_workload(name)
-    n, F = w.n_rows, w.forest.n_features
+    n, F, K = w.n_rows, w.forest.n_features, w.forest.n_outputs
+    threads = max(1, min(os.cpu_count() or 1, 16))
     rng = np.random.default_rng(wl.SEEDS[name] + 7)
     n_head = min(n, 65536)
     pick = np.unique(np.concatenate([np.arange(n_head), rng.integers(0, n, size=65536)]))
     xd = torch.empty((n, F), dtype=torch.float32, device="cuda")
     xs = np.empty((len(pick), F), dtype=np.float32)
+    ref_scores = np.empty((n, K), dtype=np.float32)
+    ref_labels = np.empty((n,), dtype=np.int32)
     pos = 0
     for chunk in w.x_chunks(n):
         xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
         sel = pick[(pick >= pos) & (pick < pos + len(chunk))]
         xs[np.searchsorted(pick, sel)] = chunk[sel - pos]
+        ref = oracle.predict(w.forest, chunk, n_threads=threads)
+        ref_scores[pos:pos + len(chunk)] = ref.scores
+        ref_labels[pos:pos + len(chunk)] = ref.labels
         pos += len(chunk)
     f = pk.forest_load(w.forest)
     try:
         scores, labels = f.predict(xd)
         torch.cuda.synchronize()
-        idx = torch.from_numpy(pick).cuda()
-        got_scores = None if scores is None else scores[idx].cpu().numpy()
-        got_labels = None if labels is None else labels[idx].cpu().numpy()
-        # leaf ids: every tree, on the first rows of the sample (through the same kernels)
-        lv = f.predict_leaves(xd[:n_head])
+        got_scores = None if scores is None else scores.cpu().numpy()
+        got_labels = None if labels is None else labels.cpu().numpy()
+        # leaf ids: every tree, on the sampled rows (a batch large enough to run the same kernels)
+        lv = f.predict_leaves(xd[torch.from_numpy(pick).cuda()].contiguous())
         torch.cuda.synchronize()
-        got_leaves = lv[:leaf_rows].cpu().numpy()
+        got_leaves = lv.cpu().numpy()
         info = f.info
     finally:
         f.close()
-    ref = oracle.predict(w.forest, xs, n_threads=16)
-    ref_leaves = oracle.predict(w.forest, xs[:leaf_rows], want_leaves=True, n_threads=16).leaf_node_id
-    assert (pick[:leaf_rows] == np.arange(leaf_rows)).all()
-    np.testing.assert_array_equal(got_leaves, ref_leaves)
+    assert len(pick) >= info["small_batch_rows"]
     if got_labels is not None:
-        np.testing.assert_array_equal(got_labels, ref.labels)
+        np.testing.assert_array_equal(got_labels, ref_labels)
     if got_scores is not None:
-        np.testing.assert_allclose(got_scores, ref.scores, rtol=RTOL, atol=ATOL)
+        np.testing.assert_allclose(got_scores, ref_scores, rtol=RTOL, atol=ATOL)
+    del got_scores, got_labels, ref_scores, ref_labels
+    ref_leaves = oracle.predict(w.forest, xs, want_leaves=True, n_threads=threads).leaf_node_id
+    np.testing.assert_array_equal(got_leaves, ref_leaves)
     return info
 
 
 @pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
-def test_full_size_sampled(name):
+def test_full_size_all_rows(name):
     info = _full_size(name)
     assert info["n_trees"] == {"c2": 500, "c3": 1000, "c4": 2000, "c5": 128}[name]
 
