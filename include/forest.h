@@ -22,7 +22,7 @@
 extern "C" {
 #endif
 
-typedef struct forest forest; /* opaque, immutable after forest_load */
+typedef struct forest forest; /* opaque; the model in it is immutable after forest_load */
 
 enum { FOREST_AGG_SUM = 0, FOREST_AGG_MEAN = 1 };
 enum { FOREST_TRANSFORM_NONE = 0, FOREST_TRANSFORM_SIGMOID = 1, FOREST_TRANSFORM_SOFTMAX = 2 };
@@ -96,9 +96,9 @@ typedef struct forest_info_t {
                                    2: packed f16 threshold-rank registers;
                                    3: packed f16 threshold ranks in LDS (any tree shape) */
     int32_t rows_per_workgroup; /* rows one workgroup owns */
-    int64_t workspace_bytes;    /* device workspace the handle owns besides the packed model */
+    int64_t workspace_bytes;    /* device workspaces (all of them) the handle owns besides the packed model */
     int64_t small_batch_rows;   /* batches below this many rows also cut the trees into shares
-                                   (more workgroups for few rows) and use the workspace */
+                                   (more workgroups for few rows) and use a workspace */
     int32_t workgroup_waves;    /* wavefronts per workgroup of the kernel the model runs */
 } forest_info_t;
 
@@ -138,10 +138,12 @@ int forest_out_layout(const forest *f, int64_t n_rows, int64_t *scores_offset, i
  * successful no-op.  The caller keeps X and out alive until the stream has run the work.
  * Allocates nothing.
  * Small batches (the latency regime of Table 6): below forest_info_t.small_batch_rows rows the
- * trees are cut into shares that run in separate workgroups, their fp64 partial sums meet in
- * the handle's workspace and a second kernel on the same stream finishes the rows.  Such calls
- * on ONE handle must not overlap in time (same stream, or ordered by events); larger batches
- * touch no shared state and may run concurrently from different streams.
+ * trees are cut into shares that run in separate workgroups, their fp64 partial sums meet in a
+ * workspace the handle owns and a second kernel on the same stream finishes the rows.  The handle
+ * owns several such workspaces and gives every stream its own (a stream under graph capture gets
+ * one for that capture), so calls on one handle may run concurrently from different streams
+ * whatever their batch size; a caller that finds every workspace taken by other streams runs its
+ * small batch unsplit, with the same result.
  */
 int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream);
 

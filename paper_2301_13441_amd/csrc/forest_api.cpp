@@ -10,13 +10,30 @@
 
 using namespace forest_impl;
 
+// Small batches cut the trees into shares whose partial sums meet in a workspace.  A handle owns
+// WS_SLOTS workspaces.  Work on one stream is ordered, so a stream keeps the slot it was given;
+// a stream under graph capture gets a slot for that capture (the graph may be replayed on any
+// stream later).  Slots are never handed back before forest_free; a caller that finds none free
+// runs its small batch unsplit, which needs no workspace.  So calls on one handle never share
+// memory unless they are ordered by their stream, whatever the batch size.
+constexpr int WS_SLOTS = 4;
+
+struct SlotOwner {
+    bool used = false;
+    bool capture = false;            // key is a capture sequence id, else a stream handle
+    unsigned long long key = 0;
+};
+
 struct forest {
     PackedModel host;  // tables kept for forest_info; large arrays are released after upload
     DevModel dev{};
-    void *blob = nullptr;  // one device allocation holding every table
+    void *blob = nullptr;  // one device allocation holding every table and the workspaces
     int64_t blob_bytes = 0;       // packed model
-    int64_t workspace_bytes = 0;  // partial sums of split launches, same allocation
+    int64_t workspace_bytes = 0;  // all slots, same allocation
     int device = 0;
+    Workspace slot[WS_SLOTS];
+    mutable std::mutex slot_mutex;
+    mutable SlotOwner owner[WS_SLOTS];
 };
 
 namespace {
@@ -53,6 +70,34 @@ int check_out_args(const forest *f, int64_t n_rows)
     if (!f || n_rows < 0) return FOREST_EINVAL;
     if (n_rows > FOREST_MAX_ROWS) return FOREST_ELIMIT;
     return FOREST_OK;
+}
+
+// The workspace slot of the caller's stream (or of the graph capture the stream is in), claiming
+// a free one the first time; null when every slot belongs to someone else.
+const Workspace *claim_slot(const forest *f, hipStream_t stream)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    unsigned long long id = 0;
+    if (hipStreamGetCaptureInfo(stream, &status, &id) != hipSuccess) {
+        (void)hipGetLastError();
+        status = hipStreamCaptureStatusNone;
+    }
+    const bool capture = status == hipStreamCaptureStatusActive;
+    const unsigned long long key = capture ? id : static_cast<unsigned long long>(reinterpret_cast<uintptr_t>(stream));
+    std::lock_guard<std::mutex> lock(f->slot_mutex);
+    for (int i = 0; i < WS_SLOTS; ++i)
+        if (f->owner[i].used && f->owner[i].capture == capture && f->owner[i].key == key) return &f->slot[i];
+    for (int i = 0; i < WS_SLOTS; ++i)
+        if (!f->owner[i].used) {
+            f->owner[i] = SlotOwner{true, capture, key};
+            return &f->slot[i];
+        }
+    return nullptr;
+}
+
+bool small_batch(const forest *f, int64_t n_rows)
+{
+    return n_rows < SPLIT_BELOW_BLOCKS * static_cast<int64_t>(family_rows_per_block(f->dev));
 }
 
 // The handle's tables live on the device it was loaded on.
@@ -111,11 +156,13 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_fbk = place<FeatBucket>(cur, m.feat_bucket.size());
     const size_t o_bst = place<int32_t>(cur, m.bucket_start.size());
     const size_t model_bytes = (cur + 255) & ~size_t{255};
-    const size_t n_partial = static_cast<size_t>(split_workspace_doubles(m.n_outputs));
-    const size_t o_part = place<double>(cur, n_partial);  // workspace of split launches, not uploaded
+    // workspaces of split launches, not uploaded
     const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
-    const size_t n_rank_words = ranks ? static_cast<size_t>(SPLIT_BELOW_BLOCKS) * m.rank_regs * 64 : 0;
-    const size_t o_rtile = place<uint32_t>(cur, n_rank_words);
+    const size_t slot_bytes = full_workspace_bytes(ranks ? m.rank_regs : 0, m.n_outputs);
+    size_t o_slot[WS_SLOTS];
+    for (int i = 0; i < WS_SLOTS; ++i) {
+        o_slot[i] = place<char>(cur, slot_bytes);
+    }
     cur = (cur + 255) & ~size_t{255};
     if (hipMalloc(&f->blob, cur) != hipSuccess) {
         (void)hipGetLastError();
@@ -179,9 +226,10 @@ int forest_load(const forest_desc *desc, forest **out)
     d.n_splits = 1;
     d.n_entries = static_cast<int64_t>(m.prog32.size() > m.prog.size() ? m.prog32.size() : m.prog.size());
     d.split_rows = 0;
-    d.partial = reinterpret_cast<double *>(b + o_part);
-    d.partial_capacity = static_cast<int64_t>(n_partial);
-    d.rank_tiles = reinterpret_cast<uint32_t *>(b + o_rtile);
+    d.partial = nullptr;  // set per launch from the workspace in use
+    d.partial_capacity = 0;
+    d.rank_tiles = nullptr;
+    for (int i = 0; i < WS_SLOTS; ++i) f->slot[i] = carve_workspace(d, b + o_slot[i], slot_bytes, SPLIT_BELOW_BLOCKS);
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
     m.prog32 = {};
@@ -253,7 +301,10 @@ int64_t forest_out_bytes(const forest *f, int64_t n_rows)
     }
 }
 
-int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream)
+namespace {
+
+// forest_predict: argument checks, output layout, launch.
+int predict_with(const forest *f, const float *X, int64_t n_rows, void *out, hipStream_t stream)
 {
     if (int rc = check_out_args(f, n_rows)) return rc;
     if (n_rows == 0) return FOREST_OK;
@@ -264,9 +315,16 @@ int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, v
     char *o = static_cast<char *>(out);
     float *scores = so >= 0 ? reinterpret_cast<float *>(o + so) : nullptr;
     int32_t *labels = lo >= 0 ? reinterpret_cast<int32_t *>(o + lo) : nullptr;
-    const hipError_t e = launch_predict(f->dev, X, n_rows, scores, labels, nullptr,
-                                        static_cast<hipStream_t>(stream));
+    const Workspace *ws = small_batch(f, n_rows) ? claim_slot(f, stream) : nullptr;
+    const hipError_t e = launch_predict(f->dev, ws, false, X, n_rows, scores, labels, nullptr, stream);
     return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
+}
+
+}  // namespace
+
+int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream)
+{
+    return predict_with(f, X, n_rows, out, static_cast<hipStream_t>(stream));
 }
 
 int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32_t *leaf_node_id,
@@ -276,8 +334,9 @@ int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32
     if (n_rows == 0 || f->host.n_trees == 0) return FOREST_OK;
     if (!X || !leaf_node_id) return FOREST_EINVAL;
     if (int rc = check_device(f)) return rc;
-    const hipError_t e = launch_predict(f->dev, X, n_rows, nullptr, nullptr, leaf_node_id,
-                                        static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Workspace *ws = small_batch(f, n_rows) ? claim_slot(f, st) : nullptr;
+    const hipError_t e = launch_predict(f->dev, ws, false, X, n_rows, nullptr, nullptr, leaf_node_id, st);
     return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
 }
 

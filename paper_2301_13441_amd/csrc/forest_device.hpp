@@ -54,13 +54,30 @@ constexpr int64_t SPLIT_MIN_ENTRIES_PER_WAVE = 512;
 // Rows one workgroup of the model's kernel family owns, and its number of wavefronts.
 int family_rows_per_block(const DevModel &m);
 int family_waves_per_block(const DevModel &m);
-// Doubles of workspace a handle needs so that no split launch is limited by it (capped).
-int64_t split_workspace_doubles(int n_outputs);
+
+// Device memory a split launch (small batch) needs besides the inputs and outputs: the tree
+// shares' fp64 partial sums and, for the rank families, the rank tiles of the batch.
+struct Workspace {
+    double *partial = nullptr;
+    int64_t partial_doubles = 0;
+    uint32_t *rank_tiles = nullptr;
+    int64_t rank_tile_words = 0;
+};
+
+// Lays a workspace out in `bytes` bytes at `base` (256-byte aligned): the rank tiles first, sized
+// for `tiles` row tiles of the model, the partial sums in the rest.
+Workspace carve_workspace(const DevModel &m, void *base, size_t bytes, int64_t tiles);
+
+// Bytes of a workspace that never limits a split launch of the model.
+size_t full_workspace_bytes(int rank_regs, int n_outputs);
 
 // Enqueues one pass over `n_rows` rows on `stream`.  `scores` / `labels` / `leaf_out` may be
-// null (that part is not written).  Returns the launch error, if any.
-hipError_t launch_predict(const DevModel &m, const float *X, int64_t n_rows, float *scores,
-                          int32_t *labels, int32_t *leaf_out, hipStream_t stream);
+// null (that part is not written).  `ws` is the workspace a small batch may use (null: the trees
+// are never cut into shares).  With `must_fit`, a small batch whose split launch does not fit
+// `ws` is refused with hipErrorMemoryAllocation instead of being run unsplit.  Returns the launch
+// error, if any.
+hipError_t launch_predict(const DevModel &m, const Workspace *ws, bool must_fit, const float *X, int64_t n_rows,
+                          float *scores, int32_t *labels, int32_t *leaf_out, hipStream_t stream);
 
 // Register-resident family (forest_kernels_reg.hip).
 hipError_t init_reg_kernels(size_t lds_limit);

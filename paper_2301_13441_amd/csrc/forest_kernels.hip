@@ -244,7 +244,7 @@ int family_rows_per_block(const DevModel &m)
 
 int family_waves_per_block(const DevModel &m) { return m.path == PATH_RANK_LDS ? m.lds_waves : WAVES; }
 
-int64_t split_workspace_doubles(int n_outputs)
+static int64_t split_workspace_doubles(int n_outputs)
 {
     // splits x rows stays below (SPLIT_TARGET_BLOCKS + SPLIT_BELOW_BLOCKS) workgroups x 128 rows
     const int64_t want = (SPLIT_TARGET_BLOCKS + SPLIT_BELOW_BLOCKS) * 128 * n_outputs;
@@ -252,11 +252,37 @@ int64_t split_workspace_doubles(int n_outputs)
     return want < cap ? want : cap;
 }
 
+static size_t rank_tile_bytes(int rank_regs, int64_t tiles)
+{
+    const size_t b = sizeof(uint32_t) * 64 * static_cast<size_t>(rank_regs > 0 ? rank_regs : 0) * static_cast<size_t>(tiles);
+    return (b + 255) & ~size_t{255};
+}
+
+size_t full_workspace_bytes(int rank_regs, int n_outputs)
+{
+    return rank_tile_bytes(rank_regs, SPLIT_BELOW_BLOCKS) + sizeof(double) * static_cast<size_t>(split_workspace_doubles(n_outputs));
+}
+
+Workspace carve_workspace(const DevModel &m, void *base, size_t bytes, int64_t tiles)
+{
+    Workspace ws;
+    const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
+    const size_t tile_bytes = ranks ? rank_tile_bytes(m.rank_regs, tiles) : 0;
+    if (!base || tile_bytes > bytes) return ws;  // nothing fits: every launch stays unsplit
+    ws.rank_tiles = static_cast<uint32_t *>(base);
+    ws.rank_tile_words = static_cast<int64_t>(tile_bytes / sizeof(uint32_t));
+    ws.partial = reinterpret_cast<double *>(static_cast<char *>(base) + tile_bytes);
+    ws.partial_doubles = static_cast<int64_t>((bytes - tile_bytes) / sizeof(double));
+    return ws;
+}
+
 namespace {
 
-// How many shares the trees are cut into for a batch of n_rows rows (1 = no split).
-int choose_splits(const DevModel &m, int64_t n_rows, bool needs_workspace)
+// How many shares the trees are cut into for a batch of n_rows rows (1 = no split); `fits`
+// tells whether the workspace allowed the split the batch asks for.
+int choose_splits(const DevModel &m, const Workspace *ws, int64_t n_rows, bool needs_sums, bool &fits)
 {
+    fits = true;
     const int64_t rb = family_rows_per_block(m);
     const int64_t n_blocks = (n_rows + rb - 1) / rb;
     if (n_blocks >= SPLIT_BELOW_BLOCKS) return 1;
@@ -265,11 +291,22 @@ int choose_splits(const DevModel &m, int64_t n_rows, bool needs_workspace)
     int64_t s = m.n_trees / (family_waves_per_block(m) * (trees_per_wave > 0 ? trees_per_wave : 1));
     const int64_t by_grid = (SPLIT_TARGET_BLOCKS + n_blocks - 1) / n_blocks;
     if (by_grid < s) s = by_grid;
-    if (needs_workspace) {
-        const int64_t by_ws = m.partial_capacity / (n_rows * m.n_outputs);
-        if (by_ws < s) s = by_ws;
+    if (s < 2) return 1;  // the model is too small to be worth cutting
+    const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
+    const int64_t tile_words = ranks ? n_blocks * m.rank_regs * 64 : 0;
+    if (tile_words > (ws ? ws->rank_tile_words : 0)) {
+        fits = false;
+        return 1;
     }
-    return s < 2 ? 1 : static_cast<int>(s);
+    if (needs_sums) {
+        const int64_t by_ws = (ws ? ws->partial_doubles : 0) / (n_rows * m.n_outputs);
+        if (by_ws < s) s = by_ws;
+        if (s < 2) {
+            fits = false;
+            return 1;
+        }
+    }
+    return static_cast<int>(s);
 }
 
 }  // namespace
@@ -292,16 +329,21 @@ static hipError_t launch_family(const DevModel &m, const float *X, int64_t n_row
     return hipGetLastError();
 }
 
-hipError_t launch_predict(const DevModel &model, const float *X, int64_t n_rows, float *scores,
-                          int32_t *labels, int32_t *leaf_out, hipStream_t stream)
+hipError_t launch_predict(const DevModel &model, const Workspace *ws, bool must_fit, const float *X, int64_t n_rows,
+                          float *scores, int32_t *labels, int32_t *leaf_out, hipStream_t stream)
 {
     if (n_rows <= 0) return hipSuccess;
     // Small batches: too few row tiles to fill the chip, so the trees are cut into shares as
     // well (grid y) and a second kernel sums the shares.  The leaf-id output needs no sums.
     DevModel m = model;
     const bool sums = leaf_out == nullptr;
-    m.n_splits = choose_splits(m, n_rows, sums);
+    bool fits = true;
+    m.n_splits = choose_splits(m, ws, n_rows, sums, fits);
+    if (!fits && must_fit) return hipErrorMemoryAllocation;
     m.split_rows = n_rows;
+    m.partial = ws ? ws->partial : nullptr;
+    m.partial_capacity = ws ? ws->partial_doubles : 0;
+    m.rank_tiles = ws ? ws->rank_tiles : nullptr;
     if (m.n_splits > 1 && (m.path == PATH_RANK || m.path == PATH_RANK_LDS)) {
         const hipError_t e = launch_rank_tiles(m, X, n_rows, stream);
         if (e != hipSuccess) return e;

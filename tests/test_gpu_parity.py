@@ -237,6 +237,36 @@ def test_predict_replays_from_a_captured_graph(rows):
         f.close()
 
 
+@pytest.mark.parametrize("n_streams", [2, 6])   # within the handle's workspaces, and more streams than it has
+def test_small_batches_from_several_streams_on_one_handle(n_streams):
+    """Calls on one handle from different streams may overlap whatever the batch size: every
+    stream gets a workspace of its own, and a stream that finds none left runs unsplit."""
+    import torch
+    import paper_2301_13441_amd as pk
+    w = wl.make_workload("c2", n_rows=1, n_trees=200)
+    F = w.forest.n_features
+    f = pk.forest_load(w.forest)
+    try:
+        rng = np.random.default_rng(n_streams)
+        streams = [torch.cuda.Stream() for _ in range(n_streams)]
+        rows = [int(r) for r in rng.integers(1, 3000, size=n_streams)]
+        xs = [rng.standard_normal((r, F)).astype(np.float32) for r in rows]
+        xd = [torch.from_numpy(x).cuda() for x in xs]
+        outs = [torch.zeros(max(f.out_bytes(r), 4), dtype=torch.uint8, device="cuda") for r in rows]
+        torch.cuda.synchronize()
+        got = [None] * n_streams
+        for rep in range(20):                     # many calls in flight on every stream
+            for i, st in enumerate(streams):
+                got[i] = f.predict(xd[i], out=outs[i], stream=st)
+        torch.cuda.synchronize()
+        for i in range(n_streams):
+            ref = oracle.predict(w.forest, xs[i], n_threads=8)
+            np.testing.assert_array_equal(got[i][1].cpu().numpy(), ref.labels)
+            np.testing.assert_allclose(got[i][0].cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        f.close()
+
+
 def test_hand_off_from_torch_ops_on_the_same_stream():
     """Hybrid use (Section 4.5): the features are the output of tensor ops on the device and
     the forest consumes them on the same stream, without a host round trip in between."""
