@@ -148,6 +148,22 @@ int forest_out_layout(const forest *f, int64_t n_rows, int64_t *scores_offset, i
 int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream);
 
 /*
+ * forest_predict for callers that cannot allocate and must not depend on memory a handle
+ * allocated: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results.  The workspace of a small batch is not the handle's but a static
+ * array of FOREST_STATIC_SCRATCH_BYTES in the library's device image (every GPU the library runs
+ * on holds one until the process ends); the call allocates and frees nothing.  A small batch
+ * whose rank tiles (ceil(n_rows / 128) * rank registers * 256 bytes for the rank kernels) and at
+ * least two shares of partial sums (n_rows * n_outputs * 8 bytes each) do not fit the array is
+ * refused with FOREST_ELIMIT; batches of forest_info_t.small_batch_rows rows or more use no
+ * workspace and always run.  Every call on a GPU shares that GPU's array, whatever the handle:
+ * calls that overlap in time on one GPU race; order them on one stream or with events.  Nothing
+ * in the array needs clearing between calls (every word a call reads it has written itself).
+ */
+#define FOREST_STATIC_SCRATCH_BYTES (8u << 20)
+int forest_predict_static(const forest *f, const float *X, int64_t n_rows, void *out, void *stream);
+
+/*
  * Output of Table 2 ("the leaf node each sample reaches"), for tests and debugging:
  * leaf_node_id is a DEVICE pointer to int32 [n_rows * n_trees]; entry (r, t) receives the
  * caller's tree-local node index of the leaf row r reaches in tree t.

@@ -51,7 +51,7 @@ class _View(ctypes.Structure):
 
 # include/forest.h: the inference ABI
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
-           "forest_predict", "forest_predict_leaves", "forest_strerror"]
+           "forest_predict", "forest_predict_static", "forest_predict_leaves", "forest_strerror"]
 # include/forest_testing.h: host-only views into the model compiler, for its tests
 TESTING_EXPORTS = ["forest_pack", "forest_pack_view", "forest_pack_free", "forest_rank_code"]
 
@@ -82,6 +82,8 @@ def load_library():
     lib.forest_out_layout.argtypes = [_p, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
     lib.forest_predict.restype = ctypes.c_int
     lib.forest_predict.argtypes = [_p, _p, _i64, _p, _p]
+    lib.forest_predict_static.restype = ctypes.c_int
+    lib.forest_predict_static.argtypes = [_p, _p, _i64, _p, _p]
     lib.forest_predict_leaves.restype = ctypes.c_int
     lib.forest_predict_leaves.argtypes = [_p, _p, _i64, _p, _p]
     lib.forest_pack.restype = ctypes.c_int
@@ -252,15 +254,17 @@ class Forest:
             raise ForestError(rc, "forest_out_layout")
         return so.value, lo.value
 
-    def predict_raw(self, x_ptr: int, n_rows: int, out_ptr: int, stream: int = 0) -> None:
-        """forest_predict on raw device pointers."""
-        rc = self._lib.forest_predict(self._h, _p(x_ptr), n_rows, _p(out_ptr), _p(stream))
+    def predict_raw(self, x_ptr: int, n_rows: int, out_ptr: int, stream: int = 0, static: bool = False) -> None:
+        """forest_predict (static: forest_predict_static) on raw device pointers."""
+        fn = self._lib.forest_predict_static if static else self._lib.forest_predict
+        rc = fn(self._h, _p(x_ptr), n_rows, _p(out_ptr), _p(stream))
         if rc != 0:
-            raise ForestError(rc, "forest_predict")
+            raise ForestError(rc, "forest_predict_static" if static else "forest_predict")
 
-    def predict(self, X, out=None, stream=None):
+    def predict(self, X, out=None, stream=None, static: bool = False):
         """X: torch float32 CUDA tensor [n_rows, F], contiguous.  Returns (scores, labels) views
-        into one uint8 output buffer (either may be None, per the model's output kind)."""
+        into one uint8 output buffer (either may be None, per the model's output kind).  With
+        `static` the call goes through forest_predict_static (pass `out`: it allocates nothing)."""
         import torch
         _check_x(X, self.n_features)
         n = X.shape[0]
@@ -271,7 +275,7 @@ class Forest:
                 and out.numel() * out.element_size() >= nbytes):
             raise ValueError(f"out must be a contiguous tensor of at least {nbytes} bytes on {X.device}")
         s = torch.cuda.current_stream(X.device) if stream is None else stream
-        self.predict_raw(X.data_ptr(), n, out.data_ptr(), s.cuda_stream)
+        self.predict_raw(X.data_ptr(), n, out.data_ptr(), s.cuda_stream, static=static)
         so, lo = self.out_layout(n)
         flat = out.view(torch.uint8).reshape(-1)
         scores = labels = None

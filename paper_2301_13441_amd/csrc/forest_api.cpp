@@ -303,8 +303,8 @@ int64_t forest_out_bytes(const forest *f, int64_t n_rows)
 
 namespace {
 
-// forest_predict: argument checks, output layout, launch.
-int predict_with(const forest *f, const float *X, int64_t n_rows, void *out, hipStream_t stream)
+// forest_predict and forest_predict_static: argument checks, output layout, launch.
+int predict_with(const forest *f, const float *X, int64_t n_rows, void *out, hipStream_t stream, bool use_static)
 {
     if (int rc = check_out_args(f, n_rows)) return rc;
     if (n_rows == 0) return FOREST_OK;
@@ -315,8 +315,18 @@ int predict_with(const forest *f, const float *X, int64_t n_rows, void *out, hip
     char *o = static_cast<char *>(out);
     float *scores = so >= 0 ? reinterpret_cast<float *>(o + so) : nullptr;
     int32_t *labels = lo >= 0 ? reinterpret_cast<int32_t *>(o + lo) : nullptr;
-    const Workspace *ws = small_batch(f, n_rows) ? claim_slot(f, stream) : nullptr;
-    const hipError_t e = launch_predict(f->dev, ws, false, X, n_rows, scores, labels, nullptr, stream);
+    hipError_t e;
+    if (use_static) {
+        // the whole array is this call's workspace, sized for the batch at hand
+        const int64_t rb = family_rows_per_block(f->dev);
+        const Workspace ws = carve_workspace(f->dev, static_scratch(f->device), static_scratch_bytes(),
+                                             (n_rows + rb - 1) / rb);
+        e = launch_predict(f->dev, &ws, true, X, n_rows, scores, labels, nullptr, stream);
+        if (e == hipErrorMemoryAllocation) return FOREST_ELIMIT;
+    } else {
+        const Workspace *ws = small_batch(f, n_rows) ? claim_slot(f, stream) : nullptr;
+        e = launch_predict(f->dev, ws, false, X, n_rows, scores, labels, nullptr, stream);
+    }
     return e == hipSuccess ? FOREST_OK : FOREST_EHIP;
 }
 
@@ -324,7 +334,12 @@ int predict_with(const forest *f, const float *X, int64_t n_rows, void *out, hip
 
 int forest_predict(const forest *f, const float *X, int64_t n_rows, void *out, void *stream)
 {
-    return predict_with(f, X, n_rows, out, static_cast<hipStream_t>(stream));
+    return predict_with(f, X, n_rows, out, static_cast<hipStream_t>(stream), false);
+}
+
+int forest_predict_static(const forest *f, const float *X, int64_t n_rows, void *out, void *stream)
+{
+    return predict_with(f, X, n_rows, out, static_cast<hipStream_t>(stream), true);
 }
 
 int forest_predict_leaves(const forest *f, const float *X, int64_t n_rows, int32_t *leaf_node_id,

@@ -79,6 +79,11 @@ size_t full_workspace_bytes(int rank_regs, int n_outputs);
 hipError_t launch_predict(const DevModel &m, const Workspace *ws, bool must_fit, const float *X, int64_t n_rows,
                           float *scores, int32_t *labels, int32_t *leaf_out, hipStream_t stream);
 
+// The calling device's copy of the library's static scratch array (set up by init_kernels), and
+// its size in bytes; null before init_kernels has run on the device.
+void *static_scratch(int device);
+size_t static_scratch_bytes();
+
 // Register-resident family (forest_kernels_reg.hip).
 hipError_t init_reg_kernels(size_t lds_limit);
 hipError_t launch_reg(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,

@@ -208,6 +208,22 @@ KernelFn pick(int kind, bool leaves, bool staged)
 
 }  // namespace
 
+// Scratch for callers that cannot allocate (forest_predict_static): one array per GPU the library
+// runs on, held until the process ends.  Host code never passes the array's name to a kernel --
+// on the host it is only a stand-in for the symbol -- but the device address looked up once per
+// device in init_kernels.
+constexpr size_t STATIC_SCRATCH_BYTES = FOREST_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int SCRATCH_MAX_DEVICES = 64;
+static void *g_scratch_ptr[SCRATCH_MAX_DEVICES] = {};
+
+void *static_scratch(int device)
+{
+    return device >= 0 && device < SCRATCH_MAX_DEVICES ? g_scratch_ptr[device] : nullptr;
+}
+
+size_t static_scratch_bytes() { return STATIC_SCRATCH_BYTES; }
+
 bool model_fits(const PackedModel &m)
 {
     if (m.path != PATH_LDS) return true;  // their LDS need is bounded at pack time
@@ -222,6 +238,12 @@ hipError_t init_kernels()
     e0 = hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
     if (e0 != hipSuccess) return e0;
     g_lds_limit = static_cast<size_t>(per_block) < LDS_LIMIT ? static_cast<size_t>(per_block) : LDS_LIMIT;
+    // this device's copy of the static scratch array (each GPU holds its own, at its own address)
+    if (dev < 0 || dev >= SCRATCH_MAX_DEVICES) return hipErrorInvalidDevice;
+    void *scratch_ptr = nullptr;
+    e0 = hipGetSymbolAddress(&scratch_ptr, HIP_SYMBOL(scratch));
+    if (e0 != hipSuccess) return e0;
+    g_scratch_ptr[dev] = scratch_ptr;
     for (int kind = 0; kind <= FULL_MAX_DEPTH; ++kind)
         for (int leaves = 0; leaves < 2; ++leaves)
             for (int staged = 0; staged < 2; ++staged) {
