@@ -100,6 +100,9 @@ typedef struct forest_info_t {
     int64_t small_batch_rows;   /* batches below this many rows also cut the trees into shares
                                    (more workgroups for few rows) and use a workspace */
     int32_t workgroup_waves;    /* wavefronts per workgroup of the kernel the model runs */
+    int32_t rank_banks;         /* kernel_path 3: 1 if batches of small_batch_rows rows or more run the
+                                   register-bank kernel (rank registers dealt to the wavefronts of a
+                                   workgroup, whole trees evaluated before the walk) */
 } forest_info_t;
 
 /*

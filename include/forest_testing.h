@@ -60,6 +60,33 @@ typedef struct forest_packed_view {
     int32_t workgroup_waves;
     const int32_t *wave_tree;
     const int32_t *program_groups; /* [n_trees] */
+    /* kernel_path 3, models whose large batches run the register-bank kernel (else bank_batches
+     * is 0 and the pointers NULL).  The rank registers are dealt to bank_waves wavefronts,
+     * bank_regs each (bank_reg[w * bank_regs + i] = rank register behind register i of wave w);
+     * the trees are taken up to bank_trees at a time (a batch, processing order).  In batch b wave
+     * w evaluates bank_span[2 * (b * bank_waves + w)] units of bank_unit entries from its stream,
+     * which starts at bank_prog[bank_stream_base[w]] and runs on from batch to batch; a unit's bits
+     * go to unit bank_span[2 * (b * bank_waves + w) + 1] + (index of the unit) of the batch's bit
+     * buffer, entry k of a unit to bit 8 * (k / 8) + 7 - k % 8.  An entry is (f16 bits of the
+     * threshold's code << 16) | register index inside the bank.  Slot = bank_unit * unit + bit.
+     * bank_batch[4 * b] .. + 2: first entry of batch b in bank_child, its number of slots, and the
+     * index of its first leaf in leaf_node / leaf_value of the processing order.
+     * bank_child[first entry + slot] = left reference | right reference << 16 of the node in that
+     * slot; a 16-bit reference is a slot of the same batch (bit 15 clear) or a leaf (bit 15 set, the
+     * low 15 bits its index from the batch's first leaf).  bank_tree[4 * (b * bank_trees + j)] .. + 3:
+     * root reference, output column, caller's tree index, 1 (0 for the records that pad a batch of
+     * fewer trees). */
+    int32_t bank_batches, bank_waves, bank_regs, bank_trees, bank_unit, bank_max_units;
+    int64_t bank_prog_entries;
+    const uint32_t *bank_prog;
+    const int32_t *bank_stream_base; /* [bank_waves] */
+    const int32_t *bank_span;        /* [bank_batches * bank_waves * 2] */
+    const uint32_t *bank_child;      /* [slots of all batches] */
+    const int32_t *bank_batch;       /* [bank_batches * 4] */
+    const int32_t *bank_tree;        /* [bank_batches * bank_trees * 4] */
+    const int32_t *bank_reg;         /* [bank_waves * bank_regs] */
+    const int32_t *order_leaf_node;  /* [sum N_L] caller's node index of each leaf, processing order */
+    const int32_t *order_leaf_tree;  /* [sum N_L] caller's tree index of each leaf, processing order */
 } forest_packed_view;
 
 typedef struct forest_packed forest_packed;

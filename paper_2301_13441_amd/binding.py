@@ -36,7 +36,7 @@ class _Info(ctypes.Structure):
     _fields_ = [("n_trees", _i32), ("n_features", _i32), ("n_outputs", _i32), ("leaf_width", _i32),
                 ("n_internal", _i64), ("n_leaves", _i64), ("max_depth", _i32), ("kernel_kind", _i32),
                 ("packed_bytes", _i64), ("x_in_registers", _i32), ("kernel_path", _i32), ("rows_per_workgroup", _i32),
-                ("workspace_bytes", _i64), ("small_batch_rows", _i64), ("workgroup_waves", _i32)]
+                ("workspace_bytes", _i64), ("small_batch_rows", _i64), ("workgroup_waves", _i32), ("rank_banks", _i32)]
 
 
 class _View(ctypes.Structure):
@@ -46,7 +46,11 @@ class _View(ctypes.Structure):
                 ("split_threshold", _p), ("child_left", _p), ("child_right", _p), ("leaf_node", _p),
                 ("leaf_value", _p), ("rank_threshold", _p), ("rank_threshold_base", _p),
                 ("rank_bucket", _p), ("rank_bucket_start", _p),
-                ("workgroup_waves", _i32), ("wave_tree", _p), ("program_groups", _p)]
+                ("workgroup_waves", _i32), ("wave_tree", _p), ("program_groups", _p),
+                ("bank_batches", _i32), ("bank_waves", _i32), ("bank_regs", _i32), ("bank_trees", _i32),
+                ("bank_unit", _i32), ("bank_max_units", _i32), ("bank_prog_entries", _i64), ("bank_prog", _p),
+                ("bank_stream_base", _p), ("bank_span", _p), ("bank_child", _p), ("bank_batch", _p),
+                ("bank_tree", _p), ("bank_reg", _p), ("order_leaf_node", _p), ("order_leaf_tree", _p)]
 
 
 # include/forest.h: the inference ABI
@@ -178,6 +182,23 @@ def forest_pack(forest) -> dict:
             rank["workgroup_waves"] = int(v.workgroup_waves)
             rank["wave_tree"] = get(v.wave_tree, int(v.workgroup_waves) + 1, np.int32)
             rank["program_groups"] = get(v.program_groups, T, np.int32)
+        if v.bank_batches > 0:
+            nb, nw, nt = int(v.bank_batches), int(v.bank_waves), int(v.bank_trees)
+            span = get(v.bank_span, nb * nw * 2, np.int32).reshape(nb, nw, 2)
+            batch = get(v.bank_batch, nb * 4, np.int32).reshape(nb, 4)
+            unit = int(v.bank_unit)
+            n_slots = int(batch[-1, 0] + batch[-1, 1])
+            rank.update(bank_batches=nb, bank_waves=nw, bank_regs=int(v.bank_regs), bank_trees=nt,
+                        bank_unit=unit, bank_max_units=int(v.bank_max_units),
+                        bank_prog=get(v.bank_prog, int(v.bank_prog_entries), np.uint32),
+                        bank_stream_base=get(v.bank_stream_base, nw, np.int32), bank_span=span,
+                        bank_child=get(v.bank_child, n_slots, np.uint32), bank_batch=batch,
+                        bank_tree=get(v.bank_tree, nb * nt * 4, np.int32).reshape(nb, nt, 4),
+                        bank_reg=get(v.bank_reg, nw * int(v.bank_regs), np.int32).reshape(nw, -1))
+        else:
+            rank["bank_batches"] = 0
+        rank["order_leaf_node"] = get(v.order_leaf_node, nl, np.int32)
+        rank["order_leaf_tree"] = get(v.order_leaf_tree, nl, np.int32)
         return dict(
             **rank,
             n_trees=T, kernel_kind=v.kernel_kind, kernel_path=v.kernel_path,

@@ -155,6 +155,12 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_fvf = place<int32_t>(cur, m.feat_vfirst.size());
     const size_t o_fbk = place<FeatBucket>(cur, m.feat_bucket.size());
     const size_t o_bst = place<int32_t>(cur, m.bucket_start.size());
+    const size_t o_bprog = place<uint32_t>(cur, m.bank_prog.size());
+    const size_t o_bchild = place<uint32_t>(cur, m.bank_child.size());
+    const size_t o_btree = place<BankTree>(cur, m.bank_tree.size());
+    const size_t o_bspan = place<BankSpan>(cur, m.bank_span.size());
+    const size_t o_bslot = place<BankBatch>(cur, m.bank_batch.size());
+    const size_t o_breg = place<int32_t>(cur, m.bank_reg.size());
     const size_t model_bytes = (cur + 255) & ~size_t{255};
     // workspaces of split launches, not uploaded
     const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
@@ -187,7 +193,13 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_ftb, m.feat_thr_base.data(), m.feat_thr_base.size() * sizeof(int32_t)) &&
                     up(o_fvf, m.feat_vfirst.data(), m.feat_vfirst.size() * sizeof(int32_t)) &&
                     up(o_fbk, m.feat_bucket.data(), m.feat_bucket.size() * sizeof(FeatBucket)) &&
-                    up(o_bst, m.bucket_start.data(), m.bucket_start.size() * sizeof(int32_t));
+                    up(o_bst, m.bucket_start.data(), m.bucket_start.size() * sizeof(int32_t)) &&
+                    up(o_bprog, m.bank_prog.data(), m.bank_prog.size() * sizeof(uint32_t)) &&
+                    up(o_bchild, m.bank_child.data(), m.bank_child.size() * sizeof(uint32_t)) &&
+                    up(o_btree, m.bank_tree.data(), m.bank_tree.size() * sizeof(BankTree)) &&
+                    up(o_bspan, m.bank_span.data(), m.bank_span.size() * sizeof(BankSpan)) &&
+                    up(o_bslot, m.bank_batch.data(), m.bank_batch.size() * sizeof(BankBatch)) &&
+                    up(o_breg, m.bank_reg.data(), m.bank_reg.size() * sizeof(int32_t));
     if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(f->blob);
@@ -223,6 +235,21 @@ int forest_load(const forest_desc *desc, forest **out)
     d.thr_sorted = reinterpret_cast<const float *>(b + o_thrs);
     d.feat_thr_base = reinterpret_cast<const int32_t *>(b + o_ftb);
     d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);
+    d.bank.prog = reinterpret_cast<const uint32_t *>(b + o_bprog);
+    d.bank.child = reinterpret_cast<const uint32_t *>(b + o_bchild);
+    d.bank.tree = reinterpret_cast<const BankTree *>(b + o_btree);
+    d.bank.span = reinterpret_cast<const BankSpan *>(b + o_bspan);
+    d.bank.batch = reinterpret_cast<const BankBatch *>(b + o_bslot);
+    d.bank.reg = reinterpret_cast<const int32_t *>(b + o_breg);
+    for (int w = 0; w < BANK_WAVES; ++w) d.bank.stream_base[w] = m.bank_stream_base[w];
+    d.bank.batches = m.bank_batches;
+    d.bank.max_units = m.bank_max_units;
+    d.bank.enabled = m.bank_enabled;
+    d.bank.passes = m.bank_passes;
+    for (int p = 0; p <= BANK_MAX_PASSES; ++p) {
+        d.bank.pass_feature[p] = m.bank_pass_feature[p];
+        d.bank.pass_reg[p] = m.bank_pass_reg[p];
+    }
     d.n_splits = 1;
     d.n_entries = static_cast<int64_t>(m.prog32.size() > m.prog.size() ? m.prog32.size() : m.prog.size());
     d.split_rows = 0;
@@ -233,6 +260,8 @@ int forest_load(const forest_desc *desc, forest **out)
     // the caller-order views are only for forest_pack_view; drop the bulk on the load path
     m.prog = {};
     m.prog32 = {};
+    m.bank_prog = {};
+    m.bank_child = {};
     m.child = {};
     m.thr_sorted = {};
     m.v_feature = {};
@@ -271,6 +300,7 @@ int forest_info(const forest *f, forest_info_t *info)
     info->workspace_bytes = f->workspace_bytes;
     info->small_batch_rows = SPLIT_BELOW_BLOCKS * info->rows_per_workgroup;
     info->workgroup_waves = family_waves_per_block(f->dev);
+    info->rank_banks = m.bank_enabled;
     return FOREST_OK;
 }
 

@@ -68,6 +68,25 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     v->workgroup_waves = m.path == PATH_RANK_LDS ? m.lds_waves : 0;
     v->wave_tree = m.path == PATH_RANK_LDS ? m.wave_tree : nullptr;
     v->program_groups = m.path == PATH_RANK_LDS ? m.v_program_groups.data() : nullptr;
+    const bool bank = m.bank_enabled != 0;
+    static_assert(sizeof(BankSpan) == 2 * sizeof(int32_t) && sizeof(BankTree) == 4 * sizeof(int32_t) &&
+                      sizeof(BankBatch) == 4 * sizeof(int32_t), "viewed as plain int32 arrays");
+    v->bank_batches = bank ? m.bank_batches : 0;
+    v->bank_waves = BANK_WAVES;
+    v->bank_regs = BANK_REGS;
+    v->bank_trees = BANK_TREES;
+    v->bank_max_units = bank ? m.bank_max_units : 0;
+    v->bank_unit = BANK_UNIT;
+    v->bank_prog_entries = bank ? static_cast<int64_t>(m.bank_prog.size()) : 0;
+    v->bank_prog = bank ? m.bank_prog.data() : nullptr;
+    v->bank_stream_base = bank ? m.bank_stream_base : nullptr;
+    v->bank_span = bank ? reinterpret_cast<const int32_t *>(m.bank_span.data()) : nullptr;
+    v->bank_child = bank ? m.bank_child.data() : nullptr;
+    v->bank_batch = bank ? reinterpret_cast<const int32_t *>(m.bank_batch.data()) : nullptr;
+    v->bank_tree = bank ? reinterpret_cast<const int32_t *>(m.bank_tree.data()) : nullptr;
+    v->bank_reg = bank ? m.bank_reg.data() : nullptr;
+    v->order_leaf_node = m.leaf_node.data();
+    v->order_leaf_tree = m.v_order_leaf_tree.data();
     return FOREST_OK;
 }
 

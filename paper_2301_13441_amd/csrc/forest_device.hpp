@@ -9,6 +9,21 @@
 
 namespace forest_impl {
 
+// Device tables of the register-bank program (forest_model.hpp, forest_pack.cpp).
+struct BankDev {
+    const uint32_t *prog;
+    const uint32_t *child;
+    const BankTree *tree;
+    const BankSpan *span;
+    const BankBatch *batch;
+    const int32_t *reg;
+    int32_t stream_base[BANK_WAVES];
+    int32_t batches, max_units, enabled;
+    int32_t passes;
+    int32_t pass_feature[BANK_MAX_PASSES + 1];
+    int32_t pass_reg[BANK_MAX_PASSES + 1];
+};
+
 struct DevModel {
     const SplitEntry *prog;
     const uint32_t *prog32;
@@ -43,6 +58,8 @@ struct DevModel {
     // Rank families, split launches: the rank tiles ([tile][rank register][lane] packed f16 pairs)
     // are computed once per row tile by forest_rank_tiles_kernel instead of by every workgroup.
     uint32_t *rank_tiles;
+    // LDS rank family: large batches of models it fits run the register-bank kernel
+    BankDev bank;
 };
 
 // Batches below this many workgroups split the trees over several workgroups per row tile.
@@ -98,6 +115,11 @@ hipError_t launch_rank(const DevModel &m, const float *X, int64_t n_rows, float 
 hipError_t init_ranklds_kernels(size_t lds_limit);
 hipError_t launch_ranklds(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream);
+
+// Register-bank kernel of the LDS rank family (forest_kernels_rankbank.hip).
+hipError_t init_rankbank_kernels(size_t lds_limit);
+hipError_t launch_rankbank(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream);
 
 // Sums the partial sums of a split launch over the splits and finishes every row.
 hipError_t launch_reduce_splits(const DevModel &m, int64_t n_rows, float *scores, int32_t *labels,

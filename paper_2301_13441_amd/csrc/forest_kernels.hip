@@ -254,7 +254,8 @@ hipError_t init_kernels()
             }
     if (hipError_t e = init_reg_kernels(g_lds_limit); e != hipSuccess) return e;
     if (hipError_t e = init_rank_kernels(g_lds_limit); e != hipSuccess) return e;
-    return init_ranklds_kernels(g_lds_limit);
+    if (hipError_t e = init_ranklds_kernels(g_lds_limit); e != hipSuccess) return e;
+    return init_rankbank_kernels(g_lds_limit);
 }
 
 int family_rows_per_block(const DevModel &m)
@@ -337,7 +338,12 @@ static hipError_t launch_family(const DevModel &m, const float *X, int64_t n_row
                                 int32_t *labels, int32_t *leaf_out, hipStream_t stream)
 {
     if (m.path == PATH_RANK) return launch_rank(m, X, n_rows, scores, labels, leaf_out, stream);
-    if (m.path == PATH_RANK_LDS) return launch_ranklds(m, X, n_rows, scores, labels, leaf_out, g_lds_limit, stream);
+    if (m.path == PATH_RANK_LDS) {
+        // large batches of the models it fits: rank registers banked over the waves' vector registers
+        if (m.n_splits == 1 && m.bank.enabled)
+            return launch_rankbank(m, X, n_rows, scores, labels, leaf_out, g_lds_limit, stream);
+        return launch_ranklds(m, X, n_rows, scores, labels, leaf_out, g_lds_limit, stream);
+    }
     if (m.path == PATH_REG) return launch_reg(m, X, n_rows, scores, labels, leaf_out, stream);
     bool staged = true;
     if (lds_bytes(m, true) > g_lds_limit) staged = false;

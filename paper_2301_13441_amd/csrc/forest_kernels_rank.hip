@@ -28,36 +28,10 @@
 namespace forest_impl {
 namespace {
 
-typedef uint32_t v32u __attribute__((ext_vector_type(32)));
-
-
-#if defined(__HIP_DEVICE_COMPILE__)
-typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
-typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
-#else
-typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
-typedef const TreeMeta *MetaPtr;
-#endif
-
-// One entry of the compact split program is one scalar register: -4 code(j') in the high half,
-// the rank register's index in the low byte.  s_set_gpr_idx_* reads only the low byte; the
-// packed multiply-add reads the high half for both rows (op_sel / op_sel_hi of the addend) and
-// the inline constant's low half for both (op_sel_hi 0: a packed inline constant fills only it).
-// The index mode lives in M0.  M0 is a register the compiler reserves: it never keeps a value of
-// its own in it across an inline-assembly statement (it sets M0 immediately before each use it
-// generates, and rejects M0 on a clobber list as having no effect), so the statements below may
-// write it freely.
-struct Entry8 {
-    uint32_t e[8];
-};
-
 // Eight entries (one outcome byte) applied to the lane's two rows.
 template <int NVR>
 struct RankStep;
 
-#define FOREST_RANK_CMP(B, n) \
-    "v_pk_fma_f16 %[d" #n "], " B ", 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
-#define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
 #define FOREST_RANK_ASM(B)                                                                       \
     "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
         FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
@@ -103,47 +77,6 @@ struct RankStep<4> {
                        "{v[128:159]}"(x[3]));
     }
 };
-
-// The eight comparisons alone; the outcomes (1.0 or 0.0 in each half) go to the matrix core.
-#define FOREST_RANK_CMP_ONLY(B)                                                                   \
-    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
-        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
-            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
-                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
-                    "s_set_gpr_idx_off"
-
-#define FOREST_RANK_CMP_OUTS                                                                                  \
-    [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]), [d5] "=&v"(d[5]), \
-        [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
-#define FOREST_RANK_CMP_INS                                                                                \
-    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]), [e5] "s"(q.e[5]), \
-        [e6] "s"(q.e[6]), [e7] "s"(q.e[7])
-
-__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[1])
-{
-    asm volatile(FOREST_RANK_CMP_ONLY("v64") : FOREST_RANK_CMP_OUTS : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]));
-}
-
-__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[2])
-{
-    asm volatile(FOREST_RANK_CMP_ONLY("v64")
-                 : FOREST_RANK_CMP_OUTS
-                 : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
-}
-
-template <int N>
-struct Batch {
-    Entry8 q[N / 8];
-};
-
-template <int N>
-__device__ __forceinline__ Batch<N> load_batch(ProgPtr p)
-{
-    Batch<N> b;
-#pragma unroll
-    for (int j = 0; j < N; ++j) b.q[j / 8].e[j % 8] = p[j];
-    return b;
-}
 
 enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
 

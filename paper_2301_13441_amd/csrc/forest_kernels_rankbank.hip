@@ -1,0 +1,321 @@
+// Register-bank kernel of the LDS rank family (gfx950): trees of any shape, large batches.
+//
+// Same exact rewrite of the comparison as the other rank kernels (rank(x) > j instead of
+// !(x <= tau_j), two rows per 32-bit register, v_pk_fma_f16 with clamp; Section 4.3.1 applied to
+// the input), arranged so that no comparison reads LDS and one write of the register index serves
+// four rows.  Every internal node of every tree is still evaluated for every row (Section 3.1.2,
+// Fig. 2 steps (1) and (2)); what changes is who evaluates it:
+//
+//   * A workgroup of 8 waves owns 256 rows, four per lane.  The rank registers (one per feature,
+//     more for a feature with very many thresholds) are dealt to the waves, up to 32 each, and stay
+//     in vector registers -- v64.. for the lane's rows l and l + 64, v96.. for rows l + 128 and
+//     l + 192 -- selected by the VGPR index mode (step (1), matmul(X, W1), costs no vector
+//     instruction, and one scalar instruction per node sets the index for both comparisons).
+//   * The trees are taken 2 at a time (a batch).  Each wave evaluates the nodes of the batch that
+//     test one of ITS registers -- a stream of entries the host compiler sorted that way, read 16
+//     entries at a time into two alternating sets of scalar registers -- and the matrix core turns
+//     every 8 outcomes into a byte per row, stored in an LDS buffer the whole workgroup shares.
+//     A node's place in that buffer is its slot.
+//   * After a barrier every lane walks one (row, tree) of the batch from the root: the outcome bit
+//     of its slot and the slot's child references pick the next slot, until a leaf (the bit-level
+//     form of matmul(., W3) + argmax).  A wave owns 32 of the workgroup's rows for all trees, so
+//     the sums over trees never leave the wave: the 2 lanes of a row add their leaf values with
+//     one cross-lane addition, in fp64.
+//
+// Against the LDS-resident rank kernel this takes the LDS read per comparison (the LDS was the
+// busiest unit there), half of the scalar instructions per comparison and the per-group
+// bookkeeping of the level-by-level walk out of the evaluation loop.  The price is a barrier pair
+// per batch and padding of every wave's share of a batch to whole units of 16 entries.  Small
+// batches, and models whose batch buffer or registers do not fit, run the LDS-resident kernel.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "forest_device.hpp"
+#include "forest_kernel_common.hpp"
+#include "forest_rank_common.hpp"
+
+#ifndef BANK_EXPERIMENT
+#define BANK_EXPERIMENT 0
+#endif
+namespace forest_impl {
+namespace {
+
+constexpr int BANK_BLOCK = TILE * BANK_WAVES;
+constexpr int BANK_ROWS_PER_WAVE = BANK_ROWS / BANK_WAVES;  // rows a wave walks
+static_assert(BANK_ROWS_PER_WAVE * BANK_TREES == TILE, "one lane per (row, tree) of a batch");
+static_assert(BANK_REGS == 32 && BANK_ROWS == 4 * TILE, "the comparison statement addresses v64..v95 and v96..v127");
+static_assert(BANK_UNIT == 16, "a unit is one 16-register scalar load: two groups of 8 entries");
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) BankSpan *SpanPtr;
+typedef const __attribute__((address_space(4))) BankBatch *BatchPtr;
+typedef const __attribute__((address_space(4))) int32_t *IntPtr;
+#else
+typedef const BankSpan *SpanPtr;  // host pass: the kernel body is only parsed
+typedef const BankBatch *BatchPtr;
+typedef const int32_t *IntPtr;
+#endif
+
+enum { BANK_SUMS = 0, BANK_LEAVES = 1 };
+
+// Eight entries applied to the lane's four rows: one index write, two comparisons per entry.
+// The outcome registers are pinned (v48.., v56..) so that the statement can name them one by one
+// and hand them to the matrix core as two 8-register operands.
+#define FOREST_BANK_CMP(n, A, B)                                                              \
+    "v_pk_fma_f16 " A ", v64, 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"      \
+    "v_pk_fma_f16 " B ", v96, 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
+__device__ __forceinline__ void bank_compare(v8i &da, v8i &db, const Entry8 &q, const v32u &xa, const v32u &xb)
+{
+    asm volatile("s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_BANK_CMP(0, "v48", "v56")
+                 "s_set_gpr_idx_idx %[e1]\n\t" FOREST_BANK_CMP(1, "v49", "v57")
+                 "s_set_gpr_idx_idx %[e2]\n\t" FOREST_BANK_CMP(2, "v50", "v58")
+                 "s_set_gpr_idx_idx %[e3]\n\t" FOREST_BANK_CMP(3, "v51", "v59")
+                 "s_set_gpr_idx_idx %[e4]\n\t" FOREST_BANK_CMP(4, "v52", "v60")
+                 "s_set_gpr_idx_idx %[e5]\n\t" FOREST_BANK_CMP(5, "v53", "v61")
+                 "s_set_gpr_idx_idx %[e6]\n\t" FOREST_BANK_CMP(6, "v54", "v62")
+                 "s_set_gpr_idx_idx %[e7]\n\t" FOREST_BANK_CMP(7, "v55", "v63")
+                 "s_set_gpr_idx_off"
+                 : "={v[48:55]}"(da), "={v[56:63]}"(db)
+                 : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
+                   [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), "{v[64:95]}"(xa), "{v[96:127]}"(xb));
+}
+
+// sum over the lanes that share a row (one per tree of the batch), the same bits in each
+__device__ __forceinline__ double row_sum(double v)
+{
+    static_assert(BANK_TREES == 2, "one cross-lane addition");
+    return v + __shfl_xor(v, 1);
+}
+
+// buf: the batch's outcome bytes ([group of 8 slots][row of the workgroup]); child_lds: the batch's
+// child references, one word per slot.
+template <int MODE>
+__device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, const v32u &xb, uint8_t *buf,
+                                           uint32_t *child_lds, double (&sum)[2], int wave, int lane, int64_t row0,
+                                           int64_t n_rows, int32_t *leaf_out)
+{
+    const int T = m.n_trees;
+    const int K = m.n_outputs;
+    const int walk_row = wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;  // the lane's row of the tile in the walk
+    const int walk_tree = lane % BANK_TREES;                            // and its tree of the batch
+    const int64_t row = row0 + walk_row;
+    BitCollector bits;
+    bits.init(lane);
+    ProgPtr p = (ProgPtr)(m.bank.prog + m.bank.stream_base[wave]);
+    SpanPtr span = (SpanPtr)m.bank.span;
+    BatchPtr batch = (BatchPtr)m.bank.batch;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    // The stream lives in two sets of 16 scalar registers used in turn: while one is evaluated
+    // the other is being loaded.
+    Batch<16> set_a = load_batch<16>(p);
+    // What a walk ends on is fetched at once and used a batch later (the gather's latency is
+    // covered by the next batch's comparisons): the leaf's values, or, for the leaf-id output,
+    // the caller's node index with the place it goes to.
+    float pend_v0 = 0.0f, pend_v1 = 0.0f;
+    int pend_node = 0, pend_tree = 0;
+    bool pend_valid = false;
+    auto consume_pending = [&]() {
+        if (MODE == BANK_LEAVES) {
+            if (pend_valid && row < n_rows) leaf_out[row * T + pend_tree] = pend_node;
+        } else {
+            // K == 1 (scalar leaves) or K == leaf width <= 2: the sums stay in registers
+            sum[0] += row_sum(pend_valid ? static_cast<double>(pend_v0) : 0.0);
+            if (K > 1) sum[1] += row_sum(pend_valid ? static_cast<double>(pend_v1) : 0.0);
+        }
+    };
+
+#if BANK_EXPERIMENT == 4
+    if (m.bank.batches >= 0) return;
+#endif
+    for (int b = 0; b < m.bank.batches; ++b) {
+        const int n_units = span[b * BANK_WAVES + wave].n_units;
+        // The batch's child references go to LDS: the walk reads one per step and lane, which
+        // the texture path serves at about one lane per cycle and the LDS far faster.  Four
+        // words per thread, fetched now, stored after the evaluation.
+        const int n_slots = batch[b].n_slots;
+        const bool stage = 4 * static_cast<int>(threadIdx.x) < n_slots;  // n_slots is a multiple of 16
+        u32x4 staged = {0u, 0u, 0u, 0u};
+        if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + batch[b].slot_base)[threadIdx.x];
+        const BankTree bt = m.bank.tree[b * BANK_TREES + walk_tree];  // used after the evaluation
+        // the bytes of the lane's four rows for a group: dst[0], dst[64], dst[128], dst[192]
+        uint8_t *dst = buf + span[b * BANK_WAVES + wave].unit_base * (2 * BANK_ROWS) + lane;
+#if BANK_EXPERIMENT != 2 && BANK_EXPERIMENT != 3
+        // ---- evaluation: this wave's nodes of the batch.  A group's byte is still being
+        // collected by the matrix core when its last comparison has issued, so it is stored
+        // after the comparisons of the next group.
+        v4f ga = bits.bias, gb = bits.bias;
+        bool pending = false;
+        auto group = [&](const Entry8 &q) {
+            v8i da, db;
+            bank_compare(da, db, q, xa, xb);
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+            if (pending) {
+                dst[0] = static_cast<uint8_t>(__float_as_uint(ga[0]));
+                dst[TILE] = static_cast<uint8_t>(__float_as_uint(ga[1]));
+                dst[2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
+                dst[3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
+                dst += BANK_ROWS;
+            }
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+            ga = bits.collect_b(da, bits.bias);
+            gb = bits.collect_b(db, bits.bias);
+            pending = true;
+        };
+        int u = 0;
+        for (; u + 1 < n_units; u += 2) {
+            const Batch<16> set_b = load_batch<16>(p + 16);
+            group(set_a.q[0]);
+            group(set_a.q[1]);
+            set_a = load_batch<16>(p + 32);
+            group(set_b.q[0]);
+            group(set_b.q[1]);
+            p += 32;
+        }
+        if (u < n_units) {
+            const Batch<16> set_b = load_batch<16>(p + 16);
+            group(set_a.q[0]);
+            group(set_a.q[1]);
+            set_a = set_b;
+            p += 16;
+        }
+        if (pending) {
+            dst[0] = static_cast<uint8_t>(__float_as_uint(ga[0]));
+            dst[TILE] = static_cast<uint8_t>(__float_as_uint(ga[1]));
+            dst[2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
+            dst[3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
+        }
+#endif
+        if (stage) reinterpret_cast<u32x4 *>(child_lds)[threadIdx.x] = staged;
+        if (b > 0) consume_pending();  // the last batch's leaves
+        __syncthreads();  // the batch's bits and child references are complete
+
+        // ---- walk: one (row, tree) per lane
+        const uint8_t *bits_of_row = buf + walk_row;
+        uint32_t ref = static_cast<uint32_t>(bt.root_ref);
+#if BANK_EXPERIMENT == 1 || BANK_EXPERIMENT == 3
+        ref = BANK_LEAF_FLAG;
+#endif
+        while (__any(!(ref & BANK_LEAF_FLAG))) {
+            if (!(ref & BANK_LEAF_FLAG)) {
+                const uint32_t byte = bits_of_row[(ref >> 3) * BANK_ROWS];
+                const uint32_t c = child_lds[ref];
+                ref = ((byte >> (ref & 7u)) & 1u) ? (c >> 16) : (c & 0xffffu);
+            }
+        }
+        // index into the per-leaf tables; the records that pad a batch give the batch's first leaf
+        const int leaf = batch[b].leaf_base + static_cast<int>(ref & 0x7fffu);
+        pend_valid = bt.valid != 0;
+        if (MODE == BANK_LEAVES) {
+            pend_node = m.leaf_node[leaf];
+            pend_tree = bt.caller_tree;
+        } else {
+            const float *v = m.leaf_value + static_cast<size_t>(leaf) * K;
+            pend_v0 = v[0];
+            if (K > 1) pend_v1 = v[1];
+        }
+        __syncthreads();  // every lane is done with the buffer
+    }
+    if (m.bank.batches > 0) consume_pending();
+}
+
+// 128 vector registers per lane at most: two workgroups of 8 waves per compute unit.
+template <int MODE>
+__global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4))) void forest_rankbank_kernel(
+    DevModel m, const float *__restrict__ X, int64_t n_rows, float *scores, int32_t *labels, int32_t *leaf_out)
+{
+    extern __shared__ __align__(16) char smem[];
+    // LDS: first the rank tiles of a prologue pass (two of [rank register of the pass][lane], two
+    // rows per word: rows 0..127 and rows 128..255 of the workgroup), then, in the same place, the
+    // batch's outcome bytes ([group of 8 slots][row of the workgroup]) and child references.
+    uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
+    const int lane = threadIdx.x & (TILE - 1);
+    const int wave = uniform(threadIdx.x >> 6);
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * BANK_ROWS;
+
+    // ranks, a pass of whole features at a time; after each pass a wave takes the registers of
+    // its bank that the pass holds
+    IntPtr bank_reg = (IntPtr)(m.bank.reg + wave * BANK_REGS);
+    v32u xa, xb;
+    for (int p = 0; p < m.bank.passes; ++p) {
+        const int reg_begin = m.bank.pass_reg[p], reg_end = m.bank.pass_reg[p + 1];
+        uint32_t *rk_hi = rk + (reg_end - reg_begin) * TILE;
+        rank_rows<BANK_WAVES, 4>(rk, m, X, row0, n_rows, wave, lane, m.bank.pass_feature[p], m.bank.pass_feature[p + 1],
+                                 reg_begin, reg_end);
+        rank_rows<BANK_WAVES, 4>(rk_hi, m, X, row0 + RROWS, n_rows, wave, lane, m.bank.pass_feature[p],
+                                 m.bank.pass_feature[p + 1], reg_begin, reg_end);
+        __syncthreads();  // the pass's ranks are complete
+#pragma unroll
+        for (int i = 0; i < BANK_REGS; ++i) {
+            const int r = bank_reg[i];  // wave-uniform
+            if (r >= reg_begin && r < reg_end) {
+                xa[i] = rk[(r - reg_begin) * TILE + lane];
+                xb[i] = rk_hi[(r - reg_begin) * TILE + lane];
+            }
+        }
+        __syncthreads();  // the tiles are free for the next pass, or for the outcome bytes
+    }
+
+    double sum[2] = {0.0, 0.0};
+    uint8_t *buf = reinterpret_cast<uint8_t *>(smem);
+    uint32_t *child_lds = reinterpret_cast<uint32_t *>(smem + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
+    bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane, row0, n_rows, leaf_out);
+    if (MODE == BANK_LEAVES) return;
+    const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;
+    // a copy with run-time indices: indexed that way `sum` itself would live in scratch memory
+    double raw[2] = {sum[0], sum[1]};
+    if (lane % BANK_TREES == 0 && row < n_rows) finish_values(m, raw, 1, row, scores, labels);
+}
+
+size_t rankbank_lds_bytes(const DevModel &m)
+{
+    int pass_regs = 0;
+    for (int p = 0; p < m.bank.passes; ++p)
+        pass_regs = m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] > pass_regs ? m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] : pass_regs;
+    const size_t tile = 2 * sizeof(uint32_t) * TILE * static_cast<size_t>(pass_regs);
+    // outcome bytes of a batch, then its child references (a word per slot)
+    const size_t bytes = (static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) + sizeof(uint32_t) * BANK_UNIT) *
+                         static_cast<size_t>(m.bank.max_units);
+    return tile > bytes ? tile : bytes;
+}
+
+}  // namespace
+
+hipError_t init_rankbank_kernels(size_t lds_limit)
+{
+    for (const void *fn : {reinterpret_cast<const void *>(forest_rankbank_kernel<BANK_SUMS>),
+                           reinterpret_cast<const void *>(forest_rankbank_kernel<BANK_LEAVES>)}) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_rankbank(const DevModel &m, const float *X, int64_t n_rows, float *scores, int32_t *labels,
+                           int32_t *leaf_out, size_t lds_limit, hipStream_t stream)
+{
+    // what the kernel assumes of the model, checked before it runs
+    const int K = m.n_outputs, W = m.leaf_width;
+    const bool sums_fit = (K == 1 && W == 1) || (W == K && K <= 2);
+    const size_t lds = rankbank_lds_bytes(m);
+    if (!m.bank.enabled || m.n_splits != 1 || !sums_fit || m.rank_regs < 1 || m.rank_regs > BANK_WAVES * BANK_REGS || m.bank.passes < 1 ||
+        m.bank.passes > BANK_MAX_PASSES ||
+        lds > lds_limit || lds > BANK_MAX_LDS)
+        return hipErrorInvalidValue;
+    const int64_t n_blocks = (n_rows + BANK_ROWS - 1) / BANK_ROWS;
+    if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>(n_blocks));
+    if (leaf_out)
+        hipLaunchKernelGGL(forest_rankbank_kernel<BANK_LEAVES>, grid, dim3(BANK_BLOCK), lds, stream, m, X, n_rows,
+                           scores, labels, leaf_out);
+    else
+        hipLaunchKernelGGL(forest_rankbank_kernel<BANK_SUMS>, grid, dim3(BANK_BLOCK), lds, stream, m, X, n_rows,
+                           scores, labels, leaf_out);
+    return hipGetLastError();
+}
+
+}  // namespace forest_impl

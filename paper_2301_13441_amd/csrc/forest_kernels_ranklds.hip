@@ -33,12 +33,6 @@
 namespace forest_impl {
 namespace {
 
-#if defined(__HIP_DEVICE_COMPILE__)
-typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
-#else
-typedef const TreeMeta *MetaPtr;  // host pass: the kernel body is only parsed
-#endif
-
 typedef uint32_t v16u __attribute__((ext_vector_type(16)));
 
 #if defined(__HIP_DEVICE_COMPILE__)

@@ -116,6 +116,48 @@ struct ChildRef {
     int32_t left, right;  // >= 0: internal ordinal (level order); < 0: ~(in-order leaf ordinal)
 };
 
+// Register-bank kernel of the LDS rank family (large batches of models it fits): a workgroup of
+// BANK_WAVES waves owns BANK_ROWS rows, four per lane.  The rank registers are dealt to the waves,
+// up to BANK_REGS each, and held in vector registers (two per rank register: two rows each).
+// Every wave evaluates, for up to BANK_TREES trees at a time (a batch), the internal nodes that
+// test one of its registers, BANK_UNIT entries of its stream at a time, and leaves their outcome
+// bits in an LDS buffer all waves share (a byte per 8 nodes and row); then every lane walks one
+// (row, tree) of the batch through those bits.  The ranks are computed in up to BANK_MAX_PASSES
+// passes of at most BANK_PASS_REGS registers (whole features), which bounds the LDS of the
+// prologue like BANK_MAX_LDS bounds that of a batch: two workgroups per compute unit.
+constexpr int BANK_WAVES = 8;
+constexpr int BANK_REGS = 32;
+constexpr int BANK_TREES = 2;
+constexpr int BANK_ROWS = 256;
+constexpr int BANK_UNIT = 16;
+constexpr int BANK_PASS_REGS = 128;
+constexpr int BANK_MAX_PASSES = 4;
+constexpr size_t BANK_MAX_LDS = 72 * 1024;     // outcome bytes and child references of a batch
+constexpr int BANK_PAD_ENTRIES = 64;        // readable entries after each wave's stream
+
+// A reference of the register-bank program, 16 bits: bit 15 clear: a slot of the batch; bit 15 set:
+// a leaf, the low 15 bits its index among the batch's leaves (processing order).
+constexpr uint32_t BANK_LEAF_FLAG = 0x8000u;
+
+struct BankTree {
+    int32_t root_ref;     // reference of the root (a leaf if the tree is a single leaf)
+    int32_t column;       // output column of a scalar-leaf tree
+    int32_t caller_tree;  // index of the tree in the caller's description
+    int32_t valid;        // 0 for the records that pad the last batch
+};
+
+struct BankBatch {
+    int32_t slot_base;  // first entry of the batch in the child table
+    int32_t n_slots;    // slots of the batch (whole units)
+    int32_t leaf_base;  // index of the batch's first leaf in the per-leaf tables
+    int32_t reserved;
+};
+
+struct BankSpan {
+    int32_t n_units;    // units of BANK_UNIT entries of this wave in this batch
+    int32_t unit_base;  // index of the first of them in the batch's bit buffer
+};
+
 struct PackedModel {
     int32_t n_trees = 0, n_features = 0, n_outputs = 0, leaf_width = 1;
     int32_t aggregate = 0, transform = 0, output = 0;
@@ -149,8 +191,23 @@ struct PackedModel {
     std::vector<double> col_trees;   // [K] number of trees feeding each column
     std::vector<float> base;         // [K]
 
+    // register-bank program (empty unless bank_enabled)
+    int32_t bank_enabled = 0;
+    int32_t bank_batches = 0;
+    int32_t bank_max_units = 0;              // most units a batch's bit buffer holds
+    int32_t bank_stream_base[BANK_WAVES] = {};  // first entry of each wave's stream in bank_prog
+    int32_t bank_passes = 0;                          // prologue passes
+    int32_t bank_pass_feature[BANK_MAX_PASSES + 1] = {};  // pass p ranks features [p], [p + 1])
+    int32_t bank_pass_reg[BANK_MAX_PASSES + 1] = {};      // which hold rank registers [p], [p + 1])
+    std::vector<uint32_t> bank_prog;         // (f16(-4 code(j')) << 16) | register index inside the bank
+    std::vector<uint32_t> bank_child;        // per batch, by slot: left reference | right reference << 16
+    std::vector<BankBatch> bank_batch;       // [batches]
+    std::vector<BankTree> bank_tree;         // [batches * BANK_TREES], processing order
+    std::vector<BankSpan> bank_span;         // [batches][BANK_WAVES]
+    std::vector<int32_t> bank_reg;           // [BANK_WAVES * BANK_REGS] rank register behind each bank register
+
     // caller-order views used only by forest_pack_view
-    std::vector<int32_t> v_n_internal, v_depth, v_is_full, v_program_groups;
+    std::vector<int32_t> v_n_internal, v_depth, v_is_full, v_program_groups, v_order_leaf_tree;
     std::vector<int64_t> v_node_base, v_leaf_base;
     std::vector<int32_t> v_feature, v_left, v_right, v_leaf_node;
     std::vector<float> v_threshold, v_leaf_value;

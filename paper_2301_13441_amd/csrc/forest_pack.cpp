@@ -478,7 +478,174 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         m.tree.push_back(tm);
     }
     if (m.path == PATH_RANK_LDS) balance_waves(m);
+    if (m.path == PATH_RANK_LDS && m.kind == KIND_GENERIC && m.rank_regs >= 1 &&
+        m.rank_regs <= BANK_WAVES * BANK_REGS && ((K == 1 && W == 1) || (W == K && K <= 2))) {
+        // Register-bank program.  Rank registers to waves: heaviest first, each to the wave with
+        // the fewest nodes so far that still has a free register.
+        std::vector<int64_t> reg_nodes(static_cast<size_t>(m.rank_regs), 0);
+        for (int32_t t = 0; t < T; ++t)
+            for (int32_t v : shape[t].internal) ++reg_nodes[entry_of(t, v).feature_slot];
+        std::vector<int32_t> by_weight(static_cast<size_t>(m.rank_regs));
+        std::iota(by_weight.begin(), by_weight.end(), 0);
+        std::stable_sort(by_weight.begin(), by_weight.end(),
+                         [&](int32_t a, int32_t b) { return reg_nodes[a] > reg_nodes[b]; });
+        std::vector<int32_t> reg_wave(static_cast<size_t>(m.rank_regs)), reg_index(static_cast<size_t>(m.rank_regs));
+        int64_t load[BANK_WAVES] = {};
+        int32_t held[BANK_WAVES] = {};
+        m.bank_reg.assign(BANK_WAVES * BANK_REGS, 0);
+        for (int32_t r : by_weight) {
+            int best = -1;
+            for (int w = 0; w < BANK_WAVES; ++w)
+                if (held[w] < BANK_REGS && (best < 0 || load[w] < load[best])) best = w;
+            reg_wave[r] = best;
+            reg_index[r] = held[best];
+            m.bank_reg[best * BANK_REGS + held[best]] = r;
+            ++held[best];
+            load[best] += reg_nodes[r];
+        }
+        // Batches of up to BANK_TREES consecutive trees (processing order): as many as keep the
+        // batch's bit buffer inside the LDS budget.  Inside a batch every wave gets the nodes that
+        // test its registers, padded to whole units of BANK_UNIT entries; a node's slot is
+        // BANK_UNIT * (index of its unit in the batch's bit buffer) + its bit.  The kernel collects
+        // the entries of a unit in groups of 8, first entry of a group in bit 7 of the group's byte.
+        std::vector<std::vector<uint32_t>> stream(BANK_WAVES);
+        uint32_t pad32;
+        std::memcpy(&pad32, &pad.threshold, sizeof(pad32));
+        pad32 &= 0xffff0000u;  // bank register 0 against the largest code: outcome 0
+        int64_t max_units = 0;
+        bool fits = true;
+        struct Node { int32_t tree, ordinal; };
+        // units of a batch made of trees [first, first + count) of the processing order
+        auto batch_units = [&](int32_t first, int32_t count) {
+            int64_t per_wave[BANK_WAVES] = {};
+            for (int32_t j = 0; j < count; ++j) {
+                const int32_t t = order[first + j];
+                for (int32_t v : shape[t].internal) ++per_wave[reg_wave[entry_of(t, v).feature_slot]];
+            }
+            int64_t units = 0;
+            for (int w = 0; w < BANK_WAVES; ++w) units += (per_wave[w] + BANK_UNIT - 1) / BANK_UNIT;
+            return units;
+        };
+        // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot
+        const int64_t budget_units = static_cast<int64_t>(BANK_MAX_LDS / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
+        int32_t n_batches = 0;
+        for (int32_t first = 0; first < T && fits; ++n_batches) {
+            int32_t count = 1;
+            while (count < BANK_TREES && first + count < T && batch_units(first, count + 1) <= budget_units) ++count;
+            if (batch_units(first, count) > budget_units) {
+                fits = false;  // a single tree too large for the buffer
+                break;
+            }
+            std::vector<Node> mine[BANK_WAVES];
+            for (int32_t j = 0; j < count; ++j) {
+                const int32_t t = order[first + j];
+                const TreeShape &sh = shape[t];
+                for (int32_t i = 0; i < static_cast<int32_t>(sh.internal.size()); ++i)
+                    mine[reg_wave[entry_of(t, sh.internal[i]).feature_slot]].push_back(Node{j, i});
+            }
+            // slots
+            std::vector<std::vector<int32_t>> slot_of(BANK_TREES);
+            for (int32_t j = 0; j < count; ++j) slot_of[j].assign(shape[order[first + j]].internal.size(), -1);
+            int32_t unit_base = 0;
+            for (int w = 0; w < BANK_WAVES; ++w) {
+                const int32_t n_units = static_cast<int32_t>((mine[w].size() + BANK_UNIT - 1) / BANK_UNIT);
+                m.bank_span.push_back(BankSpan{n_units, unit_base});
+                for (int32_t k = 0; k < n_units * BANK_UNIT; ++k) {
+                    // entry k of the wave's batch stream fills bit 8 * (group inside the unit) + 7 - k % 8
+                    // of unit k / BANK_UNIT
+                    const int32_t bit = 8 * ((k >> 3) % (BANK_UNIT / 8)) + 7 - (k & 7);
+                    const int32_t local = (k / BANK_UNIT) * BANK_UNIT + bit;  // which of the wave's nodes sits at this entry
+                    if (local < static_cast<int32_t>(mine[w].size())) {
+                        const Node nd = mine[w][local];
+                        const int32_t t = order[first + nd.tree];
+                        const SplitEntry e = entry_of(t, shape[t].internal[nd.ordinal]);
+                        uint32_t pair;
+                        std::memcpy(&pair, &e.threshold, sizeof(pair));
+                        stream[w].push_back((pair & 0xffff0000u) | static_cast<uint32_t>(reg_index[e.feature_slot]));
+                        slot_of[nd.tree][nd.ordinal] = (unit_base + k / BANK_UNIT) * BANK_UNIT + bit;
+                    } else {
+                        stream[w].push_back(pad32);
+                    }
+                }
+                unit_base += n_units;
+            }
+            max_units = std::max<int64_t>(max_units, unit_base);
+            // child references by slot, and the trees' records
+            const int32_t batch_leaf_base = m.tree[first].leaf_base;
+            m.bank_batch.push_back(BankBatch{static_cast<int32_t>(m.bank_child.size()), unit_base * BANK_UNIT,
+                                             batch_leaf_base, 0});
+            const size_t child_at = m.bank_child.size();
+            m.bank_child.resize(child_at + static_cast<size_t>(unit_base) * BANK_UNIT, 0xffffffffu);
+            for (int32_t j = 0; j < BANK_TREES; ++j) {
+                const int32_t ti = first + j;
+                if (j >= count) {
+                    m.bank_tree.push_back(BankTree{static_cast<int32_t>(BANK_LEAF_FLAG), 0, 0, 0});
+                    continue;
+                }
+                const int32_t t = order[ti];
+                const TreeShape &sh = shape[t];
+                const TreeMeta &tm = m.tree[ti];
+                const int64_t base = d.tree_offset[t];
+                auto ref_of = [&](int32_t caller_node) -> uint32_t {
+                    const int32_t o = sh.ordinal[caller_node];
+                    if (o >= 0) return static_cast<uint32_t>(slot_of[j][o]);
+                    const int32_t leaf = tm.leaf_base + ~o - batch_leaf_base;
+                    if (leaf >= static_cast<int32_t>(BANK_LEAF_FLAG)) fits = false;
+                    return BANK_LEAF_FLAG | static_cast<uint32_t>(leaf & 0x7fff);
+                };
+                for (int32_t i = 0; i < static_cast<int32_t>(sh.internal.size()); ++i) {
+                    const int32_t v = sh.internal[i];
+                    m.bank_child[child_at + slot_of[j][i]] = ref_of(d.left[base + v]) | (ref_of(d.right[base + v]) << 16);
+                }
+                m.bank_tree.push_back(BankTree{static_cast<int32_t>(ref_of(0)), tm.column, tm.caller_tree, 1});
+            }
+            first += count;
+        }
+        // prologue passes: whole features, at most BANK_PASS_REGS rank registers each
+        int32_t passes = 0;
+        for (int32_t f = 0; f < d.n_features && fits;) {
+            if (passes == BANK_MAX_PASSES) {
+                fits = false;
+                break;
+            }
+            m.bank_pass_feature[passes] = f;
+            m.bank_pass_reg[passes] = m.feat_vfirst[f];
+            int32_t regs_here = 0;
+            while (f < d.n_features) {
+                const int32_t r = (f + 1 < d.n_features ? m.feat_vfirst[f + 1] : m.rank_regs) - m.feat_vfirst[f];
+                if (regs_here + r > BANK_PASS_REGS) break;
+                regs_here += r;
+                ++f;
+            }
+            if (f == m.bank_pass_feature[passes]) fits = false;  // one feature with more registers than a pass holds
+            ++passes;
+        }
+        m.bank_pass_feature[passes] = d.n_features;
+        m.bank_pass_reg[passes] = m.rank_regs;
+        m.bank_passes = passes;
+        if (fits) {
+            m.bank_enabled = 1;
+            m.bank_batches = n_batches;
+            m.bank_max_units = static_cast<int32_t>(max_units);
+            for (int w = 0; w < BANK_WAVES; ++w) {
+                m.bank_stream_base[w] = static_cast<int32_t>(m.bank_prog.size());
+                m.bank_prog.insert(m.bank_prog.end(), stream[w].begin(), stream[w].end());
+                m.bank_prog.insert(m.bank_prog.end(), BANK_PAD_ENTRIES, pad32);
+            }
+        } else {
+            m.bank_child.clear();
+            m.bank_batch.clear();
+            m.bank_tree.clear();
+            m.bank_span.clear();
+            m.bank_reg.clear();
+        }
+    }
     for (const TreeMeta &tm : m.tree) m.v_program_groups.push_back(tm.n_words);
+    for (size_t ti = 0; ti < m.tree.size(); ++ti) {
+        const size_t end = ti + 1 < m.tree.size() ? static_cast<size_t>(m.tree[ti + 1].leaf_base) : m.leaf_node.size();
+        m.v_order_leaf_tree.insert(m.v_order_leaf_tree.end(), end - static_cast<size_t>(m.tree[ti].leaf_base),
+                                   m.tree[ti].caller_tree);
+    }
     m.tree.push_back(TreeMeta{});  // spare record: the stream kernels read the root of "the next tree"
     // Padding: the kernels prefetch (and may evaluate, without using the result) up to eleven
     // groups past the entries of their trees.

@@ -82,6 +82,15 @@ typedef const int32_t *RankTablePtr;  // host pass: the kernel body is only pars
 typedef const FeatBucket *BucketPtr;
 #endif
 
+// bucket_index without branches: the same value for every x (maximum and minimum drop a NaN
+// operand, the conversion truncates), three vector instructions after the subtraction and the
+// multiplication.  n_buckets is at most 2^20, exact in float.
+__device__ __forceinline__ int32_t bucket_index_fast(float x, float lo, float scale, int32_t n_buckets)
+{
+    const float t = (x - lo) * scale;
+    return static_cast<int32_t>(fminf(fmaxf(t, 0.0f), static_cast<float>(n_buckets - 1)));
+}
+
 // Bracket of rank(x) from the feature's bucket table; every candidate in [lo, hi] is a rank.
 struct RankBracket {
     int lo, hi;
@@ -146,16 +155,17 @@ __device__ __forceinline__ void store_rank(uint16_t *tile16, const DevModel &m, 
 // other; the rest of the tile gets rank 0.  Xt points at the tile's first row.
 template <int NWAVES>
 __device__ __forceinline__ void rank_rows_few(uint32_t *rk, const DevModel &m, const float *__restrict__ Xt,
-                                              int n_valid)
+                                              int n_valid, int f_begin, int f_end, int reg_begin, int reg_end)
 {
     const int F = m.n_features;
     const int n_threads = NWAVES * TILE;
-    for (int i = threadIdx.x; i < m.rank_regs * TILE; i += n_threads) rk[i] = 0;
+    for (int i = threadIdx.x; i < (reg_end - reg_begin) * TILE; i += n_threads) rk[i] = 0;
     __syncthreads();
-    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk);
-    for (int w = threadIdx.x; w < n_valid * F; w += n_threads) {
-        const int r = w / F, f = w - r * F;
-        store_rank(rk16, m, f, r, rank_of(m, f, Xt[w]));
+    uint16_t *rk16 = reinterpret_cast<uint16_t *>(rk) - static_cast<ptrdiff_t>(reg_begin) * TILE * 2;
+    const int nf = f_end - f_begin;
+    for (int w = threadIdx.x; w < n_valid * nf; w += n_threads) {
+        const int r = w / nf, f = f_begin + (w - r * nf);
+        store_rank(rk16, m, f, r, rank_of(m, f, Xt[r * F + f]));
     }
 }
 
@@ -188,17 +198,23 @@ struct __attribute__((aligned(4))) FloatRun {
 // The features are dealt to the waves; inside a wave every lane looks up the same feature for
 // its own two rows, U features at a time (2 U lookups in flight per lane), so the feature's
 // constants are read with scalar loads.  A lookup is a bucket (a subtraction, a multiplication,
-// a conversion), the bucket's bracket from the start table, the check of the bracket against
-// the two thresholds next to it, and the rank inside the bracket (a count over 8 thresholds, or
-// a binary search).
+// a conversion), the bucket's lower bound of the rank from the start table, and a count over a
+// window of 8 thresholds placed by that bound (or a binary search where the window does not
+// decide the rank).  The lookups are bound by the rate at which the texture path takes per-lane
+// addresses, so what counts is the number of reads per lookup: one table word and one window.
+//
+// The general form takes the features [f_begin, f_end), whose rank registers are
+// [reg_begin, reg_end), and writes register r to rk[(r - reg_begin) * 64 + lane]: a tile of a
+// part of the registers, for kernels that take the ranks out of LDS in several passes.
 template <int NWAVES, int U = 2, bool STREAM_X = false>
 __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
-                                          int64_t row0, int64_t n_rows, int wave, int lane)
+                                          int64_t row0, int64_t n_rows, int wave, int lane, int f_begin, int f_end,
+                                          int reg_begin, int reg_end)
 {
     const int F = m.n_features;
     const int64_t left = n_rows - row0;
     if (left * 4 <= RROWS) {  // workgroup-uniform
-        rank_rows_few<NWAVES>(rk, m, X + row0 * F, static_cast<int>(left));
+        rank_rows_few<NWAVES>(rk, m, X + row0 * F, static_cast<int>(left), f_begin, f_end, reg_begin, reg_end);
         return;
     }
     RankTablePtr thr_base = (RankTablePtr)m.feat_thr_base;
@@ -212,7 +228,7 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         have[r] = row < n_rows;
         xrow[r] = X + (have[r] ? row : row0) * F;
     }
-    for (int f0 = wave * U; f0 < F; f0 += NWAVES * U) {
+    for (int f0 = f_begin + wave * U; f0 < f_end; f0 += NWAVES * U) {
         float x[U][2];
         RankBracket b[U][2];
         int tb[U], n_thr[U];
@@ -220,20 +236,20 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         // all feature values first, then all bucket reads: the loads of one kind go out together
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int f = f0 + u < F ? f0 + u : F - 1;  // wave-uniform; the duplicate is not stored
+            const int f = f0 + u < f_end ? f0 + u : f_end - 1;  // wave-uniform; the duplicate is not stored
             tb[u] = thr_base[f];
             n_thr[u] = thr_base[f + 1] - tb[u];
             fb[u].lo = buckets[f].lo;
             fb[u].scale = buckets[f].scale;
             fb[u].n_buckets = buckets[f].n_buckets;
             fb[u].start_base = buckets[f].start_base;
-            if (f0 + U > F) {
+            if (f0 + U > f_end) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
                     x[u][r] = xrow[r][f];  // a row past the batch reads the tile's first row; its rank is not used
             }
         }
-        if (f0 + U <= F) {  // wave-uniform: the U neighbouring features of a row in one load
+        if (f0 + U <= f_end) {  // wave-uniform: the U neighbouring features of a row in one load
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 // STREAM_X: a non-temporal load, so that X, read once, does not push the model's
@@ -249,40 +265,70 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < 2; ++r) b[u][r] = bucket_bracket(fb[u], m.bucket_start, x[u][r]);
-        // Check of the bracket and the rank inside it.  A feature with 8 thresholds or more
-        // (wave-uniform) reads, besides the two neighbours of the check, the 8 thresholds from
-        // start = min(lo, n - 8) on: if the bracket holds, every threshold below lo is < x and
-        // none from hi on is, so rank = start + #{i < 8 : thr[start + i] < x} whenever hi <= start + 8
-        // -- no search.  What is left open (a bracket that does not hold, or a wider one, or a
-        // feature with fewer thresholds) goes through the binary search below.
+            for (int r = 0; r < 2; ++r) {
+                // a feature with 8 thresholds or more only uses the lower end of the bracket
+                if (n_thr[u] >= 8) {
+                    const int32_t *st = m.bucket_start + fb[u].start_base;
+                    b[u][r].lo = st[bucket_index_fast(x[u][r], fb[u].lo, fb[u].scale, fb[u].n_buckets)];
+                    b[u][r].hi = n_thr[u];
+                } else {
+                    b[u][r] = bucket_bracket(fb[u], m.bucket_start, x[u][r]);
+                }
+            }
+        // The rank from the bracket.  A feature with 8 thresholds or more (wave-uniform) reads one
+        // window of 8 thresholds, thr[wb .. wb + 8) with wb = clamp(lo - 1, 0, n - 8), and counts those
+        // below x: rank = wb + count, provided the window decides it -- every threshold before the
+        // window is below x (the window starts at 0, or its first threshold already is below x) and
+        // every threshold after it is not (some threshold of the window is not below x, or the
+        // window ends the list).  That holds whenever the bucket's lower bound is within 6 of the
+        // rank; it costs one table read and one window per lookup, and nothing of it rests on the
+        // table having been built with the arithmetic bucket_index runs here.  What the window does
+        // not decide, and features with fewer thresholds, go through the binary search below.
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float *thr = m.thr_sorted + tb[u];
             const int n = n_thr[u];
             if (n >= 8) {
-                float tl[2], th[2];
                 FloatRun<8> w[2];
-                int start[2];
+                int wb[2];
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
-                    const RankBracket c = b[u][r];
-                    start[r] = c.lo < n - 8 ? c.lo : n - 8;
-                    tl[r] = load_at<float>(thr, static_cast<uint32_t>(c.lo > 0 ? c.lo - 1 : 0) << 2);
-                    th[r] = load_at<float>(thr, static_cast<uint32_t>(c.hi < n - 1 ? c.hi : n - 1) << 2);
-                    w[r] = load_at<FloatRun<8>>(thr, static_cast<uint32_t>(start[r]) << 2);
+                    const int lo = b[u][r].lo - 1;
+                    wb[r] = lo < 0 ? 0 : (lo > n - 8 ? n - 8 : lo);
+                    w[r] = load_at<FloatRun<8>>(thr, static_cast<uint32_t>(wb[r]) << 2);
                 }
+                bool above[2];  // the whole window is below x and thresholds follow it: look further up
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
-                    const RankBracket c = b[u][r];
                     const float xv = x[u][r];
-                    const bool ok = ((c.lo == 0) | (tl[r] < xv)) & ((c.hi == n) | !(th[r] < xv));
-                    int rank = start[r];
+                    int count = 0;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) rank += (w[r].v[i] < xv) ? 1 : 0;
-                    const bool closed = ok & (c.hi <= start[r] + 8);
-                    b[u][r].lo = closed ? rank : (ok ? c.lo : 0);
-                    b[u][r].hi = closed ? rank : (ok ? c.hi : n);
+                    for (int i = 0; i < 8; ++i) count += (w[r].v[i] < xv) ? 1 : 0;
+                    const bool closed = ((wb[r] == 0) | (count >= 1)) & ((count < 8) | (wb[r] + 8 >= n));
+                    above[r] = (count == 8) & (wb[r] + 8 < n);
+                    b[u][r].lo = closed ? wb[r] + count : 0;
+                    b[u][r].hi = closed ? wb[r] + count : n;
+                }
+                // A bucket of a dense region can hold more thresholds than a window: slide the
+                // window up, for the lanes concerned only (the reads of the others are masked off),
+                // a few times before the search below takes over.
+                for (int round = 0; round < 3 && __any(above[0] | above[1]); ++round) {
+#pragma unroll
+                    for (int r = 0; r < 2; ++r) {
+                        if (above[r]) {
+                            wb[r] = wb[r] + 7 > n - 8 ? n - 8 : wb[r] + 7;
+                            const FloatRun<8> v = load_at<FloatRun<8>>(thr, static_cast<uint32_t>(wb[r]) << 2);
+                            const float xv = x[u][r];
+                            int count = 0;
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) count += (v.v[i] < xv) ? 1 : 0;
+                            // the window's first threshold is below x here (it was in the last window)
+                            const bool closed = (count < 8) | (wb[r] + 8 >= n);
+                            above[r] = !closed;
+                            b[u][r].lo = closed ? wb[r] + count : 0;
+                            b[u][r].hi = closed ? wb[r] + count : n;
+                        }
+                    }
                 }
             } else {
 #pragma unroll
@@ -324,7 +370,7 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (f0 + u >= F) continue;
+            if (f0 + u >= f_end) continue;
             int rank[2];
 #pragma unroll
             for (int r = 0; r < 2; ++r)
@@ -339,10 +385,92 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
                     rv = rv < 0 ? 0 : (rv > len ? len : rv);
                     packed |= static_cast<uint32_t>(rank_code_bits(rv)) << (16 * r);
                 }
-                rk[(reg0 + s) * TILE + lane] = packed;
+                rk[(reg0 + s - reg_begin) * TILE + lane] = packed;
             }
         }
     }
 }
+
+// All features, all rank registers.
+template <int NWAVES, int U = 2, bool STREAM_X = false>
+__device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const float *__restrict__ X,
+                                          int64_t row0, int64_t n_rows, int wave, int lane)
+{
+    rank_rows<NWAVES, U, STREAM_X>(rk, m, X, row0, n_rows, wave, lane, 0, m.n_features, 0, m.rank_regs);
+}
+
+
+// ---------------------------------------------------------------------------------------
+// The comparison through the vector-register index mode, shared by the kernels that keep their
+// rank registers in VGPRs.
+// ---------------------------------------------------------------------------------------
+typedef uint32_t v32u __attribute__((ext_vector_type(32)));
+
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) uint32_t *ProgPtr;
+typedef const __attribute__((address_space(4))) TreeMeta *MetaPtr;
+#else
+typedef const uint32_t *ProgPtr;  // host pass: the kernel body is only parsed
+typedef const TreeMeta *MetaPtr;
+#endif
+
+// One entry of the compact split program is one scalar register: -4 code(j') in the high half,
+// the rank register's index in the low byte.  s_set_gpr_idx_* reads only the low byte; the
+// packed multiply-add reads the high half for both rows (op_sel / op_sel_hi of the addend) and
+// the inline constant's low half for both (op_sel_hi 0: a packed inline constant fills only it).
+// The index mode lives in M0.  M0 is a register the compiler reserves: it never keeps a value of
+// its own in it across an inline-assembly statement (it sets M0 immediately before each use it
+// generates, and rejects M0 on a clobber list as having no effect), so the statements below may
+// write it freely.
+struct Entry8 {
+    uint32_t e[8];
+};
+
+#define FOREST_RANK_CMP(B, n) \
+    "v_pk_fma_f16 %[d" #n "], " B ", 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
+#define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
+
+// The eight comparisons alone; the outcomes (1.0 or 0.0 in each half) go to the matrix core.
+#define FOREST_RANK_CMP_ONLY(B)                                                                   \
+    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
+        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
+            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
+                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
+                    "s_set_gpr_idx_off"
+
+#define FOREST_RANK_CMP_OUTS                                                                                  \
+    [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]), [d5] "=&v"(d[5]), \
+        [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
+#define FOREST_RANK_CMP_INS                                                                                \
+    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]), [e5] "s"(q.e[5]), \
+        [e6] "s"(q.e[6]), [e7] "s"(q.e[7])
+
+__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[1])
+{
+    asm volatile(FOREST_RANK_CMP_ONLY("v64") : FOREST_RANK_CMP_OUTS : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]));
+}
+
+__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[2])
+{
+    asm volatile(FOREST_RANK_CMP_ONLY("v64")
+                 : FOREST_RANK_CMP_OUTS
+                 : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
+}
+
+template <int N>
+struct Batch {
+    Entry8 q[N / 8];
+};
+
+template <int N>
+__device__ __forceinline__ Batch<N> load_batch(ProgPtr p)
+{
+    Batch<N> b;
+#pragma unroll
+    for (int j = 0; j < N; ++j) b.q[j / 8].e[j % 8] = p[j];
+    return b;
+}
+
 
 }  // namespace forest_impl

@@ -75,6 +75,31 @@ def test_irregular_forests_with_ties(seed):
     assert info["kernel_kind"] == 0 and info["kernel_path"] == 3
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_register_bank_kernel_on_large_batches(seed):
+    """Irregular trees with one scalar column or at most two-wide vector leaves: batches of
+    small_batch_rows rows or more run the register-bank kernel (whole trees evaluated by the wave
+    that holds each node's rank register, one lane per (row, tree) in the walk)."""
+    rng = np.random.default_rng(300 + seed)
+    K = 1 + seed % 2
+    F = int(rng.choice([2, 31, 256]))
+    T = int(rng.choice([1, 3, 4, 5, 22]))
+    f = wl.random_forest(1300 + seed, n_trees=T, n_features=F, max_depth=int(rng.integers(1, 11)),
+                         stop_prob=float(rng.choice([0.05, 0.2])), n_outputs=K, leaf_width=K,
+                         grid_thresholds=bool(seed % 4 == 0), aggregate=int(seed % 3 == 0),
+                         transform=(wl.TRANSFORM_SOFTMAX if K == 2 and seed % 4 == 1 else wl.TRANSFORM_NONE))
+    rows = 65536 + int(rng.integers(0, 300))
+    X = rng.standard_normal((rows, F)).astype(np.float32)
+    if seed % 4 == 0:
+        X = np.round(X * 2) / 2
+    X[5, :] = np.nan
+    X[6, :] = np.inf
+    X[7, :] = -np.inf
+    info = _check(f, X)
+    if info["kernel_kind"] == 0:     # a draw of shallow trees that all came out full runs the rank kernel
+        assert info["kernel_path"] == 3 and info["rank_banks"] == 1
+
+
 @pytest.mark.parametrize("seed", range(64))
 def test_random_models_and_batches(seed):
     """Everything drawn at once: full or irregular trees, feature and tree counts, depth, output

@@ -8,6 +8,7 @@ import pytest
 import paper_2301_13441_amd as pk
 from paper_2301_13441_amd import binding
 import workloads as wl
+import oracle
 from oracle import matrix_form as mf
 
 
@@ -265,6 +266,91 @@ def test_rank_bucket_tables_bracket_every_rank(case):
             rank = int(np.sum(thr < x))
             b = _bucket_of(x, lo, scale, count)
             assert start[b] <= rank <= start[b + 1], (case, feat, float(x), b)
+
+
+def _simulate_bank_program(f, v, X):
+    """Leaf node reached per (row, caller tree), computed from the register-bank program alone:
+    every entry of every wave's stream is decoded back to (feature, threshold) and compared as
+    float32, the outcome goes to the entry's bit of the batch buffer, then the child references
+    are followed from each tree's root.  Nothing of the kernels' rank arithmetic is used."""
+    n_codes, _, _ = binding.forest_rank_code(0)
+    seg = n_codes - 1
+    entry_to_j = {binding.forest_rank_code(q)[2]: q for q in range(n_codes)}
+    tbase = v["rank_threshold_base"]
+    n_thr = np.diff(tbase)
+    regs_of = (n_thr + seg - 1) // seg
+    vfirst = np.concatenate([[0], np.cumsum(regs_of)])
+    reg_feature = np.repeat(np.arange(len(n_thr)), regs_of)
+    nb, nw, nt, U = v["bank_batches"], v["bank_waves"], v["bank_trees"], v["bank_unit"]
+    T = len(f.tree_offset) - 1
+    out = np.full((len(X), T), -1, dtype=np.int64)
+    cursor = v["bank_stream_base"].astype(np.int64).copy()
+    for b in range(nb):
+        n_units = int(v["bank_span"][b, :, 0].sum())
+        assert n_units <= v["bank_max_units"]
+        bits = np.zeros((len(X), n_units * U), dtype=bool)
+        for w in range(nw):
+            units, base = (int(z) for z in v["bank_span"][b, w])
+            for k in range(units * U):
+                e = int(v["bank_prog"][cursor[w] + k])
+                reg = int(v["bank_reg"][w, e & 0xff])
+                jl = entry_to_j[e >> 16]
+                slot = (base + k // U) * U + 8 * ((k // 8) % (U // 8)) + 7 - k % 8
+                if jl == seg:              # padding: compares against the largest code, never true
+                    continue
+                feat = int(reg_feature[reg])
+                thr = v["rank_threshold"][tbase[feat] + (reg - vfirst[feat]) * seg + jl]
+                bits[:, slot] = ~(X[:, feat] <= thr)
+            cursor[w] += units * U
+        slot_base, n_slots, leaf_base, _ = (int(z) for z in v["bank_batch"][b])
+        assert n_slots == n_units * U
+        child = v["bank_child"][slot_base:slot_base + n_slots].astype(np.int64)
+        for j in range(nt):
+            root, _, caller, valid = (int(z) for z in v["bank_tree"][b, j])
+            if not valid:
+                continue
+            ref = np.full(len(X), root, dtype=np.int64)
+            for _ in range(70):
+                on = (ref & 0x8000) == 0
+                if not on.any():
+                    break
+                idx = ref[on]
+                ref[on] = np.where(bits[on, idx], child[idx] >> 16, child[idx] & 0xffff)
+            assert ((ref & 0x8000) != 0).all()
+            leaf = leaf_base + (ref & 0x7fff)
+            assert (v["order_leaf_tree"][leaf] == caller).all()
+            out[:, caller] = v["order_leaf_node"][leaf]
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_register_bank_program_reaches_the_oracles_leaves(seed):
+    rng = np.random.default_rng(40 + seed)
+    F = int(rng.choice([3, 40, 256]))
+    f = wl.random_forest(950 + seed, n_trees=int(rng.integers(1, 14)), n_features=F, max_depth=int(rng.integers(1, 10)),
+                         stop_prob=0.15, n_outputs=(2 if seed % 2 else 1), leaf_width=(2 if seed % 2 else 1),
+                         grid_thresholds=bool(seed % 3 == 0))
+    v = pk.forest_pack(f)
+    assert v["kernel_path"] == 3 and v["bank_batches"] == -(-(len(f.tree_offset) - 1) // v["bank_trees"])
+    X = rng.standard_normal((150, F)).astype(np.float32)
+    if seed % 3 == 0:
+        X = np.round(X * 2) / 2
+    X[0, :] = np.nan
+    ref = oracle.predict(f, X, want_leaves=True)
+    np.testing.assert_array_equal(_simulate_bank_program(f, v, X), ref.leaf_node_id)
+    # every internal node sits in exactly one slot, and each wave holds at most bank_regs registers
+    used = int((v["bank_child"] != 0xffffffff).sum())
+    assert used == int(v["tree_n_internal"].sum())
+
+
+def test_register_bank_program_only_where_it_fits():
+    # one tree of thousands of internal nodes: its batch buffer would not fit the LDS budget
+    big = wl.random_forest(7, n_trees=1, n_features=20, max_depth=14, stop_prob=0.02, allow_single_leaf=False)
+    v = pk.forest_pack(big)
+    assert v["tree_n_internal"][0] > 2400 and v["kernel_path"] == 3 and v["bank_batches"] == 0
+    # many output columns keep the LDS-resident kernel
+    wide = wl.random_forest(8, n_trees=9, n_features=20, max_depth=6, n_outputs=5, leaf_width=5)
+    assert pk.forest_pack(wide)["bank_batches"] == 0
 
 
 def test_pinned_stream_register_check_catches_a_violation():
