@@ -81,6 +81,13 @@ __device__ __forceinline__ void bank_compare(v8i &da, v8i &db, const Entry8 &q, 
                    [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), "{v[64:95]}"(xa), "{v[96:127]}"(xb));
 }
 
+// Makes whatever is computed from `p` afterwards wait for `set` to have arrived: the statement
+// reads the set's first register and hands `p` back as a value the compiler knows nothing about.
+__device__ __forceinline__ void issue_after(ProgPtr &p, const Batch<16> &set)
+{
+    asm volatile("" : "+s"(p) : "s"(set.q[0].e[0]));
+}
+
 // sum over the lanes that share a row (one per tree of the batch), the same bits in each
 __device__ __forceinline__ double row_sum(double v)
 {
@@ -166,17 +173,24 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             gb = bits.collect_b(db, bits.bias);
             pending = true;
         };
+        // Scalar loads may return out of order, so a wait for one is a wait for all that are in
+        // flight: only one load of the stream is ever in flight, issued right after the wait
+        // for the set evaluated next -- tied to it through the stream pointer -- so that it has
+        // the whole evaluation of that set, two groups, to arrive.
         int u = 0;
         for (; u + 1 < n_units; u += 2) {
+            issue_after(p, set_a);
             const Batch<16> set_b = load_batch<16>(p + 16);
             group(set_a.q[0]);
             group(set_a.q[1]);
+            issue_after(p, set_b);
             set_a = load_batch<16>(p + 32);
             group(set_b.q[0]);
             group(set_b.q[1]);
             p += 32;
         }
         if (u < n_units) {
+            issue_after(p, set_a);
             const Batch<16> set_b = load_batch<16>(p + 16);
             group(set_a.q[0]);
             group(set_a.q[1]);
