@@ -35,9 +35,6 @@
 #include "forest_kernel_common.hpp"
 #include "forest_rank_common.hpp"
 
-#ifndef BANK_EXPERIMENT
-#define BANK_EXPERIMENT 0
-#endif
 namespace forest_impl {
 namespace {
 
@@ -132,9 +129,6 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         }
     };
 
-#if BANK_EXPERIMENT == 4
-    if (m.bank.batches >= 0) return;
-#endif
     for (int b = 0; b < m.bank.batches; ++b) {
         const int n_units = span[b * BANK_WAVES + wave].n_units;
         // The batch's child references go to LDS: the walk reads one per step and lane, which
@@ -145,27 +139,29 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         u32x4 staged = {0u, 0u, 0u, 0u};
         if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + batch[b].slot_base)[threadIdx.x];
         const BankTree bt = m.bank.tree[b * BANK_TREES + walk_tree];  // used after the evaluation
-        // the bytes of the lane's four rows for a group: dst[0], dst[64], dst[128], dst[192]
-        uint8_t *dst = buf + span[b * BANK_WAVES + wave].unit_base * (2 * BANK_ROWS) + lane;
-#if BANK_EXPERIMENT != 2 && BANK_EXPERIMENT != 3
+        // `prev`: where the bytes of the lane's four rows go for the group BEFORE the first group of
+        // the current pair of units (prev[0], prev[64], prev[128], prev[192]); the groups of the pair
+        // are at prev + 256, + 512, ...  The buffer starts 256 bytes into the LDS, so `prev` is a
+        // valid address for a wave's first group too (nothing is stored through it then).
+        uint8_t *prev = buf + span[b * BANK_WAVES + wave].unit_base * (2 * BANK_ROWS) + lane - BANK_ROWS;
         // ---- evaluation: this wave's nodes of the batch.  A group's byte is still being
         // collected by the matrix core when its last comparison has issued, so it is stored
         // after the comparisons of the next group.
         v4f ga = bits.bias, gb = bits.bias;
         bool pending = false;
-        auto group = [&](const Entry8 &q) {
+        auto store = [&](int k) {  // the bytes of group k - 1 of the pair (k = 0: the last one of the pair before)
+            prev[k * BANK_ROWS] = static_cast<uint8_t>(__float_as_uint(ga[0]));
+            prev[k * BANK_ROWS + TILE] = static_cast<uint8_t>(__float_as_uint(ga[1]));
+            prev[k * BANK_ROWS + 2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
+            prev[k * BANK_ROWS + 3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
+        };
+        auto group = [&](const Entry8 &q, int k) {  // k: constant at every call
             v8i da, db;
             bank_compare(da, db, q, xa, xb);
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_sched_barrier(0);
 #endif
-            if (pending) {
-                dst[0] = static_cast<uint8_t>(__float_as_uint(ga[0]));
-                dst[TILE] = static_cast<uint8_t>(__float_as_uint(ga[1]));
-                dst[2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
-                dst[3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
-                dst += BANK_ROWS;
-            }
+            if (pending) store(k);
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -181,29 +177,25 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         for (; u + 1 < n_units; u += 2) {
             issue_after(p, set_a);
             const Batch<16> set_b = load_batch<16>(p + 16);
-            group(set_a.q[0]);
-            group(set_a.q[1]);
+            group(set_a.q[0], 0);
+            group(set_a.q[1], 1);
             issue_after(p, set_b);
             set_a = load_batch<16>(p + 32);
-            group(set_b.q[0]);
-            group(set_b.q[1]);
+            group(set_b.q[0], 2);
+            group(set_b.q[1], 3);
             p += 32;
+            prev += 4 * BANK_ROWS;
         }
         if (u < n_units) {
             issue_after(p, set_a);
             const Batch<16> set_b = load_batch<16>(p + 16);
-            group(set_a.q[0]);
-            group(set_a.q[1]);
+            group(set_a.q[0], 0);
+            group(set_a.q[1], 1);
             set_a = set_b;
             p += 16;
+            prev += 2 * BANK_ROWS;
         }
-        if (pending) {
-            dst[0] = static_cast<uint8_t>(__float_as_uint(ga[0]));
-            dst[TILE] = static_cast<uint8_t>(__float_as_uint(ga[1]));
-            dst[2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
-            dst[3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
-        }
-#endif
+        if (pending) store(0);
         if (stage) reinterpret_cast<u32x4 *>(child_lds)[threadIdx.x] = staged;
         if (b > 0) consume_pending();  // the last batch's leaves
         __syncthreads();  // the batch's bits and child references are complete
@@ -211,9 +203,6 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         // ---- walk: one (row, tree) per lane
         const uint8_t *bits_of_row = buf + walk_row;
         uint32_t ref = static_cast<uint32_t>(bt.root_ref);
-#if BANK_EXPERIMENT == 1 || BANK_EXPERIMENT == 3
-        ref = BANK_LEAF_FLAG;
-#endif
         while (__any(!(ref & BANK_LEAF_FLAG))) {
             if (!(ref & BANK_LEAF_FLAG)) {
                 const uint32_t byte = bits_of_row[(ref >> 3) * BANK_ROWS];
@@ -275,8 +264,8 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     }
 
     double sum[2] = {0.0, 0.0};
-    uint8_t *buf = reinterpret_cast<uint8_t *>(smem);
-    uint32_t *child_lds = reinterpret_cast<uint32_t *>(smem + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
+    uint8_t *buf = reinterpret_cast<uint8_t *>(smem) + BANK_ROWS;  // see `prev` in bank_trees
+    uint32_t *child_lds = reinterpret_cast<uint32_t *>(buf + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
     bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane, row0, n_rows, leaf_out);
     if (MODE == BANK_LEAVES) return;
     const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;
@@ -291,9 +280,9 @@ size_t rankbank_lds_bytes(const DevModel &m)
     for (int p = 0; p < m.bank.passes; ++p)
         pass_regs = m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] > pass_regs ? m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] : pass_regs;
     const size_t tile = 2 * sizeof(uint32_t) * TILE * static_cast<size_t>(pass_regs);
-    // outcome bytes of a batch, then its child references (a word per slot)
-    const size_t bytes = (static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) + sizeof(uint32_t) * BANK_UNIT) *
-                         static_cast<size_t>(m.bank.max_units);
+    // a row of spare bytes, the outcome bytes of a batch, then its child references (a word per slot)
+    const size_t bytes = BANK_ROWS + (static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) + sizeof(uint32_t) * BANK_UNIT) *
+                                         static_cast<size_t>(m.bank.max_units);
     return tile > bytes ? tile : bytes;
 }
 

@@ -526,8 +526,10 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             for (int w = 0; w < BANK_WAVES; ++w) units += (per_wave[w] + BANK_UNIT - 1) / BANK_UNIT;
             return units;
         };
-        // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot
-        const int64_t budget_units = static_cast<int64_t>(BANK_MAX_LDS / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
+        // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot; the
+        // kernel keeps one row of bytes in front of the buffer
+        const int64_t budget_units =
+            static_cast<int64_t>((BANK_MAX_LDS - BANK_ROWS) / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
         int32_t n_batches = 0;
         for (int32_t first = 0; first < T && fits; ++n_batches) {
             int32_t count = 1;
