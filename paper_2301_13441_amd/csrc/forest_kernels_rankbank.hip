@@ -19,8 +19,8 @@
 //   * After a barrier every lane walks one (row, tree) of the batch from the root: the outcome bit
 //     of its slot and the slot's child references pick the next slot, until a leaf (the bit-level
 //     form of matmul(., W3) + argmax).  A wave owns 32 of the workgroup's rows for all trees, so
-//     the sums over trees never leave the wave: the 2 lanes of a row add their leaf values with
-//     one cross-lane addition, in fp64.
+//     the sums over trees never leave the wave: each of the 2 lanes of a row sums the trees it
+//     walked, in fp64, and one cross-lane addition at the end joins them.
 //
 // Against the LDS-resident rank kernel this takes the LDS read per comparison (the LDS was the
 // busiest unit there), half of the scalar instructions per comparison and the per-group
@@ -123,9 +123,10 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         if (MODE == BANK_LEAVES) {
             if (pend_valid && row < n_rows) leaf_out[row * T + pend_tree] = pend_node;
         } else {
-            // K == 1 (scalar leaves) or K == leaf width <= 2: the sums stay in registers
-            sum[0] += row_sum(pend_valid ? static_cast<double>(pend_v0) : 0.0);
-            if (K > 1) sum[1] += row_sum(pend_valid ? static_cast<double>(pend_v1) : 0.0);
+            // K == 1 (scalar leaves) or K == leaf width <= 2: the sums stay in registers, one per
+            // lane (the trees the lane walked); the lanes of a row add theirs up at the end
+            sum[0] += pend_valid ? static_cast<double>(pend_v0) : 0.0;
+            if (K > 1) sum[1] += pend_valid ? static_cast<double>(pend_v1) : 0.0;
         }
     };
 
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     if (MODE == BANK_LEAVES) return;
     const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;
     // a copy with run-time indices: indexed that way `sum` itself would live in scratch memory
-    double raw[2] = {sum[0], sum[1]};
+    double raw[2] = {row_sum(sum[0]), row_sum(sum[1])};
     if (lane % BANK_TREES == 0 && row < n_rows) finish_values(m, raw, 1, row, scores, labels);
 }
 
