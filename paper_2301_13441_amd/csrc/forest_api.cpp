@@ -160,7 +160,11 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_btree = place<BankTree>(cur, m.bank_tree.size());
     const size_t o_bspan = place<BankSpan>(cur, m.bank_span.size());
     const size_t o_bslot = place<BankBatch>(cur, m.bank_batch.size());
-    const size_t o_breg = place<int32_t>(cur, m.bank_reg.size());
+    const size_t o_bpass = place<BankPass>(cur, m.bank_pass.size());
+    const size_t o_bpw = place<BankPassWave>(cur, m.bank_pass_wave.size());
+    const size_t o_btodo = place<BankTodo>(cur, m.bank_todo.size());
+    const size_t o_bfeat = place<BankFeat>(cur, m.bank_feat.size());
+    const size_t o_btab = place<uint16_t>(cur, m.bank_tab.size());
     const size_t model_bytes = (cur + 255) & ~size_t{255};
     // workspaces of split launches, not uploaded
     const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
@@ -199,7 +203,11 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_btree, m.bank_tree.data(), m.bank_tree.size() * sizeof(BankTree)) &&
                     up(o_bspan, m.bank_span.data(), m.bank_span.size() * sizeof(BankSpan)) &&
                     up(o_bslot, m.bank_batch.data(), m.bank_batch.size() * sizeof(BankBatch)) &&
-                    up(o_breg, m.bank_reg.data(), m.bank_reg.size() * sizeof(int32_t));
+                    up(o_bpass, m.bank_pass.data(), m.bank_pass.size() * sizeof(BankPass)) &&
+                    up(o_bpw, m.bank_pass_wave.data(), m.bank_pass_wave.size() * sizeof(BankPassWave)) &&
+                    up(o_btodo, m.bank_todo.data(), m.bank_todo.size() * sizeof(BankTodo)) &&
+                    up(o_bfeat, m.bank_feat.data(), m.bank_feat.size() * sizeof(BankFeat)) &&
+                    up(o_btab, m.bank_tab.data(), m.bank_tab.size() * sizeof(uint16_t));
     if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(f->blob);
@@ -240,16 +248,16 @@ int forest_load(const forest_desc *desc, forest **out)
     d.bank.tree = reinterpret_cast<const BankTree *>(b + o_btree);
     d.bank.span = reinterpret_cast<const BankSpan *>(b + o_bspan);
     d.bank.batch = reinterpret_cast<const BankBatch *>(b + o_bslot);
-    d.bank.reg = reinterpret_cast<const int32_t *>(b + o_breg);
+    d.bank.pass = reinterpret_cast<const BankPass *>(b + o_bpass);
+    d.bank.pass_wave = reinterpret_cast<const BankPassWave *>(b + o_bpw);
+    d.bank.todo = reinterpret_cast<const BankTodo *>(b + o_btodo);
+    d.bank.feat = reinterpret_cast<const BankFeat *>(b + o_bfeat);
+    d.bank.tab = reinterpret_cast<const uint16_t *>(b + o_btab);
     for (int w = 0; w < BANK_WAVES; ++w) d.bank.stream_base[w] = m.bank_stream_base[w];
     d.bank.batches = m.bank_batches;
     d.bank.max_units = m.bank_max_units;
     d.bank.enabled = m.bank_enabled;
-    d.bank.passes = m.bank_passes;
-    for (int p = 0; p <= BANK_MAX_PASSES; ++p) {
-        d.bank.pass_feature[p] = m.bank_pass_feature[p];
-        d.bank.pass_reg[p] = m.bank_pass_reg[p];
-    }
+    d.bank.passes = static_cast<int32_t>(m.bank_pass.size());
     d.n_splits = 1;
     d.n_entries = static_cast<int64_t>(m.prog32.size() > m.prog.size() ? m.prog32.size() : m.prog.size());
     d.split_rows = 0;

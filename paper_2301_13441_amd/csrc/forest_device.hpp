@@ -16,12 +16,14 @@ struct BankDev {
     const BankTree *tree;
     const BankSpan *span;
     const BankBatch *batch;
-    const int32_t *reg;
+    const BankPass *pass;           // [passes]
+    const BankPassWave *pass_wave;  // [passes][BANK_WAVES]
+    const BankTodo *todo;
+    const BankFeat *feat;           // [n_features]
+    const uint16_t *tab;
     int32_t stream_base[BANK_WAVES];
     int32_t batches, max_units, enabled;
     int32_t passes;
-    int32_t pass_feature[BANK_MAX_PASSES + 1];
-    int32_t pass_reg[BANK_MAX_PASSES + 1];
 };
 
 struct DevModel {

@@ -41,17 +41,24 @@ namespace {
 constexpr int BANK_BLOCK = TILE * BANK_WAVES;
 constexpr int BANK_ROWS_PER_WAVE = BANK_ROWS / BANK_WAVES;  // rows a wave walks
 static_assert(BANK_ROWS_PER_WAVE * BANK_TREES == TILE, "one lane per (row, tree) of a batch");
+static_assert(BANK_ROWS == BANK_WAVES * 32 && BANK_PASS_FEATURES == 64, "the staging step: 16 lanes per row, 32 rows per step");
 static_assert(BANK_REGS == 32 && BANK_ROWS == 4 * TILE, "the comparison statement addresses v64..v95 and v96..v127");
 static_assert(BANK_UNIT == 16, "a unit is one 16-register scalar load: two groups of 8 entries");
 
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef const __attribute__((address_space(4))) BankSpan *SpanPtr;
 typedef const __attribute__((address_space(4))) BankBatch *BatchPtr;
-typedef const __attribute__((address_space(4))) int32_t *IntPtr;
+typedef const __attribute__((address_space(4))) BankPass *PassPtr;
+typedef const __attribute__((address_space(4))) BankPassWave *PassWavePtr;
+typedef const __attribute__((address_space(4))) BankTodo *TodoPtr;
+typedef const __attribute__((address_space(4))) BankFeat *FeatPtr;
 #else
 typedef const BankSpan *SpanPtr;  // host pass: the kernel body is only parsed
 typedef const BankBatch *BatchPtr;
-typedef const int32_t *IntPtr;
+typedef const BankPass *PassPtr;
+typedef const BankPassWave *PassWavePtr;
+typedef const BankTodo *TodoPtr;
+typedef const BankFeat *FeatPtr;
 #endif
 
 enum { BANK_SUMS = 0, BANK_LEAVES = 1 };
@@ -76,6 +83,161 @@ __device__ __forceinline__ void bank_compare(v8i &da, v8i &db, const Entry8 &q, 
                  : "={v[48:55]}"(da), "={v[56:63]}"(db)
                  : [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),
                    [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), "{v[64:95]}"(xa), "{v[96:127]}"(xb));
+}
+
+// Register `slot` (wave-uniform) of the wave's bank takes `a` (rows l and l + 64 of the lane) and `b`
+// (rows l + 128 and l + 192): a vector element written at a run-time index, which the compiler
+// turns into the index mode applied to the destination.
+__device__ __forceinline__ void bank_set(v32u &xa, v32u &xb, int slot, uint32_t a, uint32_t b)
+{
+    xa[slot] = a;
+    xb[slot] = b;
+}
+
+// The lane's four values of one column of the staged block, and where their windows begin.
+struct BankLookup {
+    float x[4];
+    uint32_t at[4];  // byte offset of the window in the feature's thresholds
+};
+
+// First half of a fast lookup: the values out of LDS, their buckets, and the table entries on
+// their way (a window begins at the last threshold of the lower buckets, or where BANK_WINDOW
+// thresholds still fit).
+__device__ __forceinline__ BankLookup bank_lookup_begin(const DevModel &m, const float *column, const BankFeat &bf)
+{
+    BankLookup q;
+    const char *tab = reinterpret_cast<const char *>(m.bank.tab) + bf.tab_off;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        q.x[j] = column[j * TILE * BANK_TILE_PITCH];
+        const float t = fminf(fmaxf((q.x[j] - bf.lo) * bf.scale, 0.0f), bf.last_bucket);  // NaN: bucket 0
+        const uint32_t bucket = static_cast<uint32_t>(static_cast<int32_t>(t));
+        q.at[j] = static_cast<uint32_t>(load_at<uint16_t>(tab, bucket << 1)) << 2;
+    }
+    return q;
+}
+
+// Second half: rank(x) = #{i : thr[i] < x} from the window thr[w .. w + BANK_WINDOW): w plus the
+// number of its thresholds below x, provided every threshold before the window is below x (the
+// window starts the list, or its first threshold is below x) and none after it is (it ends the
+// list, or its last threshold is not below x).  The check is against the thresholds themselves;
+// whatever it does not settle (a bucket fuller than a window, NaN) takes the general lookup.
+// Returns the two packed registers' worth of codes: a feature that qualifies has at most
+// BANK_FAST_MAX_THRESHOLDS thresholds, all in one register, and every rank in the lower half of
+// the codes, where code(q) = 0xf3ff - q.
+__device__ __forceinline__ void bank_lookup_end(const DevModel &m, const BankLookup &q, const BankFeat &bf, int feature,
+                                                uint32_t &pa, uint32_t &pb)
+{
+    const char *thr = reinterpret_cast<const char *>(m.thr_sorted) + bf.thr_off;
+    const uint32_t last_at = static_cast<uint32_t>(bf.n - BANK_WINDOW) << 2;
+    int rank[4];
+    bool open[4];
+    // two rows at a time: their windows are 16 registers, and the bank itself takes half the file
+#pragma unroll
+    for (int h = 0; h < 4; h += 2) {
+        FloatRun<BANK_WINDOW> w[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) w[j] = load_at<FloatRun<BANK_WINDOW>>(thr, q.at[h + j]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float x = q.x[h + j];
+            int count = 0;
+#pragma unroll
+            for (int i = 0; i < BANK_WINDOW; ++i) count += (w[j].v[i] < x) ? 1 : 0;
+            const bool first_below = w[j].v[0] < x, last_below = w[j].v[BANK_WINDOW - 1] < x;
+            open[h + j] = (!first_below & (q.at[h + j] != 0u)) | (last_below & (q.at[h + j] != last_at)) | (x != x);
+            rank[h + j] = static_cast<int>(q.at[h + j] >> 2) + count;
+        }
+    }
+    if (__any(open[0] | open[1] | open[2] | open[3])) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (open[j]) rank[j] = rank_of(m, feature, q.x[j]);
+    }
+    constexpr uint32_t CODE0 = 0x8000u | (0x5c00u + RANK_CODES / 2 - 1);  // code(0)
+    pa = (CODE0 - static_cast<uint32_t>(rank[0])) | ((CODE0 - static_cast<uint32_t>(rank[1])) << 16);
+    pb = (CODE0 - static_cast<uint32_t>(rank[2])) | ((CODE0 - static_cast<uint32_t>(rank[3])) << 16);
+}
+
+// The ranks of the workgroup's rows, straight into the waves' banks.  X is read in blocks of up to
+// BANK_PASS_FEATURES columns: every row's part of the block is contiguous in memory and goes to
+// LDS as it lies there (16 bytes per lane, 16 lanes per row, each 128-byte line read once, by one
+// wave, and not kept in the caches: the model's tables stay there instead); then every wave looks
+// up the registers of its own bank that belong to the block -- all four rows of a lane for one
+// register at a time, the feature's constants in scalar registers, the values read from LDS
+// (a column of the block, rows across lanes, odd pitch), the table reads of the next register
+// under way while the windows of this one are counted.
+__device__ __forceinline__ void bank_ranks(const DevModel &m, const float *__restrict__ X, int64_t row0, int64_t n_rows,
+                                           float *tile, v32u &xa, v32u &xb, int wave, int lane)
+{
+    const int F = m.n_features;
+    PassPtr pass = (PassPtr)m.bank.pass;
+    PassWavePtr pass_wave = (PassWavePtr)m.bank.pass_wave;
+    TodoPtr todo = (TodoPtr)m.bank.todo;
+    FeatPtr feat = (FeatPtr)m.bank.feat;
+    const int piece = threadIdx.x & 15;      // which 16 bytes of a row's part of the block
+    const int row_of_step = threadIdx.x >> 4;  // 32 rows per step
+    for (int p = 0; p < m.bank.passes; ++p) {
+        const int f_begin = pass[p].feat_begin, f_end = pass[p].feat_end;
+        const int f_mine = f_begin + 4 * piece;
+        if (f_mine < f_end) {
+            typedef float Run4 __attribute__((ext_vector_type(4), aligned(4)));
+            Run4 v[BANK_ROWS / 32];
+#pragma unroll
+            for (int s = 0; s < BANK_ROWS / 32; ++s) {
+                const int64_t row = row0 + s * 32 + row_of_step;
+                v[s] = Run4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (row < n_rows) {
+                    const float *src = X + row * F + f_mine;
+                    if (f_mine + 4 <= F) {
+                        v[s] = __builtin_nontemporal_load(reinterpret_cast<const Run4 *>(src));
+                    } else {  // the row ends inside the piece
+#pragma unroll
+                        for (int i = 0; i < 3; ++i)
+                            if (f_mine + i < F) v[s][i] = src[i];
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < BANK_ROWS / 32; ++s) {
+                float *dst = tile + (s * 32 + row_of_step) * BANK_TILE_PITCH + 4 * piece;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dst[i] = v[s][i];
+            }
+        }
+        __syncthreads();  // the block is staged
+        const BankPassWave pw = pass_wave[p * BANK_WAVES + wave];
+        const float *mine = tile + lane * BANK_TILE_PITCH - f_begin;  // + feature: the lane's first row of that column
+        if (pw.n_fast > 0) {
+            BankTodo td = todo[pw.begin];
+            BankFeat bf = feat[td.feature];
+            BankLookup q = bank_lookup_begin(m, mine + td.feature, bf);
+            for (int k = 0; k < pw.n_fast; ++k) {
+                // the next register's first half (the last one repeats itself; not used)
+                const BankTodo td_next = todo[pw.begin + (k + 1 < pw.n_fast ? k + 1 : k)];
+                const BankFeat bf_next = feat[td_next.feature];
+                const BankLookup q_next = bank_lookup_begin(m, mine + td_next.feature, bf_next);
+                uint32_t pa, pb;
+                bank_lookup_end(m, q, bf, td.feature, pa, pb);
+                bank_set(xa, xb, td.slot, pa, pb);
+                td = td_next;
+                bf = bf_next;
+                q = q_next;
+            }
+        }
+        for (int k = 0; k < pw.n_slow; ++k) {  // any number of thresholds, any register of the feature
+            const BankTodo td = todo[pw.begin + pw.n_fast + k];
+            uint32_t code[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int local = rank_of(m, td.feature, mine[td.feature + j * TILE * BANK_TILE_PITCH]) - td.first;
+                local = local < 0 ? 0 : (local > td.len ? td.len : local);
+                code[j] = rank_code_bits(local);
+            }
+            bank_set(xa, xb, td.slot, code[0] | (code[1] << 16), code[2] | (code[3] << 16));
+        }
+        __syncthreads();  // the block's place is free: for the next block, or for the outcome bytes
+    }
 }
 
 // Makes whatever is computed from `p` afterwards wait for `set` to have arrived: the statement
@@ -233,36 +395,17 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     DevModel m, const float *__restrict__ X, int64_t n_rows, float *scores, int32_t *labels, int32_t *leaf_out)
 {
     extern __shared__ __align__(16) char smem[];
-    // LDS: first the rank tiles of a prologue pass (two of [rank register of the pass][lane], two
-    // rows per word: rows 0..127 and rows 128..255 of the workgroup), then, in the same place, the
-    // batch's outcome bytes ([group of 8 slots][row of the workgroup]) and child references.
-    uint32_t *rk = reinterpret_cast<uint32_t *>(smem);
+    // LDS: first a block of X for the rank lookups ([row of the workgroup][column of the block], odd
+    // pitch), then, in the same place, the batch's outcome bytes ([group of 8 slots][row of the
+    // workgroup]) and child references.
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * BANK_ROWS;
 
-    // ranks, a pass of whole features at a time; after each pass a wave takes the registers of
-    // its bank that the pass holds
-    IntPtr bank_reg = (IntPtr)(m.bank.reg + wave * BANK_REGS);
     v32u xa, xb;
-    for (int p = 0; p < m.bank.passes; ++p) {
-        const int reg_begin = m.bank.pass_reg[p], reg_end = m.bank.pass_reg[p + 1];
-        uint32_t *rk_hi = rk + (reg_end - reg_begin) * TILE;
-        rank_rows<BANK_WAVES, 4>(rk, m, X, row0, n_rows, wave, lane, m.bank.pass_feature[p], m.bank.pass_feature[p + 1],
-                                 reg_begin, reg_end);
-        rank_rows<BANK_WAVES, 4>(rk_hi, m, X, row0 + RROWS, n_rows, wave, lane, m.bank.pass_feature[p],
-                                 m.bank.pass_feature[p + 1], reg_begin, reg_end);
-        __syncthreads();  // the pass's ranks are complete
 #pragma unroll
-        for (int i = 0; i < BANK_REGS; ++i) {
-            const int r = bank_reg[i];  // wave-uniform
-            if (r >= reg_begin && r < reg_end) {
-                xa[i] = rk[(r - reg_begin) * TILE + lane];
-                xb[i] = rk_hi[(r - reg_begin) * TILE + lane];
-            }
-        }
-        __syncthreads();  // the tiles are free for the next pass, or for the outcome bytes
-    }
+    for (int i = 0; i < BANK_REGS; ++i) xa[i] = xb[i] = 0;  // registers the bank does not use stay defined
+    bank_ranks(m, X, row0, n_rows, reinterpret_cast<float *>(smem), xa, xb, wave, lane);
 
     double sum[2] = {0.0, 0.0};
     uint8_t *buf = reinterpret_cast<uint8_t *>(smem) + BANK_ROWS;  // see `prev` in bank_trees
@@ -277,10 +420,7 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
 
 size_t rankbank_lds_bytes(const DevModel &m)
 {
-    int pass_regs = 0;
-    for (int p = 0; p < m.bank.passes; ++p)
-        pass_regs = m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] > pass_regs ? m.bank.pass_reg[p + 1] - m.bank.pass_reg[p] : pass_regs;
-    const size_t tile = 2 * sizeof(uint32_t) * TILE * static_cast<size_t>(pass_regs);
+    const size_t tile = sizeof(float) * BANK_ROWS * BANK_TILE_PITCH;
     // a row of spare bytes, the outcome bytes of a batch, then its child references (a word per slot)
     const size_t bytes = BANK_ROWS + (static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) + sizeof(uint32_t) * BANK_UNIT) *
                                          static_cast<size_t>(m.bank.max_units);
@@ -307,7 +447,6 @@ hipError_t launch_rankbank(const DevModel &m, const float *X, int64_t n_rows, fl
     const bool sums_fit = (K == 1 && W == 1) || (W == K && K <= 2);
     const size_t lds = rankbank_lds_bytes(m);
     if (!m.bank.enabled || m.n_splits != 1 || !sums_fit || m.rank_regs < 1 || m.rank_regs > BANK_WAVES * BANK_REGS || m.bank.passes < 1 ||
-        m.bank.passes > BANK_MAX_PASSES ||
         lds > lds_limit || lds > BANK_MAX_LDS)
         return hipErrorInvalidValue;
     const int64_t n_blocks = (n_rows + BANK_ROWS - 1) / BANK_ROWS;

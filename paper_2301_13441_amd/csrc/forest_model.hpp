@@ -122,18 +122,53 @@ struct ChildRef {
 // Every wave evaluates, for up to BANK_TREES trees at a time (a batch), the internal nodes that
 // test one of its registers, BANK_UNIT entries of its stream at a time, and leaves their outcome
 // bits in an LDS buffer all waves share (a byte per 8 nodes and row); then every lane walks one
-// (row, tree) of the batch through those bits.  The ranks are computed in up to BANK_MAX_PASSES
-// passes of at most BANK_PASS_REGS registers (whole features), which bounds the LDS of the
-// prologue like BANK_MAX_LDS bounds that of a batch: two workgroups per compute unit.
+// (row, tree) of the batch through those bits.  The ranks are computed in passes over blocks of
+// BANK_PASS_FEATURES columns of X: the workgroup copies the block's part of its rows to LDS, then
+// every wave looks up the registers of ITS bank that belong to the block's features.
 constexpr int BANK_WAVES = 8;
 constexpr int BANK_REGS = 32;
 constexpr int BANK_TREES = 2;
 constexpr int BANK_ROWS = 256;
 constexpr int BANK_UNIT = 16;
-constexpr int BANK_PASS_REGS = 128;
-constexpr int BANK_MAX_PASSES = 4;
+constexpr int BANK_PASS_FEATURES = 64;
+constexpr int BANK_TILE_PITCH = BANK_PASS_FEATURES + 1;  // words per row of the staged block: an odd pitch
+                                                         // keeps a column's reads free of bank conflicts
 constexpr size_t BANK_MAX_LDS = 72 * 1024;     // outcome bytes and child references of a batch
 constexpr int BANK_PAD_ENTRIES = 64;        // readable entries after each wave's stream
+constexpr int BANK_WINDOW = 8;              // thresholds a fast lookup reads
+constexpr int BANK_FAST_MAX_THRESHOLDS = RANK_CODES / 2 - 1;  // ranks 0..n all in the lower half of the codes
+constexpr int BANK_MAX_BUCKETS = 65535;     // per feature, fast lookup table
+constexpr int BANK_BUCKET_FILL = 6;         // the table is refined until no bucket holds more thresholds
+
+// A prologue pass: columns [feat_begin, feat_end) of X, at most BANK_PASS_FEATURES of them.
+struct BankPass {
+    int32_t feat_begin, feat_end;
+};
+
+// What one wave looks up in one pass: items [begin, begin + n_fast) of the to-do list take the
+// fast lookup, the n_slow items after them the general one.
+struct BankPassWave {
+    int32_t begin, n_fast, n_slow, reserved;
+};
+
+// One rank register to look up: register `slot` of the wave's bank holds thresholds
+// [first, first + len) of `feature` (one segment of the feature's sorted thresholds).
+struct BankTodo {
+    int32_t slot, feature, first, len;
+};
+
+// Constants of a feature's fast lookup (fast == 1: BANK_WINDOW <= n <= BANK_FAST_MAX_THRESHOLDS and a
+// finite positive grid): bucket = trunc(clamp((x - lo) * scale, 0, last_bucket)); the table entry
+// of the bucket (16 bits, at byte tab_off of the table) is where the window of BANK_WINDOW
+// thresholds begins, clamp(#thresholds in lower buckets - 1, 0, n - BANK_WINDOW).
+struct BankFeat {
+    float lo, scale, last_bucket;
+    int32_t n;         // distinct thresholds of the feature
+    uint32_t tab_off;  // bytes
+    uint32_t thr_off;  // byte offset of the feature's thresholds in the sorted table
+    int32_t fast;
+    int32_t reserved;
+};
 
 // A reference of the register-bank program, 16 bits: bit 15 clear: a slot of the batch; bit 15 set:
 // a leaf, the low 15 bits its index among the batch's leaves (processing order).
@@ -196,9 +231,11 @@ struct PackedModel {
     int32_t bank_batches = 0;
     int32_t bank_max_units = 0;              // most units a batch's bit buffer holds
     int32_t bank_stream_base[BANK_WAVES] = {};  // first entry of each wave's stream in bank_prog
-    int32_t bank_passes = 0;                          // prologue passes
-    int32_t bank_pass_feature[BANK_MAX_PASSES + 1] = {};  // pass p ranks features [p], [p + 1])
-    int32_t bank_pass_reg[BANK_MAX_PASSES + 1] = {};      // which hold rank registers [p], [p + 1])
+    std::vector<BankPass> bank_pass;          // prologue passes (blocks of columns with rank registers)
+    std::vector<BankPassWave> bank_pass_wave; // [passes][BANK_WAVES]
+    std::vector<BankTodo> bank_todo;          // the waves' to-do lists, pass by pass
+    std::vector<BankFeat> bank_feat;          // [F]
+    std::vector<uint16_t> bank_tab;           // fast lookup tables of all features
     std::vector<uint32_t> bank_prog;         // (f16(-4 code(j')) << 16) | register index inside the bank
     std::vector<uint32_t> bank_child;        // per batch, by slot: left reference | right reference << 16
     std::vector<BankBatch> bank_batch;       // [batches]

@@ -480,29 +480,122 @@ int compile_forest(const forest_desc &d, PackedModel &m)
     if (m.path == PATH_RANK_LDS) balance_waves(m);
     if (m.path == PATH_RANK_LDS && m.kind == KIND_GENERIC && m.rank_regs >= 1 &&
         m.rank_regs <= BANK_WAVES * BANK_REGS && ((K == 1 && W == 1) || (W == K && K <= 2))) {
-        // Register-bank program.  Rank registers to waves: heaviest first, each to the wave with
-        // the fewest nodes so far that still has a free register.
+        // Register-bank program.  A rank register's feature and segment.
+        std::vector<int32_t> reg_feature(static_cast<size_t>(m.rank_regs)), reg_segment(static_cast<size_t>(m.rank_regs));
+        for (int32_t f = 0; f < d.n_features; ++f) {
+            const int32_t r_end = f + 1 < d.n_features ? m.feat_vfirst[f + 1] : m.rank_regs;
+            for (int32_t r = m.feat_vfirst[f]; r < r_end; ++r) {
+                reg_feature[r] = f;
+                reg_segment[r] = r - m.feat_vfirst[f];
+            }
+        }
+        // Rank registers to waves, one block of BANK_PASS_FEATURES columns of X (a prologue pass)
+        // after the other: heaviest first, each to the wave with the fewest nodes so far that
+        // still has a free register and not yet its share of the block (the waves of a workgroup
+        // look the block's registers up side by side, so each should have about as many).
         std::vector<int64_t> reg_nodes(static_cast<size_t>(m.rank_regs), 0);
         for (int32_t t = 0; t < T; ++t)
             for (int32_t v : shape[t].internal) ++reg_nodes[entry_of(t, v).feature_slot];
-        std::vector<int32_t> by_weight(static_cast<size_t>(m.rank_regs));
-        std::iota(by_weight.begin(), by_weight.end(), 0);
-        std::stable_sort(by_weight.begin(), by_weight.end(),
-                         [&](int32_t a, int32_t b) { return reg_nodes[a] > reg_nodes[b]; });
         std::vector<int32_t> reg_wave(static_cast<size_t>(m.rank_regs)), reg_index(static_cast<size_t>(m.rank_regs));
         int64_t load[BANK_WAVES] = {};
         int32_t held[BANK_WAVES] = {};
         m.bank_reg.assign(BANK_WAVES * BANK_REGS, 0);
-        for (int32_t r : by_weight) {
-            int best = -1;
-            for (int w = 0; w < BANK_WAVES; ++w)
-                if (held[w] < BANK_REGS && (best < 0 || load[w] < load[best])) best = w;
-            reg_wave[r] = best;
-            reg_index[r] = held[best];
-            m.bank_reg[best * BANK_REGS + held[best]] = r;
-            ++held[best];
-            load[best] += reg_nodes[r];
+        for (int32_t f0 = 0; f0 < d.n_features; f0 += BANK_PASS_FEATURES) {
+            const int32_t f1 = std::min<int32_t>(f0 + BANK_PASS_FEATURES, d.n_features);
+            const int32_t r0 = m.feat_vfirst[f0], r1 = f1 < d.n_features ? m.feat_vfirst[f1] : m.rank_regs;
+            if (r0 == r1) continue;  // no thresholds on these columns: the block is never read
+            std::vector<int32_t> by_weight(static_cast<size_t>(r1 - r0));
+            std::iota(by_weight.begin(), by_weight.end(), r0);
+            std::stable_sort(by_weight.begin(), by_weight.end(),
+                             [&](int32_t a, int32_t b) { return reg_nodes[a] > reg_nodes[b]; });
+            const int32_t share = (r1 - r0 + BANK_WAVES - 1) / BANK_WAVES;
+            int32_t here[BANK_WAVES] = {};
+            for (int32_t r : by_weight) {
+                int best = -1;
+                for (int pass = 0; pass < 2 && best < 0; ++pass)  // second try: the share no longer binds
+                    for (int w = 0; w < BANK_WAVES; ++w)
+                        if (held[w] < BANK_REGS && (pass == 1 || here[w] < share) && (best < 0 || load[w] < load[best])) best = w;
+                reg_wave[r] = best;
+                reg_index[r] = held[best];
+                m.bank_reg[best * BANK_REGS + held[best]] = r;
+                ++held[best];
+                ++here[best];
+                load[best] += reg_nodes[r];
+            }
+            // the pass and the waves' to-do lists: fast lookups first
+            std::vector<BankTodo> mine[BANK_WAVES][2];
+            for (int32_t r = r0; r < r1; ++r) {
+                const int32_t f = reg_feature[r];
+                const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
+                const int32_t first = reg_segment[r] * RANK_SEG;
+                const bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS;  // refined below
+                mine[reg_wave[r]][fast ? 0 : 1].push_back(BankTodo{reg_index[r], f, first, std::min<int32_t>(n - first, RANK_SEG)});
+            }
+            m.bank_pass.push_back(BankPass{f0, f1});
+            for (int w = 0; w < BANK_WAVES; ++w) {
+                m.bank_pass_wave.push_back(BankPassWave{static_cast<int32_t>(m.bank_todo.size()),
+                                                        static_cast<int32_t>(mine[w][0].size()),
+                                                        static_cast<int32_t>(mine[w][1].size()), 0});
+                for (int k = 0; k < 2; ++k) m.bank_todo.insert(m.bank_todo.end(), mine[w][k].begin(), mine[w][k].end());
+            }
         }
+        // Fast lookup tables.  A uniform grid over the feature's finite thresholds, refined until
+        // no bucket holds more than BANK_BUCKET_FILL of them (or the table is as large as it may
+        // get); the entry of a bucket is where the window of thresholds the lookup reads begins.
+        // The kernel checks every window against x, so nothing rests on its arithmetic placing x
+        // in the bucket the arithmetic here does; what a window does not decide takes the general
+        // lookup.
+        m.bank_feat.assign(static_cast<size_t>(d.n_features), BankFeat{});
+        for (int32_t f = 0; f < d.n_features; ++f) {
+            const float *v = m.thr_sorted.data() + m.feat_thr_base[f];
+            const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
+            BankFeat &bf = m.bank_feat[f];
+            bf.n = n;
+            bf.thr_off = static_cast<uint32_t>(m.feat_thr_base[f]) * sizeof(float);
+            bf.tab_off = static_cast<uint32_t>(m.bank_tab.size() * sizeof(uint16_t));
+            int32_t a = 0, b = n;
+            while (a < b && !std::isfinite(v[a])) ++a;
+            while (b > a && !std::isfinite(v[b - 1])) --b;
+            bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS && b > a && v[b - 1] - v[a] > 0.0f;
+            std::vector<int32_t> start;
+            if (fast) {
+                const float lo = v[a], range = v[b - 1] - v[a];
+                for (int64_t nb = 2 * static_cast<int64_t>(n);; nb *= 2) {
+                    nb = std::min<int64_t>(nb, BANK_MAX_BUCKETS);
+                    const float scale = static_cast<float>(nb) / range;
+                    if (!std::isfinite(scale)) {
+                        fast = false;
+                        break;
+                    }
+                    start.assign(static_cast<size_t>(nb) + 1, 0);
+                    int32_t i = 0, fill = 0;
+                    for (int32_t bk = 0; bk <= nb; ++bk) {
+                        while (i < n && bucket_index(v[i], lo, scale, static_cast<int32_t>(nb)) < bk) ++i;
+                        start[bk] = i;
+                        if (bk > 0) fill = std::max(fill, start[bk] - start[bk - 1]);
+                    }
+                    bf.lo = lo;
+                    bf.scale = scale;
+                    bf.last_bucket = static_cast<float>(nb - 1);
+                    if (fill <= BANK_BUCKET_FILL || nb == BANK_MAX_BUCKETS) break;
+                }
+            }
+            bf.fast = fast ? 1 : 0;
+            if (fast)
+                for (size_t bk = 0; bk + 1 < start.size(); ++bk)
+                    m.bank_tab.push_back(static_cast<uint16_t>(std::clamp(start[bk] - 1, 0, n - BANK_WINDOW)));
+        }
+        // a to-do item is fast only if its feature's table was built
+        for (size_t pw = 0; pw < m.bank_pass_wave.size(); ++pw) {
+            BankPassWave &q = m.bank_pass_wave[pw];
+            std::stable_partition(m.bank_todo.begin() + q.begin, m.bank_todo.begin() + q.begin + q.n_fast + q.n_slow,
+                                  [&](const BankTodo &td) { return m.bank_feat[td.feature].fast != 0; });
+            const int32_t total = q.n_fast + q.n_slow;
+            q.n_fast = static_cast<int32_t>(std::count_if(m.bank_todo.begin() + q.begin, m.bank_todo.begin() + q.begin + total,
+                                                          [&](const BankTodo &td) { return m.bank_feat[td.feature].fast != 0; }));
+            q.n_slow = total - q.n_fast;
+        }
+        m.bank_tab.push_back(0);  // never empty
         // Batches of up to BANK_TREES consecutive trees (processing order): as many as keep the
         // batch's bit buffer inside the LDS budget.  Inside a batch every wave gets the nodes that
         // test its registers, padded to whole units of BANK_UNIT entries; a node's slot is
@@ -603,28 +696,6 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
             first += count;
         }
-        // prologue passes: whole features, at most BANK_PASS_REGS rank registers each
-        int32_t passes = 0;
-        for (int32_t f = 0; f < d.n_features && fits;) {
-            if (passes == BANK_MAX_PASSES) {
-                fits = false;
-                break;
-            }
-            m.bank_pass_feature[passes] = f;
-            m.bank_pass_reg[passes] = m.feat_vfirst[f];
-            int32_t regs_here = 0;
-            while (f < d.n_features) {
-                const int32_t r = (f + 1 < d.n_features ? m.feat_vfirst[f + 1] : m.rank_regs) - m.feat_vfirst[f];
-                if (regs_here + r > BANK_PASS_REGS) break;
-                regs_here += r;
-                ++f;
-            }
-            if (f == m.bank_pass_feature[passes]) fits = false;  // one feature with more registers than a pass holds
-            ++passes;
-        }
-        m.bank_pass_feature[passes] = d.n_features;
-        m.bank_pass_reg[passes] = m.rank_regs;
-        m.bank_passes = passes;
         if (fits) {
             m.bank_enabled = 1;
             m.bank_batches = n_batches;
@@ -640,6 +711,11 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             m.bank_tree.clear();
             m.bank_span.clear();
             m.bank_reg.clear();
+            m.bank_pass.clear();
+            m.bank_pass_wave.clear();
+            m.bank_todo.clear();
+            m.bank_feat.clear();
+            m.bank_tab.clear();
         }
     }
     for (const TreeMeta &tm : m.tree) m.v_program_groups.push_back(tm.n_words);
