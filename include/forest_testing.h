@@ -63,19 +63,30 @@ typedef struct forest_packed_view {
     /* kernel_path 3, models whose large batches run the register-bank kernel (else bank_batches
      * is 0 and the pointers NULL).  The rank registers are dealt to bank_waves wavefronts,
      * bank_regs each (bank_reg[w * bank_regs + i] = rank register behind register i of wave w);
-     * the trees are taken up to bank_trees at a time (a batch, processing order).  In batch b wave
+     * the trees are taken up to bank_trees at a time (a batch; which trees share one is the
+     * compiler's choice).  In batch b wave
      * w evaluates bank_span[2 * (b * bank_waves + w)] units of bank_unit entries from its stream,
      * which starts at bank_prog[bank_stream_base[w]] and runs on from batch to batch; a unit's bits
      * go to unit bank_span[2 * (b * bank_waves + w) + 1] + (index of the unit) of the batch's bit
      * buffer, entry k of a unit to bit 8 * (k / 8) + 7 - k % 8.  An entry is (f16 bits of the
      * threshold's code << 16) | register index inside the bank.  Slot = bank_unit * unit + bit.
-     * bank_batch[4 * b] .. + 2: first entry of batch b in bank_child, its number of slots, and the
-     * index of its first leaf in leaf_node / leaf_value of the processing order.
+     * bank_batch[4 * b] .. + 1: first entry of batch b in bank_child and its number of slots.
      * bank_child[first entry + slot] = left reference | right reference << 16 of the node in that
      * slot; a 16-bit reference is a slot of the same batch (bit 15 clear) or a leaf (bit 15 set, the
-     * low 15 bits its index from the batch's first leaf).  bank_tree[4 * (b * bank_trees + j)] .. + 3:
-     * root reference, output column, caller's tree index, 1 (0 for the records that pad a batch of
-     * fewer trees). */
+     * low 15 bits its in-order index among the leaves of its tree).
+     * bank_tree[4 * (b * bank_trees + j)] .. + 3: root reference, index of the tree's first leaf in
+     * order_leaf_node / order_leaf_tree, caller's tree index, 1 (0 for the record that fills a batch
+     * of one tree).
+     * The ranks are looked up in bank_passes passes over blocks of columns of X
+     * (bank_pass[2 * p], [2 * p + 1]: first column and end).  In pass p wave w looks up items
+     * [begin, begin + n_fast + n_slow) of bank_todo (bank_pass_wave[4 * (p * bank_waves + w)] .. + 2:
+     * begin, n_fast, n_slow); item i is bank_todo[4 * i] .. + 3: register index inside the bank,
+     * feature, first threshold and number of thresholds of the register's segment.  The first
+     * n_fast items take the fast lookup, whose constants are bank_feat[8 * f] .. + 7 (32-bit words:
+     * float lo, float scale, float last bucket, int thresholds, byte offset of the feature's
+     * 16-bit table in bank_tab, byte offset of its thresholds in rank_threshold, 1 if the feature
+     * has a fast lookup, 0): bucket = trunc(clamp((x - lo) * scale, 0, last bucket)), the table
+     * entry of the bucket is the index of the first of bank_window thresholds the lookup reads. */
     int32_t bank_batches, bank_waves, bank_regs, bank_trees, bank_unit, bank_max_units;
     int64_t bank_prog_entries;
     const uint32_t *bank_prog;
@@ -85,6 +96,13 @@ typedef struct forest_packed_view {
     const int32_t *bank_batch;       /* [bank_batches * 4] */
     const int32_t *bank_tree;        /* [bank_batches * bank_trees * 4] */
     const int32_t *bank_reg;         /* [bank_waves * bank_regs] */
+    int32_t bank_passes, bank_window;
+    int64_t bank_todo_items, bank_tab_entries;
+    const int32_t *bank_pass;        /* [bank_passes * 2] */
+    const int32_t *bank_pass_wave;   /* [bank_passes * bank_waves * 4] */
+    const int32_t *bank_todo;        /* [bank_todo_items * 4] */
+    const uint32_t *bank_feat;       /* [n_features * 8] */
+    const uint16_t *bank_tab;        /* [bank_tab_entries] */
     const int32_t *order_leaf_node;  /* [sum N_L] caller's node index of each leaf, processing order */
     const int32_t *order_leaf_tree;  /* [sum N_L] caller's tree index of each leaf, processing order */
 } forest_packed_view;

@@ -50,7 +50,9 @@ class _View(ctypes.Structure):
                 ("bank_batches", _i32), ("bank_waves", _i32), ("bank_regs", _i32), ("bank_trees", _i32),
                 ("bank_unit", _i32), ("bank_max_units", _i32), ("bank_prog_entries", _i64), ("bank_prog", _p),
                 ("bank_stream_base", _p), ("bank_span", _p), ("bank_child", _p), ("bank_batch", _p),
-                ("bank_tree", _p), ("bank_reg", _p), ("order_leaf_node", _p), ("order_leaf_tree", _p)]
+                ("bank_tree", _p), ("bank_reg", _p), ("bank_passes", _i32), ("bank_window", _i32),
+                ("bank_todo_items", _i64), ("bank_tab_entries", _i64), ("bank_pass", _p), ("bank_pass_wave", _p),
+                ("bank_todo", _p), ("bank_feat", _p), ("bank_tab", _p), ("order_leaf_node", _p), ("order_leaf_tree", _p)]
 
 
 # include/forest.h: the inference ABI
@@ -194,7 +196,13 @@ def forest_pack(forest) -> dict:
                         bank_stream_base=get(v.bank_stream_base, nw, np.int32), bank_span=span,
                         bank_child=get(v.bank_child, n_slots, np.uint32), bank_batch=batch,
                         bank_tree=get(v.bank_tree, nb * nt * 4, np.int32).reshape(nb, nt, 4),
-                        bank_reg=get(v.bank_reg, nw * int(v.bank_regs), np.int32).reshape(nw, -1))
+                        bank_reg=get(v.bank_reg, nw * int(v.bank_regs), np.int32).reshape(nw, -1),
+                        bank_window=int(v.bank_window),
+                        bank_pass=get(v.bank_pass, int(v.bank_passes) * 2, np.int32).reshape(-1, 2),
+                        bank_pass_wave=get(v.bank_pass_wave, int(v.bank_passes) * nw * 4, np.int32).reshape(-1, nw, 4),
+                        bank_todo=get(v.bank_todo, int(v.bank_todo_items) * 4, np.int32).reshape(-1, 4),
+                        bank_feat=get(v.bank_feat, int(forest.n_features) * 8, np.uint32).reshape(-1, 8),
+                        bank_tab=get(v.bank_tab, int(v.bank_tab_entries), np.uint16))
         else:
             rank["bank_batches"] = 0
         rank["order_leaf_node"] = get(v.order_leaf_node, nl, np.int32)

@@ -373,8 +373,8 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
                 ref = ((byte >> (ref & 7u)) & 1u) ? (c >> 16) : (c & 0xffffu);
             }
         }
-        // index into the per-leaf tables; the records that pad a batch give the batch's first leaf
-        const int leaf = batch[b].leaf_base + static_cast<int>(ref & 0x7fffu);
+        // index into the per-leaf tables; the record that fills a batch of one tree gives leaf 0
+        const int leaf = bt.leaf_base + static_cast<int>(ref & 0x7fffu);
         pend_valid = bt.valid != 0;
         if (MODE == BANK_LEAVES) {
             pend_node = m.leaf_node[leaf];

@@ -171,21 +171,20 @@ struct BankFeat {
 };
 
 // A reference of the register-bank program, 16 bits: bit 15 clear: a slot of the batch; bit 15 set:
-// a leaf, the low 15 bits its index among the batch's leaves (processing order).
+// a leaf, the low 15 bits its in-order index among the leaves of its tree.
 constexpr uint32_t BANK_LEAF_FLAG = 0x8000u;
 
 struct BankTree {
     int32_t root_ref;     // reference of the root (a leaf if the tree is a single leaf)
-    int32_t column;       // output column of a scalar-leaf tree
+    int32_t leaf_base;    // index of the tree's first leaf in the per-leaf tables
     int32_t caller_tree;  // index of the tree in the caller's description
-    int32_t valid;        // 0 for the records that pad the last batch
+    int32_t valid;        // 0 for the record that fills a batch of one tree
 };
 
 struct BankBatch {
     int32_t slot_base;  // first entry of the batch in the child table
     int32_t n_slots;    // slots of the batch (whole units)
-    int32_t leaf_base;  // index of the batch's first leaf in the per-leaf tables
-    int32_t reserved;
+    int32_t reserved[2];
 };
 
 struct BankSpan {

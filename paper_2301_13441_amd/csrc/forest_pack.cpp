@@ -35,6 +35,7 @@
 // per bucket, the number of thresholds in lower buckets (build_rank_tables below); the kernels
 // get a bracket of rank(x) from it and finish with a short search (forest_rank_common.hpp).
 #include <algorithm>
+#include <array>
 #include <cassert>
 #include <cmath>
 #include <cstring>
@@ -596,11 +597,11 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             q.n_slow = total - q.n_fast;
         }
         m.bank_tab.push_back(0);  // never empty
-        // Batches of up to BANK_TREES consecutive trees (processing order): as many as keep the
-        // batch's bit buffer inside the LDS budget.  Inside a batch every wave gets the nodes that
-        // test its registers, padded to whole units of BANK_UNIT entries; a node's slot is
-        // BANK_UNIT * (index of its unit in the batch's bit buffer) + its bit.  The kernel collects
-        // the entries of a unit in groups of 8, first entry of a group in bit 7 of the group's byte.
+        // Batches of up to BANK_TREES trees whose bit buffer fits the LDS budget.  Inside a batch every
+        // wave gets the nodes that test its registers, padded to whole units of BANK_UNIT entries;
+        // a node's slot is BANK_UNIT * (index of its unit in the batch's bit buffer) + its bit.
+        // The kernel collects the entries of a unit in groups of 8, first entry of a group in bit 7
+        // of the group's byte.
         std::vector<std::vector<uint32_t>> stream(BANK_WAVES);
         uint32_t pad32;
         std::memcpy(&pad32, &pad.threshold, sizeof(pad32));
@@ -608,39 +609,78 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         int64_t max_units = 0;
         bool fits = true;
         struct Node { int32_t tree, ordinal; };
-        // units of a batch made of trees [first, first + count) of the processing order
-        auto batch_units = [&](int32_t first, int32_t count) {
-            int64_t per_wave[BANK_WAVES] = {};
-            for (int32_t j = 0; j < count; ++j) {
-                const int32_t t = order[first + j];
-                for (int32_t v : shape[t].internal) ++per_wave[reg_wave[entry_of(t, v).feature_slot]];
+        // nodes of every tree (processing order) by wave
+        std::vector<std::array<int32_t, BANK_WAVES>> per_wave(static_cast<size_t>(T));
+        for (int32_t ti = 0; ti < T; ++ti) {
+            per_wave[ti].fill(0);
+            for (int32_t v : shape[order[ti]].internal) ++per_wave[ti][reg_wave[entry_of(order[ti], v).feature_slot]];
+        }
+        // units of a batch of trees a and b (b < 0: a alone), and the units of its busiest wave
+        auto batch_units = [&](int32_t a, int32_t b, int64_t *busiest) {
+            int64_t units = 0, most = 0;
+            for (int w = 0; w < BANK_WAVES; ++w) {
+                const int64_t u = (per_wave[a][w] + (b >= 0 ? per_wave[b][w] : 0) + BANK_UNIT - 1) / BANK_UNIT;
+                units += u;
+                most = std::max(most, u);
             }
-            int64_t units = 0;
-            for (int w = 0; w < BANK_WAVES; ++w) units += (per_wave[w] + BANK_UNIT - 1) / BANK_UNIT;
+            if (busiest) *busiest = most;
             return units;
         };
         // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot; the
         // kernel keeps one row of bytes in front of the buffer
         const int64_t budget_units =
             static_cast<int64_t>((BANK_MAX_LDS - BANK_ROWS) / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
-        int32_t n_batches = 0;
-        for (int32_t first = 0; first < T && fits; ++n_batches) {
-            int32_t count = 1;
-            while (count < BANK_TREES && first + count < T && batch_units(first, count + 1) <= budget_units) ++count;
-            if (batch_units(first, count) > budget_units) {
+        // Which trees share a batch.  Every batch costs the workgroup two barriers and a walk, and
+        // its waves wait for the busiest of them, so: as few batches as the buffer allows (largest
+        // tree first, paired with one of the largest trees that still fit beside it), and among
+        // those candidates the partner that leaves the busiest wave the least to do.  The trees of
+        // a model that takes this path all feed the same output columns, so their order only
+        // decides the order of the float64 additions.
+        static_assert(BANK_TREES == 2, "batches are pairs");
+        std::vector<int32_t> by_size(static_cast<size_t>(T));
+        std::iota(by_size.begin(), by_size.end(), 0);
+        std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t a, int32_t b) {
+            return shape[order[a]].internal.size() > shape[order[b]].internal.size();
+        });
+        std::vector<char> taken(static_cast<size_t>(T), 0);
+        std::vector<std::array<int32_t, BANK_TREES>> batches;
+        for (int32_t a : by_size) {
+            if (taken[a]) continue;
+            taken[a] = 1;
+            if (batch_units(a, -1, nullptr) > budget_units) {
                 fits = false;  // a single tree too large for the buffer
                 break;
             }
+            int32_t partner = -1, seen = 0;
+            int64_t partner_busiest = 0;
+            for (int32_t b : by_size) {
+                if (taken[b]) continue;
+                int64_t busiest;
+                if (batch_units(a, b, &busiest) > budget_units) continue;
+                if (partner < 0 || busiest < partner_busiest) {
+                    partner = b;
+                    partner_busiest = busiest;
+                }
+                if (++seen == 8) break;
+            }
+            if (partner >= 0) taken[partner] = 1;
+            batches.push_back({std::min(a, partner < 0 ? a : partner), partner < 0 ? -1 : std::max(a, partner)});
+        }
+        std::sort(batches.begin(), batches.end());
+        int32_t n_batches = 0;
+        for (size_t bi = 0; bi < batches.size() && fits; ++bi, ++n_batches) {
+            const std::array<int32_t, BANK_TREES> &members = batches[bi];
+            const int32_t count = members[1] < 0 ? 1 : 2;
             std::vector<Node> mine[BANK_WAVES];
             for (int32_t j = 0; j < count; ++j) {
-                const int32_t t = order[first + j];
+                const int32_t t = order[members[j]];
                 const TreeShape &sh = shape[t];
                 for (int32_t i = 0; i < static_cast<int32_t>(sh.internal.size()); ++i)
                     mine[reg_wave[entry_of(t, sh.internal[i]).feature_slot]].push_back(Node{j, i});
             }
             // slots
             std::vector<std::vector<int32_t>> slot_of(BANK_TREES);
-            for (int32_t j = 0; j < count; ++j) slot_of[j].assign(shape[order[first + j]].internal.size(), -1);
+            for (int32_t j = 0; j < count; ++j) slot_of[j].assign(shape[order[members[j]]].internal.size(), -1);
             int32_t unit_base = 0;
             for (int w = 0; w < BANK_WAVES; ++w) {
                 const int32_t n_units = static_cast<int32_t>((mine[w].size() + BANK_UNIT - 1) / BANK_UNIT);
@@ -652,7 +692,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                     const int32_t local = (k / BANK_UNIT) * BANK_UNIT + bit;  // which of the wave's nodes sits at this entry
                     if (local < static_cast<int32_t>(mine[w].size())) {
                         const Node nd = mine[w][local];
-                        const int32_t t = order[first + nd.tree];
+                        const int32_t t = order[members[nd.tree]];
                         const SplitEntry e = entry_of(t, shape[t].internal[nd.ordinal]);
                         uint32_t pair;
                         std::memcpy(&pair, &e.threshold, sizeof(pair));
@@ -666,17 +706,15 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
             max_units = std::max<int64_t>(max_units, unit_base);
             // child references by slot, and the trees' records
-            const int32_t batch_leaf_base = m.tree[first].leaf_base;
-            m.bank_batch.push_back(BankBatch{static_cast<int32_t>(m.bank_child.size()), unit_base * BANK_UNIT,
-                                             batch_leaf_base, 0});
+            m.bank_batch.push_back(BankBatch{static_cast<int32_t>(m.bank_child.size()), unit_base * BANK_UNIT, {0, 0}});
             const size_t child_at = m.bank_child.size();
             m.bank_child.resize(child_at + static_cast<size_t>(unit_base) * BANK_UNIT, 0xffffffffu);
             for (int32_t j = 0; j < BANK_TREES; ++j) {
-                const int32_t ti = first + j;
                 if (j >= count) {
                     m.bank_tree.push_back(BankTree{static_cast<int32_t>(BANK_LEAF_FLAG), 0, 0, 0});
                     continue;
                 }
+                const int32_t ti = members[j];
                 const int32_t t = order[ti];
                 const TreeShape &sh = shape[t];
                 const TreeMeta &tm = m.tree[ti];
@@ -684,7 +722,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 auto ref_of = [&](int32_t caller_node) -> uint32_t {
                     const int32_t o = sh.ordinal[caller_node];
                     if (o >= 0) return static_cast<uint32_t>(slot_of[j][o]);
-                    const int32_t leaf = tm.leaf_base + ~o - batch_leaf_base;
+                    const int32_t leaf = ~o;  // in-order ordinal inside the tree
                     if (leaf >= static_cast<int32_t>(BANK_LEAF_FLAG)) fits = false;
                     return BANK_LEAF_FLAG | static_cast<uint32_t>(leaf & 0x7fff);
                 };
@@ -692,9 +730,8 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                     const int32_t v = sh.internal[i];
                     m.bank_child[child_at + slot_of[j][i]] = ref_of(d.left[base + v]) | (ref_of(d.right[base + v]) << 16);
                 }
-                m.bank_tree.push_back(BankTree{static_cast<int32_t>(ref_of(0)), tm.column, tm.caller_tree, 1});
+                m.bank_tree.push_back(BankTree{static_cast<int32_t>(ref_of(0)), tm.leaf_base, tm.caller_tree, 1});
             }
-            first += count;
         }
         if (fits) {
             m.bank_enabled = 1;

@@ -302,11 +302,11 @@ def _simulate_bank_program(f, v, X):
                 thr = v["rank_threshold"][tbase[feat] + (reg - vfirst[feat]) * seg + jl]
                 bits[:, slot] = ~(X[:, feat] <= thr)
             cursor[w] += units * U
-        slot_base, n_slots, leaf_base, _ = (int(z) for z in v["bank_batch"][b])
+        slot_base, n_slots = (int(z) for z in v["bank_batch"][b, :2])
         assert n_slots == n_units * U
         child = v["bank_child"][slot_base:slot_base + n_slots].astype(np.int64)
         for j in range(nt):
-            root, _, caller, valid = (int(z) for z in v["bank_tree"][b, j])
+            root, leaf_base, caller, valid = (int(z) for z in v["bank_tree"][b, j])
             if not valid:
                 continue
             ref = np.full(len(X), root, dtype=np.int64)
@@ -341,6 +341,75 @@ def test_register_bank_program_reaches_the_oracles_leaves(seed):
     # every internal node sits in exactly one slot, and each wave holds at most bank_regs registers
     used = int((v["bank_child"] != 0xffffffff).sum())
     assert used == int(v["tree_n_internal"].sum())
+
+
+def _bank_lookup_codes(v, f, x):
+    """Ranks of the values `x` of feature `f` as the register-bank kernel's fast lookup finds them
+    (numpy float32 arithmetic in the kernel's order); -1 where the window does not settle the
+    rank and the kernel takes the general lookup instead."""
+    lo, scale, last = (v["bank_feat"][f, :3].copy().view(np.float32))
+    n, tab_off, thr_off, fast = (int(z) for z in v["bank_feat"][f, 3:7])
+    assert fast == 1
+    W = v["bank_window"]
+    thr = v["rank_threshold"][thr_off // 4: thr_off // 4 + n]
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = (x.astype(np.float32) - lo) * scale
+        t = np.where(np.isnan(t), np.float32(0), t)  # maximum and minimum drop a NaN operand
+        bucket = np.minimum(np.maximum(t, np.float32(0)), last).astype(np.int64)
+    at = v["bank_tab"][tab_off // 2 + bucket].astype(np.int64)
+    assert (at >= 0).all() and (at <= n - W).all()
+    win = thr[at[:, None] + np.arange(W)[None, :]]
+    below = win < x[:, None]
+    rank = at + below.sum(axis=1)
+    unsettled = (~below[:, 0] & (at != 0)) | (below[:, -1] & (at != n - W)) | np.isnan(x)
+    return np.where(unsettled, -1, rank)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_register_bank_prologue_plan_and_fast_lookup(seed):
+    """Every rank register is looked up exactly once, by the wave that holds it, in the pass that
+    stages its feature; and the fast lookup's table and window give rank(x) = #{thresholds < x}
+    wherever the window settles it, which is almost everywhere."""
+    rng = np.random.default_rng(90 + seed)
+    F = int(rng.choice([5, 70, 256]))
+    f = wl.random_forest(990 + seed, n_trees=12, n_features=F, max_depth=10, stop_prob=0.1,
+                         grid_thresholds=bool(seed % 2))
+    v = pk.forest_pack(f)
+    assert v["kernel_path"] == 3 and v["bank_batches"] > 0
+    tbase = v["rank_threshold_base"]
+    seen = set()
+    for p, (f0, f1) in enumerate(v["bank_pass"]):
+        assert 0 < f1 - f0 <= 64 and f0 % 64 == 0
+        for w in range(v["bank_waves"]):
+            begin, n_fast, n_slow, _ = (int(z) for z in v["bank_pass_wave"][p, w])
+            for i in range(begin, begin + n_fast + n_slow):
+                slot, feat, first, length = (int(z) for z in v["bank_todo"][i])
+                assert f0 <= feat < f1 and 0 <= slot < v["bank_regs"]
+                n = int(tbase[feat + 1] - tbase[feat])
+                assert first % 12287 == 0 and length == min(n - first, 12287)
+                assert (int(v["bank_feat"][feat, 6]) == 1) == (i < begin + n_fast)
+                reg = int(v["bank_reg"][w, slot])
+                assert reg not in seen
+                seen.add(reg)
+    assert seen == set(range(v["rank_registers"]))
+    settled = total = 0
+    for feat in range(F):
+        n = int(tbase[feat + 1] - tbase[feat])
+        if int(v["bank_feat"][feat, 6]) != 1:
+            assert n < v["bank_window"] or n > 6143
+            continue
+        thr = v["rank_threshold"][tbase[feat]:tbase[feat + 1]]
+        x = np.concatenate([rng.standard_normal(400).astype(np.float32) * 2, thr, np.nextafter(thr, np.float32(np.inf)),
+                            np.nextafter(thr, np.float32(-np.inf)),
+                            np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 3e38, -3e38], dtype=np.float32)])
+        got = _bank_lookup_codes(v, feat, x)
+        want = np.searchsorted(thr, x, side="left")  # #{thr < x}
+        ok = got >= 0
+        np.testing.assert_array_equal(got[ok], want[ok])
+        assert not ok[np.isnan(x)].any()
+        settled += int(ok.sum())
+        total += len(x)
+    assert total == 0 or settled >= 0.98 * total
 
 
 def test_register_bank_program_only_where_it_fits():
