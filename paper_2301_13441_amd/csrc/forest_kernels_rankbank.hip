@@ -39,6 +39,8 @@ namespace forest_impl {
 namespace {
 
 constexpr int BANK_BLOCK = TILE * BANK_WAVES;
+constexpr unsigned BANK_STAGGER_BLOCKS = 512;  // two workgroups on each of 256 compute units
+constexpr int BANK_STAGGER_NAPS = 30;          // of 127 * 64 cycles: about 100 microseconds in all
 constexpr int BANK_ROWS_PER_WAVE = BANK_ROWS / BANK_WAVES;  // rows a wave walks
 static_assert(BANK_ROWS_PER_WAVE * BANK_TREES == TILE, "one lane per (row, tree) of a batch");
 static_assert(BANK_ROWS == BANK_WAVES * 32 && BANK_PASS_FEATURES == 64, "the staging step: 16 lanes per row, 32 rows per step");
@@ -392,9 +394,18 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
 // 128 vector registers per lane at most: two workgroups of 8 waves per compute unit.
 template <int MODE>
 __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4))) void forest_rankbank_kernel(
-    DevModel m, const float *__restrict__ X, int64_t n_rows, float *scores, int32_t *labels, int32_t *leaf_out)
+    DevModel m, const float *__restrict__ X, int64_t n_rows, float *scores, int32_t *labels, int32_t *leaf_out,
+    int stagger)
 {
     extern __shared__ __align__(16) char smem[];
+    // Workgroups all take the same time, so those that start together read their rows of X together,
+    // round after round, and wait for memory together.  The workgroups of the first round (the
+    // ones resident at once) start up to `stagger` sleeps apart instead, which spreads the reads
+    // of every later round as well.  A bounded wait: nothing is waited FOR.
+    if (blockIdx.x < BANK_STAGGER_BLOCKS) {
+        const int naps = static_cast<int>((blockIdx.x * 40503u) % BANK_STAGGER_BLOCKS) * stagger / BANK_STAGGER_BLOCKS;
+        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
+    }
     // LDS: first a block of X for the rank lookups ([row of the workgroup][column of the block], odd
     // pitch), then, in the same place, the batch's outcome bytes ([group of 8 slots][row of the
     // workgroup]) and child references.
@@ -452,12 +463,14 @@ hipError_t launch_rankbank(const DevModel &m, const float *X, int64_t n_rows, fl
     const int64_t n_blocks = (n_rows + BANK_ROWS - 1) / BANK_ROWS;
     if (n_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid(static_cast<unsigned>(n_blocks));
+    // only where the launch runs for many rounds: a short one would just start late
+    const int stagger = n_blocks >= 8 * static_cast<int64_t>(BANK_STAGGER_BLOCKS) ? BANK_STAGGER_NAPS : 0;
     if (leaf_out)
         hipLaunchKernelGGL(forest_rankbank_kernel<BANK_LEAVES>, grid, dim3(BANK_BLOCK), lds, stream, m, X, n_rows,
-                           scores, labels, leaf_out);
+                           scores, labels, leaf_out, stagger);
     else
         hipLaunchKernelGGL(forest_rankbank_kernel<BANK_SUMS>, grid, dim3(BANK_BLOCK), lds, stream, m, X, n_rows,
-                           scores, labels, leaf_out);
+                           scores, labels, leaf_out, stagger);
     return hipGetLastError();
 }
 

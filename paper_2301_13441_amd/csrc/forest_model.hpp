@@ -133,7 +133,7 @@ constexpr int BANK_UNIT = 16;
 constexpr int BANK_PASS_FEATURES = 64;
 constexpr int BANK_TILE_PITCH = BANK_PASS_FEATURES + 1;  // words per row of the staged block: an odd pitch
                                                          // keeps a column's reads free of bank conflicts
-constexpr size_t BANK_MAX_LDS = 72 * 1024;     // outcome bytes and child references of a batch
+constexpr size_t BANK_MAX_LDS = 72 * 1024;     // outcome bytes and child references of a batch (a launch with 80 KB did not return: not used)
 constexpr int BANK_PAD_ENTRIES = 64;        // readable entries after each wave's stream
 constexpr int BANK_WINDOW = 8;              // thresholds a fast lookup reads
 constexpr int BANK_FAST_MAX_THRESHOLDS = RANK_CODES / 2 - 1;  // ranks 0..n all in the lower half of the codes
