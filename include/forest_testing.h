@@ -70,13 +70,17 @@ typedef struct forest_packed_view {
      * go to unit bank_span[2 * (b * bank_waves + w) + 1] + (index of the unit) of the batch's bit
      * buffer, entry k of a unit to bit 8 * (k / 8) + 7 - k % 8.  An entry is (f16 bits of the
      * threshold's code << 16) | register index inside the bank.  Slot = bank_unit * unit + bit.
-     * bank_batch[4 * b] .. + 1: first entry of batch b in bank_child and its number of slots.
-     * bank_child[first entry + slot] = left reference | right reference << 16 of the node in that
-     * slot; a 16-bit reference is a slot of the same batch (bit 15 clear) or a leaf (bit 15 set, the
-     * low 15 bits its in-order index among the leaves of its tree).
-     * bank_tree[4 * (b * bank_trees + j)] .. + 3: root reference, index of the tree's first leaf in
-     * order_leaf_node / order_leaf_tree, caller's tree index, 1 (0 for the record that fills a batch
-     * of one tree).
+     * bank_batch[4 * b] .. + 2: first entry of batch b in bank_child and bank_leaf, its number of
+     * slots, and the number of moves of its walk.  bank_child[first entry + slot] = left | right << 16:
+     * where the walk goes from the node in that slot for either outcome, as 4 * slot of the child,
+     * or 4 * the slot itself where the child is a leaf (0 for a slot without a node).
+     * bank_leaf[first entry + slot] = left | right << 16: the in-order index, among the leaves of its
+     * tree, of the leaf either child is (0xffff for an internal child; 0x80008000 for a slot without
+     * a node).  The walk starts at the root, moves bank_batch[4 * b + 2] times, and the outcome of
+     * the node it then stands on picks the leaf.
+     * bank_tree[4 * (b * bank_trees + j)] .. + 3: 4 * slot of the root (0x8000 if the tree is a
+     * single leaf), index of the tree's first leaf in order_leaf_node / order_leaf_tree, caller's
+     * tree index, 1 (0 for the record that fills a batch of one tree).
      * The ranks are looked up in bank_passes passes over blocks of columns of X
      * (bank_pass[2 * p], [2 * p + 1]: first column and end).  In pass p wave w looks up items
      * [begin, begin + n_fast + n_slow) of bank_todo (bank_pass_wave[4 * (p * bank_waves + w)] .. + 2:
@@ -93,6 +97,7 @@ typedef struct forest_packed_view {
     const int32_t *bank_stream_base; /* [bank_waves] */
     const int32_t *bank_span;        /* [bank_batches * bank_waves * 2] */
     const uint32_t *bank_child;      /* [slots of all batches] */
+    const uint32_t *bank_leaf;       /* [slots of all batches] */
     const int32_t *bank_batch;       /* [bank_batches * 4] */
     const int32_t *bank_tree;        /* [bank_batches * bank_trees * 4] */
     const int32_t *bank_reg;         /* [bank_waves * bank_regs] */

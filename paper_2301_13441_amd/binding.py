@@ -49,7 +49,7 @@ class _View(ctypes.Structure):
                 ("workgroup_waves", _i32), ("wave_tree", _p), ("program_groups", _p),
                 ("bank_batches", _i32), ("bank_waves", _i32), ("bank_regs", _i32), ("bank_trees", _i32),
                 ("bank_unit", _i32), ("bank_max_units", _i32), ("bank_prog_entries", _i64), ("bank_prog", _p),
-                ("bank_stream_base", _p), ("bank_span", _p), ("bank_child", _p), ("bank_batch", _p),
+                ("bank_stream_base", _p), ("bank_span", _p), ("bank_child", _p), ("bank_leaf", _p), ("bank_batch", _p),
                 ("bank_tree", _p), ("bank_reg", _p), ("bank_passes", _i32), ("bank_window", _i32),
                 ("bank_todo_items", _i64), ("bank_tab_entries", _i64), ("bank_pass", _p), ("bank_pass_wave", _p),
                 ("bank_todo", _p), ("bank_feat", _p), ("bank_tab", _p), ("order_leaf_node", _p), ("order_leaf_tree", _p)]
@@ -194,7 +194,8 @@ def forest_pack(forest) -> dict:
                         bank_unit=unit, bank_max_units=int(v.bank_max_units),
                         bank_prog=get(v.bank_prog, int(v.bank_prog_entries), np.uint32),
                         bank_stream_base=get(v.bank_stream_base, nw, np.int32), bank_span=span,
-                        bank_child=get(v.bank_child, n_slots, np.uint32), bank_batch=batch,
+                        bank_child=get(v.bank_child, n_slots, np.uint32),
+                        bank_leaf=get(v.bank_leaf, n_slots, np.uint32), bank_batch=batch,
                         bank_tree=get(v.bank_tree, nb * nt * 4, np.int32).reshape(nb, nt, 4),
                         bank_reg=get(v.bank_reg, nw * int(v.bank_regs), np.int32).reshape(nw, -1),
                         bank_window=int(v.bank_window),

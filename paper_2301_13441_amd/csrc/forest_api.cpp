@@ -157,6 +157,7 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_bst = place<int32_t>(cur, m.bucket_start.size());
     const size_t o_bprog = place<uint32_t>(cur, m.bank_prog.size());
     const size_t o_bchild = place<uint32_t>(cur, m.bank_child.size());
+    const size_t o_bleaf = place<uint32_t>(cur, m.bank_leaf.size());
     const size_t o_btree = place<BankTree>(cur, m.bank_tree.size());
     const size_t o_bspan = place<BankSpan>(cur, m.bank_span.size());
     const size_t o_bslot = place<BankBatch>(cur, m.bank_batch.size());
@@ -200,6 +201,7 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_bst, m.bucket_start.data(), m.bucket_start.size() * sizeof(int32_t)) &&
                     up(o_bprog, m.bank_prog.data(), m.bank_prog.size() * sizeof(uint32_t)) &&
                     up(o_bchild, m.bank_child.data(), m.bank_child.size() * sizeof(uint32_t)) &&
+                    up(o_bleaf, m.bank_leaf.data(), m.bank_leaf.size() * sizeof(uint32_t)) &&
                     up(o_btree, m.bank_tree.data(), m.bank_tree.size() * sizeof(BankTree)) &&
                     up(o_bspan, m.bank_span.data(), m.bank_span.size() * sizeof(BankSpan)) &&
                     up(o_bslot, m.bank_batch.data(), m.bank_batch.size() * sizeof(BankBatch)) &&
@@ -245,6 +247,7 @@ int forest_load(const forest_desc *desc, forest **out)
     d.feat_vfirst = reinterpret_cast<const int32_t *>(b + o_fvf);
     d.bank.prog = reinterpret_cast<const uint32_t *>(b + o_bprog);
     d.bank.child = reinterpret_cast<const uint32_t *>(b + o_bchild);
+    d.bank.leaf = reinterpret_cast<const uint32_t *>(b + o_bleaf);
     d.bank.tree = reinterpret_cast<const BankTree *>(b + o_btree);
     d.bank.span = reinterpret_cast<const BankSpan *>(b + o_bspan);
     d.bank.batch = reinterpret_cast<const BankBatch *>(b + o_bslot);
@@ -270,6 +273,7 @@ int forest_load(const forest_desc *desc, forest **out)
     m.prog32 = {};
     m.bank_prog = {};
     m.bank_child = {};
+    m.bank_leaf = {};
     m.child = {};
     m.thr_sorted = {};
     m.v_feature = {};

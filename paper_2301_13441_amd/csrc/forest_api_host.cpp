@@ -82,6 +82,7 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     v->bank_stream_base = bank ? m.bank_stream_base : nullptr;
     v->bank_span = bank ? reinterpret_cast<const int32_t *>(m.bank_span.data()) : nullptr;
     v->bank_child = bank ? m.bank_child.data() : nullptr;
+    v->bank_leaf = bank ? m.bank_leaf.data() : nullptr;
     v->bank_batch = bank ? reinterpret_cast<const int32_t *>(m.bank_batch.data()) : nullptr;
     v->bank_tree = bank ? reinterpret_cast<const int32_t *>(m.bank_tree.data()) : nullptr;
     v->bank_reg = bank ? m.bank_reg.data() : nullptr;

@@ -13,6 +13,7 @@ namespace forest_impl {
 struct BankDev {
     const uint32_t *prog;
     const uint32_t *child;
+    const uint32_t *leaf;
     const BankTree *tree;
     const BankSpan *span;
     const BankBatch *batch;

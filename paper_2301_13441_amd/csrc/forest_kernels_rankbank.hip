@@ -365,18 +365,25 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         if (b > 0) consume_pending();  // the last batch's leaves
         __syncthreads();  // the batch's bits and child references are complete
 
-        // ---- walk: one (row, tree) per lane
+        // ---- walk: one (row, tree) per lane.  Every lane takes the batch's number of steps: a step
+        // reads the outcome byte and the word of where the lane stands (both reads in flight
+        // together) and moves to the half of the word the outcome bit picks, which is the same
+        // place again once the next node would be a leaf; no test, no branch but the loop's.
         const uint8_t *bits_of_row = buf + walk_row;
-        uint32_t ref = static_cast<uint32_t>(bt.root_ref);
-        while (__any(!(ref & BANK_LEAF_FLAG))) {
-            if (!(ref & BANK_LEAF_FLAG)) {
-                const uint32_t byte = bits_of_row[(ref >> 3) * BANK_ROWS];
-                const uint32_t c = child_lds[ref];
-                ref = ((byte >> (ref & 7u)) & 1u) ? (c >> 16) : (c & 0xffffu);
-            }
+        const bool single_leaf = (static_cast<uint32_t>(bt.root_ref) & BANK_LEAF_FLAG) != 0u;
+        uint32_t at = single_leaf ? 0u : static_cast<uint32_t>(bt.root_ref);  // byte offset of the slot's word
+        const int steps = batch[b].steps;
+        for (int step = 0; step < steps; ++step) {
+            const uint32_t byte = bits_of_row[(at & ~31u) << 3];  // group (at / 32) of BANK_ROWS bytes
+            const uint32_t c = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(child_lds) + at);
+            at = ((byte >> ((at >> 2) & 7u)) & 1u) ? (c >> 16) : (c & 0xffffu);
         }
+        // where the lane stands now, the outcome bit picks a leaf
+        const uint32_t last_byte = bits_of_row[(at & ~31u) << 3];
+        const uint32_t leaves = m.bank.leaf[batch[b].slot_base + (at >> 2)];
+        const uint32_t picked = ((last_byte >> ((at >> 2) & 7u)) & 1u) ? (leaves >> 16) : (leaves & 0xffffu);
         // index into the per-leaf tables; the record that fills a batch of one tree gives leaf 0
-        const int leaf = bt.leaf_base + static_cast<int>(ref & 0x7fffu);
+        const int leaf = bt.leaf_base + static_cast<int>(single_leaf ? 0u : picked);
         pend_valid = bt.valid != 0;
         if (MODE == BANK_LEAVES) {
             pend_node = m.leaf_node[leaf];

@@ -170,12 +170,16 @@ struct BankFeat {
     int32_t reserved;
 };
 
-// A reference of the register-bank program, 16 bits: bit 15 clear: a slot of the batch; bit 15 set:
-// a leaf, the low 15 bits its in-order index among the leaves of its tree.
+// The register-bank program's walk.  A slot's word in the child table holds, for the left child
+// in the low half and the right child in the high half, the byte offset (4 * slot) of the word
+// the walk reads next: the child's slot, or the slot itself where the child is a leaf.  The leaf
+// table holds for the same two children their in-order index among the leaves of the tree
+// (0xffff for an internal child).  A tree record's root reference is the byte offset of the
+// root's word, or BANK_LEAF_FLAG if the tree is a single leaf.
 constexpr uint32_t BANK_LEAF_FLAG = 0x8000u;
 
 struct BankTree {
-    int32_t root_ref;     // reference of the root (a leaf if the tree is a single leaf)
+    int32_t root_ref;     // byte offset of the root's word in the batch's child table; BANK_LEAF_FLAG: a single leaf
     int32_t leaf_base;    // index of the tree's first leaf in the per-leaf tables
     int32_t caller_tree;  // index of the tree in the caller's description
     int32_t valid;        // 0 for the record that fills a batch of one tree
@@ -184,7 +188,8 @@ struct BankTree {
 struct BankBatch {
     int32_t slot_base;  // first entry of the batch in the child table
     int32_t n_slots;    // slots of the batch (whole units)
-    int32_t reserved[2];
+    int32_t steps;      // moves of the walk: internal nodes on the longest path of the batch's trees, less one
+    int32_t reserved;
 };
 
 struct BankSpan {
@@ -236,7 +241,8 @@ struct PackedModel {
     std::vector<BankFeat> bank_feat;          // [F]
     std::vector<uint16_t> bank_tab;           // fast lookup tables of all features
     std::vector<uint32_t> bank_prog;         // (f16(-4 code(j')) << 16) | register index inside the bank
-    std::vector<uint32_t> bank_child;        // per batch, by slot: left reference | right reference << 16
+    std::vector<uint32_t> bank_child;        // per batch, by slot: where the walk goes next, left | right << 16
+    std::vector<uint32_t> bank_leaf;         // same index: the leaves the two children are, left | right << 16
     std::vector<BankBatch> bank_batch;       // [batches]
     std::vector<BankTree> bank_tree;         // [batches * BANK_TREES], processing order
     std::vector<BankSpan> bank_span;         // [batches][BANK_WAVES]

@@ -706,9 +706,18 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
             max_units = std::max<int64_t>(max_units, unit_base);
             // child references by slot, and the trees' records
-            m.bank_batch.push_back(BankBatch{static_cast<int32_t>(m.bank_child.size()), unit_base * BANK_UNIT, {0, 0}});
+            // The walk takes a fixed number of steps: as many as the deepest tree of the batch has
+            // internal nodes on a path, less one.  A step moves to the child the outcome bit picks;
+            // where that child is a leaf the reference is the slot's own, so the lane stays there,
+            // and after the last step the outcome bit of where it stands picks its leaf.
+            int32_t steps = 0;
+            for (int32_t j = 0; j < count; ++j) steps = std::max(steps, shape[order[members[j]]].depth - 1);
+            m.bank_batch.push_back(BankBatch{static_cast<int32_t>(m.bank_child.size()), unit_base * BANK_UNIT, steps, 0});
             const size_t child_at = m.bank_child.size();
-            m.bank_child.resize(child_at + static_cast<size_t>(unit_base) * BANK_UNIT, 0xffffffffu);
+            // slots without a node: a word that leads to slot 0 (lanes with nothing to walk start
+            // there and must stay inside the buffer)
+            m.bank_child.resize(child_at + static_cast<size_t>(unit_base) * BANK_UNIT, 0u);
+            m.bank_leaf.resize(child_at + static_cast<size_t>(unit_base) * BANK_UNIT, 0x80008000u);
             for (int32_t j = 0; j < BANK_TREES; ++j) {
                 if (j >= count) {
                     m.bank_tree.push_back(BankTree{static_cast<int32_t>(BANK_LEAF_FLAG), 0, 0, 0});
@@ -719,18 +728,26 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 const TreeShape &sh = shape[t];
                 const TreeMeta &tm = m.tree[ti];
                 const int64_t base = d.tree_offset[t];
-                auto ref_of = [&](int32_t caller_node) -> uint32_t {
+                if (static_cast<int64_t>(sh.leaves.size()) > static_cast<int64_t>(BANK_LEAF_FLAG)) fits = false;
+                // where a step from slot `self` goes for child `caller_node`: the child's slot, or
+                // `self` again if the child is a leaf; as the byte offset of the slot's word
+                auto next_of = [&](int32_t caller_node, int32_t self) -> uint32_t {
                     const int32_t o = sh.ordinal[caller_node];
-                    if (o >= 0) return static_cast<uint32_t>(slot_of[j][o]);
-                    const int32_t leaf = ~o;  // in-order ordinal inside the tree
-                    if (leaf >= static_cast<int32_t>(BANK_LEAF_FLAG)) fits = false;
-                    return BANK_LEAF_FLAG | static_cast<uint32_t>(leaf & 0x7fff);
+                    return 4u * static_cast<uint32_t>(o >= 0 ? slot_of[j][o] : self);
+                };
+                // the leaf a child is (in-order ordinal inside the tree), 0xffff for an internal child
+                auto leaf_of = [&](int32_t caller_node) -> uint32_t {
+                    const int32_t o = sh.ordinal[caller_node];
+                    return o >= 0 ? 0xffffu : static_cast<uint32_t>(~o) & 0x7fffu;
                 };
                 for (int32_t i = 0; i < static_cast<int32_t>(sh.internal.size()); ++i) {
-                    const int32_t v = sh.internal[i];
-                    m.bank_child[child_at + slot_of[j][i]] = ref_of(d.left[base + v]) | (ref_of(d.right[base + v]) << 16);
+                    const int32_t v = sh.internal[i], self = slot_of[j][i];
+                    m.bank_child[child_at + self] = next_of(d.left[base + v], self) | (next_of(d.right[base + v], self) << 16);
+                    m.bank_leaf[child_at + self] = leaf_of(d.left[base + v]) | (leaf_of(d.right[base + v]) << 16);
                 }
-                m.bank_tree.push_back(BankTree{static_cast<int32_t>(ref_of(0)), tm.leaf_base, tm.caller_tree, 1});
+                // the root: its slot's byte offset, or, if the tree is one leaf, that leaf
+                const int32_t root_ref = sh.internal.empty() ? static_cast<int32_t>(BANK_LEAF_FLAG) : 4 * slot_of[j][0];
+                m.bank_tree.push_back(BankTree{root_ref, tm.leaf_base, tm.caller_tree, 1});
             }
         }
         if (fits) {
@@ -744,6 +761,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
         } else {
             m.bank_child.clear();
+            m.bank_leaf.clear();
             m.bank_batch.clear();
             m.bank_tree.clear();
             m.bank_span.clear();

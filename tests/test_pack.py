@@ -302,22 +302,24 @@ def _simulate_bank_program(f, v, X):
                 thr = v["rank_threshold"][tbase[feat] + (reg - vfirst[feat]) * seg + jl]
                 bits[:, slot] = ~(X[:, feat] <= thr)
             cursor[w] += units * U
-        slot_base, n_slots = (int(z) for z in v["bank_batch"][b, :2])
+        slot_base, n_slots, steps = (int(z) for z in v["bank_batch"][b, :3])
         assert n_slots == n_units * U
         child = v["bank_child"][slot_base:slot_base + n_slots].astype(np.int64)
+        leaves = v["bank_leaf"][slot_base:slot_base + n_slots].astype(np.int64)
         for j in range(nt):
             root, leaf_base, caller, valid = (int(z) for z in v["bank_tree"][b, j])
             if not valid:
                 continue
-            ref = np.full(len(X), root, dtype=np.int64)
-            for _ in range(70):
-                on = (ref & 0x8000) == 0
-                if not on.any():
-                    break
-                idx = ref[on]
-                ref[on] = np.where(bits[on, idx], child[idx] >> 16, child[idx] & 0xffff)
-            assert ((ref & 0x8000) != 0).all()
-            leaf = leaf_base + (ref & 0x7fff)
+            if root & 0x8000:  # a single leaf
+                leaf = np.full(len(X), leaf_base, dtype=np.int64)
+            else:
+                at = np.full(len(X), root, dtype=np.int64)
+                for _ in range(steps):
+                    assert (at % 4 == 0).all() and (at // 4 < n_slots).all()
+                    at = np.where(bits[np.arange(len(X)), at // 4], child[at // 4] >> 16, child[at // 4] & 0xffff)
+                picked = np.where(bits[np.arange(len(X)), at // 4], leaves[at // 4] >> 16, leaves[at // 4] & 0xffff)
+                assert (picked != 0xffff).all()  # the walk has reached a node whose chosen child is a leaf
+                leaf = leaf_base + picked
             assert (v["order_leaf_tree"][leaf] == caller).all()
             out[:, caller] = v["order_leaf_node"][leaf]
     return out
@@ -339,7 +341,7 @@ def test_register_bank_program_reaches_the_oracles_leaves(seed):
     ref = oracle.predict(f, X, want_leaves=True)
     np.testing.assert_array_equal(_simulate_bank_program(f, v, X), ref.leaf_node_id)
     # every internal node sits in exactly one slot, and each wave holds at most bank_regs registers
-    used = int((v["bank_child"] != 0xffffffff).sum())
+    used = int((v["bank_leaf"] != 0x80008000).sum())
     assert used == int(v["tree_n_internal"].sum())
 
 
