@@ -320,13 +320,34 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             prev[k * BANK_ROWS + 2 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[0]));
             prev[k * BANK_ROWS + 3 * TILE] = static_cast<uint8_t>(__float_as_uint(gb[1]));
         };
+        // The same stores for a group whose bytes the matrix core finished long ago: inside the
+        // loop a whole group of comparisons (26 instructions) lies between a matrix instruction and
+        // the store of its result, more than the 11 wait states it needs.  The compiler cannot
+        // count the instructions of the comparison statement and would pad every store with idle
+        // cycles; written as a statement of their own the stores go out at once.
+#if defined(__HIP_DEVICE_COMPILE__)
+        typedef __attribute__((address_space(3))) uint8_t *LdsBytes;
+#endif
+        auto store_late = [&](int k) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            const uint32_t to = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((LdsBytes)prev));
+            asm volatile("ds_write_b8 %0, %1 offset:%5\n\t"
+                         "ds_write_b8 %0, %2 offset:%6\n\t"
+                         "ds_write_b8 %0, %3 offset:%7\n\t"
+                         "ds_write_b8 %0, %4 offset:%8"
+                         :
+                         : "v"(to), "v"(ga[0]), "v"(ga[1]), "v"(gb[0]), "v"(gb[1]), "n"(k * BANK_ROWS),
+                           "n"(k * BANK_ROWS + TILE), "n"(k * BANK_ROWS + 2 * TILE), "n"(k * BANK_ROWS + 3 * TILE)
+                         : "memory");
+#endif
+        };
         auto group = [&](const Entry8 &q, int k) {  // k: constant at every call
             v8i da, db;
             bank_compare(da, db, q, xa, xb);
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_sched_barrier(0);
 #endif
-            if (pending) store(k);
+            if (pending) store_late(k);
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -360,9 +381,12 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             p += 16;
             prev += 2 * BANK_ROWS;
         }
-        if (pending) store(0);
+        if (pending) store(0);  // right behind its matrix instructions: the compiler's own store, with the wait
         if (stage) reinterpret_cast<u32x4 *>(child_lds)[threadIdx.x] = staged;
         if (b > 0) consume_pending();  // the last batch's leaves
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the loop's stores are not the compiler's to wait for
+#endif
         __syncthreads();  // the batch's bits and child references are complete
 
         // ---- walk: one (row, tree) per lane.  Every lane takes the batch's number of steps: a step
