@@ -276,7 +276,7 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     // The stream lives in two sets of 16 scalar registers used in turn: while one is evaluated
     // the other is being loaded.
-    Batch<16> set_a = load_batch<16>(p);
+    Batch<16> set_a = load_batch<16>(p), set_b = load_batch<16>(p + 16);
     // What a walk ends on is fetched at once and used a batch later (the gather's latency is
     // covered by the next batch's comparisons): the leaf's values, or, for the leaf-id output,
     // the caller's node index with the place it goes to.
@@ -341,9 +341,15 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
                          : "memory");
 #endif
         };
-        auto group = [&](const Entry8 &q, int k) {  // k: constant at every call
+        // One group: its comparisons, then the stores of the group before, then its bytes' turn on
+        // the matrix core.  `between` runs after the comparisons (k: constant at every call).
+        auto group = [&](const Entry8 &q, int k, auto between) {
             v8i da, db;
             bank_compare(da, db, q, xa, xb);
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+            between();
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -355,29 +361,36 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             gb = bits.collect_b(db, bits.bias);
             pending = true;
         };
-        // Scalar loads may return out of order, so a wait for one is a wait for all that are in
-        // flight: only one load of the stream is ever in flight, issued right after the wait
-        // for the set evaluated next -- tied to it through the stream pointer -- so that it has
-        // the whole evaluation of that set, two groups, to arrive.
+        auto nothing = [] {};
+        // The stream: set_a holds the unit evaluated next and has arrived, set_b the unit after it
+        // and is on its way (a wave's units follow each other from batch to batch, so this holds
+        // from one batch to the next).  Scalar loads may return out of order and share their counter
+        // with the LDS, so a wait for one is a wait for everything: the wait for the set on its
+        // way sits after the comparisons of a unit's second group -- the load has had most of two
+        // groups to arrive, the last stores a whole group -- and the set just used up is loaded
+        // again right behind it, tied to the wait through the stream pointer.
         int u = 0;
         for (; u + 1 < n_units; u += 2) {
-            issue_after(p, set_a);
-            const Batch<16> set_b = load_batch<16>(p + 16);
-            group(set_a.q[0], 0);
-            group(set_a.q[1], 1);
-            issue_after(p, set_b);
-            set_a = load_batch<16>(p + 32);
-            group(set_b.q[0], 2);
-            group(set_b.q[1], 3);
+            group(set_a.q[0], 0, nothing);
+            group(set_a.q[1], 1, [&] {
+                issue_after(p, set_b);
+                set_a = load_batch<16>(p + 32);
+            });
+            group(set_b.q[0], 2, nothing);
+            group(set_b.q[1], 3, [&] {
+                issue_after(p, set_a);
+                set_b = load_batch<16>(p + 48);
+            });
             p += 32;
             prev += 4 * BANK_ROWS;
         }
         if (u < n_units) {
-            issue_after(p, set_a);
-            const Batch<16> set_b = load_batch<16>(p + 16);
-            group(set_a.q[0], 0);
-            group(set_a.q[1], 1);
-            set_a = set_b;
+            group(set_a.q[0], 0, nothing);
+            group(set_a.q[1], 1, [&] {
+                issue_after(p, set_b);
+                set_a = set_b;
+                set_b = load_batch<16>(p + 32);
+            });
             p += 16;
             prev += 2 * BANK_ROWS;
         }
