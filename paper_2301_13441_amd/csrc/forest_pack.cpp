@@ -498,46 +498,132 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         for (int32_t t = 0; t < T; ++t)
             for (int32_t v : shape[t].internal) ++reg_nodes[entry_of(t, v).feature_slot];
         std::vector<int32_t> reg_wave(static_cast<size_t>(m.rank_regs)), reg_index(static_cast<size_t>(m.rank_regs));
-        int64_t load[BANK_WAVES] = {};
-        int32_t held[BANK_WAVES] = {};
-        m.bank_reg.assign(BANK_WAVES * BANK_REGS, 0);
-        for (int32_t f0 = 0; f0 < d.n_features; f0 += BANK_PASS_FEATURES) {
-            const int32_t f1 = std::min<int32_t>(f0 + BANK_PASS_FEATURES, d.n_features);
-            const int32_t r0 = m.feat_vfirst[f0], r1 = f1 < d.n_features ? m.feat_vfirst[f1] : m.rank_regs;
-            if (r0 == r1) continue;  // no thresholds on these columns: the block is never read
-            std::vector<int32_t> by_weight(static_cast<size_t>(r1 - r0));
-            std::iota(by_weight.begin(), by_weight.end(), r0);
-            std::stable_sort(by_weight.begin(), by_weight.end(),
-                             [&](int32_t a, int32_t b) { return reg_nodes[a] > reg_nodes[b]; });
-            const int32_t share = (r1 - r0 + BANK_WAVES - 1) / BANK_WAVES;
-            int32_t here[BANK_WAVES] = {};
-            for (int32_t r : by_weight) {
-                int best = -1;
-                for (int pass = 0; pass < 2 && best < 0; ++pass)  // second try: the share no longer binds
-                    for (int w = 0; w < BANK_WAVES; ++w)
-                        if (held[w] < BANK_REGS && (pass == 1 || here[w] < share) && (best < 0 || load[w] < load[best])) best = w;
-                reg_wave[r] = best;
-                reg_index[r] = held[best];
-                m.bank_reg[best * BANK_REGS + held[best]] = r;
-                ++held[best];
-                ++here[best];
-                load[best] += reg_nodes[r];
+        struct Block { int32_t f0, f1, r0, r1; };
+        std::vector<Block> blocks;
+        {
+            int64_t load[BANK_WAVES] = {};
+            int32_t held[BANK_WAVES] = {};
+            for (int32_t f0 = 0; f0 < d.n_features; f0 += BANK_PASS_FEATURES) {
+                const int32_t f1 = std::min<int32_t>(f0 + BANK_PASS_FEATURES, d.n_features);
+                const int32_t r0 = m.feat_vfirst[f0], r1 = f1 < d.n_features ? m.feat_vfirst[f1] : m.rank_regs;
+                if (r0 == r1) continue;  // no thresholds on these columns: the block is never read
+                blocks.push_back(Block{f0, f1, r0, r1});
+                std::vector<int32_t> by_weight(static_cast<size_t>(r1 - r0));
+                std::iota(by_weight.begin(), by_weight.end(), r0);
+                std::stable_sort(by_weight.begin(), by_weight.end(),
+                                 [&](int32_t a, int32_t b) { return reg_nodes[a] > reg_nodes[b]; });
+                const int32_t share = (r1 - r0 + BANK_WAVES - 1) / BANK_WAVES;
+                int32_t here[BANK_WAVES] = {};
+                for (int32_t r : by_weight) {
+                    int best = -1;
+                    for (int pass = 0; pass < 2 && best < 0; ++pass)  // second try: the share no longer binds
+                        for (int w = 0; w < BANK_WAVES; ++w)
+                            if (held[w] < BANK_REGS && (pass == 1 || here[w] < share) && (best < 0 || load[w] < load[best])) best = w;
+                    reg_wave[r] = best;
+                    ++held[best];
+                    ++here[best];
+                    load[best] += reg_nodes[r];
+                }
             }
-            // the pass and the waves' to-do lists: fast lookups first
-            std::vector<BankTodo> mine[BANK_WAVES][2];
-            for (int32_t r = r0; r < r1; ++r) {
-                const int32_t f = reg_feature[r];
-                const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
-                const int32_t first = reg_segment[r] * RANK_SEG;
-                const bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS;  // refined below
-                mine[reg_wave[r]][fast ? 0 : 1].push_back(BankTodo{reg_index[r], f, first, std::min<int32_t>(n - first, RANK_SEG)});
+        }
+        // nodes of every tree (processing order) by rank register
+        std::vector<std::vector<std::pair<int32_t, int32_t>>> tree_regs(static_cast<size_t>(T));  // (register, nodes)
+        for (int32_t ti = 0; ti < T; ++ti) {
+            std::vector<int32_t> count(static_cast<size_t>(m.rank_regs), 0);
+            for (int32_t v : shape[order[ti]].internal) ++count[entry_of(order[ti], v).feature_slot];
+            for (int32_t r = 0; r < m.rank_regs; ++r)
+                if (count[r]) tree_regs[ti].emplace_back(r, count[r]);
+        }
+        // nodes of every tree by wave, under the current dealing
+        std::vector<std::array<int32_t, BANK_WAVES>> per_wave(static_cast<size_t>(T));
+        auto count_per_wave = [&] {
+            for (int32_t ti = 0; ti < T; ++ti) {
+                per_wave[ti].fill(0);
+                for (const auto &rc : tree_regs[ti]) per_wave[ti][reg_wave[rc.first]] += rc.second;
             }
-            m.bank_pass.push_back(BankPass{f0, f1});
+        };
+        // units of a batch of trees a and b (b < 0: a alone), and the units of its busiest wave
+        auto batch_units = [&](int32_t a, int32_t b, int64_t *busiest) {
+            int64_t units = 0, most = 0;
             for (int w = 0; w < BANK_WAVES; ++w) {
-                m.bank_pass_wave.push_back(BankPassWave{static_cast<int32_t>(m.bank_todo.size()),
-                                                        static_cast<int32_t>(mine[w][0].size()),
-                                                        static_cast<int32_t>(mine[w][1].size()), 0});
-                for (int k = 0; k < 2; ++k) m.bank_todo.insert(m.bank_todo.end(), mine[w][k].begin(), mine[w][k].end());
+                const int64_t u = (per_wave[a][w] + (b >= 0 ? per_wave[b][w] : 0) + BANK_UNIT - 1) / BANK_UNIT;
+                units += u;
+                most = std::max(most, u);
+            }
+            if (busiest) *busiest = most;
+            return units;
+        };
+        // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot; the
+        // kernel keeps one row of bytes in front of the buffer
+        const int64_t budget_units =
+            static_cast<int64_t>((BANK_MAX_LDS - BANK_ROWS) / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
+        bool fits = true;
+        // Which trees share a batch.  Every batch costs the workgroup two barriers and a walk, and
+        // its waves wait for the busiest of them, so: as few batches as the buffer allows (largest
+        // tree first, paired with one of the largest trees that still fit beside it), and among
+        // those candidates the partner that leaves the busiest wave the least to do.  The trees of
+        // a model that takes this path all feed the same output columns, so their order only
+        // decides the order of the float64 additions.
+        static_assert(BANK_TREES == 2, "batches are pairs");
+        std::vector<int32_t> by_size(static_cast<size_t>(T));
+        std::iota(by_size.begin(), by_size.end(), 0);
+        std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t a, int32_t b) {
+            return shape[order[a]].internal.size() > shape[order[b]].internal.size();
+        });
+        std::vector<std::array<int32_t, BANK_TREES>> batches;
+        auto pair_trees = [&] {
+            count_per_wave();
+            batches.clear();
+            std::vector<char> taken(static_cast<size_t>(T), 0);
+            for (int32_t a : by_size) {
+                if (taken[a]) continue;
+                taken[a] = 1;
+                if (batch_units(a, -1, nullptr) > budget_units) {
+                    fits = false;  // a single tree too large for the buffer
+                    return;
+                }
+                int32_t partner = -1, seen = 0;
+                int64_t partner_busiest = 0;
+                for (int32_t b : by_size) {
+                    if (taken[b]) continue;
+                    int64_t busiest;
+                    if (batch_units(a, b, &busiest) > budget_units) continue;
+                    if (partner < 0 || busiest < partner_busiest) {
+                        partner = b;
+                        partner_busiest = busiest;
+                    }
+                    if (++seen == 8) break;
+                }
+                if (partner >= 0) taken[partner] = 1;
+                batches.push_back({std::min(a, partner < 0 ? a : partner), partner < 0 ? -1 : std::max(a, partner)});
+            }
+            std::sort(batches.begin(), batches.end());
+        };
+        pair_trees();
+        // the registers' places inside the banks, the passes and the waves' to-do lists (fast lookups first)
+        m.bank_reg.assign(BANK_WAVES * BANK_REGS, 0);
+        {
+            int32_t held[BANK_WAVES] = {};
+            for (const Block &blk : blocks) {
+                std::vector<BankTodo> mine[BANK_WAVES][2];
+                for (int32_t r = blk.r0; r < blk.r1; ++r) {
+                    const int w = reg_wave[r];
+                    reg_index[r] = held[w];
+                    m.bank_reg[w * BANK_REGS + held[w]] = r;
+                    ++held[w];
+                    const int32_t f = reg_feature[r];
+                    const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
+                    const int32_t first = reg_segment[r] * RANK_SEG;
+                    const bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS;  // refined below
+                    mine[w][fast ? 0 : 1].push_back(BankTodo{reg_index[r], f, first, std::min<int32_t>(n - first, RANK_SEG)});
+                }
+                m.bank_pass.push_back(BankPass{blk.f0, blk.f1});
+                for (int w = 0; w < BANK_WAVES; ++w) {
+                    m.bank_pass_wave.push_back(BankPassWave{static_cast<int32_t>(m.bank_todo.size()),
+                                                            static_cast<int32_t>(mine[w][0].size()),
+                                                            static_cast<int32_t>(mine[w][1].size()), 0});
+                    for (int k = 0; k < 2; ++k) m.bank_todo.insert(m.bank_todo.end(), mine[w][k].begin(), mine[w][k].end());
+                }
             }
         }
         // Fast lookup tables.  A uniform grid over the feature's finite thresholds, refined until
@@ -607,66 +693,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
         std::memcpy(&pad32, &pad.threshold, sizeof(pad32));
         pad32 &= 0xffff0000u;  // bank register 0 against the largest code: outcome 0
         int64_t max_units = 0;
-        bool fits = true;
         struct Node { int32_t tree, ordinal; };
-        // nodes of every tree (processing order) by wave
-        std::vector<std::array<int32_t, BANK_WAVES>> per_wave(static_cast<size_t>(T));
-        for (int32_t ti = 0; ti < T; ++ti) {
-            per_wave[ti].fill(0);
-            for (int32_t v : shape[order[ti]].internal) ++per_wave[ti][reg_wave[entry_of(order[ti], v).feature_slot]];
-        }
-        // units of a batch of trees a and b (b < 0: a alone), and the units of its busiest wave
-        auto batch_units = [&](int32_t a, int32_t b, int64_t *busiest) {
-            int64_t units = 0, most = 0;
-            for (int w = 0; w < BANK_WAVES; ++w) {
-                const int64_t u = (per_wave[a][w] + (b >= 0 ? per_wave[b][w] : 0) + BANK_UNIT - 1) / BANK_UNIT;
-                units += u;
-                most = std::max(most, u);
-            }
-            if (busiest) *busiest = most;
-            return units;
-        };
-        // a unit takes BANK_UNIT / 8 bytes per row and 4 bytes of child references per slot; the
-        // kernel keeps one row of bytes in front of the buffer
-        const int64_t budget_units =
-            static_cast<int64_t>((BANK_MAX_LDS - BANK_ROWS) / (BANK_ROWS * (BANK_UNIT / 8) + 4 * BANK_UNIT));
-        // Which trees share a batch.  Every batch costs the workgroup two barriers and a walk, and
-        // its waves wait for the busiest of them, so: as few batches as the buffer allows (largest
-        // tree first, paired with one of the largest trees that still fit beside it), and among
-        // those candidates the partner that leaves the busiest wave the least to do.  The trees of
-        // a model that takes this path all feed the same output columns, so their order only
-        // decides the order of the float64 additions.
-        static_assert(BANK_TREES == 2, "batches are pairs");
-        std::vector<int32_t> by_size(static_cast<size_t>(T));
-        std::iota(by_size.begin(), by_size.end(), 0);
-        std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t a, int32_t b) {
-            return shape[order[a]].internal.size() > shape[order[b]].internal.size();
-        });
-        std::vector<char> taken(static_cast<size_t>(T), 0);
-        std::vector<std::array<int32_t, BANK_TREES>> batches;
-        for (int32_t a : by_size) {
-            if (taken[a]) continue;
-            taken[a] = 1;
-            if (batch_units(a, -1, nullptr) > budget_units) {
-                fits = false;  // a single tree too large for the buffer
-                break;
-            }
-            int32_t partner = -1, seen = 0;
-            int64_t partner_busiest = 0;
-            for (int32_t b : by_size) {
-                if (taken[b]) continue;
-                int64_t busiest;
-                if (batch_units(a, b, &busiest) > budget_units) continue;
-                if (partner < 0 || busiest < partner_busiest) {
-                    partner = b;
-                    partner_busiest = busiest;
-                }
-                if (++seen == 8) break;
-            }
-            if (partner >= 0) taken[partner] = 1;
-            batches.push_back({std::min(a, partner < 0 ? a : partner), partner < 0 ? -1 : std::max(a, partner)});
-        }
-        std::sort(batches.begin(), batches.end());
         int32_t n_batches = 0;
         for (size_t bi = 0; bi < batches.size() && fits; ++bi, ++n_batches) {
             const std::array<int32_t, BANK_TREES> &members = batches[bi];
