@@ -100,6 +100,59 @@ def test_register_bank_kernel_on_large_batches(seed):
         assert info["kernel_path"] == 3 and info["rank_banks"] == 1
 
 
+def test_register_bank_kernel_lookup_paths():
+    """The register-bank kernel's rank lookups, every path in one model: a feature whose 13,000
+    thresholds take two registers, one with 7,000 (one register, codes of both signs), one with 3
+    (no window), one whose 500 thresholds crowd into a millionth of its range (buckets fuller
+    than a window), features in a second block of 64 columns with the block between unused, rows
+    of 70 floats at a 4-byte aligned address, values on and between thresholds, NaN and Inf."""
+    import torch
+    import paper_2301_13441_amd as pk
+    rng = np.random.default_rng(77)
+    F, n = 200, 65536 + 77
+    f = wl.random_forest(4242, n_trees=600, n_features=F, max_depth=7, stop_prob=0.05)
+    internal = np.flatnonzero(f.feature >= 0)
+    assert internal.size > 30000
+    feat = f.feature.copy()
+    thr = f.threshold.copy()
+    cut = [0, 13000, 20000, 20300, 22300, internal.size]
+    feat[internal[cut[0]:cut[1]]] = 0
+    thr[internal[cut[0]:cut[1]]] = rng.permutation(13000).astype(np.float32)
+    feat[internal[cut[1]:cut[2]]] = 1
+    thr[internal[cut[1]:cut[2]]] = rng.permutation(7000).astype(np.float32) * np.float32(0.5)
+    feat[internal[cut[2]:cut[3]]] = 2
+    thr[internal[cut[2]:cut[3]]] = rng.choice(np.float32([-0.5, 0.0, 0.75]), cut[3] - cut[2])
+    feat[internal[cut[3]:cut[4]]] = 3
+    thr[internal[cut[3]:cut[4]]] = np.float32(1.0) + rng.integers(0, 500, cut[4] - cut[3]).astype(np.float32) * np.float32(1e-6)
+    thr[internal[cut[3]:cut[3] + 2]] = np.float32([-1e30, 1e30])
+    feat[internal[cut[4]:]] = 130 + rng.integers(0, 70, internal.size - cut[4]).astype(np.int32)   # columns 64..127 unused
+    g = wl.Forest(**{**f.__dict__, "feature": feat, "threshold": thr})
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    X[:, 0] = rng.integers(-2, 26004, n).astype(np.float32) * np.float32(0.5)
+    X[:, 1] = rng.integers(-4, 14008, n).astype(np.float32) * np.float32(0.25)
+    X[:, 2] = rng.choice(np.float32([-1.0, -0.5, -0.25, 0.0, 0.5, 0.75, 1.0]), n)
+    X[:, 3] = np.float32(1.0) + rng.integers(-5, 505, n).astype(np.float32) * np.float32(1e-6)
+    X[::97, 3] = rng.choice(np.float32([-2e30, -1e30, 0.0, 1e30, 2e30]), len(X[::97]))
+    X[11, :] = np.nan
+    X[12, :] = np.inf
+    X[13, :] = -np.inf
+    buf = torch.zeros(n * F + 1, dtype=torch.float32, device="cuda")
+    xd = buf[1:].view(n, F)
+    xd.copy_(torch.from_numpy(X))
+    assert xd.data_ptr() % 8 == 4
+    ref = oracle.predict(g, X, want_leaves=True, n_threads=8)
+    h = pk.forest_load(g)
+    try:
+        assert h.info["kernel_path"] == 3 and h.info["rank_banks"] == 1
+        scores, labels = h.predict(xd)
+        leaves = h.predict_leaves(xd)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(leaves.cpu().numpy(), ref.leaf_node_id)
+        np.testing.assert_allclose(scores.cpu().numpy(), ref.scores, rtol=RTOL, atol=ATOL)
+    finally:
+        h.close()
+
+
 @pytest.mark.parametrize("seed", range(64))
 def test_random_models_and_batches(seed):
     """Everything drawn at once: full or irregular trees, feature and tree counts, depth, output
