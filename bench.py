@@ -178,6 +178,23 @@ def hbm_copy_rate() -> float:
     return 5 * 2 * 4.0 * n / (start.elapsed_time(stop) * 1e-3)
 
 
+def compare_issue_rate() -> float:
+    """(row, node) comparisons per second of a kernel that only issues the rank kernels' packed-f16
+    compare instruction (eight wavefronts per SIMD, sixteen independent chains per lane): what the
+    chip delivers where the roofline quotes 256 CU x 4 SIMD x 16 lanes x 2.4 GHz x 2."""
+    import torch
+    from paper_2301_13441_amd import binding
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.forest_probe_compare_rate(1000, word)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    n = binding.forest_probe_compare_rate(20000, word)
+    stop.record()
+    torch.cuda.synchronize()
+    return n / (start.elapsed_time(stop) * 1e-3)
+
+
 def bench_forest(name: str, args) -> dict:
     """All fields of one tree-ensemble configuration."""
     import numpy as np
@@ -356,7 +373,9 @@ def main() -> int:
                 per[name]["unit"] = "rows/s"
         line["per_config"] = per
         line["measured_peaks"] = {"hbm_copy_GBps": hbm_copy_rate() / 1e9,
-                                  "note": "device-to-device copy of 1 GiB, bytes read + written"}
+                                  "packed_f16_compare_Tps": compare_issue_rate() / 1e12,
+                                  "note": "device-to-device copy of 1 GiB, bytes read + written; a kernel of "
+                                          "nothing but v_pk_fma_f16 ... clamp, two comparisons per lane-op"}
     print(json.dumps(line))
     return 0
 

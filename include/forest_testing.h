@@ -128,6 +128,17 @@ void forest_pack_free(forest_packed *p);
  */
 int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry);
 
+/*
+ * Measurement aid: enqueues on `stream` (a hipStream_t, may be null) a kernel that does nothing
+ * but issue the packed-f16 compare instruction of the rank kernels (Section 4.3.1 applied to the
+ * input), `iterations` times 16 per lane on eight wavefronts per SIMD of the current device, and
+ * stores the number of (row, node) comparisons that amounts to in *comparisons.  Timed by the
+ * caller (events on the same stream), it gives the rate the chip delivers where the roofline
+ * quotes the nominal one.  `device_word` is 4 bytes of device memory the kernel may write.
+ * Returns FOREST_OK, FOREST_EINVAL (iterations outside 1 .. 2^24, null pointer) or FOREST_EHIP.
+ */
+int forest_probe_compare_rate(int32_t iterations, void *stream, uint32_t *device_word, int64_t *comparisons);
+
 #ifdef __cplusplus
 }
 #endif

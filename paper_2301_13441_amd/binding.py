@@ -59,7 +59,8 @@ class _View(ctypes.Structure):
 EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "forest_out_layout",
            "forest_predict", "forest_predict_static", "forest_predict_leaves", "forest_strerror"]
 # include/forest_testing.h: host-only views into the model compiler, for its tests
-TESTING_EXPORTS = ["forest_pack", "forest_pack_view", "forest_pack_free", "forest_rank_code"]
+TESTING_EXPORTS = ["forest_pack", "forest_pack_view", "forest_pack_free", "forest_rank_code",
+                   "forest_probe_compare_rate"]
 
 
 def lib_path() -> str:
@@ -234,6 +235,21 @@ def forest_rank_code(q: int) -> tuple[int, int, int]:
     if n < 0:
         raise ForestError(n, _strerror(n))
     return n, code.value, entry.value
+
+
+def forest_probe_compare_rate(iterations: int, device_word, stream=None) -> int:
+    """Enqueues the compare-issue probe on `stream` (torch stream; default: the current one) and
+    returns the number of comparisons it makes; `device_word` is an int32 device tensor."""
+    import torch
+    lib = load_library()
+    lib.forest_probe_compare_rate.restype = ctypes.c_int
+    lib.forest_probe_compare_rate.argtypes = [_i32, _p, _p, ctypes.POINTER(_i64)]
+    s = torch.cuda.current_stream(device_word.device) if stream is None else stream
+    n = _i64()
+    rc = lib.forest_probe_compare_rate(int(iterations), _p(s.cuda_stream), _p(device_word.data_ptr()), ctypes.byref(n))
+    if rc != 0:
+        raise ForestError(rc, "forest_probe_compare_rate")
+    return int(n.value)
 
 
 def _check_x(X, n_features: int) -> None:

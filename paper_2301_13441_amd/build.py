@@ -12,6 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libforest_hip.so")
 SOURCES = ["forest_pack.cpp", "forest_api_host.cpp", "forest_api.cpp", "forest_kernels.hip", "forest_kernels_reg.hip",
            "forest_kernels_rank.hip", "forest_kernels_ranklds.hip", "forest_kernels_rankbank.hip", "forest_kernels_split.hip",
+           "forest_probe.hip",
            "linear_api.cpp", "linear_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

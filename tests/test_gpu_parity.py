@@ -698,3 +698,13 @@ def test_input_larger_than_2_to_31_elements():
     ref = oracle.predict(w.forest, xs, n_threads=8)
     np.testing.assert_array_equal(got_labels, ref.labels)
     np.testing.assert_allclose(got_scores, ref.scores, rtol=RTOL, atol=ATOL)
+
+
+def test_compare_rate_probe_runs_and_counts():
+    """The bench's measurement aid: runs to completion, leaves its word alone, counts what it did."""
+    import torch
+    from paper_2301_13441_amd import binding
+    word = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    n = binding.forest_probe_compare_rate(100, word)
+    torch.cuda.synchronize()
+    assert n == 256 * 8 * 256 * 2 * 16 * 100 and int(word.item()) == 7

@@ -489,3 +489,17 @@ def test_rank_codes_compare_exactly():
     assert pk.forest_pack(f)["rank_registers"] == 1
     f.threshold[internal] = np.minimum(np.arange(internal.size), n - 1).astype(np.float32)   # n distinct
     assert pk.forest_pack(f)["rank_registers"] == 2
+
+
+def test_compare_rate_probe_refuses_bad_arguments_before_any_launch():
+    import ctypes
+    lib = binding.load_library()
+    lib.forest_probe_compare_rate.restype = ctypes.c_int
+    lib.forest_probe_compare_rate.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.POINTER(ctypes.c_int64)]
+    n = ctypes.c_int64(-1)
+    assert lib.forest_probe_compare_rate(0, None, ctypes.c_void_p(16), ctypes.byref(n)) < 0
+    assert lib.forest_probe_compare_rate(1 << 25, None, ctypes.c_void_p(16), ctypes.byref(n)) < 0
+    assert lib.forest_probe_compare_rate(10, None, None, ctypes.byref(n)) < 0
+    assert lib.forest_probe_compare_rate(10, None, ctypes.c_void_p(16), None) < 0
+    assert n.value == -1
