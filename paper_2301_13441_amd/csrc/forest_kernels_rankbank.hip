@@ -300,9 +300,10 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         // the texture path serves at about one lane per cycle and the LDS far faster.  Four
         // words per thread, fetched now, stored after the evaluation.
         const int n_slots = batch[b].n_slots;
-        const bool stage = 4 * static_cast<int>(threadIdx.x) < n_slots;  // n_slots is a multiple of 16
+        const int tid = wave * TILE + lane;
+        const bool stage = 4 * tid < n_slots;  // n_slots is a multiple of 16
         u32x4 staged = {0u, 0u, 0u, 0u};
-        if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + batch[b].slot_base)[threadIdx.x];
+        if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + batch[b].slot_base)[tid];
         const BankTree bt = m.bank.tree[b * BANK_TREES + walk_tree];  // used after the evaluation
         // `prev`: where the bytes of the lane's four rows go for the group BEFORE the first group of
         // the current pair of units (prev[0], prev[64], prev[128], prev[192]); the groups of the pair
@@ -395,7 +396,7 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             prev += 2 * BANK_ROWS;
         }
         if (pending) store(0);  // right behind its matrix instructions: the compiler's own store, with the wait
-        if (stage) reinterpret_cast<u32x4 *>(child_lds)[threadIdx.x] = staged;
+        if (stage) reinterpret_cast<u32x4 *>(child_lds)[tid] = staged;
         if (b > 0) consume_pending();  // the last batch's leaves
 #if defined(__HIP_DEVICE_COMPILE__)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the loop's stores are not the compiler's to wait for
@@ -461,16 +462,23 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
 #pragma unroll
     for (int i = 0; i < BANK_REGS; ++i) xa[i] = xb[i] = 0;  // registers the bank does not use stay defined
     bank_ranks(m, X, row0, n_rows, reinterpret_cast<float *>(smem), xa, xb, wave, lane);
+    // From here on the lane's index is counted anew (two instructions) wherever it is needed: kept
+    // in a register across the prologue, whose every register is spoken for, it would be spilled.
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int lane_now = static_cast<int>(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)));
+#else
+    const int lane_now = lane;
+#endif
 
     double sum[2] = {0.0, 0.0};
     uint8_t *buf = reinterpret_cast<uint8_t *>(smem) + BANK_ROWS;  // see `prev` in bank_trees
     uint32_t *child_lds = reinterpret_cast<uint32_t *>(buf + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
-    bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane, row0, n_rows, leaf_out);
+    bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane_now, row0, n_rows, leaf_out);
     if (MODE == BANK_LEAVES) return;
-    const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;
+    const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane_now / BANK_TREES;
     // a copy with run-time indices: indexed that way `sum` itself would live in scratch memory
     double raw[2] = {row_sum(sum[0]), row_sum(sum[1])};
-    if (lane % BANK_TREES == 0 && row < n_rows) finish_values(m, raw, 1, row, scores, labels);
+    if (lane_now % BANK_TREES == 0 && row < n_rows) finish_values(m, raw, 1, row, scores, labels);
 }
 
 size_t rankbank_lds_bytes(const DevModel &m)
