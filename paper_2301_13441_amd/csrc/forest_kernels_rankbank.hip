@@ -294,22 +294,40 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         }
     };
 
+    // The records of a batch (the wave's span, the batch's slots and steps) are read a batch ahead:
+    // read where they are needed, every batch would begin and end with a wait for a scalar load.
+    BankSpan span_next = span[wave];
+    BankBatch batch_next = batch[0];
+    // Everything loaded so far has arrived before the first batch begins, as it has at the end of
+    // every batch (the barrier's wait): the compiler then knows that the records requested at the
+    // top of a batch are all that is on its way there, and does not wait for them before the
+    // first comparisons.
+    issue_after(p, set_a);
+    issue_after(p, set_b);
+    asm volatile("" : : "s"(span_next.n_units), "s"(batch_next.n_slots));
     for (int b = 0; b < m.bank.batches; ++b) {
-        const int n_units = span[b * BANK_WAVES + wave].n_units;
+        const BankSpan my_span = span_next;
+        const BankBatch this_batch = batch_next;
+        {
+            const int nb = b + 1 < m.bank.batches ? b + 1 : b;
+            span_next = span[nb * BANK_WAVES + wave];
+            batch_next = batch[nb];
+        }
+        const int n_units = my_span.n_units;
         // The batch's child references go to LDS: the walk reads one per step and lane, which
         // the texture path serves at about one lane per cycle and the LDS far faster.  Four
         // words per thread, fetched now, stored after the evaluation.
-        const int n_slots = batch[b].n_slots;
+        const int n_slots = this_batch.n_slots;
         const int tid = wave * TILE + lane;
         const bool stage = 4 * tid < n_slots;  // n_slots is a multiple of 16
         u32x4 staged = {0u, 0u, 0u, 0u};
-        if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + batch[b].slot_base)[tid];
+        if (stage) staged = reinterpret_cast<const u32x4 *>(m.bank.child + this_batch.slot_base)[tid];
         const BankTree bt = m.bank.tree[b * BANK_TREES + walk_tree];  // used after the evaluation
         // `prev`: where the bytes of the lane's four rows go for the group BEFORE the first group of
         // the current pair of units (prev[0], prev[64], prev[128], prev[192]); the groups of the pair
         // are at prev + 256, + 512, ...  The buffer starts 256 bytes into the LDS, so `prev` is a
         // valid address for a wave's first group too (nothing is stored through it then).
-        uint8_t *prev = buf + span[b * BANK_WAVES + wave].unit_base * (2 * BANK_ROWS) + lane - BANK_ROWS;
+        uint8_t *prev = buf + my_span.unit_base * (2 * BANK_ROWS) + lane - BANK_ROWS;
         // ---- evaluation: this wave's nodes of the batch.  A group's byte is still being
         // collected by the matrix core when its last comparison has issued, so it is stored
         // after the comparisons of the next group.
@@ -410,7 +428,7 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         const uint8_t *bits_of_row = buf + walk_row;
         const bool single_leaf = (static_cast<uint32_t>(bt.root_ref) & BANK_LEAF_FLAG) != 0u;
         uint32_t at = single_leaf ? 0u : static_cast<uint32_t>(bt.root_ref);  // byte offset of the slot's word
-        const int steps = batch[b].steps;
+        const int steps = this_batch.steps;
         for (int step = 0; step < steps; ++step) {
             const uint32_t byte = bits_of_row[(at & ~31u) << 3];  // group (at / 32) of BANK_ROWS bytes
             const uint32_t c = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(child_lds) + at);
@@ -418,7 +436,7 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         }
         // where the lane stands now, the outcome bit picks a leaf
         const uint32_t last_byte = bits_of_row[(at & ~31u) << 3];
-        const uint32_t leaves = m.bank.leaf[batch[b].slot_base + (at >> 2)];
+        const uint32_t leaves = m.bank.leaf[this_batch.slot_base + (at >> 2)];
         const uint32_t picked = ((last_byte >> ((at >> 2) & 7u)) & 1u) ? (leaves >> 16) : (leaves & 0xffffu);
         // index into the per-leaf tables; the record that fills a batch of one tree gives leaf 0
         const int leaf = bt.leaf_base + static_cast<int>(single_leaf ? 0u : picked);
