@@ -388,6 +388,11 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         // way sits after the comparisons of a unit's second group -- the load has had most of two
         // groups to arrive, the last stores a whole group -- and the set just used up is loaded
         // again right behind it, tied to the wait through the stream pointer.
+        // While it evaluates, the wave goes first among the waves of its SIMD: the walks and lookups
+        // of the others are chains of waits that fill whatever issue slots it leaves (1 % on c5).
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_s_setprio(3);
+#endif
         int u = 0;
         for (; u + 1 < n_units; u += 2) {
             group(set_a.q[0], 0, nothing);
@@ -413,6 +418,9 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
             p += 16;
             prev += 2 * BANK_ROWS;
         }
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_s_setprio(0);
+#endif
         if (pending) store(0);  // right behind its matrix instructions: the compiler's own store, with the wait
         if (stage) reinterpret_cast<u32x4 *>(child_lds)[tid] = staged;
         if (b > 0) consume_pending();  // the last batch's leaves
