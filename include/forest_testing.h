@@ -86,11 +86,7 @@ typedef struct forest_packed_view {
      * [begin, begin + n_fast + n_slow) of bank_todo (bank_pass_wave[4 * (p * bank_waves + w)] .. + 2:
      * begin, n_fast, n_slow); item i is bank_todo[4 * i] .. + 3: register index inside the bank,
      * feature, first threshold and number of thresholds of the register's segment.  The first
-     * n_fast items take the fast lookup, whose constants are bank_feat[8 * f] .. + 7 (32-bit words:
-     * float lo, float scale, float last bucket, int thresholds, byte offset of the feature's
-     * 16-bit table in bank_tab, byte offset of its thresholds in rank_threshold, 1 if the feature
-     * has a fast lookup, 0): bucket = trunc(clamp((x - lo) * scale, 0, last bucket)), the table
-     * entry of the bucket is the index of the first of bank_window thresholds the lookup reads. */
+     * n_fast items take the fast lookup (below). */
     int32_t bank_batches, bank_waves, bank_regs, bank_trees, bank_unit, bank_max_units;
     int64_t bank_prog_entries;
     const uint32_t *bank_prog;
@@ -101,13 +97,21 @@ typedef struct forest_packed_view {
     const int32_t *bank_batch;       /* [bank_batches * 4] */
     const int32_t *bank_tree;        /* [bank_batches * bank_trees * 4] */
     const int32_t *bank_reg;         /* [bank_waves * bank_regs] */
-    int32_t bank_passes, bank_window;
-    int64_t bank_todo_items, bank_tab_entries;
+    int32_t bank_passes;
+    int64_t bank_todo_items;
     const int32_t *bank_pass;        /* [bank_passes * 2] */
     const int32_t *bank_pass_wave;   /* [bank_passes * bank_waves * 4] */
     const int32_t *bank_todo;        /* [bank_todo_items * 4] */
-    const uint32_t *bank_feat;       /* [n_features * 8] */
-    const uint16_t *bank_tab;        /* [bank_tab_entries] */
+    /* kernel_path 2 and 3: the fast rank lookup of features with fast_window .. 6143 distinct
+     * thresholds.  fast_feat[8 * f] .. + 7 (32-bit words): float lo, float scale, float last bucket,
+     * int thresholds, byte offset of the feature's 16-bit table in fast_tab, byte offset of its
+     * thresholds in rank_threshold, 1 if the feature has a fast lookup, 0.
+     * bucket = trunc(clamp((x - lo) * scale, 0, last bucket)); the table entry of the bucket is the
+     * index of the first of fast_window thresholds the lookup reads and counts. */
+    int32_t fast_window;
+    int64_t fast_tab_entries;
+    const uint32_t *fast_feat;       /* [n_features * 8] */
+    const uint16_t *fast_tab;        /* [fast_tab_entries] */
     const int32_t *order_leaf_node;  /* [sum N_L] caller's node index of each leaf, processing order */
     const int32_t *order_leaf_tree;  /* [sum N_L] caller's tree index of each leaf, processing order */
 } forest_packed_view;

@@ -50,9 +50,10 @@ class _View(ctypes.Structure):
                 ("bank_batches", _i32), ("bank_waves", _i32), ("bank_regs", _i32), ("bank_trees", _i32),
                 ("bank_unit", _i32), ("bank_max_units", _i32), ("bank_prog_entries", _i64), ("bank_prog", _p),
                 ("bank_stream_base", _p), ("bank_span", _p), ("bank_child", _p), ("bank_leaf", _p), ("bank_batch", _p),
-                ("bank_tree", _p), ("bank_reg", _p), ("bank_passes", _i32), ("bank_window", _i32),
-                ("bank_todo_items", _i64), ("bank_tab_entries", _i64), ("bank_pass", _p), ("bank_pass_wave", _p),
-                ("bank_todo", _p), ("bank_feat", _p), ("bank_tab", _p), ("order_leaf_node", _p), ("order_leaf_tree", _p)]
+                ("bank_tree", _p), ("bank_reg", _p), ("bank_passes", _i32),
+                ("bank_todo_items", _i64), ("bank_pass", _p), ("bank_pass_wave", _p),
+                ("bank_todo", _p), ("fast_window", _i32), ("fast_tab_entries", _i64), ("fast_feat", _p), ("fast_tab", _p),
+                ("order_leaf_node", _p), ("order_leaf_tree", _p)]
 
 
 # include/forest.h: the inference ABI
@@ -181,6 +182,9 @@ def forest_pack(forest) -> dict:
                         rank_bucket_scale=bucket[:, 1].copy().view(np.float32),
                         rank_bucket_count=bucket[:, 2].copy(), rank_bucket_base=bucket[:, 3].copy(),
                         rank_bucket_start=get(v.rank_bucket_start, n_start, np.int32))
+            rank.update(fast_window=int(v.fast_window),
+                        fast_feat=get(v.fast_feat, int(forest.n_features) * 8, np.uint32).reshape(-1, 8),
+                        fast_tab=get(v.fast_tab, int(v.fast_tab_entries), np.uint16))
         if v.wave_tree:
             rank["workgroup_waves"] = int(v.workgroup_waves)
             rank["wave_tree"] = get(v.wave_tree, int(v.workgroup_waves) + 1, np.int32)
@@ -199,12 +203,9 @@ def forest_pack(forest) -> dict:
                         bank_leaf=get(v.bank_leaf, n_slots, np.uint32), bank_batch=batch,
                         bank_tree=get(v.bank_tree, nb * nt * 4, np.int32).reshape(nb, nt, 4),
                         bank_reg=get(v.bank_reg, nw * int(v.bank_regs), np.int32).reshape(nw, -1),
-                        bank_window=int(v.bank_window),
                         bank_pass=get(v.bank_pass, int(v.bank_passes) * 2, np.int32).reshape(-1, 2),
                         bank_pass_wave=get(v.bank_pass_wave, int(v.bank_passes) * nw * 4, np.int32).reshape(-1, nw, 4),
-                        bank_todo=get(v.bank_todo, int(v.bank_todo_items) * 4, np.int32).reshape(-1, 4),
-                        bank_feat=get(v.bank_feat, int(forest.n_features) * 8, np.uint32).reshape(-1, 8),
-                        bank_tab=get(v.bank_tab, int(v.bank_tab_entries), np.uint16))
+                        bank_todo=get(v.bank_todo, int(v.bank_todo_items) * 4, np.int32).reshape(-1, 4))
         else:
             rank["bank_batches"] = 0
         rank["order_leaf_node"] = get(v.order_leaf_node, nl, np.int32)

@@ -164,8 +164,8 @@ int forest_load(const forest_desc *desc, forest **out)
     const size_t o_bpass = place<BankPass>(cur, m.bank_pass.size());
     const size_t o_bpw = place<BankPassWave>(cur, m.bank_pass_wave.size());
     const size_t o_btodo = place<BankTodo>(cur, m.bank_todo.size());
-    const size_t o_bfeat = place<BankFeat>(cur, m.bank_feat.size());
-    const size_t o_btab = place<uint16_t>(cur, m.bank_tab.size());
+    const size_t o_bfeat = place<FastLookup>(cur, m.fast_feat.size());
+    const size_t o_btab = place<uint16_t>(cur, m.fast_tab.size());
     const size_t model_bytes = (cur + 255) & ~size_t{255};
     // workspaces of split launches, not uploaded
     const bool ranks = m.path == PATH_RANK || m.path == PATH_RANK_LDS;
@@ -208,8 +208,8 @@ int forest_load(const forest_desc *desc, forest **out)
                     up(o_bpass, m.bank_pass.data(), m.bank_pass.size() * sizeof(BankPass)) &&
                     up(o_bpw, m.bank_pass_wave.data(), m.bank_pass_wave.size() * sizeof(BankPassWave)) &&
                     up(o_btodo, m.bank_todo.data(), m.bank_todo.size() * sizeof(BankTodo)) &&
-                    up(o_bfeat, m.bank_feat.data(), m.bank_feat.size() * sizeof(BankFeat)) &&
-                    up(o_btab, m.bank_tab.data(), m.bank_tab.size() * sizeof(uint16_t));
+                    up(o_bfeat, m.fast_feat.data(), m.fast_feat.size() * sizeof(FastLookup)) &&
+                    up(o_btab, m.fast_tab.data(), m.fast_tab.size() * sizeof(uint16_t));
     if (!ok) {
         (void)hipGetLastError();
         (void)hipFree(f->blob);
@@ -254,8 +254,8 @@ int forest_load(const forest_desc *desc, forest **out)
     d.bank.pass = reinterpret_cast<const BankPass *>(b + o_bpass);
     d.bank.pass_wave = reinterpret_cast<const BankPassWave *>(b + o_bpw);
     d.bank.todo = reinterpret_cast<const BankTodo *>(b + o_btodo);
-    d.bank.feat = reinterpret_cast<const BankFeat *>(b + o_bfeat);
-    d.bank.tab = reinterpret_cast<const uint16_t *>(b + o_btab);
+    d.fast_feat = reinterpret_cast<const FastLookup *>(b + o_bfeat);
+    d.fast_tab = reinterpret_cast<const uint16_t *>(b + o_btab);
     for (int w = 0; w < BANK_WAVES; ++w) d.bank.stream_base[w] = m.bank_stream_base[w];
     d.bank.batches = m.bank_batches;
     d.bank.max_units = m.bank_max_units;

@@ -87,17 +87,17 @@ int forest_pack_view(const forest_packed *p, forest_packed_view *v)
     v->bank_tree = bank ? reinterpret_cast<const int32_t *>(m.bank_tree.data()) : nullptr;
     v->bank_reg = bank ? m.bank_reg.data() : nullptr;
     static_assert(sizeof(BankPass) == 2 * sizeof(int32_t) && sizeof(BankPassWave) == 4 * sizeof(int32_t) &&
-                      sizeof(BankTodo) == 4 * sizeof(int32_t) && sizeof(BankFeat) == 8 * sizeof(uint32_t),
+                      sizeof(BankTodo) == 4 * sizeof(int32_t) && sizeof(FastLookup) == 8 * sizeof(uint32_t),
                   "viewed as plain 32-bit arrays");
     v->bank_passes = bank ? static_cast<int32_t>(m.bank_pass.size()) : 0;
-    v->bank_window = BANK_WINDOW;
+    v->fast_window = FAST_WINDOW;
     v->bank_todo_items = bank ? static_cast<int64_t>(m.bank_todo.size()) : 0;
-    v->bank_tab_entries = bank ? static_cast<int64_t>(m.bank_tab.size()) : 0;
+    v->fast_tab_entries = ranks ? static_cast<int64_t>(m.fast_tab.size()) : 0;
     v->bank_pass = bank ? reinterpret_cast<const int32_t *>(m.bank_pass.data()) : nullptr;
     v->bank_pass_wave = bank ? reinterpret_cast<const int32_t *>(m.bank_pass_wave.data()) : nullptr;
     v->bank_todo = bank ? reinterpret_cast<const int32_t *>(m.bank_todo.data()) : nullptr;
-    v->bank_feat = bank ? reinterpret_cast<const uint32_t *>(m.bank_feat.data()) : nullptr;
-    v->bank_tab = bank ? m.bank_tab.data() : nullptr;
+    v->fast_feat = ranks ? reinterpret_cast<const uint32_t *>(m.fast_feat.data()) : nullptr;
+    v->fast_tab = ranks ? m.fast_tab.data() : nullptr;
     v->order_leaf_node = m.leaf_node.data();
     v->order_leaf_tree = m.v_order_leaf_tree.data();
     return FOREST_OK;

@@ -20,8 +20,6 @@ struct BankDev {
     const BankPass *pass;           // [passes]
     const BankPassWave *pass_wave;  // [passes][BANK_WAVES]
     const BankTodo *todo;
-    const BankFeat *feat;           // [n_features]
-    const uint16_t *tab;
     int32_t stream_base[BANK_WAVES];
     int32_t batches, max_units, enabled;
     int32_t passes;
@@ -50,6 +48,8 @@ struct DevModel {
     const float *thr_sorted;
     const int32_t *feat_thr_base;
     const int32_t *feat_vfirst;
+    const FastLookup *fast_feat;  // [n_features] fast lookups (forest_rank_common.hpp)
+    const uint16_t *fast_tab;
     // Tree splitting for small batches: with n_splits > 1 the grid's y index selects a share of
     // the trees and the kernels store raw fp64 partial sums to partial[(split * split_rows + row)
     // * n_outputs + k] instead of finishing the row; reduce_splits() finishes.  Set per launch.

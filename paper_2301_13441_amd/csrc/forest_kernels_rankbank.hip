@@ -53,14 +53,12 @@ typedef const __attribute__((address_space(4))) BankBatch *BatchPtr;
 typedef const __attribute__((address_space(4))) BankPass *PassPtr;
 typedef const __attribute__((address_space(4))) BankPassWave *PassWavePtr;
 typedef const __attribute__((address_space(4))) BankTodo *TodoPtr;
-typedef const __attribute__((address_space(4))) BankFeat *FeatPtr;
 #else
 typedef const BankSpan *SpanPtr;  // host pass: the kernel body is only parsed
 typedef const BankBatch *BatchPtr;
 typedef const BankPass *PassPtr;
 typedef const BankPassWave *PassWavePtr;
 typedef const BankTodo *TodoPtr;
-typedef const BankFeat *FeatPtr;
 #endif
 
 enum { BANK_SUMS = 0, BANK_LEAVES = 1 };
@@ -96,71 +94,6 @@ __device__ __forceinline__ void bank_set(v32u &xa, v32u &xb, int slot, uint32_t 
     xb[slot] = b;
 }
 
-// The lane's four values of one column of the staged block, and where their windows begin.
-struct BankLookup {
-    float x[4];
-    uint32_t at[4];  // byte offset of the window in the feature's thresholds
-};
-
-// First half of a fast lookup: the values out of LDS, their buckets, and the table entries on
-// their way (a window begins at the last threshold of the lower buckets, or where BANK_WINDOW
-// thresholds still fit).
-__device__ __forceinline__ BankLookup bank_lookup_begin(const DevModel &m, const float *column, const BankFeat &bf)
-{
-    BankLookup q;
-    const char *tab = reinterpret_cast<const char *>(m.bank.tab) + bf.tab_off;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        q.x[j] = column[j * TILE * BANK_TILE_PITCH];
-        const float t = fminf(fmaxf((q.x[j] - bf.lo) * bf.scale, 0.0f), bf.last_bucket);  // NaN: bucket 0
-        const uint32_t bucket = static_cast<uint32_t>(static_cast<int32_t>(t));
-        q.at[j] = static_cast<uint32_t>(load_at<uint16_t>(tab, bucket << 1)) << 2;
-    }
-    return q;
-}
-
-// Second half: rank(x) = #{i : thr[i] < x} from the window thr[w .. w + BANK_WINDOW): w plus the
-// number of its thresholds below x, provided every threshold before the window is below x (the
-// window starts the list, or its first threshold is below x) and none after it is (it ends the
-// list, or its last threshold is not below x).  The check is against the thresholds themselves;
-// whatever it does not settle (a bucket fuller than a window, NaN) takes the general lookup.
-// Returns the two packed registers' worth of codes: a feature that qualifies has at most
-// BANK_FAST_MAX_THRESHOLDS thresholds, all in one register, and every rank in the lower half of
-// the codes, where code(q) = 0xf3ff - q.
-__device__ __forceinline__ void bank_lookup_end(const DevModel &m, const BankLookup &q, const BankFeat &bf, int feature,
-                                                uint32_t &pa, uint32_t &pb)
-{
-    const char *thr = reinterpret_cast<const char *>(m.thr_sorted) + bf.thr_off;
-    const uint32_t last_at = static_cast<uint32_t>(bf.n - BANK_WINDOW) << 2;
-    int rank[4];
-    bool open[4];
-    // two rows at a time: their windows are 16 registers, and the bank itself takes half the file
-#pragma unroll
-    for (int h = 0; h < 4; h += 2) {
-        FloatRun<BANK_WINDOW> w[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) w[j] = load_at<FloatRun<BANK_WINDOW>>(thr, q.at[h + j]);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float x = q.x[h + j];
-            int count = 0;
-#pragma unroll
-            for (int i = 0; i < BANK_WINDOW; ++i) count += (w[j].v[i] < x) ? 1 : 0;
-            const bool first_below = w[j].v[0] < x, last_below = w[j].v[BANK_WINDOW - 1] < x;
-            open[h + j] = (!first_below & (q.at[h + j] != 0u)) | (last_below & (q.at[h + j] != last_at)) | (x != x);
-            rank[h + j] = static_cast<int>(q.at[h + j] >> 2) + count;
-        }
-    }
-    if (__any(open[0] | open[1] | open[2] | open[3])) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (open[j]) rank[j] = rank_of(m, feature, q.x[j]);
-    }
-    constexpr uint32_t CODE0 = 0x8000u | (0x5c00u + RANK_CODES / 2 - 1);  // code(0)
-    pa = (CODE0 - static_cast<uint32_t>(rank[0])) | ((CODE0 - static_cast<uint32_t>(rank[1])) << 16);
-    pb = (CODE0 - static_cast<uint32_t>(rank[2])) | ((CODE0 - static_cast<uint32_t>(rank[3])) << 16);
-}
-
 // The ranks of the workgroup's rows, straight into the waves' banks.  X is read in blocks of up to
 // BANK_PASS_FEATURES columns: every row's part of the block is contiguous in memory and goes to
 // LDS as it lies there (16 bytes per lane, 16 lanes per row, each 128-byte line read once, by one
@@ -176,7 +109,7 @@ __device__ __forceinline__ void bank_ranks(const DevModel &m, const float *__res
     PassPtr pass = (PassPtr)m.bank.pass;
     PassWavePtr pass_wave = (PassWavePtr)m.bank.pass_wave;
     TodoPtr todo = (TodoPtr)m.bank.todo;
-    FeatPtr feat = (FeatPtr)m.bank.feat;
+    FastPtr feat = (FastPtr)m.fast_feat;
     const int piece = threadIdx.x & 15;      // which 16 bytes of a row's part of the block
     const int row_of_step = threadIdx.x >> 4;  // 32 rows per step
     for (int p = 0; p < m.bank.passes; ++p) {
@@ -212,16 +145,23 @@ __device__ __forceinline__ void bank_ranks(const DevModel &m, const float *__res
         const float *mine = tile + lane * BANK_TILE_PITCH - f_begin;  // + feature: the lane's first row of that column
         if (pw.n_fast > 0) {
             BankTodo td = todo[pw.begin];
-            BankFeat bf = feat[td.feature];
-            BankLookup q = bank_lookup_begin(m, mine + td.feature, bf);
+            FastLookup bf = feat[td.feature];
+            auto begin = [&](const BankTodo &item, const FastLookup &ff) {
+                const float *column = mine + item.feature;
+                float xs[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xs[j] = column[j * TILE * BANK_TILE_PITCH];
+                return fast_lookup_begin<4>(m, ff, xs);
+            };
+            FastWindows<4> q = begin(td, bf);
             for (int k = 0; k < pw.n_fast; ++k) {
                 // the next register's first half (the last one repeats itself; not used)
                 const BankTodo td_next = todo[pw.begin + (k + 1 < pw.n_fast ? k + 1 : k)];
-                const BankFeat bf_next = feat[td_next.feature];
-                const BankLookup q_next = bank_lookup_begin(m, mine + td_next.feature, bf_next);
-                uint32_t pa, pb;
-                bank_lookup_end(m, q, bf, td.feature, pa, pb);
-                bank_set(xa, xb, td.slot, pa, pb);
+                const FastLookup bf_next = feat[td_next.feature];
+                const FastWindows<4> q_next = begin(td_next, bf_next);
+                int rank[4];
+                fast_lookup_end<4, 2>(m, q, bf, td.feature, rank);
+                bank_set(xa, xb, td.slot, fast_code_pair(rank[0], rank[1]), fast_code_pair(rank[2], rank[3]));
                 td = td_next;
                 bf = bf_next;
                 q = q_next;

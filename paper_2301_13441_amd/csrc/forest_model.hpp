@@ -93,6 +93,29 @@ inline int32_t bucket_index(float x, float lo, float scale, int32_t n_buckets)
     return static_cast<int32_t>(t);
 }
 
+// Fast rank lookup (rank kernels; forest_rank_common.hpp).  For a feature with FAST_WINDOW ..
+// FAST_MAX_THRESHOLDS distinct thresholds over a finite positive range (fast == 1):
+// bucket = trunc(clamp((x - lo) * scale, 0, last_bucket)); the table entry of the bucket (16 bits,
+// at byte tab_off of the table) is where a window of FAST_WINDOW thresholds begins,
+// clamp(#thresholds in lower buckets - 1, 0, n - FAST_WINDOW); the rank is that plus the number
+// of the window's thresholds below x wherever the window settles it (checked against the
+// thresholds).  Such a feature has one rank register and all its ranks in the lower half of the
+// codes.  The host compiler refines a feature's grid (2, 4, 8 .. buckets per threshold) until no
+// bucket holds more than FAST_BUCKET_FILL thresholds or the table has FAST_MAX_BUCKETS entries.
+constexpr int FAST_WINDOW = 8;
+constexpr int FAST_MAX_THRESHOLDS = RANK_CODES / 2 - 1;
+constexpr int FAST_MAX_BUCKETS = 65535;
+constexpr int FAST_BUCKET_FILL = 6;
+
+struct FastLookup {
+    float lo, scale, last_bucket;
+    int32_t n;         // distinct thresholds of the feature
+    uint32_t tab_off;  // bytes
+    uint32_t thr_off;  // byte offset of the feature's thresholds in the sorted table
+    int32_t fast;
+    int32_t reserved;
+};
+
 // One entry of the split program: which feature an internal node tests and its threshold.
 struct SplitEntry {
     int32_t feature_slot;  // LDS family: feature index * 64; REG family: feature index;
@@ -135,10 +158,6 @@ constexpr int BANK_TILE_PITCH = BANK_PASS_FEATURES + 1;  // words per row of the
                                                          // keeps a column's reads free of bank conflicts
 constexpr size_t BANK_MAX_LDS = 72 * 1024;     // outcome bytes and child references of a batch (a launch with 80 KB did not return: not used)
 constexpr int BANK_PAD_ENTRIES = 64;        // readable entries after each wave's stream
-constexpr int BANK_WINDOW = 8;              // thresholds a fast lookup reads
-constexpr int BANK_FAST_MAX_THRESHOLDS = RANK_CODES / 2 - 1;  // ranks 0..n all in the lower half of the codes
-constexpr int BANK_MAX_BUCKETS = 65535;     // per feature, fast lookup table
-constexpr int BANK_BUCKET_FILL = 6;         // the table is refined until no bucket holds more thresholds
 
 // A prologue pass: columns [feat_begin, feat_end) of X, at most BANK_PASS_FEATURES of them.
 struct BankPass {
@@ -157,18 +176,6 @@ struct BankTodo {
     int32_t slot, feature, first, len;
 };
 
-// Constants of a feature's fast lookup (fast == 1: BANK_WINDOW <= n <= BANK_FAST_MAX_THRESHOLDS and a
-// finite positive grid): bucket = trunc(clamp((x - lo) * scale, 0, last_bucket)); the table entry
-// of the bucket (16 bits, at byte tab_off of the table) is where the window of BANK_WINDOW
-// thresholds begins, clamp(#thresholds in lower buckets - 1, 0, n - BANK_WINDOW).
-struct BankFeat {
-    float lo, scale, last_bucket;
-    int32_t n;         // distinct thresholds of the feature
-    uint32_t tab_off;  // bytes
-    uint32_t thr_off;  // byte offset of the feature's thresholds in the sorted table
-    int32_t fast;
-    int32_t reserved;
-};
 
 // The register-bank program's walk.  A slot's word in the child table holds, for the left child
 // in the low half and the right child in the high half, the byte offset (4 * slot) of the word
@@ -219,6 +226,8 @@ struct PackedModel {
     std::vector<float> thr_sorted;        // per feature: distinct thresholds ascending, concatenated
     std::vector<int32_t> feat_thr_base;   // [F + 1] offsets into thr_sorted
     std::vector<int32_t> feat_vfirst;     // [F] first rank register of the feature
+    std::vector<FastLookup> fast_feat;    // [F] fast lookups
+    std::vector<uint16_t> fast_tab;       // their tables
     int64_t n_internal = 0, n_leaves = 0;
 
     std::vector<TreeMeta> tree;      // processing order
@@ -238,8 +247,6 @@ struct PackedModel {
     std::vector<BankPass> bank_pass;          // prologue passes (blocks of columns with rank registers)
     std::vector<BankPassWave> bank_pass_wave; // [passes][BANK_WAVES]
     std::vector<BankTodo> bank_todo;          // the waves' to-do lists, pass by pass
-    std::vector<BankFeat> bank_feat;          // [F]
-    std::vector<uint16_t> bank_tab;           // fast lookup tables of all features
     std::vector<uint32_t> bank_prog;         // (f16(-4 code(j')) << 16) | register index inside the bank
     std::vector<uint32_t> bank_child;        // per batch, by slot: where the walk goes next, left | right << 16
     std::vector<uint32_t> bank_leaf;         // same index: the leaves the two children are, left | right << 16

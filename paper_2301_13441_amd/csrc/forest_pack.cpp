@@ -283,6 +283,53 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             }
             m.feat_bucket.push_back(fb);
         }
+        // Fast lookup tables.  A uniform grid over the feature's finite thresholds, refined until
+        // no bucket holds more than FAST_BUCKET_FILL of them (or the table is as large as it may
+        // get); the entry of a bucket is where the window of thresholds the lookup reads begins.
+        // The kernel checks every window against x, so nothing rests on its arithmetic placing x
+        // in the bucket the arithmetic here does; what a window does not decide takes the general
+        // lookup.
+        m.fast_feat.assign(static_cast<size_t>(d.n_features), FastLookup{});
+        for (int32_t f = 0; f < d.n_features; ++f) {
+            const float *v = m.thr_sorted.data() + m.feat_thr_base[f];
+            const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
+            FastLookup &bf = m.fast_feat[f];
+            bf.n = n;
+            bf.thr_off = static_cast<uint32_t>(m.feat_thr_base[f]) * sizeof(float);
+            bf.tab_off = static_cast<uint32_t>(m.fast_tab.size() * sizeof(uint16_t));
+            int32_t a = 0, b = n;
+            while (a < b && !std::isfinite(v[a])) ++a;
+            while (b > a && !std::isfinite(v[b - 1])) --b;
+            bool fast = n >= FAST_WINDOW && n <= FAST_MAX_THRESHOLDS && b > a && v[b - 1] - v[a] > 0.0f;
+            std::vector<int32_t> start;
+            if (fast) {
+                const float lo = v[a], range = v[b - 1] - v[a];
+                for (int64_t nb = 2 * static_cast<int64_t>(n);; nb *= 2) {
+                    nb = std::min<int64_t>(nb, FAST_MAX_BUCKETS);
+                    const float scale = static_cast<float>(nb) / range;
+                    if (!std::isfinite(scale)) {
+                        fast = false;
+                        break;
+                    }
+                    start.assign(static_cast<size_t>(nb) + 1, 0);
+                    int32_t i = 0, fill = 0;
+                    for (int32_t bk = 0; bk <= nb; ++bk) {
+                        while (i < n && bucket_index(v[i], lo, scale, static_cast<int32_t>(nb)) < bk) ++i;
+                        start[bk] = i;
+                        if (bk > 0) fill = std::max(fill, start[bk] - start[bk - 1]);
+                    }
+                    bf.lo = lo;
+                    bf.scale = scale;
+                    bf.last_bucket = static_cast<float>(nb - 1);
+                    if (fill <= FAST_BUCKET_FILL || nb == FAST_MAX_BUCKETS) break;
+                }
+            }
+            bf.fast = fast ? 1 : 0;
+            if (fast)
+                for (size_t bk = 0; bk + 1 < start.size(); ++bk)
+                    m.fast_tab.push_back(static_cast<uint16_t>(std::clamp(start[bk] - 1, 0, n - FAST_WINDOW)));
+        }
+        m.fast_tab.push_back(0);  // never empty
     };
     if (m.kind != KIND_GENERIC) {
         const size_t rank_lds = std::max(sizeof(double) * 4 * K * 128,
@@ -614,7 +661,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                     const int32_t f = reg_feature[r];
                     const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
                     const int32_t first = reg_segment[r] * RANK_SEG;
-                    const bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS;  // refined below
+                    const bool fast = n >= FAST_WINDOW && n <= FAST_MAX_THRESHOLDS;  // refined below
                     mine[w][fast ? 0 : 1].push_back(BankTodo{reg_index[r], f, first, std::min<int32_t>(n - first, RANK_SEG)});
                 }
                 m.bank_pass.push_back(BankPass{blk.f0, blk.f1});
@@ -626,63 +673,16 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 }
             }
         }
-        // Fast lookup tables.  A uniform grid over the feature's finite thresholds, refined until
-        // no bucket holds more than BANK_BUCKET_FILL of them (or the table is as large as it may
-        // get); the entry of a bucket is where the window of thresholds the lookup reads begins.
-        // The kernel checks every window against x, so nothing rests on its arithmetic placing x
-        // in the bucket the arithmetic here does; what a window does not decide takes the general
-        // lookup.
-        m.bank_feat.assign(static_cast<size_t>(d.n_features), BankFeat{});
-        for (int32_t f = 0; f < d.n_features; ++f) {
-            const float *v = m.thr_sorted.data() + m.feat_thr_base[f];
-            const int32_t n = m.feat_thr_base[f + 1] - m.feat_thr_base[f];
-            BankFeat &bf = m.bank_feat[f];
-            bf.n = n;
-            bf.thr_off = static_cast<uint32_t>(m.feat_thr_base[f]) * sizeof(float);
-            bf.tab_off = static_cast<uint32_t>(m.bank_tab.size() * sizeof(uint16_t));
-            int32_t a = 0, b = n;
-            while (a < b && !std::isfinite(v[a])) ++a;
-            while (b > a && !std::isfinite(v[b - 1])) --b;
-            bool fast = n >= BANK_WINDOW && n <= BANK_FAST_MAX_THRESHOLDS && b > a && v[b - 1] - v[a] > 0.0f;
-            std::vector<int32_t> start;
-            if (fast) {
-                const float lo = v[a], range = v[b - 1] - v[a];
-                for (int64_t nb = 2 * static_cast<int64_t>(n);; nb *= 2) {
-                    nb = std::min<int64_t>(nb, BANK_MAX_BUCKETS);
-                    const float scale = static_cast<float>(nb) / range;
-                    if (!std::isfinite(scale)) {
-                        fast = false;
-                        break;
-                    }
-                    start.assign(static_cast<size_t>(nb) + 1, 0);
-                    int32_t i = 0, fill = 0;
-                    for (int32_t bk = 0; bk <= nb; ++bk) {
-                        while (i < n && bucket_index(v[i], lo, scale, static_cast<int32_t>(nb)) < bk) ++i;
-                        start[bk] = i;
-                        if (bk > 0) fill = std::max(fill, start[bk] - start[bk - 1]);
-                    }
-                    bf.lo = lo;
-                    bf.scale = scale;
-                    bf.last_bucket = static_cast<float>(nb - 1);
-                    if (fill <= BANK_BUCKET_FILL || nb == BANK_MAX_BUCKETS) break;
-                }
-            }
-            bf.fast = fast ? 1 : 0;
-            if (fast)
-                for (size_t bk = 0; bk + 1 < start.size(); ++bk)
-                    m.bank_tab.push_back(static_cast<uint16_t>(std::clamp(start[bk] - 1, 0, n - BANK_WINDOW)));
-        }
         // a to-do item is fast only if its feature's table was built
         for (size_t pw = 0; pw < m.bank_pass_wave.size(); ++pw) {
             BankPassWave &q = m.bank_pass_wave[pw];
             std::stable_partition(m.bank_todo.begin() + q.begin, m.bank_todo.begin() + q.begin + q.n_fast + q.n_slow,
-                                  [&](const BankTodo &td) { return m.bank_feat[td.feature].fast != 0; });
+                                  [&](const BankTodo &td) { return m.fast_feat[td.feature].fast != 0; });
             const int32_t total = q.n_fast + q.n_slow;
             q.n_fast = static_cast<int32_t>(std::count_if(m.bank_todo.begin() + q.begin, m.bank_todo.begin() + q.begin + total,
-                                                          [&](const BankTodo &td) { return m.bank_feat[td.feature].fast != 0; }));
+                                                          [&](const BankTodo &td) { return m.fast_feat[td.feature].fast != 0; }));
             q.n_slow = total - q.n_fast;
         }
-        m.bank_tab.push_back(0);  // never empty
         // Batches of up to BANK_TREES trees whose bit buffer fits the LDS budget.  Inside a batch every
         // wave gets the nodes that test its registers, padded to whole units of BANK_UNIT entries;
         // a node's slot is BANK_UNIT * (index of its unit in the batch's bit buffer) + its bit.
@@ -796,8 +796,6 @@ int compile_forest(const forest_desc &d, PackedModel &m)
             m.bank_pass.clear();
             m.bank_pass_wave.clear();
             m.bank_todo.clear();
-            m.bank_feat.clear();
-            m.bank_tab.clear();
         }
     }
     for (const TreeMeta &tm : m.tree) m.v_program_groups.push_back(tm.n_words);

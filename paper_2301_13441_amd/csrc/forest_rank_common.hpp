@@ -193,6 +193,87 @@ struct __attribute__((aligned(4))) FloatRun {
     float v[N];
 };
 
+// ---------------------------------------------------------------------------------------
+// The fast lookup (forest_model.hpp: FastLookup), N values of one feature per lane.
+// ---------------------------------------------------------------------------------------
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) FastLookup *FastPtr;
+#else
+typedef const FastLookup *FastPtr;  // host pass: the kernel body is only parsed
+#endif
+
+// The lane's N values of one feature, and where their windows begin.
+template <int N>
+struct FastWindows {
+    float x[N];
+    uint32_t at[N];  // byte offset of the window in the feature's thresholds
+};
+
+// First half: the values' buckets, and the table entries on their way (a window begins at the
+// last threshold of the lower buckets, or where FAST_WINDOW thresholds still fit).
+template <int N>
+__device__ __forceinline__ FastWindows<N> fast_lookup_begin(const DevModel &m, const FastLookup &ff, const float (&x)[N])
+{
+    FastWindows<N> q;
+    const char *tab = reinterpret_cast<const char *>(m.fast_tab) + ff.tab_off;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        q.x[j] = x[j];
+        const float t = fminf(fmaxf((x[j] - ff.lo) * ff.scale, 0.0f), ff.last_bucket);  // NaN: bucket 0
+        const uint32_t bucket = static_cast<uint32_t>(static_cast<int32_t>(t));
+        q.at[j] = static_cast<uint32_t>(load_at<uint16_t>(tab, bucket << 1)) << 2;
+    }
+    return q;
+}
+
+// Second half: rank(x) = #{i : thr[i] < x} from the window thr[w .. w + FAST_WINDOW): w plus the
+// number of its thresholds below x, provided every threshold before the window is below x (the
+// window starts the list, or its first threshold is below x) and none after it is (it ends the
+// list, or its last threshold is not below x).  The check is against the thresholds themselves;
+// whatever it does not settle (a bucket fuller than a window, NaN) takes the general lookup.
+// The windows are read G at a time (8 registers each).
+template <int N, int G>
+__device__ __forceinline__ void fast_lookup_end(const DevModel &m, const FastWindows<N> &q, const FastLookup &ff,
+                                                int feature, int (&rank)[N])
+{
+    static_assert(N % G == 0, "whole groups of windows");
+    const char *thr = reinterpret_cast<const char *>(m.thr_sorted) + ff.thr_off;
+    const uint32_t last_at = static_cast<uint32_t>(ff.n - FAST_WINDOW) << 2;
+    bool open[N];
+    bool any_open = false;
+#pragma unroll
+    for (int h = 0; h < N; h += G) {
+        FloatRun<FAST_WINDOW> w[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) w[j] = load_at<FloatRun<FAST_WINDOW>>(thr, q.at[h + j]);
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const float x = q.x[h + j];
+            int count = 0;
+#pragma unroll
+            for (int i = 0; i < FAST_WINDOW; ++i) count += (w[j].v[i] < x) ? 1 : 0;
+            const bool first_below = w[j].v[0] < x, last_below = w[j].v[FAST_WINDOW - 1] < x;
+            open[h + j] = (!first_below & (q.at[h + j] != 0u)) | (last_below & (q.at[h + j] != last_at)) | (x != x);
+            any_open |= open[h + j];
+            rank[h + j] = static_cast<int>(q.at[h + j] >> 2) + count;
+        }
+    }
+    if (__any(any_open)) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (open[j]) rank[j] = rank_of(m, feature, q.x[j]);
+    }
+}
+
+// Two ranks of a feature with a fast lookup as the packed codes of a rank register: such a feature
+// has at most FAST_MAX_THRESHOLDS thresholds, all in one register, and every rank in the lower
+// half of the codes, where code(q) = 0xf3ff - q.
+__device__ __forceinline__ uint32_t fast_code_pair(int rank_lo, int rank_hi)
+{
+    constexpr uint32_t CODE0 = 0x8000u | (0x5c00u + RANK_CODES / 2 - 1);  // code(0)
+    return (CODE0 - static_cast<uint32_t>(rank_lo)) | ((CODE0 - static_cast<uint32_t>(rank_hi)) << 16);
+}
+
 // Ranks of rows [row0, row0 + 128) for every feature with thresholds, written as packed f16
 // pairs into rk[reg * 64 + lane] (low half: row `lane` of the tile, high half: row lane + 64).
 // The features are dealt to the waves; inside a wave every lane looks up the same feature for
@@ -260,6 +341,30 @@ __device__ __forceinline__ void rank_rows(uint32_t *rk, const DevModel &m, const
                 const XRun v = STREAM_X ? __builtin_nontemporal_load(p) : *p;
 #pragma unroll
                 for (int u = 0; u < U; ++u) x[u][r] = v[u];
+            }
+        }
+        // All U features with a fast lookup (wave-uniform; the usual case): table entry, window,
+        // count -- a third of the instructions of the general lookup below.
+        {
+            FastPtr fast = (FastPtr)m.fast_feat;
+            bool all_fast = f0 + U <= f_end;
+#pragma unroll
+            for (int u = 0; u < U; ++u) all_fast &= fast[f0 + u < f_end ? f0 + u : f_end - 1].fast != 0;
+            if (all_fast) {
+                FastLookup ff[U];
+                FastWindows<2> q[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    ff[u] = fast[f0 + u];
+                    q[u] = fast_lookup_begin<2>(m, ff[u], x[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    int rank[2];
+                    fast_lookup_end<2, 2>(m, q[u], ff[u], f0 + u, rank);
+                    rk[(vfirst[f0 + u] - reg_begin) * TILE + lane] = fast_code_pair(rank[0], rank[1]);
+                }
+                continue;
             }
         }
 #pragma unroll

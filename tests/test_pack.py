@@ -349,16 +349,16 @@ def _bank_lookup_codes(v, f, x):
     """Ranks of the values `x` of feature `f` as the register-bank kernel's fast lookup finds them
     (numpy float32 arithmetic in the kernel's order); -1 where the window does not settle the
     rank and the kernel takes the general lookup instead."""
-    lo, scale, last = (v["bank_feat"][f, :3].copy().view(np.float32))
-    n, tab_off, thr_off, fast = (int(z) for z in v["bank_feat"][f, 3:7])
+    lo, scale, last = (v["fast_feat"][f, :3].copy().view(np.float32))
+    n, tab_off, thr_off, fast = (int(z) for z in v["fast_feat"][f, 3:7])
     assert fast == 1
-    W = v["bank_window"]
+    W = v["fast_window"]
     thr = v["rank_threshold"][thr_off // 4: thr_off // 4 + n]
     with np.errstate(invalid="ignore", over="ignore"):
         t = (x.astype(np.float32) - lo) * scale
         t = np.where(np.isnan(t), np.float32(0), t)  # maximum and minimum drop a NaN operand
         bucket = np.minimum(np.maximum(t, np.float32(0)), last).astype(np.int64)
-    at = v["bank_tab"][tab_off // 2 + bucket].astype(np.int64)
+    at = v["fast_tab"][tab_off // 2 + bucket].astype(np.int64)
     assert (at >= 0).all() and (at <= n - W).all()
     win = thr[at[:, None] + np.arange(W)[None, :]]
     below = win < x[:, None]
@@ -389,7 +389,7 @@ def test_register_bank_prologue_plan_and_fast_lookup(seed):
                 assert f0 <= feat < f1 and 0 <= slot < v["bank_regs"]
                 n = int(tbase[feat + 1] - tbase[feat])
                 assert first % 12287 == 0 and length == min(n - first, 12287)
-                assert (int(v["bank_feat"][feat, 6]) == 1) == (i < begin + n_fast)
+                assert (int(v["fast_feat"][feat, 6]) == 1) == (i < begin + n_fast)
                 reg = int(v["bank_reg"][w, slot])
                 assert reg not in seen
                 seen.add(reg)
@@ -397,8 +397,8 @@ def test_register_bank_prologue_plan_and_fast_lookup(seed):
     settled = total = 0
     for feat in range(F):
         n = int(tbase[feat + 1] - tbase[feat])
-        if int(v["bank_feat"][feat, 6]) != 1:
-            assert n < v["bank_window"] or n > 6143
+        if int(v["fast_feat"][feat, 6]) != 1:
+            assert n < v["fast_window"] or n > 6143
             continue
         thr = v["rank_threshold"][tbase[feat]:tbase[feat + 1]]
         x = np.concatenate([rng.standard_normal(400).astype(np.float32) * 2, thr, np.nextafter(thr, np.float32(np.inf)),
