@@ -25,6 +25,10 @@
 #include "forest_kernel_common.hpp"
 #include "forest_rank_common.hpp"
 
+#ifndef FOREST_WIDE_FMA_TREE
+#define FOREST_WIDE_FMA_TREE 0
+#endif
+
 namespace forest_impl {
 namespace {
 
@@ -286,12 +290,240 @@ __device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// 128 rank registers (v32..v159): bit collection on the matrix core within 168 registers.
+//
+// Three waves per SIMD leave 40 registers beside the ranks, too few for two weight matrices, a
+// four-register addend and compiler-placed accumulators.  So this kernel places its matrix-core
+// operands by hand and uses ONE weight matrix: rows 4q and 4q + 1 of A weigh the row-a / row-b
+// bytes of 16-lane block q by 2^(7 - v), rows 4q + 2 and 4q + 3 weigh them by 2^(15 - v), so a
+// group's MFMA leaves its eight bits in the low byte of D[0], D[1] and in the second byte of D[2],
+// D[3].  A chain of two groups is  D1 = A B1 + bias  into v[n:n+3], then  D2 = A B2 + C  with C =
+// D = v[n+2:n+5]: the second group's low-byte sums land on the first group's second-byte sums, 16
+// bits per row in v[n+2], v[n+3]; the other elements are never read.  Registers:
+//     v[0:7]    the eight outcome registers of a group (B)
+//     v[8:15]   A;  v[16:17] = 2^23, 2^23: the addend of a chain's first MFMA is v[14:17] (its
+//               elements 0 and 1 only reach sums that are never read)
+//     v[18:27]  accumulators: v[18:21] <- first group, v[20:23] <- second (bits in v20, v21),
+//               v[22:25] <- third, v[24:27] <- fourth (bits in v24, v25)
+// The compiler does not look inside a statement, so the waits the matrix core needs are written
+// out: two idle states between a comparison and the MFMA that reads it, the 17 instructions of a
+// group between an MFMA and the next one that reads or overwrites part of its result (12 states
+// needed), and 12 idle states after a statement's last MFMA, since the compiler may read or copy
+// the results right behind the statement.
+// ---------------------------------------------------------------------------------------
+typedef float v2f __attribute__((ext_vector_type(2)));
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(1))) char *LeafBytes;  // global memory: loads with a scalar base
+typedef const __attribute__((address_space(1))) float *LeafFloat;
+#else
+typedef const char *LeafBytes;  // host pass: the kernel body is only parsed
+typedef const float *LeafFloat;
+#endif
+
+#define FOREST_WIDE_CMP(n, p) \
+    "v_pk_fma_f16 v" #n ", v32, 4.0, %[" p #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
+#define FOREST_WIDE_IDX(n, p) "s_set_gpr_idx_idx %[" p #n "]\n\t"
+#define FOREST_WIDE_GROUP(p)                                                                             \
+    "s_set_gpr_idx_on %[" p "0], 0x1\n\t" FOREST_WIDE_CMP(0, p) FOREST_WIDE_IDX(1, p) FOREST_WIDE_CMP(1, p)   \
+        FOREST_WIDE_IDX(2, p) FOREST_WIDE_CMP(2, p) FOREST_WIDE_IDX(3, p) FOREST_WIDE_CMP(3, p)               \
+            FOREST_WIDE_IDX(4, p) FOREST_WIDE_CMP(4, p) FOREST_WIDE_IDX(5, p) FOREST_WIDE_CMP(5, p)           \
+                FOREST_WIDE_IDX(6, p) FOREST_WIDE_CMP(6, p) FOREST_WIDE_IDX(7, p) FOREST_WIDE_CMP(7, p)       \
+                    "s_set_gpr_idx_off\n\t"
+#define FOREST_WIDE_MFMA(dst, c) \
+    "s_nop 1\n\tv_mfma_f32_16x16x128_f8f6f4 " dst ", v[8:15], v[0:7], " c " cbsz:1 blgp:1\n\t"
+#define FOREST_WIDE_ENTRIES(p, q)                                                                              \
+    [p##0] "s"(q.e[0]), [p##1] "s"(q.e[1]), [p##2] "s"(q.e[2]), [p##3] "s"(q.e[3]), [p##4] "s"(q.e[4]),        \
+        [p##5] "s"(q.e[5]), [p##6] "s"(q.e[6]), [p##7] "s"(q.e[7])
+#define FOREST_WIDE_X "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1]), "{v[96:127]}"(x[2]), "{v[128:159]}"(x[3])
+
+struct WideCollector {
+    v8i a;
+    v2f bias;
+
+    __device__ __forceinline__ void init(int lane)
+    {
+        const int m = lane & 15, q = lane >> 4;
+        const bool mine = (m >> 2) == q;
+        const int shift = (m & 1) == 0 ? 8 : 24;  // byte 1 = row a, byte 3 = row b
+        const int up = (m & 2) ? 8 : 0;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const uint32_t bf8 = static_cast<uint32_t>(15 + up + 7 - v) << 2;  // 2^(up + 7 - v) in e5m2
+            a[v] = mine ? static_cast<int>(bf8 << shift) : 0;
+        }
+        bias = v2f{8388608.0f, 8388608.0f};
+        asm volatile("" : "+v"(bias));  // kept in registers instead of rebuilt before every statement
+    }
+    // The comparisons of the stream's very first group.
+    __device__ __forceinline__ v8i first(const Entry8 &q, const v32u (&x)[4]) const
+    {
+        v8i d;
+        asm volatile(FOREST_WIDE_GROUP("e") : "=&{v[0:7]}"(d) : FOREST_WIDE_ENTRIES(e, q), FOREST_WIDE_X);
+        return d;
+    }
+    // One word of GW groups.  On entry d holds the outcomes of the word's first group (the one
+    // that ends up in the higher byte of a chain); every MFMA is followed by the comparisons of the
+    // next group, the last one by those of the NEXT word's first group, which d holds on return.
+    // So the last MFMA is complete when the statement ends, and the wave has comparisons to issue
+    // while it runs.  e.g[] are the groups in the order they are compared.  Returns the 16-bit
+    // halves (GW = 4: lo and hi; GW = 2: lo) or, for GW = 1, the group's bits in the second byte of lo.
+    template <int GW>
+    __device__ __forceinline__ void word(v8i &d, const Entry8 (&g)[GW], const v32u (&x)[4], v2f &lo, v2f &hi) const
+    {
+        if constexpr (GW == 4) {
+            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
+                             FOREST_WIDE_MFMA("v[20:23]", "v[20:23]") FOREST_WIDE_GROUP("b")
+                                 FOREST_WIDE_MFMA("v[22:25]", "v[14:17]") FOREST_WIDE_GROUP("c")
+                                     FOREST_WIDE_MFMA("v[24:27]", "v[24:27]") FOREST_WIDE_GROUP("e")
+                         : "={v[20:21]}"(lo), "={v[24:25]}"(hi), "+{v[0:7]}"(d)
+                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_ENTRIES(b, g[1 % GW]),
+                           FOREST_WIDE_ENTRIES(c, g[2 % GW]), FOREST_WIDE_ENTRIES(e, g[3 % GW]), FOREST_WIDE_X
+                         : "v18", "v19", "v22", "v23", "v26", "v27");
+        } else if constexpr (GW == 2) {
+            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
+                             FOREST_WIDE_MFMA("v[20:23]", "v[20:23]") FOREST_WIDE_GROUP("b")
+                         : "={v[20:21]}"(lo), "+{v[0:7]}"(d)
+                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_ENTRIES(b, g[1 % GW]),
+                           FOREST_WIDE_X
+                         : "v18", "v19", "v22", "v23");
+        } else {
+            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
+                         : "={v[20:21]}"(lo), "+{v[0:7]}"(d)
+                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_X
+                         : "v18", "v19");
+        }
+    }
+};
+
+// The groups one statement of WideCollector compares, for the word of GW groups at p: the word's
+// groups after its first one in the order 0, 3, 2 (a chain takes its higher byte first), then
+// group 1 of the next word (group 0 where a word is a single group).
+template <int GW>
+struct WideEntries {
+    Entry8 g[GW];
+};
+
+__device__ __forceinline__ Entry8 load_group(ProgPtr p)
+{
+    Entry8 e;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e.e[j] = p[j];
+    return e;
+}
+
+template <int GW>
+__device__ __forceinline__ WideEntries<GW> load_wide(ProgPtr p)
+{
+    WideEntries<GW> e;
+    if constexpr (GW == 4) {
+        e.g[0] = load_group(p);
+        e.g[1 % GW] = load_group(p + 24);
+        e.g[2 % GW] = load_group(p + 16);
+        e.g[3 % GW] = load_group(p + 32 + 8);
+    } else if constexpr (GW == 2) {
+        e.g[0] = load_group(p);
+        e.g[1 % GW] = load_group(p + 16 + 8);
+    } else {
+        e.g[0] = load_group(p + 8);
+    }
+    return e;
+}
+
+// The wave's share of the trees with WideCollector.  A word's bits are complete when its
+// statement ends, so the word is walked right away and a tree's leaf values are consumed one
+// tree later.  The statement of the wave's last word compares one group of the next wave's trees
+// or of the padding behind the program; nothing reads those outcomes.
+template <int D, int MODE>
+__device__ __forceinline__ void rank_trees_wide(const DevModel &m, const v32u (&x)[4], Accumulator<2> &accu, int wave,
+                                                int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
+{
+    constexpr int R = 2;
+    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);
+    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;
+    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;
+    constexpr int NB = GW * 8;
+    const int T = m.n_trees;
+    int t_begin, t_end;
+    tree_range(m, wave, WAVES, t_begin, t_end);
+    if (t_begin >= t_end) return;
+
+    WideCollector bits;
+    bits.init(lane);
+    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
+    MetaPtr meta = (MetaPtr)m.tree;
+    WideEntries<GW> cur = load_wide<GW>(p);
+    v8i d = bits.first(load_group(p + (GW >= 2 ? 8 : 0)), x);
+    float pending[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
+    int pending_col = 0;
+    // wave-uniform base of the current tree's leaf values, shifted so that the heap position the
+    // walk ends on indexes it directly; carried from tree to tree in scalar registers
+    LeafBytes lv = (LeafBytes)(m.leaf_value + ((t_begin << D) - (1 << D)));
+
+    for (int t = t_begin; t < t_end; ++t, lv += sizeof(float) << D) {
+        asm volatile("" : "+s"(lv));
+        const int column = meta[t].column;
+        const int caller_tree = meta[t].caller_tree;
+        uint32_t pos[R], sel[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            p += NB;
+            const WideEntries<GW> nxt = load_wide<GW>(p);  // in flight during this word's statement
+            v2f lo, hi;
+            bits.template word<GW>(d, cur.g, x, lo, hi);
+            cur = nxt;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                uint32_t word;
+                if (GW == 4) word = __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u);
+                else if (GW == 2) word = __float_as_uint(lo[r]);  // the bits above the 16 are never indexed
+                else word = __float_as_uint(lo[r]) >> 8;
+                heap_walk_word<D>(w, word, pos[r], sel[r]);
+            }
+            // a word is walked before the next one is evaluated: its halves are not copied aside
+            if (D >= 7) asm volatile("" : "+v"(pos[0]), "+v"(pos[1]), "+v"(sel[0]), "+v"(sel[1]));
+            else asm volatile("" : "+v"(pos[0]), "+v"(pos[1]));
+        }
+        if (MODE == MODE_SCALAR) {
+            accu.begin_tree(pending_col);
+#pragma unroll
+            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+            pending_col = column;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (MODE == MODE_SCALAR) {
+                const uint32_t off = pos[r] << 2;
+                pending[r] = *(LeafFloat)(lv + off);
+            } else {
+                const int leaf = (t << D) + static_cast<int>(pos[r] - (1u << D));
+                if (MODE == MODE_LEAVES) {
+                    const int64_t row = row0 + r * TILE + lane;
+                    if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
+                } else {
+                    accu.add(m, r, leaf);
+                }
+            }
+        }
+    }
+    if (MODE == MODE_SCALAR) {
+        accu.begin_tree(pending_col);
+#pragma unroll
+        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
+    }
+}
+
 template <int D, int NVR, int MODE>
 __device__ __forceinline__ void run_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
                                           int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
 {
     if constexpr (NVR <= 2) rank_trees_mfma<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
-    else rank_trees<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+    else if constexpr (FOREST_WIDE_FMA_TREE) rank_trees<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+    else rank_trees_wide<D, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
 }
 
 // Register budget: 32, 64 or 128 pinned rank registers (NVR = 1, 2, 4) plus the working set must

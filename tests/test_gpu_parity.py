@@ -554,6 +554,33 @@ def test_kernel_families(what, path):
         assert info["workgroup_waves"] == waves, info
 
 
+@pytest.mark.parametrize("depth", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("leaves", ["one_column", "columns", "vector"])
+def test_wide_rank_kernel_every_depth(depth, leaves):
+    """65 to 128 rank registers: the kernel that places its matrix-core operands by hand.  Every
+    depth has its own number of outcome groups per word (1, 2 or 4) and words per tree (1 to 8);
+    scalar leaves into one or several columns and vector leaves take different loops."""
+    rng = np.random.default_rng(1000 + depth)
+    n_trees = {1: 400, 2: 200, 3: 100, 4: 60, 7: 13, 8: 13}.get(depth, 37)   # > 64 features tested at every depth
+    if leaves == "vector":
+        arrs = wl._full_forest(rng, n_trees, depth, 100, wl._normal_thr,
+                               lambda r, s: r.standard_normal((s[0], s[1] * 3), dtype=np.float32), leaf_width=3)
+        f = wl.Forest(n_features=100, n_outputs=3, leaf_width=3, tree_output=np.zeros(n_trees, np.int32),
+                      aggregate=wl.AGG_MEAN, transform=wl.TRANSFORM_NONE, **arrs)
+    elif leaves == "columns":
+        f = _full_forest(2000 + depth, n_trees, depth, 100, n_outputs=4, transform=wl.TRANSFORM_SOFTMAX)
+    else:
+        f = _full_forest(3000 + depth, n_trees, depth, 100, transform=wl.TRANSFORM_SIGMOID)
+    X = rng.standard_normal((389, 100)).astype(np.float32)
+    thr = f.threshold[f.feature == 3]
+    if thr.size:
+        X[:64, 3] = np.resize(thr, 64)      # rows that sit exactly on thresholds
+    import paper_2301_13441_amd as pk
+    assert 64 < pk.forest_pack(f)["rank_registers"] <= 128
+    info = _check(f, X)
+    assert info["kernel_path"] == 2 and info["kernel_kind"] == depth, info
+
+
 @pytest.mark.parametrize("full", [True, False])
 def test_every_rank_code_against_every_neighbouring_threshold(full):
     """One feature with integer thresholds 0 .. n - 1 spread over more than two rank registers,
