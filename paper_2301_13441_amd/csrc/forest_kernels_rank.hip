@@ -9,11 +9,10 @@
 // (rank and j' as f16 codes, forest_model.hpp).
 // The register is selected with the VGPR index mode (s_set_gpr_idx_on / _idx: M0 = wave-uniform
 // register index), so step (1), the feature selection matmul(X, W1), costs no vector
-// instruction.  The outcomes of 8 nodes are turned into 8 bits per row either by the matrix
-// core (up to 64 rank registers: BitCollector, one MFMA per 8 nodes) or by a tree of packed
-// fused multiply-adds (128 rank registers: RankStep, 1024 + bits in each half, first entry in
-// bit 7).  Four such bytes make one 32-bit heap-ordered outcome word, the same words the other
-// kernels use, and the walk, leaf gather and reduction are shared.
+// instruction.  The outcomes of 8 nodes are turned into 8 bits per row by the matrix core
+// (HandCollector: one MFMA per 8 nodes, first entry in bit 7).  Four such bytes make one 32-bit
+// heap-ordered outcome word, the same words the other kernels use, and the walk, leaf gather and
+// reduction are shared.
 //
 // Prologue: every workgroup computes the ranks of its 128 rows from per-feature bucket tables
 // (forest_rank_common.hpp).
@@ -25,292 +24,38 @@
 #include "forest_kernel_common.hpp"
 #include "forest_rank_common.hpp"
 
-#ifndef FOREST_WIDE_FMA_TREE
-#define FOREST_WIDE_FMA_TREE 0
-#endif
-
 namespace forest_impl {
 namespace {
 
-// Eight entries (one outcome byte) applied to the lane's two rows.
-template <int NVR>
-struct RankStep;
-
-#define FOREST_RANK_ASM(B)                                                                       \
-    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
-        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
-            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
-                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
-                    "s_set_gpr_idx_off\n\t"                                                      \
-                    "v_pk_fma_f16 %[d0], %[d0], %[c2], %[d1]\n\t"                                \
-                    "v_pk_fma_f16 %[d2], %[d2], %[c2], %[d3]\n\t"                                \
-                    "v_pk_fma_f16 %[d4], %[d4], %[c2], %[d5]\n\t"                                \
-                    "v_pk_fma_f16 %[d6], %[d6], %[c2], %[d7]\n\t"                                \
-                    "v_pk_fma_f16 %[d0], %[d0], %[c4], %[d2]\n\t"                                \
-                    "v_pk_fma_f16 %[d4], %[d4], %[c4], %[d6]\n\t"                                \
-                    "v_pk_fma_f16 %[d0], %[d0], %[c16], %[d4]\n\t"                               \
-                    "v_pk_add_f16 %[a], %[d0], %[c1024]"
-#define FOREST_RANK_OUTS                                                                              \
-    [a] "=v"(acc), [d0] "=&v"(d0), [d1] "=&v"(d1), [d2] "=&v"(d2), [d3] "=&v"(d3), [d4] "=&v"(d4), \
-        [d5] "=&v"(d5), [d6] "=&v"(d6), [d7] "=&v"(d7)
-#define FOREST_RANK_INS                                                                                   \
-    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]),            \
-        [e5] "s"(q.e[5]), [e6] "s"(q.e[6]), [e7] "s"(q.e[7]), [c2] "s"(0x40004000u), [c4] "s"(0x44004400u), \
-        [c16] "s"(0x4c004c00u), [c1024] "s"(0x64006400u)
-
-template <>
-struct RankStep<2> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, const v32u (&x)[2])
-    {
-        uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
-        asm volatile(FOREST_RANK_ASM("v64")
-                     : FOREST_RANK_OUTS
-                     : FOREST_RANK_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
-    }
-};
-
-template <>
-struct RankStep<4> {
-    static __device__ __forceinline__ void step(uint32_t &acc, const Entry8 &q, const v32u (&x)[4])
-    {
-        uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
-        // base v32: with 128 pinned registers the kernel must fit 168 VGPRs for 3 waves per SIMD
-        asm volatile(FOREST_RANK_ASM("v32")
-                     : FOREST_RANK_OUTS
-                     : FOREST_RANK_INS, "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1]), "{v[96:127]}"(x[2]),
-                       "{v[128:159]}"(x[3]));
-    }
-};
-
 enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
 
-// The wave's share of the trees: dense evaluation, walk, leaf gather.  One instantiation per
-// output mode so that each loop only keeps the scalar registers it needs.
-template <int D, int NVR, int MODE>
-__device__ __forceinline__ void rank_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
-                                           int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
-{
-    constexpr int R = 2;
-    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);  // entries per tree
-    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;     // outcome words per tree and row
-    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;      // 8-entry groups (outcome bytes) per word
-    constexpr int NB = GW * 8;                          // entries per scalar load batch = one word
-    const int T = m.n_trees;
-    int t_begin, t_end;
-    tree_range(m, wave, WAVES, t_begin, t_end);
-
-    // The wave's trees are one contiguous stream of entries; the batch after the last one
-    // read here is padding the host appended to the program.
-    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
-    MetaPtr meta = (MetaPtr)m.tree;
-    Batch<NB> cur = load_batch<NB>(p);
-    // Scalar leaf values are fetched one tree ahead of their use, so the gather's latency is
-    // covered by the next tree's comparisons.
-    float pending[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
-    int pending_col = 0;
-    for (int t = t_begin; t < t_end; ++t) {
-        // scalar loads, in flight together with the first batch of the tree
-        const int column = meta[t].column;
-        const int caller_tree = meta[t].caller_tree;
-        uint32_t word[R][NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            uint32_t g[GW];
-            // first group, then issue the next word's loads, then the rest: the loads are in
-            // flight while this word is evaluated
-            RankStep<NVR>::step(g[0], cur.q[0], x);
-            p += NB;
-            const Batch<NB> nxt = load_batch<NB>(p);
-#pragma unroll
-            for (int gi = 1; gi < GW; ++gi) RankStep<NVR>::step(g[gi], cur.q[gi], x);
-            cur = nxt;
-            // low byte of each half = 8 outcome bits; gather the bytes of row A and of row B
-            if (GW == 4) {
-                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);  // A0 A1 B0 B1
-                const uint32_t t23 = __builtin_amdgcn_perm(g[3 % GW], g[2 % GW], 0x06020400u);
-                word[0][w] = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
-                word[1][w] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
-            } else if (GW == 2) {
-                const uint32_t t01 = __builtin_amdgcn_perm(g[1 % GW], g[0], 0x06020400u);
-                word[0][w] = t01 & 0xffffu;
-                word[1][w] = t01 >> 16;
-            } else {
-                word[0][w] = g[0] & 0xffu;
-                word[1][w] = (g[0] >> 16) & 0xffu;
-            }
-        }
-        if (MODE == MODE_SCALAR) {
-            accu.begin_tree(pending_col);
-#pragma unroll
-            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-            pending_col = column;
-        }
-        // wave-uniform base of the tree's leaf values, shifted so that the heap position the
-        // walk ends on indexes it directly: one vector instruction per gather address
-        const float *lv = m.leaf_value + ((t << D) - (1 << D));
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint32_t pos = heap_walk_pos<D, NW>(word[r]);
-            if (MODE == MODE_SCALAR) {
-                pending[r] = lv[pos];
-                continue;
-            }
-            const int leaf = (t << D) + static_cast<int>(pos - (1u << D));
-            if (MODE == MODE_LEAVES) {
-                const int64_t row = row0 + r * TILE + lane;
-                if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
-            } else {
-                accu.add(m, r, leaf);
-            }
-        }
-    }
-    if (MODE == MODE_SCALAR) {
-        accu.begin_tree(pending_col);
-#pragma unroll
-        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-    }
-}
-
-// The same, with the outcome bits collected by the matrix core (32 or 64 rank registers: the
-// wide kernel has no registers to spare for the weights).  A word's MFMAs are still running
-// when its last comparison has issued, so the word is read, and walked, one group later:
-// after the first comparisons of the next word, or of the next tree's first word, whose leaf
-// gather in turn is consumed one tree after that.
-template <int D, int NVR, int MODE>
-__device__ __forceinline__ void rank_trees_mfma(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
-                                                int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
-{
-    constexpr int R = 2;
-    constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);
-    constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;
-    constexpr int GW = N_ENT < 32 ? N_ENT / 8 : 4;
-    constexpr int NB = GW * 8;
-    const int T = m.n_trees;
-    int t_begin, t_end;
-    tree_range(m, wave, WAVES, t_begin, t_end);
-    if (t_begin >= t_end) return;
-
-    BitCollector bits;
-    bits.init(lane);
-    ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
-    MetaPtr meta = (MetaPtr)m.tree;
-    Batch<NB> cur = load_batch<NB>(p);
-    v4f lo = bits.bias, hi = bits.bias;
-    uint32_t pos[R], sel[R];
-    float pending[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, pending[r] = 0.0f;
-    int pending_col = 0, prev_column = 0, prev_caller = 0;
-
-    // reads the word the last four (or fewer) MFMAs produced and advances the walk by it
-    auto finish_word = [&](int w) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            // below 32 outcomes the bits above them are never indexed by the walk
-            const uint32_t word = GW == 4 ? __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u)
-                                          : __float_as_uint(lo[r]);
-            heap_walk_word<D>(w, word, pos[r], sel[r]);
-        }
-    };
-    // the walk of tree tp has ended on pos[]: consume the leaf
-    auto finish_tree = [&](int tp, int column, int caller_tree) {
-        if (MODE == MODE_SCALAR) {
-            accu.begin_tree(pending_col);
-#pragma unroll
-            for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-            pending_col = column;
-        }
-        const float *lv = m.leaf_value + ((tp << D) - (1 << D));
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (MODE == MODE_SCALAR) {
-                // wave-uniform base + 32-bit byte offset: the gather takes its base from scalar
-                // registers and needs one vector instruction for the address (a tree's leaves
-                // are within 1 KB of the base)
-                const uint32_t off = pos[r] << 2;
-                pending[r] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lv) + off);
-            } else {
-                const int leaf = (tp << D) + static_cast<int>(pos[r] - (1u << D));
-                if (MODE == MODE_LEAVES) {
-                    const int64_t row = row0 + r * TILE + lane;
-                    if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
-                } else {
-                    accu.add(m, r, leaf);
-                }
-            }
-            pos[r] = 1u;
-        }
-    };
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int column = meta[t].column;
-        const int caller_tree = meta[t].caller_tree;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            uint32_t d[8];
-            rank_compare(d, cur.q[0], x);
-#if defined(__HIP_DEVICE_COMPILE__)
-            __builtin_amdgcn_sched_barrier(0);  // the reads of the previous word stay behind these comparisons
-#endif
-            if (w > 0) {
-                finish_word(w - 1);
-            } else if (t > t_begin) {
-                finish_word(NW - 1);
-                finish_tree(t - 1, prev_column, prev_caller);
-            }
-#if defined(__HIP_DEVICE_COMPILE__)
-            __builtin_amdgcn_sched_barrier(0);
-#endif
-            lo = bits.template collect<0>(d, bits.bias);
-            p += NB;
-            const Batch<NB> nxt = load_batch<NB>(p);
-            if (GW >= 2) {
-                rank_compare(d, cur.q[1 % GW], x);
-                lo = bits.template collect<1>(d, lo);
-            }
-            if (GW == 4) {
-                rank_compare(d, cur.q[2 % GW], x);
-                hi = bits.template collect<0>(d, bits.bias);
-                rank_compare(d, cur.q[3 % GW], x);
-                hi = bits.template collect<1>(d, hi);
-            }
-            cur = nxt;
-        }
-        prev_column = column;
-        prev_caller = caller_tree;
-    }
-    finish_word(NW - 1);
-    finish_tree(t_end - 1, prev_column, prev_caller);
-    if (MODE == MODE_SCALAR) {
-        accu.begin_tree(pending_col);
-#pragma unroll
-        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-    }
-}
-
 // ---------------------------------------------------------------------------------------
-// 128 rank registers (v32..v159): bit collection on the matrix core within 168 registers.
+// Bit collection on the matrix core with operands placed by hand.
 //
-// Three waves per SIMD leave 40 registers beside the ranks, too few for two weight matrices, a
-// four-register addend and compiler-placed accumulators.  So this kernel places its matrix-core
-// operands by hand and uses ONE weight matrix: rows 4q and 4q + 1 of A weigh the row-a / row-b
-// bytes of 16-lane block q by 2^(7 - v), rows 4q + 2 and 4q + 3 weigh them by 2^(15 - v), so a
-// group's MFMA leaves its eight bits in the low byte of D[0], D[1] and in the second byte of D[2],
-// D[3].  A chain of two groups is  D1 = A B1 + bias  into v[n:n+3], then  D2 = A B2 + C  with C =
-// D = v[n+2:n+5]: the second group's low-byte sums land on the first group's second-byte sums, 16
-// bits per row in v[n+2], v[n+3]; the other elements are never read.  Registers:
+// The eight outcome registers of a group are, read as bytes, (0, a, 0, b) with a, b = 0x3c (1.0
+// in bf8) or 0 for the lane's two rows.  v_mfma_f32_16x16x128_f8f6f4 takes them as its B operand:
+// a lane of 16-lane block q supplies B[k][n] for n = lane % 16 and the 32 values of k that belong
+// to block q, and receives D[4q + i][n], i = 0..3.  With an A that is zero outside A[4q + i][k of
+// block q] every D only sums the lane's own bytes.  ONE weight matrix serves: rows 4q and 4q + 1
+// weigh the row-a / row-b bytes by 2^(7 - v) (register v of the group: first entry in bit 7), rows
+// 4q + 2 and 4q + 3 weigh them by 2^(15 - v), so a group's MFMA leaves its eight bits in the low
+// byte of D[0], D[1] and in the second byte of D[2], D[3], on top of a 2^23 addend (exact: every
+// partial sum is an integer below 2^24).  A chain of two groups is  D1 = A B1 + bias  into
+// v[n:n+3], then  D2 = A B2 + C  with C = D = v[n+2:n+5]: the second group's low-byte sums land on
+// the first group's second-byte sums, 16 bits per row in v[n+2], v[n+3]; the other elements are
+// never read.  Registers (the rank registers are v64.. or, with 128 of them, v32..v159, which
+// leaves 40 for everything else at three waves per SIMD):
 //     v[0:7]    the eight outcome registers of a group (B)
 //     v[8:15]   A;  v[16:17] = 2^23, 2^23: the addend of a chain's first MFMA is v[14:17] (its
 //               elements 0 and 1 only reach sums that are never read)
 //     v[18:27]  accumulators: v[18:21] <- first group, v[20:23] <- second (bits in v20, v21),
 //               v[22:25] <- third, v[24:27] <- fourth (bits in v24, v25)
-// The compiler does not look inside a statement, so the waits the matrix core needs are written
-// out: two idle states between a comparison and the MFMA that reads it, the 17 instructions of a
-// group between an MFMA and the next one that reads or overwrites part of its result (12 states
-// needed), and 12 idle states after a statement's last MFMA, since the compiler may read or copy
-// the results right behind the statement.
+// The compiler does not look inside a statement and knows of no matrix instruction here, so the
+// waits the matrix core needs are in the statements: two idle states between a comparison and
+// the MFMA that reads it, and the 18 instructions of a group between an MFMA and anything that
+// reads or overwrites part of its result (12 states needed) -- every MFMA of a statement is
+// followed by a group, the last one by the first group of the NEXT word, so its result is complete
+// when the statement ends and the compiler may read or copy it at once.
 // ---------------------------------------------------------------------------------------
 typedef float v2f __attribute__((ext_vector_type(2)));
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -321,23 +66,51 @@ typedef const char *LeafBytes;  // host pass: the kernel body is only parsed
 typedef const float *LeafFloat;
 #endif
 
-#define FOREST_WIDE_CMP(n, p) \
-    "v_pk_fma_f16 v" #n ", v32, 4.0, %[" p #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
-#define FOREST_WIDE_IDX(n, p) "s_set_gpr_idx_idx %[" p #n "]\n\t"
-#define FOREST_WIDE_GROUP(p)                                                                             \
-    "s_set_gpr_idx_on %[" p "0], 0x1\n\t" FOREST_WIDE_CMP(0, p) FOREST_WIDE_IDX(1, p) FOREST_WIDE_CMP(1, p)   \
-        FOREST_WIDE_IDX(2, p) FOREST_WIDE_CMP(2, p) FOREST_WIDE_IDX(3, p) FOREST_WIDE_CMP(3, p)               \
-            FOREST_WIDE_IDX(4, p) FOREST_WIDE_CMP(4, p) FOREST_WIDE_IDX(5, p) FOREST_WIDE_CMP(5, p)           \
-                FOREST_WIDE_IDX(6, p) FOREST_WIDE_CMP(6, p) FOREST_WIDE_IDX(7, p) FOREST_WIDE_CMP(7, p)       \
+#define FOREST_HAND_CMP(B, n, p) \
+    "v_pk_fma_f16 v" #n ", " B ", 4.0, %[" p #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
+#define FOREST_HAND_IDX(n, p) "s_set_gpr_idx_idx %[" p #n "]\n\t"
+#define FOREST_HAND_GROUP(B, p)                                                                                   \
+    "s_set_gpr_idx_on %[" p "0], 0x1\n\t" FOREST_HAND_CMP(B, 0, p) FOREST_HAND_IDX(1, p) FOREST_HAND_CMP(B, 1, p)      \
+        FOREST_HAND_IDX(2, p) FOREST_HAND_CMP(B, 2, p) FOREST_HAND_IDX(3, p) FOREST_HAND_CMP(B, 3, p)                  \
+            FOREST_HAND_IDX(4, p) FOREST_HAND_CMP(B, 4, p) FOREST_HAND_IDX(5, p) FOREST_HAND_CMP(B, 5, p)              \
+                FOREST_HAND_IDX(6, p) FOREST_HAND_CMP(B, 6, p) FOREST_HAND_IDX(7, p) FOREST_HAND_CMP(B, 7, p)          \
                     "s_set_gpr_idx_off\n\t"
-#define FOREST_WIDE_MFMA(dst, c) \
+#define FOREST_HAND_MFMA(dst, c) \
     "s_nop 1\n\tv_mfma_f32_16x16x128_f8f6f4 " dst ", v[8:15], v[0:7], " c " cbsz:1 blgp:1\n\t"
-#define FOREST_WIDE_ENTRIES(p, q)                                                                              \
+#define FOREST_HAND_ENTRIES(p, q)                                                                              \
     [p##0] "s"(q.e[0]), [p##1] "s"(q.e[1]), [p##2] "s"(q.e[2]), [p##3] "s"(q.e[3]), [p##4] "s"(q.e[4]),        \
         [p##5] "s"(q.e[5]), [p##6] "s"(q.e[6]), [p##7] "s"(q.e[7])
-#define FOREST_WIDE_X "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1]), "{v[96:127]}"(x[2]), "{v[128:159]}"(x[3])
+#define FOREST_HAND_X1 "{v[64:95]}"(x[0])
+#define FOREST_HAND_X2 "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1 % NVR])
+#define FOREST_HAND_X4 \
+    "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1 % NVR]), "{v[96:127]}"(x[2 % NVR]), "{v[128:159]}"(x[3 % NVR])
 
-struct WideCollector {
+// The statements, for rank registers from B on, passed as the operands X.
+#define FOREST_HAND_FIRST(B, X) \
+    asm volatile(FOREST_HAND_GROUP(B, "e") : "=&{v[0:7]}"(d) : FOREST_HAND_ENTRIES(e, q), X)
+#define FOREST_HAND_WORD4(B, X)                                                                                    \
+    asm volatile(FOREST_HAND_MFMA("v[18:21]", "v[14:17]") FOREST_HAND_GROUP(B, "a")                                \
+                     FOREST_HAND_MFMA("v[20:23]", "v[20:23]") FOREST_HAND_GROUP(B, "b")                            \
+                         FOREST_HAND_MFMA("v[22:25]", "v[14:17]") FOREST_HAND_GROUP(B, "c")                        \
+                             FOREST_HAND_MFMA("v[24:27]", "v[24:27]") FOREST_HAND_GROUP(B, "e")                    \
+                 : "={v[20:21]}"(lo), "={v[24:25]}"(hi), "+{v[0:7]}"(d)                                          \
+                 : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_HAND_ENTRIES(a, g[0]), FOREST_HAND_ENTRIES(b, g[1 % GW]), \
+                   FOREST_HAND_ENTRIES(c, g[2 % GW]), FOREST_HAND_ENTRIES(e, g[3 % GW]), X                       \
+                 : "v18", "v19", "v22", "v23", "v26", "v27")
+#define FOREST_HAND_WORD2(B, X)                                                                                    \
+    asm volatile(FOREST_HAND_MFMA("v[18:21]", "v[14:17]") FOREST_HAND_GROUP(B, "a")                                \
+                     FOREST_HAND_MFMA("v[20:23]", "v[20:23]") FOREST_HAND_GROUP(B, "b")                            \
+                 : "={v[20:21]}"(lo), "+{v[0:7]}"(d)                                                              \
+                 : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_HAND_ENTRIES(a, g[0]), FOREST_HAND_ENTRIES(b, g[1 % GW]), X \
+                 : "v18", "v19", "v22", "v23")
+#define FOREST_HAND_WORD1(B, X)                                                                                    \
+    asm volatile(FOREST_HAND_MFMA("v[18:21]", "v[14:17]") FOREST_HAND_GROUP(B, "a")                                \
+                 : "={v[20:21]}"(lo), "+{v[0:7]}"(d)                                                              \
+                 : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_HAND_ENTRIES(a, g[0]), X                            \
+                 : "v18", "v19")
+
+template <int NVR>
+struct HandCollector {
     v8i a;
     v2f bias;
 
@@ -356,47 +129,39 @@ struct WideCollector {
         asm volatile("" : "+v"(bias));  // kept in registers instead of rebuilt before every statement
     }
     // The comparisons of the stream's very first group.
-    __device__ __forceinline__ v8i first(const Entry8 &q, const v32u (&x)[4]) const
+    __device__ __forceinline__ v8i first(const Entry8 &q, const v32u (&x)[NVR]) const
     {
         v8i d;
-        asm volatile(FOREST_WIDE_GROUP("e") : "=&{v[0:7]}"(d) : FOREST_WIDE_ENTRIES(e, q), FOREST_WIDE_X);
+        if constexpr (NVR == 4) FOREST_HAND_FIRST("v32", FOREST_HAND_X4);
+        else if constexpr (NVR == 2) FOREST_HAND_FIRST("v64", FOREST_HAND_X2);
+        else FOREST_HAND_FIRST("v64", FOREST_HAND_X1);
         return d;
     }
     // One word of GW groups.  On entry d holds the outcomes of the word's first group (the one
     // that ends up in the higher byte of a chain); every MFMA is followed by the comparisons of the
     // next group, the last one by those of the NEXT word's first group, which d holds on return.
-    // So the last MFMA is complete when the statement ends, and the wave has comparisons to issue
-    // while it runs.  e.g[] are the groups in the order they are compared.  Returns the 16-bit
-    // halves (GW = 4: lo and hi; GW = 2: lo) or, for GW = 1, the group's bits in the second byte of lo.
+    // g[] are the groups in the order they are compared.  Returns the 16-bit halves (GW = 4: lo
+    // and hi; GW = 2: lo) or, for GW = 1, the group's bits in the second byte of lo.
     template <int GW>
-    __device__ __forceinline__ void word(v8i &d, const Entry8 (&g)[GW], const v32u (&x)[4], v2f &lo, v2f &hi) const
+    __device__ __forceinline__ void word(v8i &d, const Entry8 (&g)[GW], const v32u (&x)[NVR], v2f &lo, v2f &hi) const
     {
         if constexpr (GW == 4) {
-            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
-                             FOREST_WIDE_MFMA("v[20:23]", "v[20:23]") FOREST_WIDE_GROUP("b")
-                                 FOREST_WIDE_MFMA("v[22:25]", "v[14:17]") FOREST_WIDE_GROUP("c")
-                                     FOREST_WIDE_MFMA("v[24:27]", "v[24:27]") FOREST_WIDE_GROUP("e")
-                         : "={v[20:21]}"(lo), "={v[24:25]}"(hi), "+{v[0:7]}"(d)
-                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_ENTRIES(b, g[1 % GW]),
-                           FOREST_WIDE_ENTRIES(c, g[2 % GW]), FOREST_WIDE_ENTRIES(e, g[3 % GW]), FOREST_WIDE_X
-                         : "v18", "v19", "v22", "v23", "v26", "v27");
+            if constexpr (NVR == 4) FOREST_HAND_WORD4("v32", FOREST_HAND_X4);
+            else if constexpr (NVR == 2) FOREST_HAND_WORD4("v64", FOREST_HAND_X2);
+            else FOREST_HAND_WORD4("v64", FOREST_HAND_X1);
         } else if constexpr (GW == 2) {
-            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
-                             FOREST_WIDE_MFMA("v[20:23]", "v[20:23]") FOREST_WIDE_GROUP("b")
-                         : "={v[20:21]}"(lo), "+{v[0:7]}"(d)
-                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_ENTRIES(b, g[1 % GW]),
-                           FOREST_WIDE_X
-                         : "v18", "v19", "v22", "v23");
+            if constexpr (NVR == 4) FOREST_HAND_WORD2("v32", FOREST_HAND_X4);
+            else if constexpr (NVR == 2) FOREST_HAND_WORD2("v64", FOREST_HAND_X2);
+            else FOREST_HAND_WORD2("v64", FOREST_HAND_X1);
         } else {
-            asm volatile(FOREST_WIDE_MFMA("v[18:21]", "v[14:17]") FOREST_WIDE_GROUP("a")
-                         : "={v[20:21]}"(lo), "+{v[0:7]}"(d)
-                         : "{v[8:15]}"(a), "{v[16:17]}"(bias), FOREST_WIDE_ENTRIES(a, g[0]), FOREST_WIDE_X
-                         : "v18", "v19");
+            if constexpr (NVR == 4) FOREST_HAND_WORD1("v32", FOREST_HAND_X4);
+            else if constexpr (NVR == 2) FOREST_HAND_WORD1("v64", FOREST_HAND_X2);
+            else FOREST_HAND_WORD1("v64", FOREST_HAND_X1);
         }
     }
 };
 
-// The groups one statement of WideCollector compares, for the word of GW groups at p: the word's
+// The groups one statement of HandCollector compares, for the word of GW groups at p: the word's
 // groups after its first one in the order 0, 3, 2 (a chain takes its higher byte first), then
 // group 1 of the next word (group 0 where a word is a single group).
 template <int GW>
@@ -410,6 +175,19 @@ __device__ __forceinline__ Entry8 load_group(ProgPtr p)
 #pragma unroll
     for (int j = 0; j < 8; ++j) e.e[j] = p[j];
     return e;
+}
+
+// Makes the compiler place its wait for the loads of e here.
+template <int GW>
+__device__ __forceinline__ void wait_for(const WideEntries<GW> &e)
+{
+#pragma unroll
+    for (int i = 0; i < GW; ++i)
+        asm volatile("" : : "s"(e.g[i].e[0]), "s"(e.g[i].e[1]), "s"(e.g[i].e[2]), "s"(e.g[i].e[3]), "s"(e.g[i].e[4]),
+                     "s"(e.g[i].e[5]), "s"(e.g[i].e[6]), "s"(e.g[i].e[7]));
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_sched_barrier(0);
+#endif
 }
 
 template <int GW>
@@ -430,12 +208,17 @@ __device__ __forceinline__ WideEntries<GW> load_wide(ProgPtr p)
     return e;
 }
 
-// The wave's share of the trees with WideCollector.  A word's bits are complete when its
-// statement ends, so the word is walked right away and a tree's leaf values are consumed one
-// tree later.  The statement of the wave's last word compares one group of the next wave's trees
-// or of the padding behind the program; nothing reads those outcomes.
-template <int D, int MODE>
-__device__ __forceinline__ void rank_trees_wide(const DevModel &m, const v32u (&x)[4], Accumulator<2> &accu, int wave,
+// The wave's share of the trees.  A word's bits are complete when its statement ends, so the
+// word is walked right away; a tree's leaf values are gathered at the end of its iteration and
+// added one tree later.  The statement of the wave's last word compares one group of the next
+// wave's trees or of the padding behind the program; nothing reads those outcomes.
+//
+// Scalar leaves: the trees are sorted by output column, so the wave's trees are a few runs of one
+// column each (the runs' ends are the running sums of the columns' tree counts), and inside a
+// run the loop over the trees is one basic block -- no test of the column per tree, and the
+// requests for the next tree's entries stay in front of the statement they are to overlap.
+template <int D, int NVR, int MODE>
+__device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
                                                 int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
 {
     constexpr int R = 2;
@@ -448,31 +231,28 @@ __device__ __forceinline__ void rank_trees_wide(const DevModel &m, const v32u (&
     tree_range(m, wave, WAVES, t_begin, t_end);
     if (t_begin >= t_end) return;
 
-    WideCollector bits;
+    HandCollector<NVR> bits;
     bits.init(lane);
     ProgPtr p = (ProgPtr)(m.prog32 + static_cast<size_t>(t_begin) * N_ENT);
-    MetaPtr meta = (MetaPtr)m.tree;
     WideEntries<GW> cur = load_wide<GW>(p);
     v8i d = bits.first(load_group(p + (GW >= 2 ? 8 : 0)), x);
-    float pending[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) pending[r] = 0.0f;
-    int pending_col = 0;
-    // wave-uniform base of the current tree's leaf values, shifted so that the heap position the
-    // walk ends on indexes it directly; carried from tree to tree in scalar registers
-    LeafBytes lv = (LeafBytes)(m.leaf_value + ((t_begin << D) - (1 << D)));
 
-    for (int t = t_begin; t < t_end; ++t, lv += sizeof(float) << D) {
-        asm volatile("" : "+s"(lv));
-        const int column = meta[t].column;
-        const int caller_tree = meta[t].caller_tree;
-        uint32_t pos[R], sel[R];
+    // evaluates and walks the next tree of the stream: pos[r] = heap position row r ends on
+    auto walk_tree = [&](uint32_t (&pos)[R]) {
+        uint32_t sel[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
+            // Scalar loads return in any order, so the only wait there is waits for all of them: the
+            // entries of this word are waited for (they were requested a statement ago) BEFORE the
+            // next word's are requested, which then have the whole statement to arrive.
+            wait_for(cur);
             p += NB;
-            const WideEntries<GW> nxt = load_wide<GW>(p);  // in flight during this word's statement
+            const WideEntries<GW> nxt = load_wide<GW>(p);
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);  // requested before the statement, not behind it
+#endif
             v2f lo, hi;
             bits.template word<GW>(d, cur.g, x, lo, hi);
             cur = nxt;
@@ -488,18 +268,42 @@ __device__ __forceinline__ void rank_trees_wide(const DevModel &m, const v32u (&
             if (D >= 7) asm volatile("" : "+v"(pos[0]), "+v"(pos[1]), "+v"(sel[0]), "+v"(sel[1]));
             else asm volatile("" : "+v"(pos[0]), "+v"(pos[1]));
         }
-        if (MODE == MODE_SCALAR) {
-            accu.begin_tree(pending_col);
+    };
+
+    if constexpr (MODE == MODE_SCALAR) {
+        // wave-uniform base of the current tree's leaf values, shifted so that the heap position
+        // the walk ends on indexes it directly; carried from tree to tree in scalar registers
+        LeafBytes lv = (LeafBytes)(m.leaf_value + ((t_begin << D) - (1 << D)));
+        int t = t_begin, column = 0;
+        int column_end = uniform(static_cast<int>(m.col_trees[0]));
+        while (t < t_end) {
+            while (column_end <= t) column_end += uniform(static_cast<int>(m.col_trees[++column]));
+            const int run_end = column_end < t_end ? column_end : t_end;
+            accu.begin_tree(column);
+            float pending[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) pending[r] = 0.0f;
+            for (; t < run_end; ++t, lv += sizeof(float) << D) {
+                asm volatile("" : "+s"(lv));
+                uint32_t pos[R];
+                walk_tree(pos);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    accu.add_value(r, pending[r]);
+                    pending[r] = *(LeafFloat)(lv + (pos[r] << 2));
+                }
+            }
 #pragma unroll
             for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-            pending_col = column;
         }
+    } else {
+        MetaPtr meta = (MetaPtr)m.tree;
+        for (int t = t_begin; t < t_end; ++t) {
+            const int caller_tree = meta[t].caller_tree;
+            uint32_t pos[R];
+            walk_tree(pos);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (MODE == MODE_SCALAR) {
-                const uint32_t off = pos[r] << 2;
-                pending[r] = *(LeafFloat)(lv + off);
-            } else {
+            for (int r = 0; r < R; ++r) {
                 const int leaf = (t << D) + static_cast<int>(pos[r] - (1u << D));
                 if (MODE == MODE_LEAVES) {
                     const int64_t row = row0 + r * TILE + lane;
@@ -510,20 +314,6 @@ __device__ __forceinline__ void rank_trees_wide(const DevModel &m, const v32u (&
             }
         }
     }
-    if (MODE == MODE_SCALAR) {
-        accu.begin_tree(pending_col);
-#pragma unroll
-        for (int r = 0; r < R; ++r) accu.add_value(r, pending[r]);
-    }
-}
-
-template <int D, int NVR, int MODE>
-__device__ __forceinline__ void run_trees(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
-                                          int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
-{
-    if constexpr (NVR <= 2) rank_trees_mfma<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
-    else if constexpr (FOREST_WIDE_FMA_TREE) rank_trees<D, NVR, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
-    else rank_trees_wide<D, MODE>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
 }
 
 // Register budget: 32, 64 or 128 pinned rank registers (NVR = 1, 2, 4) plus the working set must
@@ -560,11 +350,11 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 5 : NVR == 2 ? 4 : 3)) void fore
     Accumulator<R> accu;
     accu.init(acc, wave, lane, m);
     if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
-        run_trees<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+        rank_trees_hand<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
         return;
     }
-    if (m.leaf_width == 1) run_trees<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
-    else run_trees<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    if (m.leaf_width == 1) rank_trees_hand<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    else rank_trees_hand<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
     accu.flush();
     __syncthreads();
     const int li = threadIdx.x;

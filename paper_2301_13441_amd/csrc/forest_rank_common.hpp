@@ -23,17 +23,16 @@ constexpr int RROWS = 128;  // rows per workgroup: lane l holds rows l (low half
 // supplies B[k][n] for n = lane % 16 and the 32 values of k that belong to block q, and
 // receives D[4q + i][n], i = 0..3.  With an A that is zero outside A[4q + i][k of block q],
 // D[4q + i][n] only sums the lane's own bytes: i = 0 weighs the row-a bytes by 2^(7 - v)
-// (register v of the group: first entry in bit 7), i = 1 the row-b bytes; a second matrix
-// weighs by 2^(15 - v).  Two chained MFMAs on top of a 2^23 addend therefore leave the 16
-// outcome bits of two groups in the low mantissa bits of D[..][0] and D[..][1]: exact, every
-// product and partial sum being an integer below 2^24.  The matrix core runs beside the
-// vector ALU, so collecting a group costs the vector ALU the MFMA's issue instead of the eight
-// instructions of a packed fused-multiply-add tree.
+// (register v of the group: first entry in bit 7), i = 1 the row-b bytes.  On top of a 2^23
+// addend the MFMA therefore leaves the 8 outcome bits of a group in the low mantissa bits of
+// D[..][0] and D[..][1]: exact, every product and partial sum being an integer below 2^24.  The
+// matrix core runs beside the vector ALU, so collecting a group costs the vector ALU the MFMA's
+// issue instead of the eight instructions of a packed fused-multiply-add tree.
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct BitCollector {
-    v8i a[2];  // weights 2^(7 - v) and 2^(15 - v)
+    v8i a;  // weights 2^(7 - v)
     v4f bias;
 
     __device__ __forceinline__ void init(int lane)
@@ -42,32 +41,19 @@ struct BitCollector {
         const bool mine = (m >> 2) == q && (m & 3) < 2;
         const int shift = (m & 3) == 0 ? 8 : 24;  // byte 1 = row a, byte 3 = row b
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const uint32_t bf8 = static_cast<uint32_t>(15 + 8 * j + 7 - v) << 2;  // 2^(8j + 7 - v)
-                a[j][v] = mine ? static_cast<int>(bf8 << shift) : 0;
-            }
+        for (int v = 0; v < 8; ++v) {
+            const uint32_t bf8 = static_cast<uint32_t>(15 + 7 - v) << 2;  // 2^(7 - v) in e5m2
+            a[v] = mine ? static_cast<int>(bf8 << shift) : 0;
+        }
         bias = v4f{8388608.0f, 8388608.0f, 8388608.0f, 8388608.0f};
         // keep the addend in registers instead of rebuilding it before every chain
         asm volatile("" : "+v"(bias));
     }
-    // the same with the eight outcome registers already in one tuple (weights 2^(7 - v))
+    // the eight outcome registers of a group, in one tuple
     __device__ __forceinline__ v4f collect_b(const v8i &b, v4f c) const
     {
 #if defined(__HIP_DEVICE_COMPILE__)
-        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[0], b, c, 1, 1, 0, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#endif
-        return c;
-    }
-    template <int J>
-    __device__ __forceinline__ v4f collect(const uint32_t (&d)[8], v4f c) const
-    {
-#if defined(__HIP_DEVICE_COMPILE__)
-        const v8i b = {static_cast<int>(d[0]), static_cast<int>(d[1]), static_cast<int>(d[2]), static_cast<int>(d[3]),
-                       static_cast<int>(d[4]), static_cast<int>(d[5]), static_cast<int>(d[6]), static_cast<int>(d[7])};
-        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[J], b, c, 1, 1, 0, 0, 0, 0);  // A, B: bf8, unscaled
+        c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 1, 1, 0, 0, 0, 0);  // A, B: bf8, unscaled
         __builtin_amdgcn_sched_barrier(0);
 #endif
         return c;
@@ -531,37 +517,6 @@ typedef const TreeMeta *MetaPtr;
 struct Entry8 {
     uint32_t e[8];
 };
-
-#define FOREST_RANK_CMP(B, n) \
-    "v_pk_fma_f16 %[d" #n "], " B ", 4.0, %[e" #n "] op_sel:[0,0,1] op_sel_hi:[1,0,1] clamp\n\t"
-#define FOREST_RANK_IDX(n) "s_set_gpr_idx_idx %[e" #n "]\n\t"
-
-// The eight comparisons alone; the outcomes (1.0 or 0.0 in each half) go to the matrix core.
-#define FOREST_RANK_CMP_ONLY(B)                                                                   \
-    "s_set_gpr_idx_on %[e0], 0x1\n\t" FOREST_RANK_CMP(B, 0) FOREST_RANK_IDX(1) FOREST_RANK_CMP(B, 1)    \
-        FOREST_RANK_IDX(2) FOREST_RANK_CMP(B, 2) FOREST_RANK_IDX(3) FOREST_RANK_CMP(B, 3)              \
-            FOREST_RANK_IDX(4) FOREST_RANK_CMP(B, 4) FOREST_RANK_IDX(5) FOREST_RANK_CMP(B, 5)          \
-                FOREST_RANK_IDX(6) FOREST_RANK_CMP(B, 6) FOREST_RANK_IDX(7) FOREST_RANK_CMP(B, 7)      \
-                    "s_set_gpr_idx_off"
-
-#define FOREST_RANK_CMP_OUTS                                                                                  \
-    [d0] "=&v"(d[0]), [d1] "=&v"(d[1]), [d2] "=&v"(d[2]), [d3] "=&v"(d[3]), [d4] "=&v"(d[4]), [d5] "=&v"(d[5]), \
-        [d6] "=&v"(d[6]), [d7] "=&v"(d[7])
-#define FOREST_RANK_CMP_INS                                                                                \
-    [e0] "s"(q.e[0]), [e1] "s"(q.e[1]), [e2] "s"(q.e[2]), [e3] "s"(q.e[3]), [e4] "s"(q.e[4]), [e5] "s"(q.e[5]), \
-        [e6] "s"(q.e[6]), [e7] "s"(q.e[7])
-
-__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[1])
-{
-    asm volatile(FOREST_RANK_CMP_ONLY("v64") : FOREST_RANK_CMP_OUTS : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]));
-}
-
-__device__ __forceinline__ void rank_compare(uint32_t (&d)[8], const Entry8 &q, const v32u (&x)[2])
-{
-    asm volatile(FOREST_RANK_CMP_ONLY("v64")
-                 : FOREST_RANK_CMP_OUTS
-                 : FOREST_RANK_CMP_INS, "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1]));
-}
 
 template <int N>
 struct Batch {
