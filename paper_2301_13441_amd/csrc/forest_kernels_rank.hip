@@ -43,8 +43,8 @@ enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
 // partial sum is an integer below 2^24).  A chain of two groups is  D1 = A B1 + bias  into
 // v[n:n+3], then  D2 = A B2 + C  with C = D = v[n+2:n+5]: the second group's low-byte sums land on
 // the first group's second-byte sums, 16 bits per row in v[n+2], v[n+3]; the other elements are
-// never read.  Registers (the rank registers are v64.. or, with 128 of them, v32..v159, which
-// leaves 40 for everything else at three waves per SIMD):
+// never read.  Registers (the rank registers follow from v28, v64 or, with 128 of them, v32 on,
+// which leaves 40 for everything else at three waves per SIMD):
 //     v[0:7]    the eight outcome registers of a group (B)
 //     v[8:15]   A;  v[16:17] = 2^23, 2^23: the addend of a chain's first MFMA is v[14:17] (its
 //               elements 0 and 1 only reach sums that are never read)
@@ -80,7 +80,7 @@ typedef const float *LeafFloat;
 #define FOREST_HAND_ENTRIES(p, q)                                                                              \
     [p##0] "s"(q.e[0]), [p##1] "s"(q.e[1]), [p##2] "s"(q.e[2]), [p##3] "s"(q.e[3]), [p##4] "s"(q.e[4]),        \
         [p##5] "s"(q.e[5]), [p##6] "s"(q.e[6]), [p##7] "s"(q.e[7])
-#define FOREST_HAND_X1 "{v[64:95]}"(x[0])
+#define FOREST_HAND_X1 "{v[28:59]}"(x[0])
 #define FOREST_HAND_X2 "{v[64:95]}"(x[0]), "{v[96:127]}"(x[1 % NVR])
 #define FOREST_HAND_X4 \
     "{v[32:63]}"(x[0]), "{v[64:95]}"(x[1 % NVR]), "{v[96:127]}"(x[2 % NVR]), "{v[128:159]}"(x[3 % NVR])
@@ -134,7 +134,7 @@ struct HandCollector {
         v8i d;
         if constexpr (NVR == 4) FOREST_HAND_FIRST("v32", FOREST_HAND_X4);
         else if constexpr (NVR == 2) FOREST_HAND_FIRST("v64", FOREST_HAND_X2);
-        else FOREST_HAND_FIRST("v64", FOREST_HAND_X1);
+        else FOREST_HAND_FIRST("v28", FOREST_HAND_X1);
         return d;
     }
     // One word of GW groups.  On entry d holds the outcomes of the word's first group (the one
@@ -148,15 +148,15 @@ struct HandCollector {
         if constexpr (GW == 4) {
             if constexpr (NVR == 4) FOREST_HAND_WORD4("v32", FOREST_HAND_X4);
             else if constexpr (NVR == 2) FOREST_HAND_WORD4("v64", FOREST_HAND_X2);
-            else FOREST_HAND_WORD4("v64", FOREST_HAND_X1);
+            else FOREST_HAND_WORD4("v28", FOREST_HAND_X1);
         } else if constexpr (GW == 2) {
             if constexpr (NVR == 4) FOREST_HAND_WORD2("v32", FOREST_HAND_X4);
             else if constexpr (NVR == 2) FOREST_HAND_WORD2("v64", FOREST_HAND_X2);
-            else FOREST_HAND_WORD2("v64", FOREST_HAND_X1);
+            else FOREST_HAND_WORD2("v28", FOREST_HAND_X1);
         } else {
             if constexpr (NVR == 4) FOREST_HAND_WORD1("v32", FOREST_HAND_X4);
             else if constexpr (NVR == 2) FOREST_HAND_WORD1("v64", FOREST_HAND_X2);
-            else FOREST_HAND_WORD1("v64", FOREST_HAND_X1);
+            else FOREST_HAND_WORD1("v28", FOREST_HAND_X1);
         }
     }
 };
@@ -316,10 +316,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     }
 }
 
-// Register budget: 32, 64 or 128 pinned rank registers (NVR = 1, 2, 4) plus the working set must
-// leave room for 5, 4 resp. 3 waves per SIMD (96, 128 resp. 168 VGPRs).
+// Register budget: the 28 hand-placed registers, 32, 64 or 128 pinned rank registers (NVR = 1, 2,
+// 4: from v28, v64 resp. v32 on) and the compiler's working set leave room for 6, 4 resp. 3 waves
+// per SIMD (80, 128 resp. 168 VGPRs; a seventh wave of the smallest kernel needs spills and
+// measured no faster).
 template <int D, int NVR>
-__global__ __launch_bounds__(BLOCK, (NVR == 1 ? 5 : NVR == 2 ? 4 : 3)) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
+__global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void forest_rank_kernel(DevModel m, const float *__restrict__ X,
                                                             int64_t n_rows, float *scores,
                                                             int32_t *labels, int32_t *leaf_out)
 {
