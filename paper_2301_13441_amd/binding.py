@@ -61,7 +61,7 @@ EXPORTS = ["forest_load", "forest_free", "forest_info", "forest_out_bytes", "for
            "forest_predict", "forest_predict_static", "forest_predict_leaves", "forest_strerror"]
 # include/forest_testing.h: host-only views into the model compiler, for its tests
 TESTING_EXPORTS = ["forest_pack", "forest_pack_view", "forest_pack_free", "forest_rank_code",
-                   "forest_probe_compare_rate"]
+                   "forest_staged_position", "forest_probe_compare_rate"]
 
 
 def lib_path() -> str:
@@ -102,6 +102,8 @@ def load_library():
     lib.forest_pack_free.argtypes = [_p]
     lib.forest_rank_code.restype = ctypes.c_int
     lib.forest_rank_code.argtypes = [_i32, ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_uint16)]
+    lib.forest_staged_position.restype = ctypes.c_int
+    lib.forest_staged_position.argtypes = [_i32, _i32, ctypes.POINTER(_i32)]
     lib.forest_strerror.restype = ctypes.c_char_p
     lib.forest_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -236,6 +238,15 @@ def forest_rank_code(q: int) -> tuple[int, int, int]:
     if n < 0:
         raise ForestError(n, _strerror(n))
     return n, code.value, entry.value
+
+
+def forest_staged_position(depth: int, pos: int) -> int:
+    """Level-order ordinal of the node at bit position `pos` of a depth-4..6 full tree, -1 for none."""
+    node = ctypes.c_int32()
+    rc = load_library().forest_staged_position(int(depth), int(pos), ctypes.byref(node))
+    if rc != 0:
+        raise ForestError(rc, _strerror(rc))
+    return node.value
 
 
 def forest_probe_compare_rate(iterations: int, device_word, stream=None) -> int:

@@ -40,6 +40,14 @@ int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry)
     return RANK_CODES;
 }
 
+int forest_staged_position(int32_t depth, int32_t pos, int32_t *node)
+{
+    if (!node || depth < STAGED_MIN_DEPTH || depth > STAGED_MAX_DEPTH || pos < 0 || pos >= (1 << depth))
+        return FOREST_EINVAL;
+    *node = staged_position_node(depth, pos);
+    return FOREST_OK;
+}
+
 int forest_pack_view(const forest_packed *p, forest_packed_view *v)
 {
     if (!p || !v) return FOREST_EINVAL;

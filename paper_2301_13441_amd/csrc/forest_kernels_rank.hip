@@ -28,6 +28,7 @@ namespace forest_impl {
 namespace {
 
 enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
+constexpr int WALK_TABLE_BYTES = 384;  // 128 x 2 + 128 bytes at the start of the LDS
 
 // ---------------------------------------------------------------------------------------
 // Bit collection on the matrix core with operands placed by hand.
@@ -219,8 +220,10 @@ __device__ __forceinline__ WideEntries<GW> load_wide(ProgPtr p)
 // requests for the next tree's entries stay in front of the statement they are to overlap.
 template <int D, int NVR, int MODE>
 __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&x)[NVR], Accumulator<2> &accu, int wave,
-                                                int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out)
+                                                int lane, int64_t row0, int64_t n_rows, int32_t *leaf_out,
+                                                const uint8_t *walk_tables)
 {
+    constexpr bool STAGED = D >= STAGED_MIN_DEPTH && D <= STAGED_MAX_DEPTH;
     constexpr int R = 2;
     constexpr int N_ENT = (1 << D) < 8 ? 8 : (1 << D);
     constexpr int NW = N_ENT < 32 ? 1 : N_ENT / 32;
@@ -237,17 +240,45 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     WideEntries<GW> cur = load_wide<GW>(p);
     v8i d = bits.first(load_group(p + (GW >= 2 ? 8 : 0)), x);
 
-    // evaluates and walks the next tree of the stream: pos[r] = heap position row r ends on
-    auto walk_tree = [&](uint32_t (&pos)[R]) {
-        uint32_t sel[R];
+    // The walk's tables, read at LDS addresses the instruction can hold: the tables are the first
+    // thing in the kernel's LDS (address 0: the kernel has no static LDS, init_rank_kernels checks).
+    auto table16 = [](uint32_t byte_index) -> uint32_t {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t *>(static_cast<uintptr_t>(byte_index));
+#else
+        return byte_index;
+#endif
+    };
+    auto table8 = [](uint32_t index) -> uint32_t {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return *reinterpret_cast<const __attribute__((address_space(3))) uint8_t *>(static_cast<uintptr_t>(256u + index));
+#else
+        return index;
+#endif
+    };
+    (void)walk_tables;
+    // Whether the first table is read while the tree's second word is evaluated (two more registers
+    // live across that statement, which the 128-register kernel does not have).
+    constexpr bool EARLY = NVR < 4 && NW == 2;
+
+    // evaluates and walks the next tree of the stream: leaf4[r] = 4 x the ordinal of the leaf row r
+    // ends on (heap walks: 4 x the heap position, 2^D + ordinal)
+    auto walk_tree = [&](uint32_t (&leaf4)[R]) {
+        uint32_t pos[R], sel[R], word0[R], first[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u;
+        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, word0[r] = 0u, first[r] = 0u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             // Scalar loads return in any order, so the only wait there is waits for all of them: the
             // entries of this word are waited for (they were requested a statement ago) BEFORE the
             // next word's are requested, which then have the whole statement to arrive.
             wait_for(cur);
+            if constexpr (STAGED && EARLY) {
+                if (w == 1) {  // behind the wait, so that this read is not waited for before the statement
+#pragma unroll
+                    for (int r = 0; r < R; ++r) first[r] = table16(word0[r] & 0xfeu);
+                }
+            }
             p += NB;
             const WideEntries<GW> nxt = load_wide<GW>(p);
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -256,24 +287,61 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             v2f lo, hi;
             bits.template word<GW>(d, cur.g, x, lo, hi);
             cur = nxt;
+            uint32_t word[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                uint32_t word;
-                if (GW == 4) word = __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u);
-                else if (GW == 2) word = __float_as_uint(lo[r]);  // the bits above the 16 are never indexed
-                else word = __float_as_uint(lo[r]) >> 8;
-                heap_walk_word<D>(w, word, pos[r], sel[r]);
+                if (GW == 4) word[r] = __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u);
+                else if (GW == 2) word[r] = __float_as_uint(lo[r]);  // the bits above the 16 are never indexed
+                else word[r] = __float_as_uint(lo[r]) >> 8;
             }
-            // a word is walked before the next one is evaluated: its halves are not copied aside
-            if (D >= 7) asm volatile("" : "+v"(pos[0]), "+v"(pos[1]), "+v"(sel[0]), "+v"(sel[1]));
+            if constexpr (STAGED) {
+                // Three levels at a time from two tables in LDS (forest_model.hpp has the bit
+                // layout).  Bits 1..7 of the tree's first word are the outcomes of levels 0..2 and
+                // index, times two, the table of 16-bit records {where the field of the level-3
+                // subtree they lead to begins, 4 x the ordinal of that subtree's first leaf}; the
+                // field's bits index the table of 4 x the leaf's ordinal inside the subtree.  Both
+                // tables span at most 64 banks once: lanes never collide.  The reads of the two
+                // rows go out together.
+                constexpr uint32_t FIELD = (1u << (D - 3)) - 1u;
+                if (w == 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) word0[r] = word[r];
+                }
+                if (w == NW - 1) {
+                    if (!EARLY) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) first[r] = table16(word0[r] & 0xfeu);
+                    }
+                    uint32_t inner[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        uint32_t field;  // the shifts read the low 6 (5) bits of their count only
+                        if (NW == 2) field = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (first[r] & 63u));
+                        else field = word[r] >> (first[r] & 31u);
+                        inner[r] = table8(field & ((1u << FIELD) - 1u));
+                    }
+#pragma unroll
+                    for (int r = 0; r < R; ++r) leaf4[r] = (first[r] >> 8) + inner[r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    heap_walk_word<D>(w, word[r], pos[r], sel[r]);
+                    if (w == NW - 1) leaf4[r] = pos[r] << 2;
+                }
+            }
+            // a word is dealt with before the next one is evaluated: its halves are not copied aside
+            if constexpr (STAGED) asm volatile("" : "+v"(word0[0]), "+v"(word0[1]));
+            else if (D >= 7) asm volatile("" : "+v"(pos[0]), "+v"(pos[1]), "+v"(sel[0]), "+v"(sel[1]));
             else asm volatile("" : "+v"(pos[0]), "+v"(pos[1]));
         }
     };
+    constexpr int LEAF0 = STAGED ? 0 : (1 << D);  // what leaf4 / 4 counts from
 
     if constexpr (MODE == MODE_SCALAR) {
-        // wave-uniform base of the current tree's leaf values, shifted so that the heap position
-        // the walk ends on indexes it directly; carried from tree to tree in scalar registers
-        LeafBytes lv = (LeafBytes)(m.leaf_value + ((t_begin << D) - (1 << D)));
+        // wave-uniform base of the current tree's leaf values, shifted so that what the walk ends
+        // on indexes it directly; carried from tree to tree in scalar registers
+        LeafBytes lv = (LeafBytes)(m.leaf_value + ((t_begin << D) - LEAF0));
         int t = t_begin, column = 0;
         int column_end = uniform(static_cast<int>(m.col_trees[0]));
         while (t < t_end) {
@@ -285,12 +353,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             for (int r = 0; r < R; ++r) pending[r] = 0.0f;
             for (; t < run_end; ++t, lv += sizeof(float) << D) {
                 asm volatile("" : "+s"(lv));
-                uint32_t pos[R];
-                walk_tree(pos);
+                uint32_t leaf4[R];
+                walk_tree(leaf4);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     accu.add_value(r, pending[r]);
-                    pending[r] = *(LeafFloat)(lv + (pos[r] << 2));
+                    pending[r] = *(LeafFloat)(lv + leaf4[r]);
                 }
             }
 #pragma unroll
@@ -300,11 +368,11 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
         MetaPtr meta = (MetaPtr)m.tree;
         for (int t = t_begin; t < t_end; ++t) {
             const int caller_tree = meta[t].caller_tree;
-            uint32_t pos[R];
-            walk_tree(pos);
+            uint32_t leaf4[R];
+            walk_tree(leaf4);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const int leaf = (t << D) + static_cast<int>(pos[r] - (1u << D));
+                const int leaf = (t << D) + static_cast<int>(leaf4[r] >> 2) - LEAF0;
                 if (MODE == MODE_LEAVES) {
                     const int64_t row = row0 + r * TILE + lane;
                     if (row < n_rows) leaf_out[row * T + caller_tree] = m.leaf_node[leaf];
@@ -327,12 +395,24 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void fore
 {
     constexpr int R = 2;
     extern __shared__ __align__(16) char smem[];
-    uint32_t *rk = reinterpret_cast<uint32_t *>(smem);  // [32 * NVR][64] packed ranks, then reused as:
-    double *acc = reinterpret_cast<double *>(smem);     // [WAVES][K][128] partial sums
+    // The walk's tables come first, at addresses the compiler knows: 128 16-bit records, then 128
+    // bytes (rank_trees_hand; only the depths with the field layout read them).
+    uint8_t *walk_tables = reinterpret_cast<uint8_t *>(smem);
+    uint32_t *rk = reinterpret_cast<uint32_t *>(smem + WALK_TABLE_BYTES);  // [32 * NVR][64] packed ranks, then reused as:
+    double *acc = reinterpret_cast<double *>(smem + WALK_TABLE_BYTES);     // [WAVES][K][128] partial sums
 
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
+
+    if (D >= STAGED_MIN_DEPTH && D <= STAGED_MAX_DEPTH && threadIdx.x < 128) {
+        constexpr int LOWER = D - 3 > 0 ? D - 3 : 0;   // levels below the top three
+        constexpr int FIELD = (1 << LOWER) - 1;        // bits of a lower subtree's field
+        const int t = threadIdx.x, path = staged_path(t);
+        reinterpret_cast<uint16_t *>(walk_tables)[t] =
+            static_cast<uint16_t>((STAGED_FIELDS_AT + FIELD * path) | ((path * (4 << LOWER)) << 8));
+        walk_tables[256 + t] = static_cast<uint8_t>((path >> (3 - LOWER)) * 4);
+    }
 
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
         load_rank_tile(rk, m, BLOCK);
@@ -352,11 +432,11 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void fore
     Accumulator<R> accu;
     accu.init(acc, wave, lane, m);
     if (leaf_out != nullptr) {  // wave-uniform: debug output instead of scores
-        rank_trees_hand<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out);
+        rank_trees_hand<D, NVR, MODE_LEAVES>(m, x, accu, wave, lane, row0, n_rows, leaf_out, walk_tables);
         return;
     }
-    if (m.leaf_width == 1) rank_trees_hand<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
-    else rank_trees_hand<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr);
+    if (m.leaf_width == 1) rank_trees_hand<D, NVR, MODE_SCALAR>(m, x, accu, wave, lane, row0, n_rows, nullptr, walk_tables);
+    else rank_trees_hand<D, NVR, MODE_VECTOR>(m, x, accu, wave, lane, row0, n_rows, nullptr, walk_tables);
     accu.flush();
     __syncthreads();
     const int li = threadIdx.x;
@@ -367,7 +447,7 @@ size_t rank_lds_bytes(const DevModel &m, int nvr)
 {
     const size_t a = sizeof(double) * WAVES * m.n_outputs * RROWS;
     const size_t b = sizeof(uint32_t) * 32 * nvr * TILE;
-    return a > b ? a : b;
+    return WALK_TABLE_BYTES + (a > b ? a : b);
 }
 
 template <int NVR>
@@ -400,6 +480,12 @@ hipError_t init_rank_kernels(size_t lds_limit)
                                                hipFuncAttributeMaxDynamicSharedMemorySize,
                                                static_cast<int>(lds_limit));
             if (e != hipSuccess) return e;
+            // the walk's tables are read at literal LDS addresses from 0 on: the kernel's dynamic
+            // LDS must begin there, i.e. the kernel must have no static LDS
+            hipFuncAttributes attr;
+            e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(pick_rank(nvr, d)));
+            if (e != hipSuccess) return e;
+            if (attr.sharedSizeBytes != 0) return hipErrorInvalidConfiguration;
         }
     return hipSuccess;
 }

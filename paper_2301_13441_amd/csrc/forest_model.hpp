@@ -59,6 +59,47 @@ inline uint16_t rank_entry_bits(int q)
     const uint16_t c = rank_code_bits(q);
     return static_cast<uint16_t>(((c ^ 0x8000u) & 0x8000u) | ((c & 0x7fffu) + (2u << 10)));
 }
+// Full trees of depth 4, 5 or 6 on the rank path: where in a tree's outcome bit string each
+// internal node sits.  The walk of these trees takes three levels at a time from a table (the 7
+// outcomes of a complete 3-level subtree index it, the path through the subtree comes out), so the
+// bits of such a subtree must be adjacent: position 0 is empty, positions 1..7 hold levels 0..2
+// (position = heap index), then the 8 subtrees rooted at level 3 follow from position 8 on, one
+// field of 2^(depth - 3) - 1 bits each (local heap order: root, its children, their children), in
+// the order of their roots.  Returns the node's level-order ordinal (heap index - 1), or -1 for a
+// position no node has.  (Other depths keep the heap order: position = heap index.)
+constexpr int STAGED_MIN_DEPTH = 4, STAGED_MAX_DEPTH = 6;
+constexpr int STAGED_FIELDS_AT = 8;  // first position of the lower subtrees' fields
+
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int staged_position_node(int depth, int pos)
+{
+    const int lower = depth - 3;                 // levels below the top three
+    const int field = (1 << lower) - 1;          // nodes of a lower subtree
+    if (pos < 1) return -1;
+    if (pos < STAGED_FIELDS_AT) return pos - 1;  // heap index pos
+    const int q = pos - STAGED_FIELDS_AT;
+    if (q >= 8 * field) return -1;
+    const int subtree = q / field, local = q % field + 1;  // local heap index 1 .. field
+    int level = 0;
+    while ((2 << level) <= local) ++level;       // level of `local` inside its subtree
+    const int heap = ((8 + subtree) << level) + (local - (1 << level));
+    return heap - 1;
+}
+
+// The path (0..7, first decision in bit 2) through a complete 3-level subtree whose 7 outcome
+// bits are t (bit l - 1 = outcome of the node with local heap index l; 1 = right).
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline int staged_path(int t)
+{
+    int p = 1;
+    for (int l = 0; l < 3; ++l) p = p + p + ((t >> (p - 1)) & 1);
+    return p - 8;
+}
+
 constexpr int RANK_MAX_REGS = 128;
 constexpr int RANK_BUCKETS_PER_THRESHOLD = 1;  // resolution of the per-feature bucket tables
 constexpr int RANK_MAX_BUCKETS = 1 << 20;      // per feature

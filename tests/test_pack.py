@@ -503,3 +503,40 @@ def test_compare_rate_probe_refuses_bad_arguments_before_any_launch():
     assert lib.forest_probe_compare_rate(10, None, None, ctypes.byref(n)) < 0
     assert lib.forest_probe_compare_rate(10, None, ctypes.c_void_p(16), None) < 0
     assert n.value == -1
+
+
+def test_staged_positions_of_full_trees_and_the_table_walk():
+    """Depths 4..6 on the rank path keep a tree's outcome bits in fields a table walk reads three
+    levels at a time (Section 3.1.2: all internal nodes are evaluated; the leaf reached is the one
+    whose root path agrees with the outcomes).  The position map must be a bijection onto the
+    tree's nodes, and the walk over it -- simulated here exactly as the kernel takes it -- must end
+    on the leaf the heap walk ends on, for every depth and many outcome patterns."""
+    rng = np.random.default_rng(46)
+    for depth in (4, 5, 6):
+        n_pos, n_int = 1 << depth, (1 << depth) - 1
+        node_at = [binding.forest_staged_position(depth, pos) for pos in range(n_pos)]
+        assert sorted(v for v in node_at if v >= 0) == list(range(n_int))
+        assert node_at[0] == -1 and [node_at[p] for p in range(1, 8)] == list(range(7))
+        lower = depth - 3
+        field = (1 << lower) - 1
+
+        def path3(t):       # path through a complete 3-level subtree, local heap order
+            p = 1
+            for _ in range(3):
+                p = 2 * p + ((t >> (p - 1)) & 1)
+            return p - 8
+
+        for trial in range(300):
+            outcome = rng.integers(0, 2, n_int)            # by level-order ordinal; 1 = right
+            h = 1
+            for _ in range(depth):
+                h = 2 * h + int(outcome[h - 1])
+            want = h - n_pos                                # in-order leaf ordinal
+            bits = sum(int(outcome[v]) << pos for pos, v in enumerate(node_at) if v >= 0)
+            top = path3((bits >> 1) & 0x7f)
+            start = 8 + field * top
+            inner = path3((bits >> start) & ((1 << field) - 1)) >> (3 - lower)
+            assert top * (1 << lower) + inner == want
+    for depth, pos in ((3, 0), (7, 0), (4, 16), (6, -1)):
+        with pytest.raises(binding.ForestError):
+            binding.forest_staged_position(depth, pos)
