@@ -11,7 +11,9 @@
 // register index), so step (1), the feature selection matmul(X, W1), costs no vector
 // instruction.  The outcomes of 8 nodes are turned into 8 bits per row by the matrix core
 // (HandCollector: one MFMA per 8 nodes, first entry in bit 7).  Four such bytes make one 32-bit
-// heap-ordered outcome word, the same words the other kernels use, and the walk, leaf gather and
+// outcome word.  Trees of depth 4..6 keep their bits in subtree fields and are walked three levels
+// at a time through two small tables in LDS (the bit form of matmul(., W3) + argmax, Fig. 2 step
+// (3)); the other depths keep heap order and the bit walk of the other kernels.  Leaf gather and
 // reduction are shared.
 //
 // Prologue: every workgroup computes the ranks of its 128 rows from per-feature bucket tables
@@ -258,7 +260,8 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     };
     (void)walk_tables;
     // Whether the first table is read while the tree's second word is evaluated (two more registers
-    // live across that statement, which the 128-register kernel does not have).
+    // live across that statement; the 128-register kernel has none to spare and measured the same
+    // either way).
     constexpr bool EARLY = NVR < 4 && NW == 2;
 
     // evaluates and walks the next tree of the stream: leaf4[r] = 4 x the ordinal of the leaf row r
@@ -309,17 +312,34 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                 }
                 if (w == NW - 1) {
                     if (!EARLY) {
+                        uint32_t top[R];
 #pragma unroll
-                        for (int r = 0; r < R; ++r) first[r] = table16(word0[r] & 0xfeu);
+                        for (int r = 0; r < R; ++r) top[r] = word0[r] & 0xfeu;
+#if defined(__HIP_DEVICE_COMPILE__)
+                        __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                        for (int r = 0; r < R; ++r) first[r] = table16(top[r]);
+#if defined(__HIP_DEVICE_COMPILE__)
+                        __builtin_amdgcn_sched_barrier(0);
+#endif
                     }
-                    uint32_t inner[R];
+                    uint32_t inner[R], field[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        uint32_t field;  // the shifts read the low 6 (5) bits of their count only
-                        if (NW == 2) field = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (first[r] & 63u));
-                        else field = word[r] >> (first[r] & 31u);
-                        inner[r] = table8(field & ((1u << FIELD) - 1u));
+                        // the shifts read the low 6 (5) bits of their count only
+                        if (NW == 2) field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (first[r] & 63u));
+                        else field[r] = word[r] >> (first[r] & 31u);
+                        field[r] &= (1u << FIELD) - 1u;
                     }
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_sched_barrier(0);  // both rows' reads go out before either is waited for
+#endif
+#pragma unroll
+                    for (int r = 0; r < R; ++r) inner[r] = table8(field[r]);
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
                     for (int r = 0; r < R; ++r) leaf4[r] = (first[r] >> 8) + inner[r];
                 }
