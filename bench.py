@@ -10,7 +10,8 @@ what bounds it.  The rank kernels compare two rows per lane with one packed-f16 
 their peak is two comparisons per lane and clock; the fp32 kernels' peak is one.
 `cpu_baseline` is the CPU oracle timed on this machine's host cores over all rows of the
 configuration (one warm-up pass, median of three timed passes), and `parity` compares every row
-of the timed output with it.
+of the timed output with it.  The configurations are set up first and timed back to back, so
+that none of the short ones starts on a GPU that has idled since the one before.
 """
 from __future__ import annotations
 
@@ -195,116 +196,131 @@ def compare_issue_rate() -> float:
     return n / (start.elapsed_time(stop) * 1e-3)
 
 
-def bench_forest(name: str, args) -> dict:
-    """All fields of one tree-ensemble configuration."""
-    import numpy as np
-    import torch
+class ForestRun:
+    """One tree-ensemble configuration, measured in three steps so that the GPU timing of several
+    configurations can run back to back: prepare (model and X to the device), time (W warm-up and
+    K timed forest_predict calls), finish (oracle baseline, parity, the result fields)."""
 
-    import paper_2301_13441_amd as pk
-    import workloads as wl
+    def __init__(self, name: str, args):
+        import numpy as np
+        import torch
 
-    w = wl.make_workload(name, n_rows=args.rows)
-    n_rows, F = w.n_rows, w.forest.n_features
-    f = pk.forest_load(w.forest)
-    info = f.info
+        import paper_2301_13441_amd as pk
+        import workloads as wl
 
-    # X: generated on the host in chunks, copied to HBM before the timed region; the host copy is
-    # kept for the oracle
-    want_host = not args.no_cpu_baseline
-    xd = torch.empty((n_rows, F), dtype=torch.float32, device="cuda")
-    xh = np.empty((n_rows, F), dtype=np.float32) if want_host else None
-    pos = 0
-    for chunk in w.x_chunks(n_rows):
-        xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
-        if want_host:
-            xh[pos:pos + len(chunk)] = chunk
-        pos += len(chunk)
-    out = torch.empty(max(f.out_bytes(n_rows), 4), dtype=torch.uint8, device="cuda")
-    torch.cuda.synchronize()
+        self.name, self.args = name, args
+        self.w = wl.make_workload(name, n_rows=args.rows)
+        self.n_rows, self.F = self.w.n_rows, self.w.forest.n_features
+        self.f = pk.forest_load(self.w.forest)
+        self.info = self.f.info
+        # X: generated on the host in chunks, copied to HBM before the timed region; the host copy
+        # is kept for the oracle
+        self.want_host = not args.no_cpu_baseline
+        self.xd = torch.empty((self.n_rows, self.F), dtype=torch.float32, device="cuda")
+        self.xh = np.empty((self.n_rows, self.F), dtype=np.float32) if self.want_host else None
+        pos = 0
+        for chunk in self.w.x_chunks(self.n_rows):
+            self.xd[pos:pos + len(chunk)].copy_(torch.from_numpy(chunk))
+            if self.want_host:
+                self.xh[pos:pos + len(chunk)] = chunk
+            pos += len(chunk)
+        self.out = torch.empty(max(self.f.out_bytes(self.n_rows), 4), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
 
-    stream = torch.cuda.current_stream()   # forest_predict is enqueued on this stream
-    for _ in range(args.warmup):
-        f.predict(xd, out=out)
-    torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        starts[i].record(stream)
-        f.predict(xd, out=out)
-        stops[i].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kernel_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
-    kernel_s = float(np.mean(kernel_ms)) * 1e-3
-    scores, labels = f.predict(xd, out=out)
-    torch.cuda.synchronize()
+    def time(self):
+        import torch
+        args = self.args
+        stream = torch.cuda.current_stream()   # forest_predict is enqueued on this stream
+        for _ in range(args.warmup):
+            self.f.predict(self.xd, out=self.out)
+        torch.cuda.synchronize()
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            starts[i].record(stream)
+            self.f.predict(self.xd, out=self.out)
+            stops[i].record(stream)
+        torch.cuda.synchronize()
+        self.wall = time.perf_counter() - t0
+        self.kernel_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
 
-    compares = float(info["n_internal"]) * n_rows          # one per (row, internal node)
-    achieved = compares / kernel_s
-    algo_bytes = n_rows * (4.0 * F) + f.out_bytes(n_rows)
-    packed = info["kernel_path"] in (2, 3, 4)  # rank kernels: two comparisons per packed-f16 lane-op
-    peak = ALU_PEAK_LANE_OPS * (2 if packed else 1)
-    traffic = MEASURED_TRAFFIC.get(name) if args.rows is None else None
-    roofline = {
-        "bound": "alu",
-        "kernel": "forest_predict (fused compare + leaf resolution + reduction)",
-        "achieved": achieved / 1e12,
-        "peak": peak / 1e12,
-        "unit": "Tcompare/s",
-        "frac": achieved / peak,
-        "peak_basis": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz x "
-                      + ("2 comparisons per packed-f16 lane-op" if packed else "1 float32 comparison per lane-op"),
-        # against one float32 compare per (row, node) and lane-op, the floor a plain fp32 kernel has
-        "frac_vs_fp32_compare_peak": achieved / ALU_PEAK_LANE_OPS,
-        "kernel_ms_avg": kernel_s * 1e3,
-        "kernel_ms_min": float(np.min(kernel_ms)),
-        "algorithmic_bytes": algo_bytes,
-        "hbm_GBps": algo_bytes / kernel_s / 1e9,
-        "hbm_frac": algo_bytes / kernel_s / HBM_PEAK,
-        "traffic": traffic["bytes"] if traffic else None,
-        "traffic_source": ({k: traffic[k] for k in ("profile", "commit")} if traffic else None),
-    }
+    def finish(self) -> dict:
+        import numpy as np
+        import torch
+        args, name, info, n_rows, F, f = self.args, self.name, self.info, self.n_rows, self.F, self.f
+        kernel_ms, wall = self.kernel_ms, self.wall
+        kernel_s = float(np.mean(kernel_ms)) * 1e-3
+        scores, labels = f.predict(self.xd, out=self.out)
+        torch.cuda.synchronize()
 
-    cpu_baseline = None
-    parity = None
-    if want_host:
-        threads = _host_threads()
-        dt, ref = _time_oracle(w.forest, xh, threads)
-        cpu_baseline = {"value": n_rows / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
-                        "host_cpu_count": os.cpu_count(),
-                        "sample": f"all {n_rows} rows of {name}: one warm-up pass, median of 3 timed passes, "
-                                  f"{threads} threads over contiguous row blocks"}
-        parity = {"rows_checked": n_rows}
-        if scores is not None:
-            got = scores.cpu().numpy()
-            err = np.abs(got - ref.scores)
-            parity["scores_within_tol"] = bool((err <= 1e-6 + 1e-5 * np.abs(ref.scores)).all())
-            parity["max_abs_err"] = float(err.max())
-        if labels is not None:
-            parity["labels_equal"] = bool((labels.cpu().numpy() == ref.labels).all())
-        if name == "c1":   # the small configuration also on one thread
-            dt1, _ = _time_oracle(w.forest, xh, 1)
-            cpu_baseline["one_thread_value"] = n_rows / dt1
+        compares = float(info["n_internal"]) * n_rows          # one per (row, internal node)
+        achieved = compares / kernel_s
+        algo_bytes = n_rows * (4.0 * F) + f.out_bytes(n_rows)
+        packed = info["kernel_path"] in (2, 3, 4)  # rank kernels: two comparisons per packed-f16 lane-op
+        peak = ALU_PEAK_LANE_OPS * (2 if packed else 1)
+        traffic = MEASURED_TRAFFIC.get(name) if args.rows is None else None
+        roofline = {
+            "bound": "alu",
+            "kernel": "forest_predict (fused compare + leaf resolution + reduction)",
+            "achieved": achieved / 1e12,
+            "peak": peak / 1e12,
+            "unit": "Tcompare/s",
+            "frac": achieved / peak,
+            "peak_basis": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz x "
+                          + ("2 comparisons per packed-f16 lane-op" if packed else "1 float32 comparison per lane-op"),
+            # against one float32 compare per (row, node) and lane-op, the floor a plain fp32 kernel has
+            "frac_vs_fp32_compare_peak": achieved / ALU_PEAK_LANE_OPS,
+            "kernel_ms_avg": kernel_s * 1e3,
+            "kernel_ms_min": float(np.min(kernel_ms)),
+            "kernel_ms_median": float(np.median(kernel_ms)),
+            "algorithmic_bytes": algo_bytes,
+            "hbm_GBps": algo_bytes / kernel_s / 1e9,
+            "hbm_frac": algo_bytes / kernel_s / HBM_PEAK,
+            "traffic": traffic["bytes"] if traffic else None,
+            "traffic_source": ({k: traffic[k] for k in ("profile", "commit")} if traffic else None),
+        }
 
-    res = {
-        "value": n_rows * args.steps / wall,
-        "ms_per_step": wall / args.steps * 1e3,
-        "dtype": ("f16 threshold ranks (exact rewrite of the f32 compare), f64 accumulate"
-                  if packed else "f32 compare, f64 accumulate"),
-        "config": {"workload": name, "n_rows": n_rows, "n_features": F,
-                   "n_trees": info["n_trees"], "max_depth": info["max_depth"],
-                   "n_internal_nodes": info["n_internal"], "n_outputs": info["n_outputs"],
-                   "kernel_kind": info["kernel_kind"], "kernel_path": info["kernel_path"],
-                   "packed_bytes": info["packed_bytes"]},
-        "roofline": roofline,
-        "cpu_baseline": cpu_baseline,
-        "parity": parity,
-    }
-    f.close()
-    del xd, out, scores, labels
-    torch.cuda.empty_cache()
-    return res
+        cpu_baseline = None
+        parity = None
+        if self.want_host:
+            threads = _host_threads()
+            dt, ref = _time_oracle(self.w.forest, self.xh, threads)
+            cpu_baseline = {"value": n_rows / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
+                            "host_cpu_count": os.cpu_count(),
+                            "sample": f"all {n_rows} rows of {name}: one warm-up pass, median of 3 timed passes, "
+                                      f"{threads} threads over contiguous row blocks"}
+            parity = {"rows_checked": n_rows}
+            if scores is not None:
+                got = scores.cpu().numpy()
+                err = np.abs(got - ref.scores)
+                parity["scores_within_tol"] = bool((err <= 1e-6 + 1e-5 * np.abs(ref.scores)).all())
+                parity["max_abs_err"] = float(err.max())
+            if labels is not None:
+                parity["labels_equal"] = bool((labels.cpu().numpy() == ref.labels).all())
+            if name == "c1":   # the small configuration also on one thread
+                dt1, _ = _time_oracle(self.w.forest, self.xh, 1)
+                cpu_baseline["one_thread_value"] = n_rows / dt1
+
+        res = {
+            "value": n_rows * args.steps / wall,
+            "ms_per_step": wall / args.steps * 1e3,
+            "dtype": ("f16 threshold ranks (exact rewrite of the f32 compare), f64 accumulate"
+                      if packed else "f32 compare, f64 accumulate"),
+            "config": {"workload": name, "n_rows": n_rows, "n_features": F,
+                       "n_trees": info["n_trees"], "max_depth": info["max_depth"],
+                       "n_internal_nodes": info["n_internal"], "n_outputs": info["n_outputs"],
+                       "kernel_kind": info["kernel_kind"], "kernel_path": info["kernel_path"],
+                       "packed_bytes": info["packed_bytes"]},
+            "roofline": roofline,
+            "cpu_baseline": cpu_baseline,
+            "parity": parity,
+        }
+        f.close()
+        self.xd = self.out = self.xh = None
+        del scores, labels
+        torch.cuda.empty_cache()
+        return res
 
 
 def main() -> int:
@@ -334,10 +350,21 @@ def main() -> int:
         return bench_linear(args)
 
     names = [args.workload] if args.workload else ["c5", "c4", "c3", "c2", "c1"]
-    results = {}
+    # Every configuration is set up first (model and X on the device), then the configurations are
+    # timed one right after the other -- W warm-up and K timed calls each, nothing but a
+    # synchronisation between them, so the clocks the first one has raised stay up for the short
+    # ones (after an idle gap the first 25 ms or so of kernel time run up to 15 % slower) -- and the
+    # CPU oracle is timed and compared afterwards.
+    runs = []
     for name in names:
-        print(f"bench: {name} ...", file=sys.stderr, flush=True)
-        results[name] = bench_forest(name, args)
+        print(f"bench: setting up {name} ...", file=sys.stderr, flush=True)
+        runs.append(ForestRun(name, args))
+    for r in runs:
+        r.time()
+    results = {}
+    for r in runs:
+        print(f"bench: oracle and parity of {r.name} ...", file=sys.stderr, flush=True)
+        results[r.name] = r.finish()
     head = results[names[0]]
     line = {
         "metric": "rows/sec scored (fp32 X), 1 MI355X",

@@ -244,18 +244,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
 
     // The walk's tables, read at LDS addresses the instruction can hold: the tables are the first
     // thing in the kernel's LDS (address 0: the kernel has no static LDS, init_rank_kernels checks).
-    auto table16 = [](uint32_t byte_index) -> uint32_t {
+    // byte `offset + index` of the tables
+    auto table = [](uint32_t index, uint32_t offset) -> uint32_t {
 #if defined(__HIP_DEVICE_COMPILE__)
-        return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t *>(static_cast<uintptr_t>(byte_index));
+        return *reinterpret_cast<const __attribute__((address_space(3))) uint8_t *>(static_cast<uintptr_t>(offset + index));
 #else
-        return byte_index;
-#endif
-    };
-    auto table8 = [](uint32_t index) -> uint32_t {
-#if defined(__HIP_DEVICE_COMPILE__)
-        return *reinterpret_cast<const __attribute__((address_space(3))) uint8_t *>(static_cast<uintptr_t>(256u + index));
-#else
-        return index;
+        return index + offset;
 #endif
     };
     (void)walk_tables;
@@ -267,9 +261,9 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     // evaluates and walks the next tree of the stream: leaf4[r] = 4 x the ordinal of the leaf row r
     // ends on (heap walks: 4 x the heap position, 2^D + ordinal)
     auto walk_tree = [&](uint32_t (&leaf4)[R]) {
-        uint32_t pos[R], sel[R], word0[R], first[R];
+        uint32_t pos[R], sel[R], word0[R], start[R], base4[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, word0[r] = 0u, first[r] = 0u;
+        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, word0[r] = 0u, start[r] = 0u, base4[r] = 0u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             // Scalar loads return in any order, so the only wait there is waits for all of them: the
@@ -277,9 +271,13 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             // next word's are requested, which then have the whole statement to arrive.
             wait_for(cur);
             if constexpr (STAGED && EARLY) {
-                if (w == 1) {  // behind the wait, so that this read is not waited for before the statement
+                if (w == 1) {  // behind the wait, so that these reads are not waited for before the statement
 #pragma unroll
-                    for (int r = 0; r < R; ++r) first[r] = table16(word0[r] & 0xfeu);
+                    for (int r = 0; r < R; ++r) {
+                        const uint32_t top = word0[r] & 0xfeu;
+                        start[r] = table(top, 0u);
+                        base4[r] = table(top, 1u);
+                    }
                 }
             }
             p += NB;
@@ -300,11 +298,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             if constexpr (STAGED) {
                 // Three levels at a time from two tables in LDS (forest_model.hpp has the bit
                 // layout).  Bits 1..7 of the tree's first word are the outcomes of levels 0..2 and
-                // index, times two, the table of 16-bit records {where the field of the level-3
-                // subtree they lead to begins, 4 x the ordinal of that subtree's first leaf}; the
-                // field's bits index the table of 4 x the leaf's ordinal inside the subtree.  Both
-                // tables span at most 64 banks once: lanes never collide.  The reads of the two
-                // rows go out together.
+                // index, times two, the table of two-byte records {where the field of the level-3
+                // subtree they lead to begins, 4 x the ordinal of that subtree's first leaf}, read
+                // byte by byte (an LDS read costs the vector ALU nothing, taking a 16-bit record
+                // apart does); the field's bits index the table of 4 x the leaf's ordinal inside
+                // the subtree.  Both tables span at most 64 banks once: lanes never collide.  The
+                // reads of the two rows go out together.
                 constexpr uint32_t FIELD = (1u << (D - 3)) - 1u;
                 if (w == 0) {
 #pragma unroll
@@ -319,7 +318,10 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                         __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                        for (int r = 0; r < R; ++r) first[r] = table16(top[r]);
+                        for (int r = 0; r < R; ++r) {
+                            start[r] = table(top[r], 0u);
+                            base4[r] = table(top[r], 1u);
+                        }
 #if defined(__HIP_DEVICE_COMPILE__)
                         __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -328,20 +330,23 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
                         // the shifts read the low 6 (5) bits of their count only
-                        if (NW == 2) field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (first[r] & 63u));
-                        else field[r] = word[r] >> (first[r] & 31u);
+                        if (NW == 2) field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (start[r] & 63u));
+                        else field[r] = word[r] >> (start[r] & 31u);
                         field[r] &= (1u << FIELD) - 1u;
                     }
 #if defined(__HIP_DEVICE_COMPILE__)
                     __builtin_amdgcn_sched_barrier(0);  // both rows' reads go out before either is waited for
 #endif
 #pragma unroll
-                    for (int r = 0; r < R; ++r) inner[r] = table8(field[r]);
+                    for (int r = 0; r < R; ++r) inner[r] = table(field[r], 256u);
 #if defined(__HIP_DEVICE_COMPILE__)
                     __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                    for (int r = 0; r < R; ++r) leaf4[r] = (first[r] >> 8) + inner[r];
+                    for (int r = 0; r < R; ++r) leaf4[r] = base4[r] + inner[r];
+                    // one 32-bit sum per row, used as the offset of the gather (left to itself the
+                    // compiler adds the two bytes to the 64-bit base one after the other)
+                    asm volatile("" : "+v"(leaf4[0]), "+v"(leaf4[1]));
                 }
             } else {
 #pragma unroll
