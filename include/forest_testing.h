@@ -134,13 +134,14 @@ int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry);
 
 /*
  * Host-only view of where the rank kernels (kernel_path 2) keep the outcome bit of every internal
- * node of a full tree of depth 4, 5 or 6 (Section 3.1.2: every internal node is evaluated; this is
- * the order their outcomes are collected in): positions 0..6 hold levels 0..2, then one field per
- * subtree rooted at level 3 follows, so that a table indexed by the 7 (3, 1) outcomes of a complete
- * 3- (2-, 1-) level subtree gives the path through it.  Stores in *node the level-order ordinal
- * (heap index - 1) of the node at bit position `pos` of a tree's 2^depth positions, -1 for a
- * position no node has.  Returns FOREST_OK, or FOREST_EINVAL for a depth outside 4..6, a position
- * outside the tree's or a null pointer.
+ * node of a full tree of depth 4 to 8 (Section 3.1.2: every internal node is evaluated; this is
+ * the order their outcomes are collected in): positions 1..7 hold levels 0..2, then one field per
+ * subtree rooted at level 3 follows from position 8 on, so that a table indexed by the 7 (3, 1)
+ * outcomes of a complete 3- (2-, 1-) level subtree gives the path through it; at depth 7 and 8
+ * this covers levels 0..4 (positions below 32) and the deeper levels keep position = heap index.
+ * Stores in *node the level-order ordinal (heap index - 1) of the node at bit position `pos` of a
+ * tree's 2^depth positions, -1 for a position no node has.  Returns FOREST_OK, or FOREST_EINVAL for
+ * a depth outside 4..8, a position outside the tree's or a null pointer.
  */
 int forest_staged_position(int32_t depth, int32_t pos, int32_t *node);
 

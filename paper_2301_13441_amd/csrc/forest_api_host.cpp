@@ -42,7 +42,7 @@ int forest_rank_code(int32_t q, uint16_t *code, uint16_t *entry)
 
 int forest_staged_position(int32_t depth, int32_t pos, int32_t *node)
 {
-    if (!node || depth < STAGED_MIN_DEPTH || depth > STAGED_MAX_DEPTH || pos < 0 || pos >= (1 << depth))
+    if (!node || depth < STAGED_MIN_DEPTH || depth > STAGED_TOP_MAX_DEPTH || pos < 0 || pos >= (1 << depth))
         return FOREST_EINVAL;
     *node = staged_position_node(depth, pos);
     return FOREST_OK;

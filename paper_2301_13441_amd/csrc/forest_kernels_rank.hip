@@ -13,8 +13,8 @@
 // (HandCollector: one MFMA per 8 nodes, first entry in bit 7).  Four such bytes make one 32-bit
 // outcome word.  Trees of depth 4..6 keep their bits in subtree fields and are walked three levels
 // at a time through two small tables in LDS (the bit form of matmul(., W3) + argmax, Fig. 2 step
-// (3)); the other depths keep heap order and the bit walk of the other kernels.  Leaf gather and
-// reduction are shared.
+// (3)); depths 7 and 8 do so for their first five levels and go on with the bit walk of the other
+// kernels, which depths 1..3 use throughout.  Leaf gather and reduction are shared.
 //
 // Prologue: every workgroup computes the ranks of its 128 rows from per-feature bucket tables
 // (forest_rank_common.hpp).
@@ -329,10 +329,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                     uint32_t inner[R], field[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        // the shifts read the low 6 (5) bits of their count only
-                        if (NW == 2) field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (start[r] & 63u));
-                        else field[r] = word[r] >> (start[r] & 31u);
-                        field[r] &= (1u << FIELD) - 1u;
+                        // the shift and the extraction read the low 6 (5) bits of their count only
+                        if (NW == 2)
+                            field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(word[r]) << 32) | word0[r]) >> (start[r] & 63u)) &
+                                       ((1u << FIELD) - 1u);
+                        else
+                            field[r] = __builtin_amdgcn_ubfe(word[r], start[r], FIELD);
                     }
 #if defined(__HIP_DEVICE_COMPILE__)
                     __builtin_amdgcn_sched_barrier(0);  // both rows' reads go out before either is waited for
@@ -348,6 +350,35 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                     // compiler adds the two bytes to the 64-bit base one after the other)
                     asm volatile("" : "+v"(leaf4[0]), "+v"(leaf4[1]));
                 }
+            } else if (D > STAGED_MAX_DEPTH && w == 0) {
+                // Depths 7, 8: levels 0..4 (the first word) by the same tables, which give the heap
+                // position after five levels; the deeper levels take the bit walk from there.
+                uint32_t top[R], field[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) top[r] = word[r] & 0xfeu;
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    start[r] = table(top[r], 0u);
+                    base4[r] = table(top[r], 1u);
+                }
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                for (int r = 0; r < R; ++r) field[r] = __builtin_amdgcn_ubfe(word[r], start[r], 3u);  // reads 5 bits of start
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                for (int r = 0; r < R; ++r) pos[r] = table(field[r], 256u);
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                for (int r = 0; r < R; ++r) pos[r] += base4[r];
             } else {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
@@ -430,13 +461,17 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void fore
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
-    if (D >= STAGED_MIN_DEPTH && D <= STAGED_MAX_DEPTH && threadIdx.x < 128) {
-        constexpr int LOWER = D - 3 > 0 ? D - 3 : 0;   // levels below the top three
-        constexpr int FIELD = (1 << LOWER) - 1;        // bits of a lower subtree's field
+    if (D >= STAGED_MIN_DEPTH && threadIdx.x < 128) {
+        // Depths 4..6: the records hold 4 x leaf ordinals.  Depths 7, 8: the tables cover levels
+        // 0..4 and hold heap positions (32 + the path through five levels), where the bit walk of
+        // the deeper levels goes on.
+        constexpr bool WHOLE = D <= STAGED_MAX_DEPTH;
+        constexpr int LOWER = WHOLE ? (D - 3 > 0 ? D - 3 : 0) : 2;   // levels below the top three
+        constexpr int FIELD = (1 << LOWER) - 1;                     // bits of a lower subtree's field
         const int t = threadIdx.x, path = staged_path(t);
-        reinterpret_cast<uint16_t *>(walk_tables)[t] =
-            static_cast<uint16_t>((STAGED_FIELDS_AT + FIELD * path) | ((path * (4 << LOWER)) << 8));
-        walk_tables[256 + t] = static_cast<uint8_t>((path >> (3 - LOWER)) * 4);
+        walk_tables[2 * t] = static_cast<uint8_t>(STAGED_FIELDS_AT + FIELD * path);
+        walk_tables[2 * t + 1] = static_cast<uint8_t>(WHOLE ? path * (4 << LOWER) : 32 + 4 * path);
+        walk_tables[256 + t] = static_cast<uint8_t>((path >> (3 - LOWER)) * (WHOLE ? 4 : 1));
     }
 
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory

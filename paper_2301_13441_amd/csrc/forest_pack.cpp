@@ -511,7 +511,7 @@ int compile_forest(const forest_desc &d, PackedModel &m)
                 const int32_t pos = w * block + (block - 1 - j);
                 // where a node sits in the tree's bit string: by heap index, or in the fields
                 // the table walk of the rank kernels reads (forest_model.hpp)
-                const bool staged = m.path == PATH_RANK && m.kind >= STAGED_MIN_DEPTH && m.kind <= STAGED_MAX_DEPTH;
+                const bool staged = m.path == PATH_RANK && m.kind >= STAGED_MIN_DEPTH && m.kind <= STAGED_TOP_MAX_DEPTH;
                 const int32_t i = staged ? staged_position_node(m.kind, pos) : pos - shift;
                 if (i < 0 || i >= n_int) {
                     m.prog.push_back(pad);

@@ -506,26 +506,30 @@ def test_compare_rate_probe_refuses_bad_arguments_before_any_launch():
 
 
 def test_staged_positions_of_full_trees_and_the_table_walk():
-    """Depths 4..6 on the rank path keep a tree's outcome bits in fields a table walk reads three
+    """Depths 4..8 on the rank path keep a tree's outcome bits in fields a table walk reads three
     levels at a time (Section 3.1.2: all internal nodes are evaluated; the leaf reached is the one
-    whose root path agrees with the outcomes).  The position map must be a bijection onto the
-    tree's nodes, and the walk over it -- simulated here exactly as the kernel takes it -- must end
-    on the leaf the heap walk ends on, for every depth and many outcome patterns."""
+    whose root path agrees with the outcomes); depths 7 and 8 do so for levels 0..4 and keep the heap
+    order below.  The position map must be a bijection onto the tree's nodes, and the walk over it
+    -- simulated here exactly as the kernel takes it -- must end on the leaf the heap walk ends on,
+    for every depth and many outcome patterns."""
     rng = np.random.default_rng(46)
-    for depth in (4, 5, 6):
+
+    def path3(t):       # path through a complete 3-level subtree, local heap order
+        p = 1
+        for _ in range(3):
+            p = 2 * p + ((t >> (p - 1)) & 1)
+        return p - 8
+
+    for depth in (4, 5, 6, 7, 8):
         n_pos, n_int = 1 << depth, (1 << depth) - 1
         node_at = [binding.forest_staged_position(depth, pos) for pos in range(n_pos)]
         assert sorted(v for v in node_at if v >= 0) == list(range(n_int))
         assert node_at[0] == -1 and [node_at[p] for p in range(1, 8)] == list(range(7))
-        lower = depth - 3
+        levels = depth if depth <= 6 else 5            # levels the fields cover
+        lower = levels - 3
         field = (1 << lower) - 1
-
-        def path3(t):       # path through a complete 3-level subtree, local heap order
-            p = 1
-            for _ in range(3):
-                p = 2 * p + ((t >> (p - 1)) & 1)
-            return p - 8
-
+        if depth > 6:
+            assert [node_at[p] for p in range(32, n_pos)] == list(range(31, n_int))
         for trial in range(300):
             outcome = rng.integers(0, 2, n_int)            # by level-order ordinal; 1 = right
             h = 1
@@ -536,7 +540,13 @@ def test_staged_positions_of_full_trees_and_the_table_walk():
             top = path3((bits >> 1) & 0x7f)
             start = 8 + field * top
             inner = path3((bits >> start) & ((1 << field) - 1)) >> (3 - lower)
-            assert top * (1 << lower) + inner == want
-    for depth, pos in ((3, 0), (7, 0), (4, 16), (6, -1)):
+            got = top * (1 << lower) + inner                # path through `levels` levels
+            if depth > 6:                                   # the bit walk goes on from heap position 32 + path
+                h = 32 + got
+                for _ in range(depth - 5):
+                    h = 2 * h + ((bits >> h) & 1)
+                got = h - n_pos
+            assert got == want
+    for depth, pos in ((3, 0), (9, 0), (4, 16), (6, -1)):
         with pytest.raises(binding.ForestError):
             binding.forest_staged_position(depth, pos)
