@@ -30,7 +30,12 @@ namespace forest_impl {
 namespace {
 
 enum { MODE_SCALAR = 0, MODE_VECTOR = 1, MODE_LEAVES = 2 };
-constexpr int WALK_TABLE_BYTES = 384;  // 128 x 2 + 128 bytes at the start of the LDS
+constexpr int WALK_TABLE_BYTES = 512;  // 128 two-byte records and two tables of 128 bytes at the start of the LDS
+// Depths 7, 8: every wave keeps the words behind a tree's first one in LDS, one dword per word and
+// row ([word][row slot][lane], one spare word): which of them holds the field of a lane's level-5
+// subtree differs from lane to lane, and registers cannot be indexed per lane.
+constexpr int deep_words(int depth) { return depth > STAGED_MAX_DEPTH ? (1 << depth) / 32 : 0; }
+constexpr int deep_bytes_per_wave(int depth) { return deep_words(depth) * 2 * TILE * 4; }
 
 // ---------------------------------------------------------------------------------------
 // Bit collection on the matrix core with operands placed by hand.
@@ -253,6 +258,14 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
 #endif
     };
     (void)walk_tables;
+    // the wave's strip for the words of deep trees, at a literal address plus the lane's: indexed
+    // as an array, so that constant parts of an index end up in the instruction
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) uint32_t *DeepPtr;
+#else
+    typedef uint32_t *DeepPtr;  // host pass: the kernel body is only parsed
+#endif
+    const DeepPtr deep = (DeepPtr)(static_cast<uintptr_t>(WALK_TABLE_BYTES + wave * deep_bytes_per_wave(D) + lane * 4));
     // Whether the first table is read while the tree's second word is evaluated (two more registers
     // live across that statement; the 128-register kernel has none to spare and measured the same
     // either way).
@@ -350,35 +363,75 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                     // compiler adds the two bytes to the 64-bit base one after the other)
                     asm volatile("" : "+v"(leaf4[0]), "+v"(leaf4[1]));
                 }
-            } else if (D > STAGED_MAX_DEPTH && w == 0) {
-                // Depths 7, 8: levels 0..4 (the first word) by the same tables, which give the heap
-                // position after five levels; the deeper levels take the bit walk from there.
-                uint32_t top[R], field[R];
+            } else if constexpr (D > STAGED_MAX_DEPTH) {
+                // Depths 7, 8.  The first word (levels 0..4) by the same two tables, which give the
+                // ordinal of the level-5 subtree the row reaches.  The other words go to the wave's
+                // strip of LDS as they come; after the last one every lane reads the two words its
+                // subtree's field lies in (7 or 3 bits at 7 or 3 times the ordinal), and a third
+                // table gives 4 x the leaf's ordinal inside the subtree.
+                constexpr uint32_t DL = D - 5, DFIELD = (1u << DL) - 1u;
+                if (w == 0) {
+                    uint32_t top[R], field[R];
 #pragma unroll
-                for (int r = 0; r < R; ++r) top[r] = word[r] & 0xfeu;
+                    for (int r = 0; r < R; ++r) top[r] = word[r] & 0xfeu;
 #if defined(__HIP_DEVICE_COMPILE__)
-                __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    start[r] = table(top[r], 0u);
-                    base4[r] = table(top[r], 1u);
+                    for (int r = 0; r < R; ++r) {
+                        start[r] = table(top[r], 0u);
+                        base4[r] = table(top[r], 1u);
+                    }
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                    for (int r = 0; r < R; ++r) field[r] = __builtin_amdgcn_ubfe(word[r], start[r], 3u);  // reads 5 bits of start
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                    for (int r = 0; r < R; ++r) pos[r] = table(field[r], 256u);
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+                    for (int r = 0; r < R; ++r) pos[r] += base4[r];  // ordinal of the level-5 subtree, 0..31
+                } else {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) deep[(w - 1) * (2 * TILE) + r * TILE] = word[r];
                 }
+                if (w == NW - 1) {
+                    uint32_t lo_w[R], hi_w[R], shift[R], field[R], inner[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        uint32_t bit = pos[r] << DL;
+                        asm volatile("" : "+v"(bit));  // (kept from being turned back into a 32-bit multiplication)
+                        bit -= pos[r];                 // DFIELD x the ordinal: where the field begins
+                        const DeepPtr at = deep + (bit >> 5) * (2 * TILE);
+                        shift[r] = bit & 31u;
+                        lo_w[r] = at[r * TILE];
+                        hi_w[r] = at[r * TILE + 2 * TILE];                        // the spare word behind the last one
+                    }
 #if defined(__HIP_DEVICE_COMPILE__)
-                __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                for (int r = 0; r < R; ++r) field[r] = __builtin_amdgcn_ubfe(word[r], start[r], 3u);  // reads 5 bits of start
+                    for (int r = 0; r < R; ++r)
+                        field[r] = static_cast<uint32_t>(((static_cast<uint64_t>(hi_w[r]) << 32) | lo_w[r]) >> shift[r]) &
+                                   ((1u << DFIELD) - 1u);
 #if defined(__HIP_DEVICE_COMPILE__)
-                __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                for (int r = 0; r < R; ++r) pos[r] = table(field[r], 256u);
+                    for (int r = 0; r < R; ++r) inner[r] = table(field[r], 384u);
 #if defined(__HIP_DEVICE_COMPILE__)
-                __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_sched_barrier(0);
 #endif
 #pragma unroll
-                for (int r = 0; r < R; ++r) pos[r] += base4[r];
+                    for (int r = 0; r < R; ++r) leaf4[r] = (pos[r] << (DL + 2)) + inner[r];
+                    asm volatile("" : "+v"(leaf4[0]), "+v"(leaf4[1]));
+                }
             } else {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
@@ -388,11 +441,10 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             }
             // a word is dealt with before the next one is evaluated: its halves are not copied aside
             if constexpr (STAGED) asm volatile("" : "+v"(word0[0]), "+v"(word0[1]));
-            else if (D >= 7) asm volatile("" : "+v"(pos[0]), "+v"(pos[1]), "+v"(sel[0]), "+v"(sel[1]));
             else asm volatile("" : "+v"(pos[0]), "+v"(pos[1]));
         }
     };
-    constexpr int LEAF0 = STAGED ? 0 : (1 << D);  // what leaf4 / 4 counts from
+    constexpr int LEAF0 = D >= STAGED_MIN_DEPTH ? 0 : (1 << D);  // what leaf4 / 4 counts from
 
     if constexpr (MODE == MODE_SCALAR) {
         // wave-uniform base of the current tree's leaf values, shifted so that what the walk ends
@@ -454,24 +506,27 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void fore
     // The walk's tables come first, at addresses the compiler knows: 128 16-bit records, then 128
     // bytes (rank_trees_hand; only the depths with the field layout read them).
     uint8_t *walk_tables = reinterpret_cast<uint8_t *>(smem);
-    uint32_t *rk = reinterpret_cast<uint32_t *>(smem + WALK_TABLE_BYTES);  // [32 * NVR][64] packed ranks, then reused as:
-    double *acc = reinterpret_cast<double *>(smem + WALK_TABLE_BYTES);     // [WAVES][K][128] partial sums
+    constexpr int FRONT = WALK_TABLE_BYTES + WAVES * deep_bytes_per_wave(D);  // tables, then the waves' strips for deep trees
+    uint32_t *rk = reinterpret_cast<uint32_t *>(smem + FRONT);  // [32 * NVR][64] packed ranks, then reused as:
+    double *acc = reinterpret_cast<double *>(smem + FRONT);     // [WAVES][K][128] partial sums
 
     const int lane = threadIdx.x & (TILE - 1);
     const int wave = uniform(threadIdx.x >> 6);
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RROWS;
 
     if (D >= STAGED_MIN_DEPTH && threadIdx.x < 128) {
-        // Depths 4..6: the records hold 4 x leaf ordinals.  Depths 7, 8: the tables cover levels
-        // 0..4 and hold heap positions (32 + the path through five levels), where the bit walk of
-        // the deeper levels goes on.
+        // Depths 4..6: the records hold 4 x leaf ordinals.  Depths 7, 8: the first two tables cover
+        // levels 0..4 and hold ordinals of level-5 subtrees, the third one the path through such a
+        // subtree (4 x the leaf's ordinal inside it).
         constexpr bool WHOLE = D <= STAGED_MAX_DEPTH;
         constexpr int LOWER = WHOLE ? (D - 3 > 0 ? D - 3 : 0) : 2;   // levels below the top three
         constexpr int FIELD = (1 << LOWER) - 1;                     // bits of a lower subtree's field
+        constexpr int DEEP = WHOLE ? 0 : D - 5;                     // levels of a level-5 subtree
         const int t = threadIdx.x, path = staged_path(t);
         walk_tables[2 * t] = static_cast<uint8_t>(STAGED_FIELDS_AT + FIELD * path);
-        walk_tables[2 * t + 1] = static_cast<uint8_t>(WHOLE ? path * (4 << LOWER) : 32 + 4 * path);
+        walk_tables[2 * t + 1] = static_cast<uint8_t>(WHOLE ? path * (4 << LOWER) : 4 * path);
         walk_tables[256 + t] = static_cast<uint8_t>((path >> (3 - LOWER)) * (WHOLE ? 4 : 1));
+        walk_tables[384 + t] = static_cast<uint8_t>((path >> (3 - DEEP)) * 4);
     }
 
     if (m.n_splits > 1) {  // launch-uniform: the ranks of the tile are already in global memory
@@ -507,7 +562,7 @@ size_t rank_lds_bytes(const DevModel &m, int nvr)
 {
     const size_t a = sizeof(double) * WAVES * m.n_outputs * RROWS;
     const size_t b = sizeof(uint32_t) * 32 * nvr * TILE;
-    return WALK_TABLE_BYTES + (a > b ? a : b);
+    return WALK_TABLE_BYTES + static_cast<size_t>(WAVES) * deep_bytes_per_wave(m.kind) + (a > b ? a : b);
 }
 
 template <int NVR>

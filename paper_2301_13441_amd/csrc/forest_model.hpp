@@ -60,35 +60,40 @@ inline uint16_t rank_entry_bits(int q)
     return static_cast<uint16_t>(((c ^ 0x8000u) & 0x8000u) | ((c & 0x7fffu) + (2u << 10)));
 }
 // Full trees of depth 4 and more on the rank path: where in a tree's outcome bit string each
-// internal node sits.  The walk of these trees takes three levels at a time from a table (the 7
-// outcomes of a complete 3-level subtree index it, the path through the subtree comes out), so the
-// bits of such a subtree must be adjacent: position 0 is empty, positions 1..7 hold levels 0..2
-// (position = heap index), then the 8 subtrees rooted at level 3 follow from position 8 on, one
-// field of 2^(levels - 3) - 1 bits each (local heap order: root, its children, their children), in
-// the order of their roots.  Depths 4..6: the whole tree (levels = depth).  Depths 7 and 8: the
-// first word only, i.e. levels 0..4 (levels = 5); from position 32 on the deeper levels keep
-// position = heap index and the bit walk.  Returns the node's level-order ordinal (heap index
-// - 1), or -1 for a position no node has.  (Depths 1..3 keep the heap order throughout.)
+// internal node sits.  The walk of these trees takes up to three levels at a time from a table
+// (the 7 outcomes of a complete 3-level subtree index it, the path through the subtree comes out),
+// so the bits of such a subtree must be adjacent: position 0 is empty, positions 1..7 hold levels
+// 0..2 (position = heap index), then the 8 subtrees rooted at level 3 follow from position 8 on,
+// one field of 2^(levels - 3) - 1 bits each (local heap order: root, its children, their
+// children), in the order of their roots.  Depths 4..6: that is the whole tree (levels = depth).
+// Depths 7 and 8: that is the first word, levels 0..4 (levels = 5); from position 32 on follow the
+// 32 subtrees rooted at level 5, one field of 2^(depth - 5) - 1 bits each, which fill the other
+// words exactly.  Returns the node's level-order ordinal (heap index - 1), or -1 for a position no
+// node has.  (Depths 1..3 keep the heap order: position = heap index.)
 constexpr int STAGED_MIN_DEPTH = 4, STAGED_MAX_DEPTH = 6, STAGED_TOP_MAX_DEPTH = 8;
-constexpr int STAGED_FIELDS_AT = 8;  // first position of the lower subtrees' fields
+constexpr int STAGED_FIELDS_AT = 8;  // first position of the fields of the subtrees rooted at level 3
+constexpr int STAGED_DEEP_AT = 32;   // and of those rooted at level 5
 
 #if defined(__HIPCC__)
 __host__ __device__
 #endif
 inline int staged_position_node(int depth, int pos)
 {
-    const int levels = depth > STAGED_MAX_DEPTH ? 5 : depth;  // levels the fields cover
-    if (pos >= (1 << levels)) return pos - 1;    // deeper levels of depth 7, 8: heap index pos
-    const int lower = levels - 3;                // levels below the top three
-    const int field = (1 << lower) - 1;          // nodes of a lower subtree
-    if (pos < 1) return -1;
-    if (pos < STAGED_FIELDS_AT) return pos - 1;  // heap index pos
-    const int q = pos - STAGED_FIELDS_AT;
-    if (q >= 8 * field) return -1;
+    int root0, q, field;  // heap index of the first subtree root, position inside the fields, field size
+    if (depth > STAGED_MAX_DEPTH && pos >= STAGED_DEEP_AT) {
+        root0 = 32, q = pos - STAGED_DEEP_AT, field = (1 << (depth - 5)) - 1;
+        if (q >= 32 * field) return -1;
+    } else {
+        const int levels = depth > STAGED_MAX_DEPTH ? 5 : depth;  // levels the first fields cover
+        if (pos < 1) return -1;
+        if (pos < STAGED_FIELDS_AT) return pos - 1;  // heap index pos
+        root0 = 8, q = pos - STAGED_FIELDS_AT, field = (1 << (levels - 3)) - 1;
+        if (q >= 8 * field) return -1;
+    }
     const int subtree = q / field, local = q % field + 1;  // local heap index 1 .. field
     int level = 0;
     while ((2 << level) <= local) ++level;       // level of `local` inside its subtree
-    const int heap = ((8 + subtree) << level) + (local - (1 << level));
+    const int heap = ((root0 + subtree) << level) + (local - (1 << level));
     return heap - 1;
 }
 

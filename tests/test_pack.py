@@ -508,8 +508,8 @@ def test_compare_rate_probe_refuses_bad_arguments_before_any_launch():
 def test_staged_positions_of_full_trees_and_the_table_walk():
     """Depths 4..8 on the rank path keep a tree's outcome bits in fields a table walk reads three
     levels at a time (Section 3.1.2: all internal nodes are evaluated; the leaf reached is the one
-    whose root path agrees with the outcomes); depths 7 and 8 do so for levels 0..4 and keep the heap
-    order below.  The position map must be a bijection onto the tree's nodes, and the walk over it
+    whose root path agrees with the outcomes); depths 7 and 8 do so for levels 0..4 and keep the
+    subtrees rooted at level 5 in fields of their own behind position 32.  The position map must be a bijection onto the tree's nodes, and the walk over it
     -- simulated here exactly as the kernel takes it -- must end on the leaf the heap walk ends on,
     for every depth and many outcome patterns."""
     rng = np.random.default_rng(46)
@@ -528,8 +528,6 @@ def test_staged_positions_of_full_trees_and_the_table_walk():
         levels = depth if depth <= 6 else 5            # levels the fields cover
         lower = levels - 3
         field = (1 << lower) - 1
-        if depth > 6:
-            assert [node_at[p] for p in range(32, n_pos)] == list(range(31, n_int))
         for trial in range(300):
             outcome = rng.integers(0, 2, n_int)            # by level-order ordinal; 1 = right
             h = 1
@@ -541,11 +539,11 @@ def test_staged_positions_of_full_trees_and_the_table_walk():
             start = 8 + field * top
             inner = path3((bits >> start) & ((1 << field) - 1)) >> (3 - lower)
             got = top * (1 << lower) + inner                # path through `levels` levels
-            if depth > 6:                                   # the bit walk goes on from heap position 32 + path
-                h = 32 + got
-                for _ in range(depth - 5):
-                    h = 2 * h + ((bits >> h) & 1)
-                got = h - n_pos
+            if depth > 6:                                   # the field of the level-5 subtree the path leads to
+                deep = depth - 5
+                width = (1 << deep) - 1
+                inner = path3((bits >> (32 + width * got)) & ((1 << width) - 1)) >> (3 - deep)
+                got = got * (1 << deep) + inner
             assert got == want
     for depth, pos in ((3, 0), (9, 0), (4, 16), (6, -1)):
         with pytest.raises(binding.ForestError):
