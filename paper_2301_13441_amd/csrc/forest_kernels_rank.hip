@@ -262,8 +262,10 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     // as an array, so that constant parts of an index end up in the instruction
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) uint32_t *DeepPtr;
+    typedef volatile __attribute__((address_space(3))) uint16_t *DeepHalfPtr;  // volatile: not merged back into words
 #else
     typedef uint32_t *DeepPtr;  // host pass: the kernel body is only parsed
+    typedef volatile uint16_t *DeepHalfPtr;
 #endif
     const DeepPtr deep = (DeepPtr)(static_cast<uintptr_t>(WALK_TABLE_BYTES + wave * deep_bytes_per_wave(D) + lane * 4));
     // Whether the first table is read while the tree's second word is evaluated (two more registers
@@ -304,7 +306,8 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
             uint32_t word[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                if (GW == 4) word[r] = __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u);
+                if (D > STAGED_MAX_DEPTH && w > 0) word[r] = 0u;  // its halves go to LDS as they are
+                else if (GW == 4) word[r] = __builtin_amdgcn_perm(__float_as_uint(hi[r]), __float_as_uint(lo[r]), 0x05040100u);
                 else if (GW == 2) word[r] = __float_as_uint(lo[r]);  // the bits above the 16 are never indexed
                 else word[r] = __float_as_uint(lo[r]) >> 8;
             }
@@ -399,7 +402,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                     for (int r = 0; r < R; ++r) pos[r] += base4[r];  // ordinal of the level-5 subtree, 0..31
                 } else {
 #pragma unroll
-                    for (int r = 0; r < R; ++r) deep[(w - 1) * (2 * TILE) + r * TILE] = word[r];
+                    for (int r = 0; r < R; ++r) {
+                        // the word's two halves, stored as 16 bits each: no instruction to join them
+                        const DeepHalfPtr half = (DeepHalfPtr)(deep + (w - 1) * (2 * TILE) + r * TILE);
+                        half[0] = static_cast<uint16_t>(__float_as_uint(lo[r]));
+                        half[1] = static_cast<uint16_t>(__float_as_uint(hi[r]));
+                    }
                 }
                 if (w == NW - 1) {
                     uint32_t lo_w[R], hi_w[R], shift[R], field[R], inner[R];
