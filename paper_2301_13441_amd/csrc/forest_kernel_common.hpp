@@ -198,28 +198,6 @@ __device__ __forceinline__ uint32_t heap_walk(const uint32_t (&word)[NW])
     return heap_walk_pos<D, NW>(word) - (1u << D);
 }
 
-// The same walk taken word by word as the outcome words are produced (w = 0, 1, ...), so only
-// the position and one selected word stay live: word 0 serves levels 0-4, word 1 level 5,
-// words 2-3 level 6 (chosen by bit 5 of the position), words 4-7 level 7 (bits 5-6).
-template <int D>
-__device__ __forceinline__ void heap_walk_word(int w, uint32_t word, uint32_t &pos, uint32_t &sel)
-{
-    if (w == 0) {
-#pragma unroll
-        for (int l = 0; l < (D < 5 ? D : 5); ++l) pos = pos + pos + __builtin_amdgcn_ubfe(word, pos, 1u);
-    } else if (w == 1) {
-        pos = pos + pos + __builtin_amdgcn_ubfe(word, pos, 1u);
-    } else if (w == 2 || w == 4) {
-        sel = word;
-    } else if (w == 3) {
-        sel = (pos & 32u) ? word : sel;
-        pos = pos + pos + __builtin_amdgcn_ubfe(sel, pos, 1u);
-    } else {
-        sel = (((pos >> 5) & 3u) == static_cast<uint32_t>(w - 4)) ? word : sel;
-        if (w == 7) pos = pos + pos + __builtin_amdgcn_ubfe(sel, pos, 1u);
-    }
-}
-
 using KernelFn = void (*)(DevModel, const float *, int64_t, float *, int32_t *, int32_t *);
 
 }  // namespace forest_impl

@@ -274,11 +274,11 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
     constexpr bool EARLY = NVR < 4 && NW == 2;
 
     // evaluates and walks the next tree of the stream: leaf4[r] = 4 x the ordinal of the leaf row r
-    // ends on (heap walks: 4 x the heap position, 2^D + ordinal)
+    // ends on (depths 1..3: 4 x the heap position, 2^D + ordinal)
     auto walk_tree = [&](uint32_t (&leaf4)[R]) {
-        uint32_t pos[R], sel[R], word0[R], start[R], base4[R];
+        uint32_t pos[R], word0[R], start[R], base4[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) pos[r] = 1u, sel[r] = 0u, word0[r] = 0u, start[r] = 0u, base4[r] = 0u;
+        for (int r = 0; r < R; ++r) pos[r] = 1u, word0[r] = 0u, start[r] = 0u, base4[r] = 0u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             // Scalar loads return in any order, so the only wait there is waits for all of them: the
@@ -441,10 +441,12 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
                     asm volatile("" : "+v"(leaf4[0]), "+v"(leaf4[1]));
                 }
             } else {
+                // Depths 1..3: one word in heap order (bit = heap index), one step per level.
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    heap_walk_word<D>(w, word[r], pos[r], sel[r]);
-                    if (w == NW - 1) leaf4[r] = pos[r] << 2;
+#pragma unroll
+                    for (int l = 0; l < D; ++l) pos[r] = pos[r] + pos[r] + __builtin_amdgcn_ubfe(word[r], pos[r], 1u);
+                    leaf4[r] = pos[r] << 2;
                 }
             }
             // a word is dealt with before the next one is evaluated: its halves are not copied aside
