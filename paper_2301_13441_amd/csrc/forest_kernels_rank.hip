@@ -249,7 +249,7 @@ __device__ __forceinline__ void rank_trees_hand(const DevModel &m, const v32u (&
 
     // The walk's tables, read at LDS addresses the instruction can hold: the tables are the first
     // thing in the kernel's LDS (address 0: the kernel has no static LDS, init_rank_kernels checks).
-    // byte `offset + index` of the tables
+    // table(index, offset) is byte `offset + index` of them.
     auto table = [](uint32_t index, uint32_t offset) -> uint32_t {
 #if defined(__HIP_DEVICE_COMPILE__)
         return *reinterpret_cast<const __attribute__((address_space(3))) uint8_t *>(static_cast<uintptr_t>(offset + index));
@@ -513,8 +513,8 @@ __global__ __launch_bounds__(BLOCK, (NVR == 1 ? 6 : NVR == 2 ? 4 : 3)) void fore
 {
     constexpr int R = 2;
     extern __shared__ __align__(16) char smem[];
-    // The walk's tables come first, at addresses the compiler knows: 128 16-bit records, then 128
-    // bytes (rank_trees_hand; only the depths with the field layout read them).
+    // The walk's tables come first, at addresses the compiler knows: 128 two-byte records and two
+    // tables of 128 bytes (rank_trees_hand; depths 4 and more read them).
     uint8_t *walk_tables = reinterpret_cast<uint8_t *>(smem);
     constexpr int FRONT = WALK_TABLE_BYTES + WAVES * deep_bytes_per_wave(D);  // tables, then the waves' strips for deep trees
     uint32_t *rk = reinterpret_cast<uint32_t *>(smem + FRONT);  // [32 * NVR][64] packed ranks, then reused as:
