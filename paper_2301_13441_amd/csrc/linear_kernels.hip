@@ -116,6 +116,30 @@ __device__ __forceinline__ void load_chunk(Piece<V> (&pre)[CHUNK / V], const flo
     }
 }
 
+// The same pieces when the tile has all 64 rows and the chunk all 32 columns (every tile and chunk
+// but the last ones): nothing to test, and nothing is done to the values once they are requested,
+// so the loads stay in flight until the chunk is parked.  `chunk` is the tile's first row at the
+// chunk's first column (wave-uniform), `lane_bytes` the lane's place in piece 0.
+template <int V>
+__device__ __forceinline__ void load_chunk_full(Piece<V> (&pre)[CHUNK / V], const float *__restrict__ chunk, int F,
+                                                uint32_t lane_bytes)
+{
+    constexpr int RPI = LANES / (CHUNK / V);
+#pragma unroll
+    for (int i = 0; i < CHUNK / V; ++i) {
+        const char *q = reinterpret_cast<const char *>(chunk + static_cast<int64_t>(i) * RPI * F) + lane_bytes;
+        if (V == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(q);
+            pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y, pre[i].v[2 % V] = t.z, pre[i].v[3 % V] = t.w;
+        } else if (V == 2) {
+            const float2 t = *reinterpret_cast<const float2 *>(q);
+            pre[i].v[0] = t.x, pre[i].v[1 % V] = t.y;
+        } else {
+            pre[i].v[0] = *reinterpret_cast<const float *>(q);
+        }
+    }
+}
+
 template <int V>
 __device__ __forceinline__ void park_chunk(float *xs, const Piece<V> (&pre)[CHUNK / V], int lane)
 {
@@ -151,15 +175,26 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
 #pragma unroll
     for (int k = 0; k < KP; ++k) acc[k] = m.bias[k];
 
-    // The next two chunks are on their way from HBM (held in registers) while the current one is used.
+    // Chunks that are whole (all 64 rows, all 32 columns) go through a loop of fixed shape: two
+    // chunks are on their way from HBM, held in registers, while the current one is used, and every
+    // step requests eight loads -- past the last whole chunk they all read the tile's first floats,
+    // one cache line, and are dropped -- so the number of loads between a request and its use is
+    // known and a wave waits only for the chunk it is about to park.  What is left (the last
+    // columns of a matrix whose width is not a multiple of 32; every chunk of the last tile) goes
+    // one chunk at a time through the loads that test and mask.
     Piece<V> pre0[CHUNK / V], pre1[CHUNK / V];
-    auto fetch = [&](Piece<V> (&pre)[CHUNK / V], int c) {
-        if (c < F) load_chunk<V>(pre, src, F, c, F - c < CHUNK ? F - c : CHUNK, rows_here, lane);
+    const int n_whole = rows_here == LANES ? F / CHUNK : 0;  // wave-uniform
+    const uint32_t lane_bytes =
+        static_cast<uint32_t>(sizeof(float)) * (static_cast<uint32_t>(lane / (CHUNK / V)) * static_cast<uint32_t>(F) + (lane % (CHUNK / V)) * V);
+    auto fetch = [&](Piece<V> (&pre)[CHUNK / V], int chunk) {
+        const bool there = chunk < n_whole;
+        load_chunk_full<V>(pre, there ? src + chunk * CHUNK : src, there ? F : 0, there ? lane_bytes : 0u);
     };
-    auto use = [&](int c0) {
+    // The feature loop runs through all chunks as one stream of weights.
+    WeightPtr w = (WeightPtr)m.weight;
+    auto use = [&]() {
         // the tile holds zeros past the last feature and the weight matrix has zero rows there,
         // so every chunk runs all 32 columns without a test
-        WeightPtr w = (WeightPtr)(m.weight + static_cast<int64_t>(c0) * KP);
         const float4 *row = reinterpret_cast<const float4 *>(xs + lane * STRIDE);
 #pragma unroll 2
         for (int c = 0; c < CHUNK; c += 4) {
@@ -169,21 +204,33 @@ __global__ __launch_bounds__(LANES *LWAVES) void linear_kernel(LinDev m, const f
             for (int j = 0; j < 4; ++j) {
                 const double x = static_cast<double>(x4[j]);
 #pragma unroll
-                for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[(c + j) * KP + k], acc[k]);
+                for (int k = 0; k < KP; ++k) acc[k] = __builtin_fma(x, w[j * KP + k], acc[k]);
             }
+            w += 4 * KP;
         }
     };
-    fetch(pre0, 0);
-    fetch(pre1, CHUNK);
-    for (int c0 = 0; c0 < F; c0 += 2 * CHUNK) {
-        park_chunk<V>(xs, pre0, lane);
-        fetch(pre0, c0 + 2 * CHUNK);
-        use(c0);
-        if (c0 + CHUNK < F) {
+    int chunk = 0;
+    if (n_whole > 0) {
+        fetch(pre0, 0);
+        fetch(pre1, 1);
+        for (; chunk + 2 <= n_whole; chunk += 2) {
+            park_chunk<V>(xs, pre0, lane);
+            fetch(pre0, chunk + 2);
+            use();
             park_chunk<V>(xs, pre1, lane);
-            fetch(pre1, c0 + 3 * CHUNK);
-            use(c0 + CHUNK);
+            fetch(pre1, chunk + 3);
+            use();
         }
+        if (chunk < n_whole) {
+            park_chunk<V>(xs, pre0, lane);
+            use();
+            ++chunk;
+        }
+    }
+    for (int c0 = chunk * CHUNK; c0 < F; c0 += CHUNK) {
+        load_chunk<V>(pre0, src, F, c0, F - c0 < CHUNK ? F - c0 : CHUNK, rows_here, lane);
+        park_chunk<V>(xs, pre0, lane);
+        use();
     }
 
     if (lane < rows_here) finish_linear_row<KP>(m, acc, row0 + lane, scores, labels);
