@@ -189,6 +189,16 @@ __device__ __forceinline__ void issue_after(ProgPtr &p, const Batch<16> &set)
     asm volatile("" : "+s"(p) : "s"(set.q[0].e[0]));
 }
 
+// The row of the workgroup's tile that a lane walks: lanes 2 i and 2 i + 1 of wave w take row
+// 8 i + w (one tree of the batch each).  A wave's 32 rows are 8 apart, so their outcome bytes of one
+// group lie in 32 different LDS banks (rows next to each other would share 8 banks, and the walk's
+// byte reads, which every lane makes at every step, would queue eight deep).
+__device__ __forceinline__ int bank_walk_row(int wave, int lane)
+{
+    static_assert(BANK_ROWS_PER_WAVE * BANK_WAVES == BANK_ROWS, "every row of the tile is walked by one wave");
+    return (lane / BANK_TREES) * BANK_WAVES + wave;
+}
+
 // sum over the lanes that share a row (one per tree of the batch), the same bits in each
 __device__ __forceinline__ double row_sum(double v)
 {
@@ -205,7 +215,7 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
 {
     const int T = m.n_trees;
     const int K = m.n_outputs;
-    const int walk_row = wave * BANK_ROWS_PER_WAVE + lane / BANK_TREES;  // the lane's row of the tile in the walk
+    const int walk_row = bank_walk_row(wave, lane);                      // the lane's row of the tile in the walk
     const int walk_tree = lane % BANK_TREES;                            // and its tree of the batch
     const int64_t row = row0 + walk_row;
     BitCollector bits;
@@ -441,7 +451,7 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
     uint32_t *child_lds = reinterpret_cast<uint32_t *>(buf + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
     bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane_now, row0, n_rows, leaf_out);
     if (MODE == BANK_LEAVES) return;
-    const int64_t row = row0 + wave * BANK_ROWS_PER_WAVE + lane_now / BANK_TREES;
+    const int64_t row = row0 + bank_walk_row(wave, lane_now);
     // a copy with run-time indices: indexed that way `sum` itself would live in scratch memory
     double raw[2] = {row_sum(sum[0]), row_sum(sum[1])};
     if (lane_now % BANK_TREES == 0 && row < n_rows) finish_values(m, raw, 1, row, scores, labels);
