@@ -42,8 +42,9 @@ MEASURED_TRAFFIC = {
     "c4": {"bytes": 6.861e8, "profile": "profiles/forest_rank_kernel_c3_c4.md", "commit": "8101bd8"},
     "c3": {"bytes": 2.130e8, "profile": "profiles/forest_rank_kernel_c3_c4.md", "commit": "8101bd8"},
     "c2": {"bytes": 1.595e8, "profile": "profiles/forest_rank_kernel_c2.md", "commit": "8101bd8"},
-    "l2": {"bytes": 1.456e9, "profile": "profiles/linear_kernels.md", "commit": "90d5834"},
-    "l3": {"bytes": 1.117e9, "profile": "profiles/linear_kernels.md", "commit": "1f84bb3"},
+    "l2": {"bytes": 1.456e9, "profile": "profiles/linear_kernels.md", "commit": "65bfc7c"},
+    "l3": {"bytes": 1.120e9, "profile": "profiles/linear_kernels.md", "commit": "65bfc7c"},
+    "l4": {"bytes": 9.600e8, "profile": "profiles/linear_kernels.md", "commit": "65bfc7c"},
 }
 
 
