@@ -116,7 +116,7 @@ def test_rows_of_whole_16_byte_pieces(F):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("F", [28, 64, 90, 130])
+@pytest.mark.parametrize("F", [28, 40, 64, 90, 100, 130])
 def test_x_that_starts_off_a_16_byte_boundary_and_absent_bias(F):
     """X may start at any float: 4, 8 or 12 bytes past a 16-byte boundary the kernels fall back
     to narrower loads.  The bias pointer may be NULL (zeros)."""
