@@ -199,6 +199,19 @@ __device__ __forceinline__ int bank_walk_row(int wave, int lane)
     return (lane / BANK_TREES) * BANK_WAVES + wave;
 }
 
+// The half of `pair` that the outcome bit of the slot at byte offset `at` picks (`byte`: the
+// outcome byte of the slot's group): three bit-field extractions and a shift, no comparison and
+// no select.
+__device__ __forceinline__ uint32_t pick_half(uint32_t pair, uint32_t byte, uint32_t at)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t bit = __builtin_amdgcn_ubfe(byte, __builtin_amdgcn_ubfe(at, 2u, 3u), 1u);
+    return __builtin_amdgcn_ubfe(pair, bit << 4, 16u);
+#else
+    return ((byte >> ((at >> 2) & 7u)) & 1u) ? (pair >> 16) : (pair & 0xffffu);
+#endif
+}
+
 // sum over the lanes that share a row (one per tree of the batch), the same bits in each
 __device__ __forceinline__ double row_sum(double v)
 {
@@ -383,19 +396,45 @@ __device__ __forceinline__ void bank_trees(const DevModel &m, const v32u &xa, co
         // reads the outcome byte and the word of where the lane stands (both reads in flight
         // together) and moves to the half of the word the outcome bit picks, which is the same
         // place again once the next node would be a leaf; no test, no branch but the loop's.
-        const uint8_t *bits_of_row = buf + walk_row;
+        // Both reads at literal LDS addresses (the kernel has no static LDS, so its dynamic LDS
+        // begins at address 0; init_rankbank_kernels checks that): a slot's word at the constant
+        // place of the child table plus the slot's offset, its group's byte at 256 bytes per
+        // group from the row's byte of group 0.
+#if defined(__HIP_DEVICE_COMPILE__)
+        typedef const __attribute__((address_space(3))) uint8_t *LdsByte;
+        typedef const __attribute__((address_space(3))) uint32_t *LdsWord;
+        const uint32_t row_byte = static_cast<uint32_t>(BANK_ROWS + sizeof(uint32_t) * BANK_UNIT * m.bank.max_units) + static_cast<uint32_t>(walk_row);
+        auto outcome_byte = [&](uint32_t where) -> uint32_t {
+            uint32_t group = where >> 5;
+            asm volatile("" : "+v"(group));  // keeps shift and shift-and-add apart: two instructions, not three
+            return *(LdsByte)static_cast<uintptr_t>(row_byte + (group << 8));
+        };
+        auto child_word = [&](uint32_t where) -> uint32_t { return *(LdsWord)static_cast<uintptr_t>(BANK_ROWS + where); };
+#else
+        const uint8_t *bits_of_row = buf + walk_row;  // host pass: the kernel body is only parsed
+        auto outcome_byte = [&](uint32_t where) -> uint32_t { return bits_of_row[(where >> 5) << 8]; };
+        auto child_word = [&](uint32_t where) -> uint32_t { return child_lds[where >> 2]; };
+#endif
         const bool single_leaf = (static_cast<uint32_t>(bt.root_ref) & BANK_LEAF_FLAG) != 0u;
         uint32_t at = single_leaf ? 0u : static_cast<uint32_t>(bt.root_ref);  // byte offset of the slot's word
         const int steps = this_batch.steps;
-        for (int step = 0; step < steps; ++step) {
-            const uint32_t byte = bits_of_row[(at & ~31u) << 3];  // group (at / 32) of BANK_ROWS bytes
-            const uint32_t c = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(child_lds) + at);
-            at = ((byte >> ((at >> 2) & 7u)) & 1u) ? (c >> 16) : (c & 0xffffu);
+        auto move = [&] {
+            const uint32_t byte = outcome_byte(at);  // group (at / 32) of BANK_ROWS bytes
+            const uint32_t c = child_word(at);
+            at = pick_half(c, byte, at);
+        };
+        int step = 0;
+        for (; step + 4 <= steps; step += 4) {  // (written out: the statement in outcome_byte keeps the compiler from unrolling)
+            move();
+            move();
+            move();
+            move();
         }
+        for (; step < steps; ++step) move();
         // where the lane stands now, the outcome bit picks a leaf
-        const uint32_t last_byte = bits_of_row[(at & ~31u) << 3];
+        const uint32_t last_byte = outcome_byte(at);
         const uint32_t leaves = m.bank.leaf[this_batch.slot_base + (at >> 2)];
-        const uint32_t picked = ((last_byte >> ((at >> 2) & 7u)) & 1u) ? (leaves >> 16) : (leaves & 0xffffu);
+        const uint32_t picked = pick_half(leaves, last_byte, at);
         // index into the per-leaf tables; the record that fills a batch of one tree gives leaf 0
         const int leaf = bt.leaf_base + static_cast<int>(single_leaf ? 0u : picked);
         pend_valid = bt.valid != 0;
@@ -447,8 +486,11 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
 #endif
 
     double sum[2] = {0.0, 0.0};
-    uint8_t *buf = reinterpret_cast<uint8_t *>(smem) + BANK_ROWS;  // see `prev` in bank_trees
-    uint32_t *child_lds = reinterpret_cast<uint32_t *>(buf + static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) * m.bank.max_units);
+    // a row of spare bytes, the batch's child references at a place the compiler knows (the walk
+    // then reads a slot's word at the slot's offset plus a constant, no addition), the outcome
+    // bytes behind them (`prev` in bank_trees may point one group in front of them)
+    uint32_t *child_lds = reinterpret_cast<uint32_t *>(smem + BANK_ROWS);
+    uint8_t *buf = reinterpret_cast<uint8_t *>(child_lds) + sizeof(uint32_t) * BANK_UNIT * static_cast<size_t>(m.bank.max_units);
     bank_trees<MODE>(m, xa, xb, buf, child_lds, sum, wave, lane_now, row0, n_rows, leaf_out);
     if (MODE == BANK_LEAVES) return;
     const int64_t row = row0 + bank_walk_row(wave, lane_now);
@@ -460,7 +502,7 @@ __global__ __launch_bounds__(BANK_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4
 size_t rankbank_lds_bytes(const DevModel &m)
 {
     const size_t tile = sizeof(float) * BANK_ROWS * BANK_TILE_PITCH;
-    // a row of spare bytes, the outcome bytes of a batch, then its child references (a word per slot)
+    // a row of spare bytes, a batch's child references (a word per slot), then its outcome bytes
     const size_t bytes = BANK_ROWS + (static_cast<size_t>(BANK_ROWS) * (BANK_UNIT / 8) + sizeof(uint32_t) * BANK_UNIT) *
                                          static_cast<size_t>(m.bank.max_units);
     return tile > bytes ? tile : bytes;
@@ -472,8 +514,14 @@ hipError_t init_rankbank_kernels(size_t lds_limit)
 {
     for (const void *fn : {reinterpret_cast<const void *>(forest_rankbank_kernel<BANK_SUMS>),
                            reinterpret_cast<const void *>(forest_rankbank_kernel<BANK_LEAVES>)}) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_limit));
         if (e != hipSuccess) return e;
+        // the walk reads LDS at literal addresses from 0 on: the kernel's dynamic LDS must begin
+        // there, i.e. the kernel must have no static LDS
+        hipFuncAttributes attr;
+        e = hipFuncGetAttributes(&attr, fn);
+        if (e != hipSuccess) return e;
+        if (attr.sharedSizeBytes != 0) return hipErrorInvalidConfiguration;
     }
     return hipSuccess;
 }
